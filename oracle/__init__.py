@@ -1,0 +1,243 @@
+"""ctypes front-end of the CPU oracle (``pulsed_update_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the test-suite, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this package; the product package never does.
+Nothing here touches the HIP library.
+
+Every function marshals numpy arrays into the C oracle and returns numpy
+arrays; the arithmetic lives in the C file, which cites the passages of
+arXiv 2104.02184 (Sec. 3, Eq. (2)) it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pulsed_update_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+CONSTANT_STEP, LINEAR_STEP, SOFT_BOUNDS = 0, 1, 2
+TAG_X, TAG_D, TAG_C2C, TAG_D2D = 1, 2, 3, 4
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no FMA contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+               "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        _lib = ctypes.CDLL(_LIB)
+        _declare(_lib)
+    return _lib
+
+
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+_u64p = ctypes.POINTER(ctypes.c_uint64)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_i8p = ctypes.POINTER(ctypes.c_int8)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_f, _i, _u32, _u64 = ctypes.c_float, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint64
+
+
+def _declare(L):
+    L.orc_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
+    L.orc_philox4x32_10.restype = None
+    L.orc_gauss_block_f64.argtypes = [_u64, _u32, _u32, _u32, _u32, _f64p]
+    L.orc_gauss_block_f64.restype = None
+    L.orc_gauss.argtypes = [_u64, _u32, _u32, _u32, _u32]
+    L.orc_gauss.restype = _f
+    L.orc_device_planes.argtypes = [_i] + [_f] * 11 + [_u64, _i, _i] + [_f32p] * 6
+    L.orc_device_planes.restype = None
+    L.orc_line_scale.argtypes = [_f32p, _f32p, _i, _i, _i, _f, _f, _i, _i, _f64p, _f64p]
+    L.orc_line_scale.restype = None
+    L.orc_threshold.argtypes = [ctypes.c_double, _f]
+    L.orc_threshold.restype = _u64
+    L.orc_pulse_word.argtypes = [_u64, _u32, _u32, _u32, _u32, ctypes.c_double, _f, _i]
+    L.orc_pulse_word.restype = _u64
+    L.orc_pulse_words.argtypes = [_f32p, _f32p, _i, _i, _i, _f, _f, _i, _i, _u64, _u32, _u64p, _u64p]
+    L.orc_pulse_words.restype = None
+    L.orc_counts.argtypes = [_u64p, _u64p, _i, _i, _i, _i, _i8p]
+    L.orc_counts.restype = None
+    L.orc_device_step.argtypes = [_i, _f, _i, _f, _f, _f, _f, _f, _f, _f, _f]
+    L.orc_device_step.restype = _f
+    L.orc_apply_words.argtypes = ([_f32p] * 7 + [_i, _f, _u64p, _u64p, _i, _i, _i, _i, _u64, _u32,
+                                                 _i64p, ctypes.c_int64])
+    L.orc_apply_words.restype = ctypes.c_int64
+    L.orc_pulsed_update.argtypes = ([_f32p] * 7 + [_i, _f, _f, _i, _i, _f32p, _f32p, _i, _i, _i, _f,
+                                                   _u64, _u32, _i64p, ctypes.c_int64])
+    L.orc_pulsed_update.restype = ctypes.c_int64
+    L.orc_num_threads.argtypes = []
+    L.orc_num_threads.restype = _i
+    L.orc_set_num_threads.argtypes = [_i]
+    L.orc_set_num_threads.restype = None
+
+
+def _p(a, typ):
+    return a.ctypes.data_as(typ)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+@dataclass
+class DeviceParams:
+    """Scalar device description in normalised units (names after the paper's
+    ``dw_min``, ``dw_min_dtod``, ``dw_min_std`` of its Tiki-Taka listing)."""
+    kind: int = CONSTANT_STEP
+    dw_min: float = 0.001
+    dw_min_dtod: float = 0.0
+    dw_min_std: float = 0.0      # pulse-to-pulse (cycle-to-cycle) relative std
+    up_down: float = 0.0
+    up_down_dtod: float = 0.0
+    w_max: float = 1.0
+    w_max_dtod: float = 0.0
+    w_min: float = -1.0
+    w_min_dtod: float = 0.0
+    gamma_up: float = 0.0
+    gamma_down: float = 0.0
+    gamma_dtod: float = 0.0
+
+
+PLANE_NAMES = ("dw_up", "dw_down", "b_max", "b_min", "slope_up", "slope_down")
+
+
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(_p(c, _u32p), _p(k, _u32p), _p(out, _u32p))
+    return out
+
+
+def gauss_block_f64(seed, index, t, blk, tag):
+    z = np.zeros(4, dtype=np.float64)
+    lib().orc_gauss_block_f64(seed, index, t, blk, tag, _p(z, _f64p))
+    return z
+
+
+def gauss(seed, index, t, q, tag):
+    return float(lib().orc_gauss(seed, index, t, q, tag))
+
+
+def device_planes(p: DeviceParams, seed: int, R: int, C: int):
+    """dict name -> float32 [R][C] plane."""
+    planes = {n: np.zeros((R, C), dtype=np.float32) for n in PLANE_NAMES}
+    lib().orc_device_planes(p.kind, p.dw_min, p.dw_min_dtod, p.up_down, p.up_down_dtod, p.w_max,
+                            p.w_max_dtod, p.w_min, p.w_min_dtod, p.gamma_up, p.gamma_down,
+                            p.gamma_dtod, seed, R, C, *[_p(planes[n], _f32p) for n in PLANE_NAMES])
+    return planes
+
+
+def line_scale(x, d, lr, dw_min, BL, update_management):
+    x, d = _f32(x), _f32(d)
+    B, C = x.shape
+    R = d.shape[1]
+    a_x = np.zeros(B, dtype=np.float64)
+    a_d = np.zeros(B, dtype=np.float64)
+    lib().orc_line_scale(_p(x, _f32p), _p(d, _f32p), B, R, C, lr, dw_min, BL,
+                         int(update_management), _p(a_x, _f64p), _p(a_d, _f64p))
+    return a_x, a_d
+
+
+def threshold(a, v):
+    return int(lib().orc_threshold(float(a), float(np.float32(v))))
+
+
+def pulse_word(seed, t, tag, index, b, a, v, BL):
+    return int(lib().orc_pulse_word(seed, t, tag, index, b, float(a), float(np.float32(v)), BL))
+
+
+def pulse_words(x, d, lr, dw_min, BL, update_management, seed, t):
+    """(xw[B][C], dw[B][R]) uint64 pulse words of the call at step t."""
+    x, d = _f32(x), _f32(d)
+    B, C = x.shape
+    R = d.shape[1]
+    assert d.shape[0] == B
+    xw = np.zeros((B, C), dtype=np.uint64)
+    dw = np.zeros((B, R), dtype=np.uint64)
+    lib().orc_pulse_words(_p(x, _f32p), _p(d, _f32p), B, R, C, lr, dw_min, BL,
+                          int(update_management), seed, t, _p(xw, _u64p), _p(dw, _u64p))
+    return xw, dw
+
+
+def counts(xw, dw, b, BL):
+    """int8 [R][C]: +n (UP) / -n (DOWN) coincidences of sample b."""
+    xw = np.ascontiguousarray(xw, dtype=np.uint64)
+    dw = np.ascontiguousarray(dw, dtype=np.uint64)
+    C, R = xw.shape[1], dw.shape[1]
+    out = np.zeros((R, C), dtype=np.int8)
+    lib().orc_counts(_p(xw, _u64p), _p(dw, _u64p), b, R, C, BL, _p(out, _i8p))
+    return out
+
+
+def device_step(kind, w, up, xi, c2c, s_up, s_dn, bmax, bmin, slope_up=0.0, slope_dn=0.0):
+    return float(lib().orc_device_step(kind, w, int(up), xi, c2c, s_up, s_dn, bmax, bmin,
+                                       slope_up, slope_dn))
+
+
+def _plane_ptrs(planes):
+    arrs = [_f32(planes[n]) for n in PLANE_NAMES]
+    return arrs, [_p(a, _f32p) for a in arrs]
+
+
+def _cells_arg(cells):
+    if cells is None:
+        return None, None, 0
+    c = np.ascontiguousarray(cells, dtype=np.int64)
+    return c, _p(c, _i64p), c.size
+
+
+def apply_words(W, planes, kind, c2c, xw, dw, BL, seed, t, cells=None):
+    """Apply given pulse words in place to W (float32 [R][C]); returns pulses applied."""
+    assert W.dtype == np.float32 and W.flags.c_contiguous
+    R, C = W.shape
+    xw = np.ascontiguousarray(xw, dtype=np.uint64)
+    dw = np.ascontiguousarray(dw, dtype=np.uint64)
+    B = xw.shape[0]
+    assert xw.shape == (B, C) and dw.shape == (B, R)
+    keep, ptrs = _plane_ptrs(planes)
+    ckeep, cptr, nc = _cells_arg(cells)
+    return int(lib().orc_apply_words(_p(W, _f32p), *ptrs, kind, c2c, _p(xw, _u64p), _p(dw, _u64p),
+                                     B, R, C, BL, seed, t, cptr, nc))
+
+
+def pulsed_update(W, planes, p: DeviceParams, BL, update_management, x, d, lr, seed, t,
+                  cells=None):
+    """One whole update call at step t, in place on W; returns pulses applied.
+    With ``cells`` (flat indices) only those cells are updated."""
+    assert W.dtype == np.float32 and W.flags.c_contiguous
+    R, C = W.shape
+    x, d = _f32(x), _f32(d)
+    B = x.shape[0]
+    assert x.shape == (B, C) and d.shape == (B, R)
+    keep, ptrs = _plane_ptrs(planes)
+    ckeep, cptr, nc = _cells_arg(cells)
+    return int(lib().orc_pulsed_update(_p(W, _f32p), *ptrs, p.kind, p.dw_min_std, p.dw_min, BL,
+                                       int(update_management), _p(x, _f32p), _p(d, _f32p), B, R, C,
+                                       lr, seed, t, cptr, nc))
+
+
+def num_threads():
+    return int(lib().orc_num_threads())
+
+
+def set_num_threads(n):
+    lib().orc_set_num_threads(int(n))

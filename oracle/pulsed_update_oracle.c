@@ -1,0 +1,385 @@
+/*
+ * CPU oracle for the analog tile's stochastic pulsed rank-update.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, scalar
+ * reference that only the test-suite, the smoke check and the benchmark's
+ * "cpu_baseline" leg may call.  It shares no source, header, table or helper
+ * with the HIP library; the two are compared against each other.
+ *
+ * What it follows (arXiv 2104.02184, Sec. 3 "Analog tile model simulation"):
+ *   - Eq. (2): the rank update w_ij <- w_ij + lambda d_i x_j that the pulsed
+ *     scheme realises in the mean (sign convention below).
+ *   - Sec. 3, paragraph after Eq. (2): stochastic pulse sequences of fixed
+ *     length on every row and column, pulse probability proportional to
+ *     |x_j| and |d_i|; a coincidence at cross-point ij changes w_ij by a
+ *     finite step.
+ *   - Sec. 3, next paragraph: the step varies from device to device, can be
+ *     biased between up and down pulses, and can depend on the present
+ *     weight; pulse-to-pulse variation on top.
+ *   - Sec. 3, paragraph on batches/convolutions: the p rank-1 updates of a
+ *     mini-batch act on the analog weights one after the other, never as a
+ *     digital sum.
+ *   - Sec. 3, paragraph on the update kernels: the pulse trains are drawn
+ *     and the coincidences are applied SEQUENTIALLY through the device
+ *     response curve.
+ *
+ * The paper fixes the structure only.  Every constant, formula and tie-break
+ * it leaves open is a reading of this build (readings R1..R12 listed in the
+ * project's design notes); the ones that matter here:
+ *   R1  sign: d is the back-propagated error and the tile descends,
+ *       W -= lr * d x^T; a coincidence with x_j*d_i > 0 is a DOWN pulse.
+ *   R2  p = min(1, a*|v|), a = sqrt(lr / (dw_min * BL)) (nominal dw_min).
+ *   R3  update management: a_x = a*sqrt(m_d/m_x), a_d = a*sqrt(m_x/m_d)
+ *       with m = per-sample max |.| over finite entries; m_x==0 or m_d==0
+ *       skips the sample.
+ *   R4  a line value that is zero or not finite produces the all-zero word.
+ *   R5  threshold T = floor(min(1,a|v|) * 2^32) in fp64; bit n is set iff
+ *       (32-bit random) < T.
+ *   R6  Philox4x32-10, key = 64-bit seed, counter words
+ *       (line index, sample, step, tag<<24 | n>>2), output word n&3.
+ *       tags: 1 = x trains, 2 = d trains, 3 = pulse-to-pulse noise,
+ *       4 = device-to-device planes.
+ *   R7  the k-th coincidence a cell sees within one call uses Gaussian k of
+ *       the cell's (cell, step) stream.
+ *   R8  Gaussian = Box-Muller on 24-bit uniforms, evaluated in fp64, rounded
+ *       once to fp32.
+ *   R9  device step in fp32, clip after every pulse.
+ *
+ * Parity pins: see tests/test_oracle_*.py.  The SHAPE of the response curves
+ * against measured ReRAM data (the paper's Fig. 2B) is "parity unpinned": the
+ * figure's data is not available.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_CONSTANT_STEP = 0, ORC_LINEAR_STEP = 1, ORC_SOFT_BOUNDS = 2 };
+enum { ORC_TAG_X = 1, ORC_TAG_D = 2, ORC_TAG_C2C = 3, ORC_TAG_D2D = 4 };
+
+/* ------------------------------------------------------------------------
+ * Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of
+ *   (c0,c1,c2,c3) <- (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0))
+ * with the key advanced by the Weyl constants between rounds.
+ * ---------------------------------------------------------------------- */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = M0 * (uint64_t)c0;
+        uint64_t p1 = M1 * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += W0; k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+static void seed_key(uint64_t seed, uint32_t key[2])
+{
+    key[0] = (uint32_t)(seed & 0xFFFFFFFFu);
+    key[1] = (uint32_t)(seed >> 32);
+}
+
+/* ------------------------------------------------------------------------
+ * Gaussian stream (R8).  Block `blk` of stream (index, t, tag) holds four
+ * N(0,1) numbers: words (r0,r1) give numbers 0,1 and (r2,r3) give 2,3 via
+ *   u1 = ((ra>>8)+1) * 2^-24 in (0,1],  u2 = (rb>>8) * 2^-24 in [0,1)
+ *   z_even = sqrt(-2 ln u1) cos(2 pi u2),  z_odd = sqrt(-2 ln u1) sin(2 pi u2)
+ * ---------------------------------------------------------------------- */
+void orc_gauss_block_f64(uint64_t seed, uint32_t index, uint32_t t, uint32_t blk,
+                         uint32_t tag, double z[4])
+{
+    uint32_t key[2], ctr[4], r[4];
+    seed_key(seed, key);
+    ctr[0] = index; ctr[1] = blk; ctr[2] = t; ctr[3] = tag << 24;
+    orc_philox4x32_10(ctr, key, r);
+    const double two_pi = 6.283185307179586476925286766559;
+    for (int pair = 0; pair < 2; ++pair) {
+        double u1 = ((double)(r[2 * pair] >> 8) + 1.0) / 16777216.0;
+        double u2 = (double)(r[2 * pair + 1] >> 8) / 16777216.0;
+        double rad = sqrt(-2.0 * log(u1));
+        z[2 * pair] = rad * cos(two_pi * u2);
+        z[2 * pair + 1] = rad * sin(two_pi * u2);
+    }
+}
+
+/* Gaussian number q of stream (index, t, tag), rounded once to fp32. */
+float orc_gauss(uint64_t seed, uint32_t index, uint32_t t, uint32_t q, uint32_t tag)
+{
+    double z[4];
+    orc_gauss_block_f64(seed, index, t, q >> 2, tag, z);
+    return (float)z[q & 3];
+}
+
+/* ------------------------------------------------------------------------
+ * Per-cell device planes (device-to-device variation; drawn once at tile
+ * creation, Sec. 3 paragraph on device-to-device variations).  Gaussians
+ * g1..g6 are numbers 0..5 of stream (cell, t=0, tag 4).  Arithmetic in fp32
+ * on the fp32-rounded Gaussians.
+ *   dw      = dw_min * |1 + dw_min_dtod*g1|
+ *   a       = up_down + up_down_dtod*g2
+ *   dw_up   = dw*(1+a),  dw_down = dw*(1-a)
+ *   b_max   = max(0, w_max*(1 + w_max_dtod*g3))
+ *   b_min   = min(0, w_min*(1 + w_min_dtod*g4))
+ *   LinearStep: slope_up = gamma_up*(1+gamma_dtod*g5) / b_max   (0 if b_max==0)
+ *               slope_down = gamma_down*(1+gamma_dtod*g6) / b_min (0 if b_min==0)
+ *   SoftBounds: slope_up = 1/b_max, slope_down = 1/b_min (0 if the bound is 0)
+ *   ConstantStep: slopes are 0.
+ * ---------------------------------------------------------------------- */
+void orc_device_planes(int kind, float dw_min, float dw_min_dtod, float up_down,
+                       float up_down_dtod, float w_max, float w_max_dtod, float w_min,
+                       float w_min_dtod, float gamma_up, float gamma_down, float gamma_dtod,
+                       uint64_t seed, int R, int C, float *dw_up, float *dw_down,
+                       float *b_max, float *b_min, float *slope_up, float *slope_down)
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < R; ++i) {
+        for (int j = 0; j < C; ++j) {
+            uint32_t cell = (uint32_t)i * (uint32_t)C + (uint32_t)j;
+            float g[6];
+            for (uint32_t q = 0; q < 6; ++q) g[q] = orc_gauss(seed, cell, 0u, q, ORC_TAG_D2D);
+            float dw = dw_min * fabsf(1.0f + dw_min_dtod * g[0]);
+            float a = up_down + up_down_dtod * g[1];
+            float bmax = fmaxf(0.0f, w_max * (1.0f + w_max_dtod * g[2]));
+            float bmin = fminf(0.0f, w_min * (1.0f + w_min_dtod * g[3]));
+            float su = 0.0f, sd = 0.0f;
+            if (kind == ORC_LINEAR_STEP) {
+                float gu = gamma_up * (1.0f + gamma_dtod * g[4]);
+                float gd = gamma_down * (1.0f + gamma_dtod * g[5]);
+                su = (bmax != 0.0f) ? gu / bmax : 0.0f;
+                sd = (bmin != 0.0f) ? gd / bmin : 0.0f;
+            } else if (kind == ORC_SOFT_BOUNDS) {
+                su = (bmax != 0.0f) ? 1.0f / bmax : 0.0f;
+                sd = (bmin != 0.0f) ? 1.0f / bmin : 0.0f;
+            }
+            size_t k = (size_t)i * C + j;
+            dw_up[k] = dw * (1.0f + a);
+            dw_down[k] = dw * (1.0f - a);
+            b_max[k] = bmax;
+            b_min[k] = bmin;
+            slope_up[k] = su;
+            slope_down[k] = sd;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Line scaling (R2, R3).  a_x[b], a_d[b] are the fp64 factors that turn a
+ * line value into a pulse probability; both 0 marks a skipped sample.
+ * ---------------------------------------------------------------------- */
+static int is_active(float v) { return isfinite(v) && v != 0.0f; }
+
+void orc_line_scale(const float *x, const float *d, int B, int R, int C, float lr,
+                    float dw_min, int BL, int update_management, double *a_x, double *a_d)
+{
+    double A = sqrt((double)lr / ((double)dw_min * (double)BL));
+    for (int b = 0; b < B; ++b) {
+        if (!update_management) { a_x[b] = A; a_d[b] = A; continue; }
+        double m_x = 0.0, m_d = 0.0;
+        for (int j = 0; j < C; ++j) {
+            float v = x[(size_t)b * C + j];
+            if (is_active(v) && fabs((double)v) > m_x) m_x = fabs((double)v);
+        }
+        for (int i = 0; i < R; ++i) {
+            float v = d[(size_t)b * R + i];
+            if (is_active(v) && fabs((double)v) > m_d) m_d = fabs((double)v);
+        }
+        if (m_x == 0.0 || m_d == 0.0) { a_x[b] = 0.0; a_d[b] = 0.0; continue; }
+        a_x[b] = A * sqrt(m_d / m_x);
+        a_d[b] = A * sqrt(m_x / m_d);
+    }
+}
+
+/* 33-bit threshold (R5): 0 .. 2^32 inclusive. */
+uint64_t orc_threshold(double a, float v)
+{
+    if (!is_active(v)) return 0;
+    double p = a * fabs((double)v);
+    if (!(p < 1.0)) p = 1.0;          /* min(1, p); also catches +inf */
+    return (uint64_t)floor(p * 4294967296.0);
+}
+
+/* One pulse word (R4..R6): bit n (n < BL) = pulse n, bit 63 = (v < 0). */
+uint64_t orc_pulse_word(uint64_t seed, uint32_t t, uint32_t tag, uint32_t index, uint32_t b,
+                        double a, float v, int BL)
+{
+    if (!is_active(v) || !(a > 0.0)) return 0;    /* R4; a == 0 marks a skipped sample (R3) */
+    uint64_t T = orc_threshold(a, v);
+    uint32_t key[2], ctr[4], r[4];
+    seed_key(seed, key);
+    uint64_t word = 0;
+    for (int n = 0; n < BL; ++n) {
+        ctr[0] = index; ctr[1] = b; ctr[2] = t; ctr[3] = (tag << 24) | (uint32_t)(n >> 2);
+        orc_philox4x32_10(ctr, key, r);
+        if ((uint64_t)r[n & 3] < T) word |= (uint64_t)1 << n;
+    }
+    if (v < 0.0f) word |= (uint64_t)1 << 63;
+    return word;
+}
+
+/* All pulse words of one call: xw[B][C], dw[B][R]. */
+void orc_pulse_words(const float *x, const float *d, int B, int R, int C, float lr, float dw_min,
+                     int BL, int update_management, uint64_t seed, uint32_t t, uint64_t *xw,
+                     uint64_t *dw)
+{
+    double *a_x = (double *)malloc(sizeof(double) * (size_t)(B > 0 ? B : 1));
+    double *a_d = (double *)malloc(sizeof(double) * (size_t)(B > 0 ? B : 1));
+    orc_line_scale(x, d, B, R, C, lr, dw_min, BL, update_management, a_x, a_d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int j = 0; j < C; ++j)
+            xw[(size_t)b * C + j] = orc_pulse_word(seed, t, ORC_TAG_X, (uint32_t)j, (uint32_t)b,
+                                                   a_x[b], x[(size_t)b * C + j], BL);
+        for (int i = 0; i < R; ++i)
+            dw[(size_t)b * R + i] = orc_pulse_word(seed, t, ORC_TAG_D, (uint32_t)i, (uint32_t)b,
+                                                   a_d[b], d[(size_t)b * R + i], BL);
+    }
+    free(a_x);
+    free(a_d);
+}
+
+/* Coincidences of cell (i,j) in one sample: count and direction. */
+static int coincidences(uint64_t xword, uint64_t dword, int BL, int *up)
+{
+    uint64_t mask = ((uint64_t)1 << BL) - 1;      /* BL <= 63 */
+    uint64_t both = xword & dword & mask;
+    int n = 0;
+    while (both) { n += (int)(both & 1); both >>= 1; }
+    *up = (int)(((xword ^ dword) >> 63) & 1);     /* x_j*d_i < 0  =>  UP (R1) */
+    return n;
+}
+
+/* Signed counts of sample b: +n for UP pulses, -n for DOWN pulses. */
+void orc_counts(const uint64_t *xw, const uint64_t *dw, int b, int R, int C, int BL,
+                int8_t *signed_counts)
+{
+    for (int i = 0; i < R; ++i)
+        for (int j = 0; j < C; ++j) {
+            int up;
+            int n = coincidences(xw[(size_t)b * C + j], dw[(size_t)b * R + i], BL, &up);
+            signed_counts[(size_t)i * C + j] = (int8_t)(up ? n : -n);
+        }
+}
+
+/* One pulse through the device response curve (R9), all in fp32. */
+float orc_device_step(int kind, float w, int up, float xi, float c2c, float s_up, float s_dn,
+                      float bmax, float bmin, float slope_up, float slope_dn)
+{
+    float s = up ? s_up : s_dn;
+    float f = 1.0f;
+    if (kind != ORC_CONSTANT_STEP) {
+        float slope = up ? slope_up : slope_dn;
+        float prod = slope * w;
+        f = fmaxf(0.0f, 1.0f - prod);
+    }
+    float step = s * f;
+    float cx = c2c * xi;
+    float noise = 1.0f + cx;
+    float delta = step * noise;
+    float wn = up ? (w + delta) : (w - delta);
+    wn = fmaxf(wn, bmin);
+    wn = fminf(wn, bmax);
+    return wn;
+}
+
+/* Apply the B samples' coincidences, in sample order, to the selected cells.
+ * cells == NULL: every cell.  Returns the number of applied pulses. */
+int64_t orc_apply_words(float *W, const float *dw_up, const float *dw_down, const float *b_max,
+                        const float *b_min, const float *slope_up, const float *slope_down,
+                        int kind, float c2c, const uint64_t *xw, const uint64_t *dw, int B,
+                        int R, int C, int BL, uint64_t seed, uint32_t t, const int64_t *cells,
+                        int64_t n_cells)
+{
+    /* lookup copies with the sample index innermost (cells walk over b) */
+    uint64_t *xwT = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)C * (size_t)(B > 0 ? B : 1));
+    uint64_t *dwT = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)R * (size_t)(B > 0 ? B : 1));
+    for (int b = 0; b < B; ++b) {
+        for (int j = 0; j < C; ++j) xwT[(size_t)j * B + b] = xw[(size_t)b * C + j];
+        for (int i = 0; i < R; ++i) dwT[(size_t)i * B + b] = dw[(size_t)b * R + i];
+    }
+    int64_t total = cells ? n_cells : (int64_t)R * C;
+    int64_t pulses = 0;
+#pragma omp parallel for schedule(dynamic, 256) reduction(+ : pulses)
+    for (int64_t idx = 0; idx < total; ++idx) {
+        int64_t k = cells ? cells[idx] : idx;
+        int i = (int)(k / C), j = (int)(k % C);
+        uint32_t cell = (uint32_t)k;
+        float w = W[k];
+        uint32_t q = 0;                     /* pulse counter of this call (R7) */
+        double zblk[4] = {0, 0, 0, 0};
+        for (int b = 0; b < B; ++b) {
+            int up;
+            int n = coincidences(xwT[(size_t)j * B + b], dwT[(size_t)i * B + b], BL, &up);
+            for (int p = 0; p < n; ++p) {
+                float xi = 0.0f;
+                if (c2c > 0.0f) {
+                    if ((q & 3) == 0) orc_gauss_block_f64(seed, cell, t, q >> 2, ORC_TAG_C2C, zblk);
+                    xi = (float)zblk[q & 3];
+                }
+                w = orc_device_step(kind, w, up, xi, c2c, dw_up[k], dw_down[k], b_max[k],
+                                    b_min[k], slope_up[k], slope_down[k]);
+                ++q;
+            }
+        }
+        W[k] = w;
+        pulses += q;
+    }
+    free(xwT);
+    free(dwT);
+    return pulses;
+}
+
+/* The whole update call at step t: words, then cells.  Returns applied pulses. */
+int64_t orc_pulsed_update(float *W, const float *dw_up, const float *dw_down, const float *b_max,
+                          const float *b_min, const float *slope_up, const float *slope_down,
+                          int kind, float c2c, float dw_min, int BL, int update_management,
+                          const float *x, const float *d, int B, int R, int C, float lr,
+                          uint64_t seed, uint32_t t, const int64_t *cells, int64_t n_cells)
+{
+    if (B <= 0 || !(lr > 0.0f)) return 0;
+    uint64_t *xw = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)B * C);
+    uint64_t *dw = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)B * R);
+    orc_pulse_words(x, d, B, R, C, lr, dw_min, BL, update_management, seed, t, xw, dw);
+    int64_t pulses = orc_apply_words(W, dw_up, dw_down, b_max, b_min, slope_up, slope_down, kind,
+                                     c2c, xw, dw, B, R, C, BL, seed, t, cells, n_cells);
+    free(xw);
+    free(dw);
+    return pulses;
+}
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* Bulk draw for the statistical tests: out[k*nq + q] = gauss(seed, index0+k, t, q, tag). */
+void orc_gauss_fill(uint64_t seed, uint32_t index0, int n_index, uint32_t t, int nq, uint32_t tag,
+                    float *out)
+{
+    for (int k = 0; k < n_index; ++k)
+        for (int q = 0; q < nq; ++q)
+            out[(size_t)k * nq + q] = orc_gauss(seed, index0 + (uint32_t)k, t, (uint32_t)q, tag);
+}

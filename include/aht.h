@@ -1,0 +1,167 @@
+/*
+ * aht.h -- C ABI of the analog-tile stochastic pulsed update for AMD MI355X (gfx950).
+ *
+ * One tile = one 2-D weight matrix W[rows][cols] (row-major, fp32, y_i = sum_j w_ij x_j)
+ * living on a simulated resistive crossbar, configured at creation (arXiv 2104.02184,
+ * Sec. 3, first paragraph).  The library implements the tile's in-situ parallel update:
+ * the rank update of Eq. (2) carried out with stochastic pulse trains whose coincidences
+ * step each cross-point through a device response model (Sec. 3, paragraphs after Eq. (2)),
+ * the update vectors of a mini-batch or convolution acting on the analog weights one after
+ * the other (Sec. 3, paragraph on batch sizes larger than one and convolutions).
+ *
+ * Conventions
+ *   - every pointer named *_dev is a DEVICE pointer on the current HIP device; the caller
+ *     owns x, d and every output buffer; the tile owns W, the device planes and scratch;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); calls are
+ *     asynchronous on it and never synchronise the host, except create/destroy;
+ *   - every function returns aht_status and never throws or aborts; on an error the tile
+ *     is unchanged; aht_last_error() gives a thread-local message;
+ *   - one tile must not be used from two streams at the same time;
+ *   - all quantities are in the paper's normalised units (Sec. 3, after Eq. (1)).
+ */
+#ifndef AHT_H
+#define AHT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct aht_tile aht_tile; /* opaque */
+
+typedef enum {
+    AHT_OK = 0,
+    AHT_ERR_INVALID_ARG = 1,
+    AHT_ERR_UNSUPPORTED = 2,
+    AHT_ERR_OOM = 3,
+    AHT_ERR_DEVICE = 4
+} aht_status;
+
+/* Device response models (Sec. 3: the step per coincidence may depend on the direction and,
+ * non-linearly, on the present weight):
+ *   CONSTANT_STEP  step independent of w
+ *   LINEAR_STEP    step * max(0, 1 - gamma * w / bound)   (per direction)
+ *   SOFT_BOUNDS    step * max(0, 1 - w / bound)           (= LINEAR_STEP with gamma == 1) */
+typedef enum { AHT_CONSTANT_STEP = 0, AHT_LINEAR_STEP = 1, AHT_SOFT_BOUNDS = 2 } aht_device_kind;
+
+/* Scalar description of the device population.  *_dtod = relative std of the device-to-
+ * device (per cross-point, fixed at creation) Gaussian variation; dw_min_std = relative std
+ * of the pulse-to-pulse Gaussian variation of every single step (names as in the paper's
+ * device-configuration listing: dw_min, dw_min_dtod, dw_min_std). */
+typedef struct {
+    int32_t kind;        /* aht_device_kind */
+    float dw_min;        /* nominal step per coincidence, > 0 */
+    float dw_min_dtod;   /* >= 0 */
+    float dw_min_std;    /* >= 0 */
+    float up_down;       /* mean asymmetry: dw_up = dw*(1+a), dw_down = dw*(1-a) */
+    float up_down_dtod;  /* absolute std of the asymmetry a */
+    float w_max;         /* upper bound, >= 0 */
+    float w_max_dtod;
+    float w_min;         /* lower bound, <= 0 */
+    float w_min_dtod;
+    float gamma_up;      /* LINEAR_STEP only */
+    float gamma_down;    /* LINEAR_STEP only */
+    float gamma_dtod;    /* LINEAR_STEP only, relative */
+} aht_device_params;
+
+typedef struct {
+    int32_t bl;                /* pulse-train length, 1..63 */
+    int32_t update_management; /* 0/1: per update vector, rescale the two pulse probabilities
+                                  by sqrt(max|d| / max|x|) and its inverse */
+} aht_update_params;
+
+/* Indices of the per-cell planes (fp32 [rows][cols]). */
+enum {
+    AHT_PLANE_DW_UP = 0,
+    AHT_PLANE_DW_DOWN = 1,
+    AHT_PLANE_B_MAX = 2,
+    AHT_PLANE_B_MIN = 3,
+    AHT_PLANE_SLOPE_UP = 4,   /* gamma_up_ij / b_max_ij   (1 / b_max_ij for SOFT_BOUNDS) */
+    AHT_PLANE_SLOPE_DOWN = 5, /* gamma_down_ij / b_min_ij (1 / b_min_ij for SOFT_BOUNDS) */
+    AHT_NUM_PLANES = 6
+};
+
+/* Create a tile on the current HIP device: allocates W (zeros), draws the device planes
+ * from (params, seed) with the library's counter-based random stream (device-to-device
+ * variation, Sec. 3), sets the step counter to 0.  May synchronise.
+ * Errors: INVALID_ARG for null pointers, rows/cols <= 0, rows*cols >= 2^32, bl outside
+ * 1..63, dw_min <= 0, negative std, w_min > 0 or w_max < 0, unknown kind; OOM; DEVICE. */
+aht_status aht_tile_create(aht_tile** out, int32_t rows, int32_t cols,
+                           const aht_device_params* device, const aht_update_params* update,
+                           uint64_t seed);
+
+/* Frees everything the tile owns.  Synchronises the device.  NULL is accepted. */
+aht_status aht_tile_destroy(aht_tile* tile);
+
+/* Copy weights in / out (device to device, fp32 [rows][cols]).  aht_set_weights stores the
+ * values as given (the caller keeps them inside the per-cell bounds if that matters). */
+aht_status aht_set_weights(aht_tile* tile, const float* w_dev, void* stream);
+aht_status aht_get_weights(const aht_tile* tile, float* w_dev_out, void* stream);
+
+/* The stochastic pulsed update (Sec. 3, Eq. (2) and the paragraphs after it):
+ *   for b = 0..B-1, in order:   W <- W - lr * d[b] x[b]^T   in the mean,
+ * realised by drawing a pulse train of `bl` pulses for every column j (probability
+ * min(1, a_x |x[b][j]|)) and every row i (probability min(1, a_d |d[b][i]|)),
+ * a_x a_d = lr / (dw_min * bl), and stepping cell ij once per coincidence, sequentially,
+ * through its device response with pulse-to-pulse noise and clipping to the cell's bounds.
+ * A coincidence with x_j * d_i > 0 is a DOWN pulse, < 0 an UP pulse.
+ *   x_dev  [B][cols] fp32, d_dev [B][rows] fp32 (zero, NaN and Inf entries send no pulses)
+ *   B >= 0 update vectors (B == 0 or lr == 0: weights unchanged; the step counter still
+ *   advances), lr >= 0.
+ * Every random draw is a pure function of (seed, step counter, line or cell index, sample,
+ * pulse number), so a sequence of calls is reproducible and resumable.  Increments the
+ * tile's step counter.  Asynchronous on `stream`; x and d must stay valid until the
+ * stream has passed the call.
+ * Errors: INVALID_ARG (null pointers with B > 0, B < 0, lr < 0 or NaN); OOM (scratch for
+ * the pulse words could not be grown); DEVICE. */
+aht_status aht_pulsed_update(aht_tile* tile, const float* x_dev, const float* d_dev, int32_t B,
+                             float lr, void* stream);
+
+/* Step counter (number of aht_pulsed_update calls so far); together with the weights, the
+ * planes and the seed it makes a run resumable bit for bit. */
+aht_status aht_get_step(const aht_tile* tile, uint32_t* step);
+aht_status aht_set_step(aht_tile* tile, uint32_t step);
+
+/* Number of coincidence pulses applied by all calls so far on this tile (device counter,
+ * read back with a synchronising copy on `stream`). */
+aht_status aht_get_pulse_count(const aht_tile* tile, uint64_t* pulses, void* stream);
+
+/* Per-cell device planes, `plane` = AHT_PLANE_*; fp32 [rows][cols] device buffers.
+ * Planes 4,5 exist for every kind (all-zero for CONSTANT_STEP). */
+aht_status aht_get_device_planes(const aht_tile* tile, int32_t plane, float* dev_out, void* stream);
+aht_status aht_set_device_planes(aht_tile* tile, int32_t plane, const float* dev_in, void* stream);
+
+/* Test hooks for the bit-exact part of the contract.
+ * aht_debug_pulse_words: the pulse words aht_pulsed_update would draw at the CURRENT step
+ *   for (x, d, B, lr); no state change.  Word layout: bit n (n < bl) = pulse n, bit 63 = the
+ *   line value is negative.  xw_dev [B][cols], dw_dev [B][rows] uint64.
+ * aht_debug_counts: signed coincidence counts of sample b from given words:
+ *   +n for n UP pulses (x_j d_i < 0), -n for n DOWN pulses; int8 [rows][cols].
+ * aht_debug_apply_words: applies given words (B samples, in order) to the tile as step
+ *   `step` without touching the step counter. */
+aht_status aht_debug_pulse_words(aht_tile* tile, const float* x_dev, const float* d_dev, int32_t B,
+                                 float lr, uint64_t* xw_dev, uint64_t* dw_dev, void* stream);
+aht_status aht_debug_counts(aht_tile* tile, const uint64_t* xw_dev, const uint64_t* dw_dev,
+                            int32_t B, int32_t b, int8_t* signed_counts_dev, void* stream);
+aht_status aht_debug_apply_words(aht_tile* tile, const uint64_t* xw_dev, const uint64_t* dw_dev,
+                                 int32_t B, uint32_t step, void* stream);
+
+/* Raw streams of the library's random generator, for pinning it from tests:
+ * out_dev[4*k..4*k+3] = Philox4x32-10 block of counter ctr_dev[4*k..] under key_dev[2*k..];
+ * gauss_dev[k] = fp32 Gaussian number q0+k of stream (index, t, tag) as the update kernel
+ * evaluates it (fast = 1) or as tile creation evaluates it (fast = 0). */
+aht_status aht_debug_philox(const uint32_t* ctr_dev, const uint32_t* key_dev, int32_t n,
+                            uint32_t* out_dev, void* stream);
+aht_status aht_debug_gauss(uint64_t seed, uint32_t index, uint32_t t, uint32_t tag, uint32_t q0,
+                           int32_t n, int32_t fast, float* gauss_dev, void* stream);
+
+const char* aht_status_string(aht_status s);
+const char* aht_last_error(void);
+/* Library version string; also tells which architecture the kernels were built for. */
+const char* aht_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AHT_H */

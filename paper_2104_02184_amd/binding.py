@@ -1,0 +1,260 @@
+"""ctypes binding of the C ABI declared in ``include/aht.h``.
+
+Argument marshalling only: every function here forwards device pointers of
+torch tensors and the current HIP stream to the library.  Function and
+structure names follow the header.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass, fields
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libaht.so")
+
+CONSTANT_STEP, LINEAR_STEP, SOFT_BOUNDS = 0, 1, 2
+PLANE_NAMES = ("dw_up", "dw_down", "b_max", "b_min", "slope_up", "slope_down")
+
+# every symbol include/aht.h declares
+EXPORTS = (
+    "aht_tile_create", "aht_tile_destroy", "aht_set_weights", "aht_get_weights", "aht_pulsed_update",
+    "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
+    "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
+    "aht_debug_philox", "aht_debug_gauss", "aht_status_string", "aht_last_error", "aht_version",
+)
+
+
+class AhtError(RuntimeError):
+    def __init__(self, status, name, message):
+        super().__init__(f"{name} ({status}): {message}")
+        self.status = status
+        self.status_name = name
+
+
+class aht_device_params(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("dw_min", ctypes.c_float), ("dw_min_dtod", ctypes.c_float),
+                ("dw_min_std", ctypes.c_float), ("up_down", ctypes.c_float), ("up_down_dtod", ctypes.c_float),
+                ("w_max", ctypes.c_float), ("w_max_dtod", ctypes.c_float), ("w_min", ctypes.c_float),
+                ("w_min_dtod", ctypes.c_float), ("gamma_up", ctypes.c_float), ("gamma_down", ctypes.c_float),
+                ("gamma_dtod", ctypes.c_float)]
+
+
+class aht_update_params(ctypes.Structure):
+    _fields_ = [("bl", ctypes.c_int32), ("update_management", ctypes.c_int32)]
+
+
+@dataclass
+class DeviceParams:
+    kind: int = CONSTANT_STEP
+    dw_min: float = 0.001
+    dw_min_dtod: float = 0.0
+    dw_min_std: float = 0.0
+    up_down: float = 0.0
+    up_down_dtod: float = 0.0
+    w_max: float = 1.0
+    w_max_dtod: float = 0.0
+    w_min: float = -1.0
+    w_min_dtod: float = 0.0
+    gamma_up: float = 0.0
+    gamma_down: float = 0.0
+    gamma_dtod: float = 0.0
+
+    def to_c(self) -> aht_device_params:
+        return aht_device_params(**{f.name: getattr(self, f.name) for f in fields(self)})
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libaht.so; raises if it is missing (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2104_02184_amd.build` "
+                          "(hipcc, gfx950); there is no CPU fallback")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, u32, u64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float
+    L.aht_tile_create.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(aht_device_params),
+                                  ctypes.POINTER(aht_update_params), u64]
+    L.aht_tile_destroy.argtypes = [vp]
+    L.aht_set_weights.argtypes = [vp, vp, vp]
+    L.aht_get_weights.argtypes = [vp, vp, vp]
+    L.aht_pulsed_update.argtypes = [vp, vp, vp, i32, f32, vp]
+    L.aht_get_step.argtypes = [vp, ctypes.POINTER(u32)]
+    L.aht_set_step.argtypes = [vp, u32]
+    L.aht_get_pulse_count.argtypes = [vp, ctypes.POINTER(u64), vp]
+    L.aht_get_device_planes.argtypes = [vp, i32, vp, vp]
+    L.aht_set_device_planes.argtypes = [vp, i32, vp, vp]
+    L.aht_debug_pulse_words.argtypes = [vp, vp, vp, i32, f32, vp, vp, vp]
+    L.aht_debug_counts.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    L.aht_debug_apply_words.argtypes = [vp, vp, vp, i32, u32, vp]
+    L.aht_debug_philox.argtypes = [vp, vp, i32, vp, vp]
+    L.aht_debug_gauss.argtypes = [u64, u32, u32, u32, u32, i32, i32, vp, vp]
+    for name in EXPORTS:
+        getattr(L, name).restype = ctypes.c_int
+    L.aht_status_string.argtypes = [ctypes.c_int]
+    L.aht_status_string.restype = ctypes.c_char_p
+    L.aht_last_error.argtypes = []
+    L.aht_last_error.restype = ctypes.c_char_p
+    L.aht_version.argtypes = []
+    L.aht_version.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(status: int):
+    if status != 0:
+        L = load_library()
+        raise AhtError(status, L.aht_status_string(status).decode(), L.aht_last_error().decode())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t, dtype, shape=None):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("expected a CUDA/HIP tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"expected a contiguous {dtype} tensor, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Tile:
+    """One analog tile on the current HIP device (wraps ``aht_tile``)."""
+
+    def __init__(self, rows: int, cols: int, device: DeviceParams, bl: int, update_management: bool = False,
+                 seed: int = 0):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        self.rows, self.cols, self.bl = int(rows), int(cols), int(bl)
+        self.device_params = device
+        dp = device.to_c()
+        up = aht_update_params(int(bl), int(bool(update_management)))
+        _check(self._lib.aht_tile_create(ctypes.byref(self._h), rows, cols, ctypes.byref(dp), ctypes.byref(up),
+                                         ctypes.c_uint64(seed & (2**64 - 1))))
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            _check(self._lib.aht_tile_destroy(self._h))
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    # -- weights ---------------------------------------------------------------------------
+    def set_weights(self, w):
+        import torch
+        _check(self._lib.aht_set_weights(self._h, _ptr(w, torch.float32, (self.rows, self.cols)), _stream()))
+
+    def get_weights(self, out=None):
+        import torch
+        if out is None:
+            out = torch.empty((self.rows, self.cols), dtype=torch.float32, device="cuda")
+        _check(self._lib.aht_get_weights(self._h, _ptr(out, torch.float32, (self.rows, self.cols)), _stream()))
+        return out
+
+    # -- the update ------------------------------------------------------------------------
+    def pulsed_update(self, x, d, lr: float):
+        import torch
+        B = int(x.shape[0]) if x.dim() == 2 else -1
+        if B > 0:
+            xp, dp = _ptr(x, torch.float32, (B, self.cols)), _ptr(d, torch.float32, (B, self.rows))
+        else:
+            xp = dp = ctypes.c_void_p()
+        _check(self._lib.aht_pulsed_update(self._h, xp, dp, B, ctypes.c_float(lr), _stream()))
+
+    # -- state -----------------------------------------------------------------------------
+    @property
+    def step(self) -> int:
+        v = ctypes.c_uint32()
+        _check(self._lib.aht_get_step(self._h, ctypes.byref(v)))
+        return v.value
+
+    @step.setter
+    def step(self, value: int):
+        _check(self._lib.aht_set_step(self._h, ctypes.c_uint32(value)))
+
+    def pulse_count(self) -> int:
+        v = ctypes.c_uint64()
+        _check(self._lib.aht_get_pulse_count(self._h, ctypes.byref(v), _stream()))
+        return v.value
+
+    def get_plane(self, name):
+        import torch
+        idx = PLANE_NAMES.index(name) if isinstance(name, str) else int(name)
+        out = torch.empty((self.rows, self.cols), dtype=torch.float32, device="cuda")
+        _check(self._lib.aht_get_device_planes(self._h, idx, _ptr(out, torch.float32), _stream()))
+        return out
+
+    def set_plane(self, name, values):
+        import torch
+        idx = PLANE_NAMES.index(name) if isinstance(name, str) else int(name)
+        _check(self._lib.aht_set_device_planes(self._h, idx, _ptr(values, torch.float32, (self.rows, self.cols)),
+                                               _stream()))
+
+    # -- test hooks ------------------------------------------------------------------------
+    def debug_pulse_words(self, x, d, lr: float):
+        """(xw[B][cols], dw[B][rows]) as int64 tensors holding the uint64 bit patterns."""
+        import torch
+        B = int(x.shape[0])
+        xw = torch.empty((B, self.cols), dtype=torch.int64, device="cuda")
+        dw = torch.empty((B, self.rows), dtype=torch.int64, device="cuda")
+        _check(self._lib.aht_debug_pulse_words(self._h, _ptr(x, torch.float32, (B, self.cols)),
+                                               _ptr(d, torch.float32, (B, self.rows)), B, ctypes.c_float(lr),
+                                               _ptr(xw, torch.int64), _ptr(dw, torch.int64), _stream()))
+        return xw, dw
+
+    def debug_counts(self, xw, dw, b: int):
+        import torch
+        B = int(xw.shape[0])
+        out = torch.empty((self.rows, self.cols), dtype=torch.int8, device="cuda")
+        _check(self._lib.aht_debug_counts(self._h, _ptr(xw, torch.int64, (B, self.cols)),
+                                          _ptr(dw, torch.int64, (B, self.rows)), B, b, _ptr(out, torch.int8),
+                                          _stream()))
+        return out
+
+    def debug_apply_words(self, xw, dw, step: int):
+        import torch
+        B = int(xw.shape[0])
+        _check(self._lib.aht_debug_apply_words(self._h, _ptr(xw, torch.int64, (B, self.cols)),
+                                               _ptr(dw, torch.int64, (B, self.rows)), B, ctypes.c_uint32(step),
+                                               _stream()))
+
+
+def debug_philox(ctr, key):
+    """ctr int32[n][4], key int32[n][2] device tensors (bit patterns) -> int32[n][4]."""
+    import torch
+    n = int(ctr.shape[0])
+    out = torch.empty((n, 4), dtype=torch.int32, device="cuda")
+    _check(load_library().aht_debug_philox(_ptr(ctr, torch.int32, (n, 4)), _ptr(key, torch.int32, (n, 2)), n,
+                                           _ptr(out, torch.int32), _stream()))
+    return out
+
+
+def debug_gauss(seed: int, index: int, t: int, tag: int, q0: int, n: int, fast: bool):
+    import torch
+    out = torch.empty((n,), dtype=torch.float32, device="cuda")
+    _check(load_library().aht_debug_gauss(ctypes.c_uint64(seed), index, t, tag, q0, n, int(fast),
+                                          _ptr(out, torch.float32), _stream()))
+    return out

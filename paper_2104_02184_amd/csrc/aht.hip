@@ -1,0 +1,522 @@
+// Host side of the C ABI declared in include/aht.h: argument checks, tile state, scratch
+// management and kernel launches.  All arithmetic of the update runs in the kernels of
+// aht_kernels.hpp; nothing here computes on the host and there is no CPU fallback.
+#include "../../include/aht.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "aht_kernels.hpp"
+
+using namespace aht;
+
+struct aht_tile {
+    int rows = 0, cols = 0;
+    aht_device_params dev{};
+    aht_update_params upd{};
+    uint64_t seed = 0;
+    uint32_t step = 0;
+    int device = 0;
+    float* W = nullptr;
+    float* planes[AHT_NUM_PLANES] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    // scratch owned by the tile, grown on demand
+    void* xw = nullptr;
+    void* dw = nullptr;
+    size_t xw_bytes = 0, dw_bytes = 0;
+    double* a_x = nullptr;
+    double* a_d = nullptr;
+    int a_cap = 0;
+    unsigned long long* pulse_count = nullptr;
+};
+
+namespace {
+
+thread_local std::string g_last_error;
+
+aht_status fail(aht_status s, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return s;
+}
+
+aht_status hip_fail(hipError_t e, const char* what)
+{
+    return fail(e == hipErrorOutOfMemory ? AHT_ERR_OOM : AHT_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define AHT_HIP(call)                                       \
+    do {                                                    \
+        hipError_t e_ = (call);                             \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);   \
+    } while (0)
+
+inline bool use_u32(const aht_tile* t) { return t->upd.bl <= 31; }
+inline size_t word_bytes(const aht_tile* t) { return use_u32(t) ? 4 : 8; }
+inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
+// internal word buffers are padded so that the cell kernel needs no edge masks
+inline int cpad(const aht_tile* t) { return (t->cols + 63) & ~63; }
+inline int rpad(const aht_tile* t) { return (t->rows + 15) & ~15; }
+
+int env_int(const char* name, int dflt)
+{
+    const char* v = getenv(name);
+    if (!v || !*v) return dflt;
+    return atoi(v);
+}
+
+aht_status check_device(const aht_tile* t)
+{
+    int cur = -1;
+    AHT_HIP(hipGetDevice(&cur));
+    if (cur != t->device)
+        return fail(AHT_ERR_INVALID_ARG, "tile lives on device %d but the current device is %d", t->device, cur);
+    return AHT_OK;
+}
+
+aht_status ensure_scratch(aht_tile* t, int B)
+{
+    const size_t need_x = (size_t)B * cpad(t) * word_bytes(t);
+    const size_t need_d = (size_t)B * rpad(t) * word_bytes(t);
+    if (need_x > t->xw_bytes) {
+        if (t->xw) AHT_HIP(hipFree(t->xw));
+        t->xw = nullptr; t->xw_bytes = 0;
+        AHT_HIP(hipMalloc(&t->xw, need_x));
+        t->xw_bytes = need_x;
+    }
+    if (need_d > t->dw_bytes) {
+        if (t->dw) AHT_HIP(hipFree(t->dw));
+        t->dw = nullptr; t->dw_bytes = 0;
+        AHT_HIP(hipMalloc(&t->dw, need_d));
+        t->dw_bytes = need_d;
+    }
+    if (t->upd.update_management && B > t->a_cap) {
+        if (t->a_x) AHT_HIP(hipFree(t->a_x));
+        if (t->a_d) AHT_HIP(hipFree(t->a_d));
+        t->a_x = t->a_d = nullptr; t->a_cap = 0;
+        AHT_HIP(hipMalloc((void**)&t->a_x, sizeof(double) * (size_t)B));
+        AHT_HIP(hipMalloc((void**)&t->a_d, sizeof(double) * (size_t)B));
+        t->a_cap = B;
+    }
+    return AHT_OK;
+}
+
+// pulse trains of the call at step `step` into the tile's scratch
+aht_status launch_words(aht_tile* t, const float* x, const float* d, int B, float lr, uint32_t step,
+                        hipStream_t s)
+{
+    const double A = std::sqrt((double)lr / ((double)t->dev.dw_min * (double)t->upd.bl));
+    const double *ax = nullptr, *ad = nullptr;
+    if (t->upd.update_management) {
+        hipLaunchKernelGGL(k_line_scale, dim3((unsigned)B), dim3(256), 0, s, x, d, t->rows, t->cols, A, t->a_x, t->a_d);
+        ax = t->a_x;
+        ad = t->a_d;
+    }
+    const uint32_t k0 = (uint32_t)t->seed, k1 = (uint32_t)(t->seed >> 32);
+    const int Cp = cpad(t), Rp = rpad(t);
+    const dim3 grid(blocks_for((size_t)Cp + Rp), (unsigned)(B < 32768 ? B : 32768));
+    if (use_u32(t))
+        hipLaunchKernelGGL(k_pulse_words<uint32_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp,
+                           t->upd.bl, A, ax, ad, k0, k1, step, (uint32_t*)t->xw, (uint32_t*)t->dw);
+    else
+        hipLaunchKernelGGL(k_pulse_words<uint64_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp,
+                           t->upd.bl, A, ax, ad, k0, k1, step, (uint64_t*)t->xw, (uint64_t*)t->dw);
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+struct CellPtrs {
+    float* W;
+    const float *dw_up, *dw_down, *b_max, *b_min, *slope_up, *slope_down;
+    const void *xw, *dw;
+    unsigned long long* pulse_count;
+};
+
+template <int KIND, typename WordT, bool NOISE, int RPL>
+void launch_cells_one(dim3 grid, size_t lds, hipStream_t s, const CellPtrs& p, const CellArgs& a)
+{
+    hipLaunchKernelGGL((k_cell_update<KIND, WordT, NOISE, RPL>), grid, dim3(256), lds, s, p.W, p.dw_up, p.dw_down,
+                       p.b_max, p.b_min, p.slope_up, p.slope_down, (const WordT*)p.xw, (const WordT*)p.dw,
+                       p.pulse_count, a);
+}
+
+template <int KIND, typename WordT, bool NOISE>
+void launch_cells_rpl(int rpl, dim3 grid, size_t lds, hipStream_t s, const CellPtrs& p, const CellArgs& a)
+{
+    switch (rpl) {
+        case 1: launch_cells_one<KIND, WordT, NOISE, 1>(grid, lds, s, p, a); break;
+        case 2: launch_cells_one<KIND, WordT, NOISE, 2>(grid, lds, s, p, a); break;
+        default: launch_cells_one<KIND, WordT, NOISE, 4>(grid, lds, s, p, a); break;
+    }
+}
+
+template <int KIND, typename WordT>
+void launch_cells_noise(bool noise, int rpl, dim3 grid, size_t lds, hipStream_t s, const CellPtrs& p, const CellArgs& a)
+{
+    if (noise) launch_cells_rpl<KIND, WordT, true>(rpl, grid, lds, s, p, a);
+    else launch_cells_rpl<KIND, WordT, false>(rpl, grid, lds, s, p, a);
+}
+
+template <typename WordT>
+void launch_cells_kind(int kind, bool noise, int rpl, dim3 grid, size_t lds, hipStream_t s, const CellPtrs& p,
+                       const CellArgs& a)
+{
+    switch (kind) {
+        case AHT_CONSTANT_STEP: launch_cells_noise<kConstantStep, WordT>(noise, rpl, grid, lds, s, p, a); break;
+        case AHT_LINEAR_STEP: launch_cells_noise<kLinearStep, WordT>(noise, rpl, grid, lds, s, p, a); break;
+        default: launch_cells_noise<kSoftBounds, WordT>(noise, rpl, grid, lds, s, p, a); break;
+    }
+}
+
+// Rows per lane: enough waves to fill 256 CUs x 4 SIMDs several times over, otherwise as many
+// cells per lane as possible (reuse of the x word, independent chains for the scheduler).
+int choose_rpl(const aht_tile* t)
+{
+    const int forced = env_int("AHT_RPL", 0);
+    if (forced == 1 || forced == 2 || forced == 4) return forced;
+    const size_t cells = (size_t)t->rows * t->cols;
+    const size_t want_waves = 8192;
+    if (cells / (64 * 4) >= want_waves) return 4;
+    if (cells / (64 * 2) >= want_waves) return 2;
+    return 1;
+}
+
+// the cell update of step `step` from the words in the tile's scratch
+aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s)
+{
+    const int rpl = choose_rpl(t);
+    int qcap = env_int("AHT_QCAP", 0);
+    if (qcap < 8 || qcap > 120) qcap = 40;
+    qcap &= ~3;
+    const int qstride = qcap + 12;                // terminator + dword read-ahead; odd dword count
+    CellPtrs p{};
+    p.W = t->W;
+    p.dw_up = t->planes[AHT_PLANE_DW_UP];
+    p.dw_down = t->planes[AHT_PLANE_DW_DOWN];
+    p.b_max = t->planes[AHT_PLANE_B_MAX];
+    p.b_min = t->planes[AHT_PLANE_B_MIN];
+    p.slope_up = t->planes[AHT_PLANE_SLOPE_UP];
+    p.slope_down = t->planes[AHT_PLANE_SLOPE_DOWN];
+    p.xw = t->xw;
+    p.dw = t->dw;
+    p.pulse_count = t->pulse_count;
+    CellArgs a{};
+    a.R = t->rows;
+    a.C = t->cols;
+    a.B = B;
+    a.Rpad = rpad(t);
+    a.Cpad = cpad(t);
+    a.nbx = (uint32_t)((t->cols + 63) / 64);
+    a.nby = (uint32_t)((t->rows + 4 * rpl - 1) / (4 * rpl));
+    a.k0 = (uint32_t)t->seed;
+    a.k1 = (uint32_t)(t->seed >> 32);
+    a.t = step;
+    a.c2c = t->dev.dw_min_std;
+    a.qcap = qcap;
+    a.qstride = qstride;
+    const uint64_t total = (uint64_t)a.nbx * a.nby;
+    const uint64_t per = (total + 7) / 8;
+    if (per * 8 > 0x7FFFFFFFull) return fail(AHT_ERR_UNSUPPORTED, "tile too large for one launch");
+    const dim3 grid((unsigned)(per * 8));
+    const size_t lds = (size_t)4 * rpl * 64 * qstride + 16;
+    const bool noise = t->dev.dw_min_std > 0.0f;
+    if (use_u32(t)) launch_cells_kind<uint32_t>(t->dev.kind, noise, rpl, grid, lds, s, p, a);
+    else launch_cells_kind<uint64_t>(t->dev.kind, noise, rpl, grid, lds, s, p, a);
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+bool finite_nonneg(float v) { return std::isfinite(v) && v >= 0.0f; }
+
+}  // namespace
+
+extern "C" {
+
+const char* aht_status_string(aht_status s)
+{
+    switch (s) {
+        case AHT_OK: return "AHT_OK";
+        case AHT_ERR_INVALID_ARG: return "AHT_ERR_INVALID_ARG";
+        case AHT_ERR_UNSUPPORTED: return "AHT_ERR_UNSUPPORTED";
+        case AHT_ERR_OOM: return "AHT_ERR_OOM";
+        case AHT_ERR_DEVICE: return "AHT_ERR_DEVICE";
+    }
+    return "AHT_ERR_UNKNOWN";
+}
+
+const char* aht_last_error(void) { return g_last_error.c_str(); }
+
+const char* aht_version(void) { return "aht 0.1 (HIP, gfx950, wave64)"; }
+
+aht_status aht_tile_create(aht_tile** out, int32_t rows, int32_t cols, const aht_device_params* dev,
+                           const aht_update_params* upd, uint64_t seed)
+{
+    if (!out || !dev || !upd) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    *out = nullptr;
+    if (rows <= 0 || cols <= 0) return fail(AHT_ERR_INVALID_ARG, "rows and cols must be positive");
+    if ((uint64_t)rows * (uint64_t)cols >= (1ull << 32))
+        return fail(AHT_ERR_INVALID_ARG, "rows*cols must stay below 2^32");
+    if (upd->bl < 1 || upd->bl > 63) return fail(AHT_ERR_INVALID_ARG, "bl must be in 1..63");
+    if (dev->kind < AHT_CONSTANT_STEP || dev->kind > AHT_SOFT_BOUNDS)
+        return fail(AHT_ERR_INVALID_ARG, "unknown device kind %d", dev->kind);
+    if (!(dev->dw_min > 0.0f) || !std::isfinite(dev->dw_min)) return fail(AHT_ERR_INVALID_ARG, "dw_min must be > 0");
+    if (!finite_nonneg(dev->dw_min_dtod) || !finite_nonneg(dev->dw_min_std) || !finite_nonneg(dev->up_down_dtod) ||
+        !finite_nonneg(dev->w_max_dtod) || !finite_nonneg(dev->w_min_dtod) || !finite_nonneg(dev->gamma_dtod))
+        return fail(AHT_ERR_INVALID_ARG, "standard deviations must be finite and >= 0");
+    if (!(dev->w_max >= 0.0f) || !(dev->w_min <= 0.0f) || !std::isfinite(dev->w_max) || !std::isfinite(dev->w_min))
+        return fail(AHT_ERR_INVALID_ARG, "need w_min <= 0 <= w_max");
+    if (!std::isfinite(dev->up_down) || !std::isfinite(dev->gamma_up) || !std::isfinite(dev->gamma_down))
+        return fail(AHT_ERR_INVALID_ARG, "non-finite device parameter");
+
+    aht_tile* t = new (std::nothrow) aht_tile();
+    if (!t) return fail(AHT_ERR_OOM, "host allocation failed");
+    t->rows = rows;
+    t->cols = cols;
+    t->dev = *dev;
+    t->upd = *upd;
+    t->upd.update_management = upd->update_management ? 1 : 0;
+    t->seed = seed;
+    aht_status st = AHT_OK;
+    const size_t n = (size_t)rows * cols;
+    const int nplanes = (dev->kind == AHT_LINEAR_STEP) ? 6 : 4;
+    auto cleanup = [&](aht_status s) { aht_tile_destroy(t); return s; };
+    hipError_t e = hipGetDevice(&t->device);
+    if (e != hipSuccess) return cleanup(hip_fail(e, "hipGetDevice"));
+    if ((e = hipMalloc((void**)&t->W, n * sizeof(float))) != hipSuccess) return cleanup(hip_fail(e, "hipMalloc(W)"));
+    for (int p = 0; p < nplanes; ++p)
+        if ((e = hipMalloc((void**)&t->planes[p], n * sizeof(float))) != hipSuccess)
+            return cleanup(hip_fail(e, "hipMalloc(plane)"));
+    if ((e = hipMalloc((void**)&t->pulse_count, sizeof(unsigned long long))) != hipSuccess)
+        return cleanup(hip_fail(e, "hipMalloc(counter)"));
+    if ((e = hipMemset(t->W, 0, n * sizeof(float))) != hipSuccess) return cleanup(hip_fail(e, "hipMemset"));
+    if ((e = hipMemset(t->pulse_count, 0, sizeof(unsigned long long))) != hipSuccess)
+        return cleanup(hip_fail(e, "hipMemset"));
+    PlaneArgs pa{};
+    pa.kind = dev->kind;
+    pa.dw_min = dev->dw_min; pa.dw_min_dtod = dev->dw_min_dtod;
+    pa.up_down = dev->up_down; pa.up_down_dtod = dev->up_down_dtod;
+    pa.w_max = dev->w_max; pa.w_max_dtod = dev->w_max_dtod;
+    pa.w_min = dev->w_min; pa.w_min_dtod = dev->w_min_dtod;
+    pa.gamma_up = dev->gamma_up; pa.gamma_down = dev->gamma_down; pa.gamma_dtod = dev->gamma_dtod;
+    pa.k0 = (uint32_t)seed; pa.k1 = (uint32_t)(seed >> 32);
+    pa.R = rows; pa.C = cols;
+    pa.dw_up = t->planes[0]; pa.dw_down = t->planes[1]; pa.b_max = t->planes[2]; pa.b_min = t->planes[3];
+    pa.slope_up = t->planes[4]; pa.slope_down = t->planes[5];
+    unsigned nb = blocks_for(n);
+    if (nb > 65536u) nb = 65536u;
+    hipLaunchKernelGGL(k_gen_planes, dim3(nb), dim3(256), 0, 0, pa);
+    if ((e = hipGetLastError()) != hipSuccess) return cleanup(hip_fail(e, "k_gen_planes launch"));
+    if ((e = hipDeviceSynchronize()) != hipSuccess) return cleanup(hip_fail(e, "k_gen_planes"));
+    (void)st;
+    *out = t;
+    return AHT_OK;
+}
+
+aht_status aht_tile_destroy(aht_tile* t)
+{
+    if (!t) return AHT_OK;
+    hipError_t first = hipDeviceSynchronize();
+    auto rel = [&](void* p) {
+        if (p) {
+            hipError_t e = hipFree(p);
+            if (first == hipSuccess) first = e;
+        }
+    };
+    rel(t->W);
+    for (auto* p : t->planes) rel(p);
+    rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->pulse_count);
+    delete t;
+    if (first != hipSuccess) return hip_fail(first, "aht_tile_destroy");
+    return AHT_OK;
+}
+
+aht_status aht_set_weights(aht_tile* t, const float* w_dev, void* stream)
+{
+    if (!t || !w_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    AHT_HIP(hipMemcpyAsync(t->W, w_dev, (size_t)t->rows * t->cols * sizeof(float), hipMemcpyDeviceToDevice,
+                           (hipStream_t)stream));
+    return AHT_OK;
+}
+
+aht_status aht_get_weights(const aht_tile* t, float* w_dev_out, void* stream)
+{
+    if (!t || !w_dev_out) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    AHT_HIP(hipMemcpyAsync(w_dev_out, t->W, (size_t)t->rows * t->cols * sizeof(float), hipMemcpyDeviceToDevice,
+                           (hipStream_t)stream));
+    return AHT_OK;
+}
+
+aht_status aht_pulsed_update(aht_tile* t, const float* x_dev, const float* d_dev, int32_t B, float lr, void* stream)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    if (B < 0) return fail(AHT_ERR_INVALID_ARG, "B must be >= 0");
+    if (!(lr >= 0.0f) || !std::isfinite(lr)) return fail(AHT_ERR_INVALID_ARG, "lr must be finite and >= 0");
+    if (B > 0 && (!x_dev || !d_dev)) return fail(AHT_ERR_INVALID_ARG, "null x or d");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    if (B > 0 && lr > 0.0f) {
+        if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
+        hipStream_t s = (hipStream_t)stream;
+        if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s)) != AHT_OK) return st;
+        if ((st = launch_cells(t, B, t->step, s)) != AHT_OK) return st;
+    }
+    t->step += 1;
+    return AHT_OK;
+}
+
+aht_status aht_get_step(const aht_tile* t, uint32_t* step)
+{
+    if (!t || !step) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    *step = t->step;
+    return AHT_OK;
+}
+
+aht_status aht_set_step(aht_tile* t, uint32_t step)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    t->step = step;
+    return AHT_OK;
+}
+
+aht_status aht_get_pulse_count(const aht_tile* t, uint64_t* pulses, void* stream)
+{
+    if (!t || !pulses) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    unsigned long long v = 0;
+    AHT_HIP(hipMemcpyAsync(&v, t->pulse_count, sizeof(v), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    AHT_HIP(hipStreamSynchronize((hipStream_t)stream));
+    *pulses = v;
+    return AHT_OK;
+}
+
+aht_status aht_get_device_planes(const aht_tile* t, int32_t plane, float* dev_out, void* stream)
+{
+    if (!t || !dev_out) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (plane < 0 || plane >= AHT_NUM_PLANES) return fail(AHT_ERR_INVALID_ARG, "plane index %d out of range", plane);
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    const size_t n = (size_t)t->rows * t->cols;
+    hipStream_t s = (hipStream_t)stream;
+    if (t->planes[plane]) {
+        AHT_HIP(hipMemcpyAsync(dev_out, t->planes[plane], n * sizeof(float), hipMemcpyDeviceToDevice, s));
+        return AHT_OK;
+    }
+    // slope planes that are not stored: 1/bound for SoftBounds, 0 for ConstantStep
+    const float* bound = nullptr;
+    if (t->dev.kind == AHT_SOFT_BOUNDS)
+        bound = t->planes[plane == AHT_PLANE_SLOPE_UP ? AHT_PLANE_B_MAX : AHT_PLANE_B_MIN];
+    unsigned nb = blocks_for(n);
+    if (nb > 65536u) nb = 65536u;
+    hipLaunchKernelGGL(k_derived_slope, dim3(nb), dim3(256), 0, s, bound, dev_out, n);
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+aht_status aht_set_device_planes(aht_tile* t, int32_t plane, const float* dev_in, void* stream)
+{
+    if (!t || !dev_in) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (plane < 0 || plane >= AHT_NUM_PLANES) return fail(AHT_ERR_INVALID_ARG, "plane index %d out of range", plane);
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    if (!t->planes[plane])
+        return fail(AHT_ERR_UNSUPPORTED, "slope planes can only be set on a LINEAR_STEP tile (they are derived otherwise)");
+    AHT_HIP(hipMemcpyAsync(t->planes[plane], dev_in, (size_t)t->rows * t->cols * sizeof(float),
+                           hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return AHT_OK;
+}
+
+aht_status aht_debug_pulse_words(aht_tile* t, const float* x_dev, const float* d_dev, int32_t B, float lr,
+                                 uint64_t* xw_dev, uint64_t* dw_dev, void* stream)
+{
+    if (!t || !x_dev || !d_dev || !xw_dev || !dw_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (B <= 0) return fail(AHT_ERR_INVALID_ARG, "B must be > 0");
+    if (!(lr >= 0.0f) || !std::isfinite(lr)) return fail(AHT_ERR_INVALID_ARG, "lr must be finite and >= 0");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s)) != AHT_OK) return st;
+    const size_t nx = (size_t)B * t->cols, nd = (size_t)B * t->rows;
+    if (use_u32(t)) {
+        hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint32_t*)t->xw, xw_dev, B, t->cols, cpad(t));
+        hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nd)), dim3(256), 0, s, (const uint32_t*)t->dw, dw_dev, B, t->rows, rpad(t));
+    } else {
+        hipLaunchKernelGGL(k_words_to_public<uint64_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint64_t*)t->xw, xw_dev, B, t->cols, cpad(t));
+        hipLaunchKernelGGL(k_words_to_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, (const uint64_t*)t->dw, dw_dev, B, t->rows, rpad(t));
+    }
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+aht_status aht_debug_counts(aht_tile* t, const uint64_t* xw_dev, const uint64_t* dw_dev, int32_t B, int32_t b,
+                            int8_t* out_dev, void* stream)
+{
+    if (!t || !xw_dev || !dw_dev || !out_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (B <= 0 || b < 0 || b >= B) return fail(AHT_ERR_INVALID_ARG, "sample index out of range");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    const size_t n = (size_t)t->rows * t->cols;
+    hipLaunchKernelGGL(k_counts, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, xw_dev, dw_dev, b, t->rows,
+                       t->cols, t->upd.bl, out_dev);
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+aht_status aht_debug_apply_words(aht_tile* t, const uint64_t* xw_dev, const uint64_t* dw_dev, int32_t B,
+                                 uint32_t step, void* stream)
+{
+    if (!t || !xw_dev || !dw_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (B <= 0) return fail(AHT_ERR_INVALID_ARG, "B must be > 0");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t nx = (size_t)B * cpad(t), nd = (size_t)B * rpad(t);
+    if (use_u32(t)) {
+        hipLaunchKernelGGL(k_words_from_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, xw_dev, (uint32_t*)t->xw, B, t->cols, cpad(t), t->upd.bl);
+        hipLaunchKernelGGL(k_words_from_public<uint32_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint32_t*)t->dw, B, t->rows, rpad(t), t->upd.bl);
+    } else {
+        hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nx)), dim3(256), 0, s, xw_dev, (uint64_t*)t->xw, B, t->cols, cpad(t), t->upd.bl);
+        hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint64_t*)t->dw, B, t->rows, rpad(t), t->upd.bl);
+    }
+    AHT_HIP(hipGetLastError());
+    return launch_cells(t, B, step, s);
+}
+
+aht_status aht_debug_philox(const uint32_t* ctr_dev, const uint32_t* key_dev, int32_t n, uint32_t* out_dev, void* stream)
+{
+    if (!ctr_dev || !key_dev || !out_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (n <= 0) return fail(AHT_ERR_INVALID_ARG, "n must be > 0");
+    hipLaunchKernelGGL(k_debug_philox, dim3(blocks_for((size_t)n)), dim3(256), 0, (hipStream_t)stream, ctr_dev, key_dev, n, out_dev);
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+aht_status aht_debug_gauss(uint64_t seed, uint32_t index, uint32_t t, uint32_t tag, uint32_t q0, int32_t n,
+                           int32_t fast, float* gauss_dev, void* stream)
+{
+    if (!gauss_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (n <= 0) return fail(AHT_ERR_INVALID_ARG, "n must be > 0");
+    hipLaunchKernelGGL(k_debug_gauss, dim3(blocks_for((size_t)n)), dim3(256), 0, (hipStream_t)stream,
+                       (uint32_t)seed, (uint32_t)(seed >> 32), index, t, tag, q0, n, fast, gauss_dev);
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+}  // extern "C"

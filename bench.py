@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the stochastic pulsed update on one MI355X.
+
+A step = one aht_pulsed_update call (line scaling + pulse trains + cell update) on the
+headline workload: 4096x4096 LinearStep tile, update management, B = 256 update vectors,
+BL = 63, fresh seeded synthetic x ~ N(0,1), d ~ N(0,0.01) already resident in HBM.
+Prints ONE JSON line: Gcell-pulse-updates/s (cells * B * BL per call / time), the roofline
+of the dominant kernel (the cell update, bound by plain vector-ALU issue) and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# ---- roofline model of the cell-update kernel ("Roofline") -------------------
+# Peak plain vector-ALU issue of the chip: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.
+PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+# Algorithmic issue slots (full-rate instruction = 1 slot, quarter-rate instruction = 4 slots).
+#   per (cell, sample), 64-bit words: 2 AND + 2 BCNT + 1 XOR (direction) + 1 compare     = 6
+#   per (cell, sample), 32-bit words: 1 AND + 1 BCNT + 1 XOR + 1 compare                 = 4
+#   per applied pulse with pulse-to-pulse noise:
+#       1/4 Philox4x32-10 block  (20 quarter-rate 32x32->64 multiplies + 20 XOR3)/4      = 25
+#       1/2 Box-Muller pair      (4 transcendentals x 4 + 10 full-rate)/2                = 13
+#       device step: ConstantStep 4 (select, noise fma, w fma, clamp); LinearStep/SoftBounds 8
+C_CS = {8: 6.0, 4: 4.0}
+C_PULSE_NOISE = 25.0 + 13.0
+C_STEP = {0: 4.0, 1: 8.0, 2: 8.0}
+# HBM bytes of one headline call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (profiles/): filled in once measured, None otherwise.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_lane_ops(w, pulses_per_call):
+    word_bytes = 4 if w.bl <= 31 else 8
+    c_p = C_STEP[w.device["kind"]] + (C_PULSE_NOISE if w.device["dw_min_std"] > 0 else 0.0)
+    if not w.device["dw_min_std"] > 0:
+        c_p -= 1.0                                   # no noise fma
+    return C_CS[word_bytes] * w.rows * w.cols * w.batch + c_p * pulses_per_call
+
+
+def cpu_baseline(w, target_rows):
+    """The oracle, as it stands, on a row slice of the same workload (same device law, same
+    input law, same B and BL); all host threads."""
+    import numpy as np
+
+    import oracle
+    from paper_2104_02184_amd import workloads as wl
+
+    s = wl.scaled(w, rows=target_rows, steps=1, name=w.name + "_cpu_sample")
+    p = oracle.DeviceParams(**s.device)
+    planes = oracle.device_planes(p, s.seed, s.rows, s.cols)
+    W = np.clip(wl.initial_weights(s), planes["b_min"], planes["b_max"]).astype(np.float32)
+    _, x, d = next(iter(wl.input_stream(s)))
+    t0 = time.perf_counter()
+    pulses = oracle.pulsed_update(W, planes, p, s.bl, s.update_management, x, d, s.lr, s.seed, 0)
+    dt = time.perf_counter() - t0
+    return {
+        "value": s.cell_pulse_updates_per_call / dt / 1e9,
+        "unit": "Gcell-pulse-updates/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"{s.rows}x{s.cols} row slice of the headline tile, B={s.batch}, BL={s.bl}, 1 call "
+                  f"({pulses} pulses, {dt:.2f} s wall)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None, help="workload name (default: the headline one)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--cpu-rows", type=int, default=512)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the pulsed update of one tile runs on a single MI355X "
+              "(see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2104_02184_amd as aht
+    from paper_2104_02184_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    aht.load_library()
+    w = wl.WORKLOADS[args.workload or wl.HEADLINE]
+    K, Wm = args.steps, args.warmup
+
+    tile = aht.Tile(w.rows, w.cols, aht.DeviceParams(**w.device), w.bl, w.update_management, w.seed)
+    bmax, bmin = tile.get_plane("b_max"), tile.get_plane("b_min")
+    W0 = torch.from_numpy(wl.initial_weights(w)).cuda()
+    tile.set_weights(torch.minimum(torch.maximum(W0, bmin), bmax))
+    del bmax, bmin, W0
+
+    # fresh inputs for every step, uploaded before the timed region
+    g = wl.rng_for(w, 2)
+    pool = min(K + Wm, 24 if w.batch <= 1024 else 4)
+    xs = [torch.from_numpy(wl.draw_x(w, g)).cuda() for _ in range(pool)]
+    ds = [torch.from_numpy(wl.draw_d(w, g)).cuda() for _ in range(pool)]
+
+    for i in range(Wm):
+        tile.pulsed_update(xs[i % pool], ds[i % pool], w.lr)
+    torch.cuda.synchronize()
+    p0 = tile.pulse_count()
+    tile.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        tile.pulsed_update(xs[(Wm + i) % pool], ds[(Wm + i) % pool], w.lr)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_words, ms_cells, calls = tile.profile_read()
+    tile.profile_enable(False)
+    pulses = (tile.pulse_count() - p0) / max(K, 1)
+    tile.close()
+
+    sec = t1 - t0
+    ms_per_step = sec / K * 1e3
+    value = w.cell_pulse_updates_per_call * K / sec / 1e9
+    cell_ms = ms_cells / max(calls, 1)
+    ops = algorithmic_lane_ops(w, pulses)
+    achieved = ops / (cell_ms * 1e-3)
+    out = {
+        "metric": "Gcell-pulse-updates/s of pulsed_update",
+        "value": value,
+        "unit": "Gcell-pulse-updates/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": Wm,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "rows": w.rows, "cols": w.cols, "batch": w.batch, "bl": w.bl,
+                   "update_management": w.update_management, "lr": w.lr,
+                   "pulses_per_call": pulses, "applied_pulses_per_s": pulses / (sec / K)},
+        "roofline": {
+            "bound": "alu",
+            "kernel": "k_cell_update",
+            "achieved": achieved / 1e12,
+            "peak": PEAK_LANE_OPS / 1e12,
+            "unit": "Tlane-op/s",
+            "frac": achieved / PEAK_LANE_OPS,
+            "traffic": MEASURED_TRAFFIC_BYTES,
+            "kernel_ms": cell_ms,
+            "words_ms": ms_words / max(calls, 1),
+            "algorithmic_lane_ops_per_launch": ops,
+        },
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_rows)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

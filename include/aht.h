@@ -156,6 +156,14 @@ aht_status aht_debug_philox(const uint32_t* ctr_dev, const uint32_t* key_dev, in
 aht_status aht_debug_gauss(uint64_t seed, uint32_t index, uint32_t t, uint32_t tag, uint32_t q0,
                            int32_t n, int32_t fast, float* gauss_dev, void* stream);
 
+/* Measurement hook.  While enabled, every aht_pulsed_update records HIP events on its stream
+ * before the pulse-train kernels, between them and the cell-update kernel, and after it.
+ * aht_profile_read waits for the recorded events, returns the summed durations in
+ * milliseconds (line scaling + pulse words; cell update) and the number of calls they cover,
+ * and clears the record.  At most 4096 calls are recorded between two reads. */
+aht_status aht_profile_enable(aht_tile* tile, int32_t enable);
+aht_status aht_profile_read(aht_tile* tile, double* ms_words, double* ms_cells, int32_t* calls);
+
 const char* aht_status_string(aht_status s);
 const char* aht_last_error(void);
 /* Library version string; also tells which architecture the kernels were built for. */

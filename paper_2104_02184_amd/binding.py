@@ -21,7 +21,8 @@ EXPORTS = (
     "aht_tile_create", "aht_tile_destroy", "aht_set_weights", "aht_get_weights", "aht_pulsed_update",
     "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
     "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
-    "aht_debug_philox", "aht_debug_gauss", "aht_status_string", "aht_last_error", "aht_version",
+    "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
+    "aht_status_string", "aht_last_error", "aht_version",
 )
 
 
@@ -97,6 +98,9 @@ def load_library() -> ctypes.CDLL:
     L.aht_debug_apply_words.argtypes = [vp, vp, vp, i32, u32, vp]
     L.aht_debug_philox.argtypes = [vp, vp, i32, vp, vp]
     L.aht_debug_gauss.argtypes = [u64, u32, u32, u32, u32, i32, i32, vp, vp]
+    L.aht_profile_enable.argtypes = [vp, i32]
+    L.aht_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                   ctypes.POINTER(i32)]
     for name in EXPORTS:
         getattr(L, name).restype = ctypes.c_int
     L.aht_status_string.argtypes = [ctypes.c_int]
@@ -212,6 +216,16 @@ class Tile:
         idx = PLANE_NAMES.index(name) if isinstance(name, str) else int(name)
         _check(self._lib.aht_set_device_planes(self._h, idx, _ptr(values, torch.float32, (self.rows, self.cols)),
                                                _stream()))
+
+    # -- measurement hook ------------------------------------------------------------------
+    def profile_enable(self, enable: bool = True):
+        _check(self._lib.aht_profile_enable(self._h, int(bool(enable))))
+
+    def profile_read(self):
+        """(ms in line scaling + pulse words, ms in the cell update, calls covered)"""
+        a, b, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int32()
+        _check(self._lib.aht_profile_read(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)))
+        return a.value, b.value, n.value
 
     # -- test hooks ------------------------------------------------------------------------
     def debug_pulse_words(self, x, d, lr: float):

@@ -12,6 +12,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "aht_kernels.hpp"
 
@@ -34,6 +35,10 @@ struct aht_tile {
     double* a_d = nullptr;
     int a_cap = 0;
     unsigned long long* pulse_count = nullptr;
+    // measurement hook: three events per recorded call
+    bool profiling = false;
+    std::vector<hipEvent_t> events;
+    size_t events_used = 0;
 };
 
 namespace {
@@ -146,6 +151,14 @@ struct CellPtrs {
 template <int KIND, typename WordT, bool NOISE, int RPL>
 void launch_cells_one(dim3 grid, size_t lds, hipStream_t s, const CellPtrs& p, const CellArgs& a)
 {
+    if (lds > 64 * 1024) {   // more dynamic LDS than the default limit: opt in (gfx950 has 160 KB per CU)
+        static size_t allowed = 0;
+        if (lds > allowed) {
+            (void)hipFuncSetAttribute((const void*)k_cell_update<KIND, WordT, NOISE, RPL>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            allowed = lds;
+        }
+    }
     hipLaunchKernelGGL((k_cell_update<KIND, WordT, NOISE, RPL>), grid, dim3(256), lds, s, p.W, p.dw_up, p.dw_down,
                        p.b_max, p.b_min, p.slope_up, p.slope_down, (const WordT*)p.xw, (const WordT*)p.dw,
                        p.pulse_count, a);
@@ -196,10 +209,9 @@ int choose_rpl(const aht_tile* t)
 aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s)
 {
     const int rpl = choose_rpl(t);
-    int qcap = env_int("AHT_QCAP", 0);
-    if (qcap < 8 || qcap > 120) qcap = 40;
-    qcap &= ~3;
-    const int qstride = qcap + 12;                // terminator + dword read-ahead; odd dword count
+    // stream storage per cell: 12 words hold 320 pulses before an early drain is needed
+    int qwords = env_int("AHT_QWORDS", 0);
+    if (qwords < 5 || qwords > 160) qwords = 12;
     CellPtrs p{};
     p.W = t->W;
     p.dw_up = t->planes[AHT_PLANE_DW_UP];
@@ -223,13 +235,12 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s)
     a.k1 = (uint32_t)(t->seed >> 32);
     a.t = step;
     a.c2c = t->dev.dw_min_std;
-    a.qcap = qcap;
-    a.qstride = qstride;
+    a.qwords = qwords;
     const uint64_t total = (uint64_t)a.nbx * a.nby;
     const uint64_t per = (total + 7) / 8;
     if (per * 8 > 0x7FFFFFFFull) return fail(AHT_ERR_UNSUPPORTED, "tile too large for one launch");
     const dim3 grid((unsigned)(per * 8));
-    const size_t lds = (size_t)4 * rpl * 64 * qstride + 16;
+    const size_t lds = (size_t)4 * rpl * 64 * qwords * 4;
     const bool noise = t->dev.dw_min_std > 0.0f;
     if (use_u32(t)) launch_cells_kind<uint32_t>(t->dev.kind, noise, rpl, grid, lds, s, p, a);
     else launch_cells_kind<uint64_t>(t->dev.kind, noise, rpl, grid, lds, s, p, a);
@@ -336,6 +347,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     rel(t->W);
     for (auto* p : t->planes) rel(p);
     rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->pulse_count);
+    for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
     delete t;
     if (first != hipSuccess) return hip_fail(first, "aht_tile_destroy");
     return AHT_OK;
@@ -372,10 +384,51 @@ aht_status aht_pulsed_update(aht_tile* t, const float* x_dev, const float* d_dev
     if (B > 0 && lr > 0.0f) {
         if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
         hipStream_t s = (hipStream_t)stream;
+        hipEvent_t* ev = nullptr;
+        if (t->profiling && t->events_used + 3 <= 3 * 4096) {
+            while (t->events.size() < t->events_used + 3) {
+                hipEvent_t e;
+                AHT_HIP(hipEventCreate(&e));
+                t->events.push_back(e);
+            }
+            ev = &t->events[t->events_used];
+        }
+        if (ev) AHT_HIP(hipEventRecord(ev[0], s));
         if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s)) != AHT_OK) return st;
+        if (ev) AHT_HIP(hipEventRecord(ev[1], s));
         if ((st = launch_cells(t, B, t->step, s)) != AHT_OK) return st;
+        if (ev) {
+            AHT_HIP(hipEventRecord(ev[2], s));
+            t->events_used += 3;
+        }
     }
     t->step += 1;
+    return AHT_OK;
+}
+
+aht_status aht_profile_enable(aht_tile* t, int32_t enable)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    t->profiling = enable != 0;
+    return AHT_OK;
+}
+
+aht_status aht_profile_read(aht_tile* t, double* ms_words, double* ms_cells, int32_t* calls)
+{
+    if (!t || !ms_words || !ms_cells || !calls) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    double w = 0.0, c = 0.0;
+    for (size_t k = 0; k + 3 <= t->events_used; k += 3) {
+        AHT_HIP(hipEventSynchronize(t->events[k + 2]));
+        float a = 0.0f, b = 0.0f;
+        AHT_HIP(hipEventElapsedTime(&a, t->events[k], t->events[k + 1]));
+        AHT_HIP(hipEventElapsedTime(&b, t->events[k + 1], t->events[k + 2]));
+        w += a;
+        c += b;
+    }
+    *ms_words = w;
+    *ms_cells = c;
+    *calls = (int32_t)(t->events_used / 3);
+    t->events_used = 0;
     return AHT_OK;
 }
 

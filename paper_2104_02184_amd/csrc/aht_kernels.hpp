@@ -235,27 +235,34 @@ __global__ void __launch_bounds__(256) k_debug_gauss(uint32_t k0, uint32_t k1, u
 // ------------------------------------------------------------------------------------------
 // The cell update.
 //
-// Work split: lane <-> column j (coalesced rows of W, the row word is wave-uniform), each lane
-// owns RPL cells (rows i0 .. i0+RPL-1 of its column); a workgroup is 4 independent waves
-// stacked along the rows.  Weights and device parameters are loaded once, stay in registers
-// for all B update vectors and are stored once.
+// Work split: lane <-> column j (coalesced rows of W, the row word is wave-uniform and comes
+// through scalar loads), each lane owns RPL cells (rows i0 .. i0+RPL-1 of its column); a
+// workgroup is 4 independent waves stacked along the rows.  Weights and device parameters are
+// loaded once, stay in registers for all B update vectors and are stored once.
 //
-// A cell's coincidences are few per sample and their number differs from lane to lane, so the
-// samples are not applied in lock-step.  Phase A walks the samples at full lane occupancy and
-// appends one byte (count | direction<<7) per non-empty sample to a per-cell queue in LDS;
-// when a queue in the wave is (nearly) full, or after the last sample, phase B drains the
-// queues: every iteration draws one Philox block = four Gaussians per cell and applies up to
-// four pulses.  Pulses of one cell stay in sample order, which is all the sequential
-// application asks for (cells are independent).  The Gaussian a pulse uses is fixed by the
-// cell's running pulse counter q, so the split into phases does not change any result.
+// A cell sees few coincidences per sample and their number differs from lane to lane, so the
+// samples are not applied in lock-step.
+//   Phase A walks the samples at full lane occupancy: count = popcount(x word AND d word), and
+//   `count` copies of the direction bit (1 = up) are shifted into a per-cell bit stream, one bit
+//   per pulse, in sample order.  Full 32-bit words of the stream go to LDS (lane-interleaved,
+//   free of bank conflicts); a 64-bit register pair holds the unflushed tail.
+//   Phase B drains the streams: iteration i handles stream bits 4i..4i+3 of every cell with
+//   one Philox block = four Gaussians per cell; all cells of the wave run the same number of
+//   iterations (the wave's longest stream).
+// Bit p of a cell's stream is pulse number (q & ~31) + p of the call, q being the cell's pulse
+// count when the stream was (re)started; the stream therefore starts at bit q & 31 and the
+// Gaussian block of iteration i is (q >> 5) * 8 + i.  Pulses of one cell stay in sample order,
+// which is all the sequential application asks for (cells are independent), and the Gaussian a
+// pulse uses is fixed by its number, so the phase split does not change any result.
+// Normally the whole call fits one stream; if a stream runs out of LDS room the wave drains
+// early and starts new streams.
 // ------------------------------------------------------------------------------------------
 struct CellArgs {
     int R, C, B, Rpad, Cpad;
     uint32_t nbx, nby;            // tiles along columns / rows
     uint32_t k0, k1, t;
     float c2c;
-    int qcap;                     // queue capacity (entries) per cell, multiple of 4
-    int qstride;                  // bytes between the queues of neighbouring lanes
+    int qwords;                   // 32-bit words of stream storage per cell (>= 5)
 };
 
 // select by an all-ones / all-zeros mask: (m & a) | (~m & b), one v_bfi_b32
@@ -280,11 +287,20 @@ __device__ __forceinline__ float device_step(float w, uint32_t dmask, float z, f
     return __builtin_amdgcn_fmed3f(wn, bmin, bmax);      // clamp; bmin <= 0 <= bmax
 }
 
-// LDS bytes are addressed through 32-bit local pointers kept in registers
-typedef __attribute__((address_space(3))) unsigned char lds_u8;
+// LDS is addressed through 32-bit local pointers kept in registers
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
-__device__ __forceinline__ void lds_store_u8(uint32_t addr, uint32_t v) { *(lds_u8*)(size_t)addr = (unsigned char)v; }
+__device__ __forceinline__ void lds_store_u32(uint32_t addr, uint32_t v) { *(lds_u32*)(size_t)addr = v; }
 __device__ __forceinline__ uint32_t lds_load_u32(uint32_t addr) { return *(const lds_u32*)(size_t)addr; }
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
+        v = v > o ? v : o;
+    }
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
+}
 
 // W [R][C] in/out; planes [R][C]; xw[B][Cpad], dw[B][Rpad]: internal zero-padded pulse words.
 // The pointers are separate restrict-qualified parameters so that the wave-uniform row words
@@ -298,10 +314,11 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
               unsigned long long* __restrict__ pulse_count, CellArgs a)
 {
     extern __shared__ __align__(16) unsigned char lds[];
-    const uint32_t lds0 = (uint32_t)(size_t)(lds_u8*)lds;
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
     constexpr int kSign = WordTraits<WordT>::kSignBit;
     constexpr WordT kBits = (WordT)(~((WordT)1 << kSign));
-    constexpr int G = 4;                          // samples per group (prefetch depth, fill check)
+    constexpr int G = 4;                          // samples per group (one stream flush per group)
+    constexpr uint32_t kWordStride = 64 * 4;      // bytes between consecutive words of one stream
 
     // XCD-aware tile mapping: consecutive workgroup ids go round-robin to the 8 XCDs, so give
     // each XCD one contiguous range of tiles; tiles of one column strip are neighbours and
@@ -323,7 +340,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     const WordT* __restrict__ dp = dw + i0;
 
     float w[RPL], s_up[RPL], s_dn_neg[RPL], bmax[RPL], bmin[RPL], sl_up[RPL], sl_dn[RPL];
-    uint32_t q[RPL], wr[RPL], qb[RPL], cellid[RPL];
+    uint32_t q[RPL], cellid[RPL], qb[RPL];
+    uint32_t acc_lo[RPL], acc_hi[RPL], fill[RPL], wp[RPL];   // stream tail, its length, LDS write pointer
     bool cv[RPL];
 #pragma unroll
     for (int c = 0; c < RPL; ++c) {
@@ -345,126 +363,169 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             sl_dn[c] = (bmin[c] != 0.0f) ? 1.0f / bmin[c] : 0.0f;
         }
         q[c] = 0;
-        qb[c] = lds0 + (uint32_t)(((wave * RPL + c) * 64 + lane) * a.qstride);
-        wr[c] = qb[c];
+        qb[c] = lds0 + (uint32_t)(((wave * RPL + c) * a.qwords * 64 + lane) * 4);
+        acc_lo[c] = 0;
+        acc_hi[c] = 0;
+        fill[c] = 0;
+        wp[c] = qb[c];
     }
 
-    // ---- phase B: drain the queues ----------------------------------------------------
+    // Append `n` (<= 31, and fill + n <= 64) copies of the direction bit to the stream tail.
+    auto append = [&](int c, uint32_t n, uint32_t m) __attribute__((always_inline)) {
+        const uint64_t acc = (((uint64_t)acc_hi[c] << 32) | acc_lo[c]) << n;
+        const uint32_t ones = (1u << n) - 1u;                        // n <= 31; one v_bfm_b32
+        acc_lo[c] = (ones & m) | (uint32_t)acc;
+        acc_hi[c] = (uint32_t)(acc >> 32);
+        fill[c] += n;
+    };
+    // Move one full word (the oldest 32 bits of the tail) to LDS if there is one.  The store is
+    // unconditional; the write pointer only moves when the word was full.
+    auto flush = [&](int c) __attribute__((always_inline)) {
+        const uint64_t acc = ((uint64_t)acc_hi[c] << 32) | acc_lo[c];
+        lds_store_u32(wp[c], (uint32_t)(acc >> ((fill[c] - 32u) & 63u)));
+        wp[c] += (fill[c] >> 5) * kWordStride;                       // fill < 64
+        fill[c] &= 31u;
+    };
+
+    // ---- phase B: drain the streams ---------------------------------------------------
     auto drain = [&]() __attribute__((always_inline)) {
-        uint32_t rd[RPL], nrem[RPL], dmask[RPL];
+        uint32_t endpos[RPL], start[RPL], blk0[RPL], D[RPL];
+        uint32_t longest = 0;
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
-            lds_store_u8(wr[c], 0);               // terminator: an entry with count 0
-            rd[c] = qb[c];
-            nrem[c] = 0;
-            dmask[c] = 0;
+            lds_store_u32(wp[c], acc_lo[c] << ((32u - fill[c]) & 31u));      // left-aligned partial word
+            endpos[c] = ((wp[c] - qb[c]) >> 3) + fill[c];                    // 32 bits per 256-byte step
+            start[c] = q[c] & 31u;
+            blk0[c] = (q[c] >> 5) << 3;
+            D[c] = 0;
+            longest = longest > endpos[c] ? longest : endpos[c];
         }
-        for (;;) {
-            bool pending = false;
+        const int niter = (int)((wave_max_u32(longest) + 3u) >> 2);
+        for (int i = 0; i < niter; ++i) {
+            if ((i & 7) == 0) {
 #pragma unroll
-            for (int c = 0; c < RPL; ++c) pending |= (rd[c] != wr[c]) | (nrem[c] != 0);
-            if (!__any(pending)) break;
+                for (int c = 0; c < RPL; ++c) D[c] = lds_load_u32(qb[c] + (uint32_t)(i >> 3) * kWordStride);
+            }
 #pragma unroll
             for (int c = 0; c < RPL; ++c) {
-                const uint32_t ph = q[c] & 3u;
                 float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (NOISE) gauss4_fast(a.k0, a.k1, cellid[c], q[c] >> 2, a.t, kTagC2C, z);
-                // the next four queue bytes, fetched as two aligned dwords
-                const uint32_t al = rd[c] & ~3u;
-                const uint32_t lo = lds_load_u32(al);
-                const uint32_t hi = lds_load_u32(al + 4);
-                uint32_t E = __builtin_amdgcn_alignbyte(hi, lo, rd[c] & 3u);
+                if (NOISE) gauss4_fast(a.k0, a.k1, cellid[c], blk0[c] + (uint32_t)i, a.t, kTagC2C, z);
+                const int lo = (int)start[c] - 4 * i, hi = (int)endpos[c] - 4 * i;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    // branch-free: fetch the next entry when the current one is used up; the
-                    // terminator (count 0) is never stepped over
-                    const bool need = nrem[c] == 0;
-                    const uint32_t n_new = E & 0x7Fu;
-                    const uint32_t d_new = (uint32_t)__builtin_amdgcn_sbfe((int)E, 7, 1);
-                    const bool adv = need & (n_new != 0);
-                    nrem[c] = need ? n_new : nrem[c];
-                    dmask[c] = need ? d_new : dmask[c];
-                    E = adv ? (E >> 8) : E;
-                    rd[c] += adv ? 1u : 0u;
-                    const bool act = (nrem[c] != 0) & ((uint32_t)k >= ph);
-                    const float wn = device_step<KIND, NOISE>(w[c], dmask[c], z[k], a.c2c, s_up[c], s_dn_neg[c],
+                    const bool act = (k >= lo) & (k < hi);
+                    const uint32_t dmask = (uint32_t)__builtin_amdgcn_sbfe((int)D[c], 31 - k, 1);
+                    const float wn = device_step<KIND, NOISE>(w[c], dmask, z[k], a.c2c, s_up[c], s_dn_neg[c],
                                                               bmax[c], bmin[c], sl_up[c], sl_dn[c]);
                     w[c] = act ? wn : w[c];
-                    nrem[c] -= act ? 1u : 0u;
-                    q[c] += act ? 1u : 0u;
                 }
+                D[c] <<= 4;
             }
         }
 #pragma unroll
-        for (int c = 0; c < RPL; ++c) wr[c] = qb[c];
-    };
-
-    // ---- phase A: counts of one sample, appended to the queues --------------------------
-    // entry byte = count + 128 * (x_j d_i < 0); the byte is always stored, the write pointer
-    // only moves past it when the count is non-zero.  Seven vector instructions per cell and
-    // sample: two ANDs, one XOR for the direction, two popcounts that accumulate on top of the
-    // direction bit, a compare and an add-with-carry.  The empty asm statements only stop the
-    // compiler from re-associating the direction bit into per-cell shifts.
-    auto sample = [&](WordT xv, const WordT (&dv)[RPL]) __attribute__((always_inline)) {
-        uint32_t xs = (uint32_t)(xv >> (kSign - 7)) & 0x80u;
-        asm volatile("" : "+v"(xs));
-#pragma unroll
-        for (int c = 0; c < RPL; ++c) {
-            const uint32_t dsg = (uint32_t)(dv[c] >> (kSign - 7)) & 0x80u;     // wave-uniform
-            const WordT both = xv & (dv[c] & kBits);
-            uint32_t xd = xs ^ dsg;
-            asm volatile("" : "+v"(xd));
-            uint32_t e;
-            if (sizeof(WordT) == 8)
-                e = (uint32_t)__popc((uint32_t)((uint64_t)both >> 32)) + ((uint32_t)__popc((uint32_t)both) + xd);
-            else
-                e = (uint32_t)__popc((uint32_t)both) + xd;
-            lds_store_u8(wr[c], e);
-            wr[c] += (e != xd) ? 1u : 0u;
+        for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31
+            q[c] += endpos[c] - start[c];
+            acc_lo[c] = 0;
+            acc_hi[c] = 0;
+            fill[c] = q[c] & 31u;
+            wp[c] = qb[c];
         }
     };
+
+    // ---- phase A ----------------------------------------------------------------------
     auto load_x = [&](int b0, WordT (&xg)[G]) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < G; ++u) xg[u] = xp[(size_t)(b0 + u) * xstride];
     };
+    // counts and direction masks of one sample for the lane's cells
+    auto count = [&](WordT xv, const WordT (&dv)[RPL], uint32_t (&n)[RPL], uint32_t (&m)[RPL])
+                     __attribute__((always_inline)) {
+        const uint32_t xm = (uint32_t)((int32_t)(uint32_t)(xv >> (kSign - 31)) >> 31);   // ~0 if x < 0
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) {
+            const uint32_t dm = (uint32_t)((int32_t)(uint32_t)(dv[c] >> (kSign - 31)) >> 31);   // wave-uniform
+            const WordT both = xv & (dv[c] & kBits);
+            n[c] = (sizeof(WordT) == 8)
+                       ? (uint32_t)__popc((uint32_t)((uint64_t)both >> 32)) + (uint32_t)__popc((uint32_t)both)
+                       : (uint32_t)__popc((uint32_t)both);
+            m[c] = xm ^ dm;                                          // ~0: x_j d_i < 0, an UP pulse
+        }
+    };
+    // a sample with any count: at most 16 bits at a time, flushing in between
+    auto append_slow = [&](const uint32_t (&n)[RPL], const uint32_t (&m)[RPL]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) {
+            uint32_t left = n[c];
+#pragma unroll
+            for (int part = 0; part < 4; ++part) {                   // 4 x 16 >= 63
+                const uint32_t take = left < 16u ? left : 16u;
+                append(c, take, m[c]);
+                flush(c);
+                left -= take;
+            }
+        }
+    };
 
-    const uint32_t limit = (uint32_t)(a.qcap - G);
+    // A stream may be extended while its word index is <= qwords - 3: one sample adds at most
+    // two words and the word under the write pointer must exist.
+    const uint32_t last_ok = (uint32_t)(a.qwords - 3) * kWordStride;
     WordT xg[G];
+    int xb = -1;                                  // first sample of the group held in xg
     int b = 0;
-    if (G <= B) load_x(0, xg);
     bool done = false;
     do {
         bool full = false;
-        while (!full && b + G <= B) {
-            WordT dg[G][RPL];                     // row words of this group (scalar registers)
+        while (!full && b < B) {
+            if (b + G <= B) {
+                if (xb != b) load_x(b, xg);
+                WordT dg[G][RPL];                 // row words of this group (scalar registers)
 #pragma unroll
-            for (int u = 0; u < G; ++u)
+                for (int u = 0; u < G; ++u)
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) dg[u][c] = dp[(size_t)(b + u) * dstride + c];
-            WordT xn[G];
-            const bool more = b + 2 * G <= B;
-            if (more) load_x(b + G, xn);          // next group's column words in flight meanwhile
+                    for (int c = 0; c < RPL; ++c) dg[u][c] = dp[(size_t)(b + u) * dstride + c];
+                WordT xn[G];
+                const bool more = b + 2 * G <= B;
+                if (more) load_x(b + G, xn);      // next group's column words in flight meanwhile
+                uint32_t n[G][RPL], m[G][RPL];
 #pragma unroll
-            for (int u = 0; u < G; ++u) sample(xg[u], dg[u]);
-            b += G;
-            bool nearly_full = false;
+                for (int u = 0; u < G; ++u) count(xg[u], dg[u], n[u], m[u]);
+                bool big = false;
 #pragma unroll
-            for (int c = 0; c < RPL; ++c) nearly_full |= (wr[c] - qb[c]) > limit;
-            full = __any(nearly_full) != 0;
-            if (more) {
+                for (int c = 0; c < RPL; ++c) big |= (n[0][c] + n[1][c] + n[2][c] + n[3][c]) > 31u;
+                if (!__any(big)) {                // usual case: the group adds < 32 bits per cell
 #pragma unroll
-                for (int u = 0; u < G; ++u) xg[u] = xn[u];
-            }
-        }
-        if (!full) {                              // fewer than G samples left and room for them
-            for (; b < B; ++b) {
+                    for (int c = 0; c < RPL; ++c) {
+#pragma unroll
+                        for (int u = 0; u < G; ++u) append(c, n[u][c], m[u][c]);
+                        flush(c);
+                    }
+                    b += G;
+                    xb = -1;
+                    if (more) {
+#pragma unroll
+                        for (int u = 0; u < G; ++u) xg[u] = xn[u];
+                        xb = b;
+                    }
+                } else {                          // a large count somewhere: one sample at a time
+                    append_slow(n[0], m[0]);
+                    b += 1;
+                    xb = -1;
+                }
+            } else {                              // fewer than G samples left
                 WordT dv[RPL];
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) dv[c] = dp[(size_t)b * dstride + c];
-                sample(xp[(size_t)b * xstride], dv);
+                uint32_t n1[RPL], m1[RPL];
+                count(xp[(size_t)b * xstride], dv, n1, m1);
+                append_slow(n1, m1);
+                b += 1;
             }
-            done = true;
+            bool nearly_full = false;
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) nearly_full |= (wp[c] - qb[c]) > last_ok;
+            full = __any(nearly_full) != 0;
         }
+        done = b >= B;
         drain();
     } while (!done);
 

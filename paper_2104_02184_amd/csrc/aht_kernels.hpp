@@ -320,14 +320,20 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     constexpr int G = 4;                          // samples per group (one stream flush per group)
     constexpr uint32_t kWordStride = 64 * 4;      // bytes between consecutive words of one stream
 
-    // XCD-aware tile mapping: consecutive workgroup ids go round-robin to the 8 XCDs, so give
-    // each XCD one contiguous range of tiles; tiles of one column strip are neighbours and
-    // share their x words in that XCD's L2.
-    const uint32_t total = a.nbx * a.nby;
+    // XCD-aware tile mapping.  Consecutive workgroup ids go round-robin to the 8 XCDs, so each
+    // XCD gets one contiguous range of the tile sequence; the sequence walks super-tiles of
+    // kSuperY row blocks x kSuperX column strips so that the x words (per strip) and d words
+    // (per row block) a range touches stay resident in that XCD's 4 MB L2.
+    constexpr uint32_t kSuperY = 64, kSuperX = 8;
+    const uint32_t nsy = (a.nby + kSuperY - 1) / kSuperY, nsx = (a.nbx + kSuperX - 1) / kSuperX;
+    const uint32_t total = nsy * nsx * kSuperY * kSuperX;            // padded tile sequence
     const uint32_t per = (total + 7u) >> 3;
-    const uint32_t tile = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
-    if (tile >= total) return;
-    const uint32_t bx = tile / a.nby, by = tile - bx * a.nby;
+    const uint32_t seq = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
+    if (seq >= total) return;
+    const uint32_t st = seq / (kSuperY * kSuperX), in = seq - st * (kSuperY * kSuperX);
+    const uint32_t sy = st % nsy, sx = st / nsy;
+    const uint32_t by = sy * kSuperY + (in % kSuperY), bx = sx * kSuperX + (in / kSuperY);
+    if (by >= a.nby || bx >= a.nbx) return;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -433,14 +439,17 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     };
 
     // ---- phase A ----------------------------------------------------------------------
-    auto load_x = [&](int b0, WordT (&xg)[G]) __attribute__((always_inline)) {
+    const WordT* __restrict__ xcur = xp;          // column words of sample b
+    const WordT* __restrict__ dcur = dp;          // row words of sample b (wave-uniform)
+    auto load_x = [&](const WordT* __restrict__ p0, WordT (&xg)[G]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < G; ++u) xg[u] = xp[(size_t)(b0 + u) * xstride];
+        for (int u = 0; u < G; ++u) xg[u] = p0[(size_t)u * xstride];
     };
     // counts and direction masks of one sample for the lane's cells
     auto count = [&](WordT xv, const WordT (&dv)[RPL], uint32_t (&n)[RPL], uint32_t (&m)[RPL])
                      __attribute__((always_inline)) {
-        const uint32_t xm = (uint32_t)((int32_t)(uint32_t)(xv >> (kSign - 31)) >> 31);   // ~0 if x < 0
+        uint32_t xm = (uint32_t)((int32_t)(uint32_t)(xv >> (kSign - 31)) >> 31);        // ~0 if x < 0
+        asm volatile("" : "+v"(xm));              // keep the row part of the direction on the scalar unit
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
             const uint32_t dm = (uint32_t)((int32_t)(uint32_t)(dv[c] >> (kSign - 31)) >> 31);   // wave-uniform
@@ -470,22 +479,22 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     // two words and the word under the write pointer must exist.
     const uint32_t last_ok = (uint32_t)(a.qwords - 3) * kWordStride;
     WordT xg[G];
-    int xb = -1;                                  // first sample of the group held in xg
+    bool have_x = false;                          // xg holds the words of samples b .. b+G-1
     int b = 0;
     bool done = false;
     do {
         bool full = false;
         while (!full && b < B) {
             if (b + G <= B) {
-                if (xb != b) load_x(b, xg);
+                if (!have_x) load_x(xcur, xg);
                 WordT dg[G][RPL];                 // row words of this group (scalar registers)
 #pragma unroll
                 for (int u = 0; u < G; ++u)
 #pragma unroll
-                    for (int c = 0; c < RPL; ++c) dg[u][c] = dp[(size_t)(b + u) * dstride + c];
+                    for (int c = 0; c < RPL; ++c) dg[u][c] = dcur[(size_t)u * dstride + c];
                 WordT xn[G];
                 const bool more = b + 2 * G <= B;
-                if (more) load_x(b + G, xn);      // next group's column words in flight meanwhile
+                if (more) load_x(xcur + (size_t)G * xstride, xn);    // next group in flight meanwhile
                 uint32_t n[G][RPL], m[G][RPL];
 #pragma unroll
                 for (int u = 0; u < G; ++u) count(xg[u], dg[u], n[u], m[u]);
@@ -500,25 +509,30 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                         flush(c);
                     }
                     b += G;
-                    xb = -1;
+                    xcur += (size_t)G * xstride;
+                    dcur += (size_t)G * dstride;
+                    have_x = more;
                     if (more) {
 #pragma unroll
                         for (int u = 0; u < G; ++u) xg[u] = xn[u];
-                        xb = b;
                     }
                 } else {                          // a large count somewhere: one sample at a time
                     append_slow(n[0], m[0]);
                     b += 1;
-                    xb = -1;
+                    xcur += xstride;
+                    dcur += dstride;
+                    have_x = false;
                 }
             } else {                              // fewer than G samples left
                 WordT dv[RPL];
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) dv[c] = dp[(size_t)b * dstride + c];
+                for (int c = 0; c < RPL; ++c) dv[c] = dcur[c];
                 uint32_t n1[RPL], m1[RPL];
-                count(xp[(size_t)b * xstride], dv, n1, m1);
+                count(*xcur, dv, n1, m1);
                 append_slow(n1, m1);
                 b += 1;
+                xcur += xstride;
+                dcur += dstride;
             }
             bool nearly_full = false;
 #pragma unroll

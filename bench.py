@@ -18,22 +18,26 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# ---- roofline model of the cell-update kernel ("Roofline") -------------------
-# Peak plain vector-ALU issue of the chip: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.
-PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
-# Algorithmic issue slots (full-rate instruction = 1 slot, quarter-rate instruction = 4 slots).
-#   per (cell, sample), 64-bit words: 2 AND + 2 BCNT + 1 XOR (direction) + 1 compare     = 6
-#   per (cell, sample), 32-bit words: 1 AND + 1 BCNT + 1 XOR + 1 compare                 = 4
+# ---- roofline model of the cell-update kernel (derivation in DESIGN.md, "Roofline") ---------
+# The kernel is bound by plain vector-ALU issue.  Peak = one lane-op per lane and clock:
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz (the rate of v_fma_f32, i.e. half the 157.3 TFLOP/s
+# packed-fp32 figure).  Algorithmic work = the minimal ISA instruction stream of the method,
+# one lane-op per instruction and lane:
+#   per (cell, sample), 64-bit words: 2 AND + 2 BCNT + 1 XOR (direction) + 1 to record  = 6
+#   per (cell, sample), 32-bit words: 1 AND + 1 BCNT + 1 XOR + 1                       = 4
 #   per applied pulse with pulse-to-pulse noise:
-#       1/4 Philox4x32-10 block  (20 quarter-rate 32x32->64 multiplies + 20 XOR3)/4      = 25
-#       1/2 Box-Muller pair      (4 transcendentals x 4 + 10 full-rate)/2                = 13
+#       1/4 Philox4x32-10 block  (20 v_mad_u64_u32 + 20 three-input XOR) / 4           = 10
+#       1/2 Box-Muller pair      (2 shift, add, 2 cvt, 5 mul, log, sqrt, sin, cos) / 2 = 7
 #       device step: ConstantStep 4 (select, noise fma, w fma, clamp); LinearStep/SoftBounds 8
+#       (two selects, slope fma, max, mul, noise fma, w fma, clamp)
+PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 C_CS = {8: 6.0, 4: 4.0}
-C_PULSE_NOISE = 25.0 + 13.0
+C_PULSE_NOISE = 10.0 + 7.0
 C_STEP = {0: 4.0, 1: 8.0, 2: 8.0}
-# HBM bytes of one headline call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (profiles/): filled in once measured, None otherwise.
-MEASURED_TRAFFIC_BYTES = None
+# HBM-side bytes of one headline call of the cell-update kernel, from rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE (profiles/cell_update_cfg5_counters.md; FETCH_SIZE scaled by the
+# factor a plain copy of known size gives).  None for other workloads.
+MEASURED_TRAFFIC_BYTES = {"cfg5_4096x4096_linearstep": 635.0e6}
 
 
 def algorithmic_lane_ops(w, pulses_per_call):
@@ -153,7 +157,7 @@ def main():
             "peak": PEAK_LANE_OPS / 1e12,
             "unit": "Tlane-op/s",
             "frac": achieved / PEAK_LANE_OPS,
-            "traffic": MEASURED_TRAFFIC_BYTES,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
             "kernel_ms": cell_ms,
             "words_ms": ms_words / max(calls, 1),
             "algorithmic_lane_ops_per_launch": ops,

@@ -39,6 +39,18 @@ def build(force: bool = True, verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+def build_valu_rates() -> str:
+    """The instruction issue-rate microbenchmark (measurement support, not part of the library)."""
+    out = os.path.join(HERE, "valu_rates")
+    cmd = [hipcc(), "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", out, os.path.join(CSRC, "valu_rates.hip")]
+    subprocess.run(cmd, check=True)
+    return out
+
+
 if __name__ == "__main__":
-    build(force=True, verbose=True, extra=sys.argv[1:])
-    print(LIB)
+    if len(sys.argv) > 1 and sys.argv[1] == "valu_rates":
+        print(build_valu_rates())
+    else:
+        build(force=True, verbose=True, extra=sys.argv[1:])
+        print(LIB)

@@ -354,16 +354,18 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         cv[c] = ((i0 + c) < R) && (j < C);
         const size_t k = cv[c] ? ((size_t)(i0 + c) * C + j) : 0;
         cellid[c] = (uint32_t)k;
-        w[c] = W[k];
-        s_up[c] = p_dw_up[k];
-        s_dn_neg[c] = -p_dw_down[k];
-        bmax[c] = p_b_max[k];
-        bmin[c] = p_b_min[k];
+        // weights and planes are touched once per call: stream them past the L2 so that the
+        // pulse words, which every tile of a super-tile re-reads, stay resident
+        w[c] = __builtin_nontemporal_load(W + k);
+        s_up[c] = __builtin_nontemporal_load(p_dw_up + k);
+        s_dn_neg[c] = -__builtin_nontemporal_load(p_dw_down + k);
+        bmax[c] = __builtin_nontemporal_load(p_b_max + k);
+        bmin[c] = __builtin_nontemporal_load(p_b_min + k);
         sl_up[c] = 0.0f;
         sl_dn[c] = 0.0f;
         if (KIND == kLinearStep) {
-            sl_up[c] = p_slope_up[k];
-            sl_dn[c] = p_slope_down[k];
+            sl_up[c] = __builtin_nontemporal_load(p_slope_up + k);
+            sl_dn[c] = __builtin_nontemporal_load(p_slope_down + k);
         } else if (KIND == kSoftBounds) {
             sl_up[c] = (bmax[c] != 0.0f) ? 1.0f / bmax[c] : 0.0f;
             sl_dn[c] = (bmin[c] != 0.0f) ? 1.0f / bmin[c] : 0.0f;
@@ -547,7 +549,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 #pragma unroll
     for (int c = 0; c < RPL; ++c) {
         if (cv[c]) {
-            W[(size_t)(i0 + c) * C + j] = w[c];
+            __builtin_nontemporal_store(w[c], W + (size_t)(i0 + c) * C + j);
             pulses += q[c];
         }
     }

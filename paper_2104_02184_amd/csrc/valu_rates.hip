@@ -1,0 +1,160 @@
+// Issue-rate microbenchmark for single vector-ALU instructions on gfx950.
+//
+// Each kernel runs eight independent dependency chains of one instruction, 4096 iterations,
+// from 2048 workgroups of 256 lanes (8 waves per SIMD), timed with HIP events.  The result is
+// the sustained rate in lane-ops per second, which calibrates the ALU roofline of the
+// cell-update kernel: v_fma_f32 defines the nominal rate (256 CUs x 64 lanes x 2.4 GHz),
+// transcendentals run at about half of it, simple two-operand integer ops faster.
+// Build: python -m paper_2104_02184_amd.build valu_rates ; run: paper_2104_02184_amd/valu_rates
+#include <hip/hip_runtime.h>
+#include <cstdio>
+#include <cstdint>
+#define ITERS 4096
+#define CHK(x) do{hipError_t e=(x); if(e!=hipSuccess){printf("err %s line %d\n", hipGetErrorString(e), __LINE__); return 1;}}while(0)
+
+#define KERNEL(NAME, ASMSTR, CONSTRAINT_T)                                                 \
+__global__ void __launch_bounds__(256) NAME(uint32_t* out, uint32_t seed) {                \
+    CONSTRAINT_T a0 = (CONSTRAINT_T)(threadIdx.x + seed), a1 = a0 + 1, a2 = a0 + 2, a3 = a0 + 3,           \
+                 a4 = a0 + 4, a5 = a0 + 5, a6 = a0 + 6, a7 = a0 + 7;                     \
+    CONSTRAINT_T b = (CONSTRAINT_T)(seed | 3);                                                              \
+    for (int i = 0; i < ITERS; ++i) {                                                      \
+        asm volatile(ASMSTR : "+v"(a0) : "v"(b));                                        \
+        asm volatile(ASMSTR : "+v"(a1) : "v"(b));                                        \
+        asm volatile(ASMSTR : "+v"(a2) : "v"(b));                                        \
+        asm volatile(ASMSTR : "+v"(a3) : "v"(b));                                        \
+        asm volatile(ASMSTR : "+v"(a4) : "v"(b));                                        \
+        asm volatile(ASMSTR : "+v"(a5) : "v"(b));                                        \
+        asm volatile(ASMSTR : "+v"(a6) : "v"(b));                                        \
+        asm volatile(ASMSTR : "+v"(a7) : "v"(b));                                        \
+    }                                                                                      \
+    CONSTRAINT_T s = a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7;                                \
+    if (s == (CONSTRAINT_T)12345) out[0] = 1;                                              \
+}
+
+KERNEL(k_and, "v_and_b32 %0, %0, %1", uint32_t)
+KERNEL(k_add, "v_add_u32 %0, %0, %1", uint32_t)
+KERNEL(k_bcnt, "v_bcnt_u32_b32 %0, %1, %0", uint32_t)
+KERNEL(k_mul_lo, "v_mul_lo_u32 %0, %0, %1", uint32_t)
+KERNEL(k_mul_hi, "v_mul_hi_u32 %0, %0, %1", uint32_t)
+KERNEL(k_mul24, "v_mul_u32_u24 %0, %0, %1", uint32_t)
+KERNEL(k_bitop3, "v_bitop3_b32 %0, %0, %1, %1 bitop3:0x96", uint32_t)
+KERNEL(k_cndmask, "v_cndmask_b32 %0, %0, %1, vcc", uint32_t)
+KERNEL(k_bfi, "v_bfi_b32 %0, %1, %0, %1", uint32_t)
+KERNEL(k_fma, "v_fma_f32 %0, %0, %1, %1", float)
+KERNEL(k_mulf, "v_mul_f32 %0, %0, %1", float)
+KERNEL(k_log, "v_log_f32 %0, %0", float)
+KERNEL(k_sin, "v_sin_f32 %0, %0", float)
+KERNEL(k_sqrt, "v_sqrt_f32 %0, %0", float)
+KERNEL(k_rcp, "v_rcp_f32 %0, %0", float)
+KERNEL(k_cvt, "v_cvt_f32_u32 %0, %0", uint32_t)
+KERNEL(k_med3, "v_med3_f32 %0, %0, %1, %1", float)
+KERNEL(k_lshr, "v_lshrrev_b32 %0, 1, %0", uint32_t)
+KERNEL(k_cmp, "v_cmp_ne_u32 vcc, %0, %1", uint32_t)
+KERNEL(k_addc, "v_addc_co_u32 %0, vcc, %0, %1, vcc", uint32_t)
+
+
+KERNEL(k_bfm, "v_bfm_b32 %0, %0, %1", uint32_t)
+KERNEL(k_andor, "v_and_or_b32 %0, %0, %1, %1", uint32_t)
+KERNEL(k_bfei, "v_bfe_i32 %0, %0, 3, 1", uint32_t)
+KERNEL(k_lshladd, "v_lshl_add_u32 %0, %0, 2, %1", uint32_t)
+KERNEL(k_max3, "v_max3_u32 %0, %0, %1, %1", uint32_t)
+KERNEL(k_ashr, "v_ashrrev_i32 %0, 31, %0", uint32_t)
+KERNEL(k_xor, "v_xor_b32 %0, %0, %1", uint32_t)
+KERNEL(k_or, "v_or_b32 %0, %0, %1", uint32_t)
+KERNEL(k_sub, "v_sub_u32 %0, %0, %1", uint32_t)
+KERNEL(k_maxf, "v_max_f32 %0, %0, %1", float)
+KERNEL(k_cmpgt, "v_cmp_gt_i32 vcc, %0, %1", uint32_t)
+KERNEL(k_cnd64, "v_cndmask_b32_e64 %0, %0, %1, s[8:9]", uint32_t)
+KERNEL(k_alignbit, "v_alignbit_b32 %0, %0, %1, %1", uint32_t)
+KERNEL(k_logfma, "v_log_f32 %0, %0\n v_fma_f32 %1, %1, %1, %1", float)
+KERNEL(k_logfma2, "v_log_f32 %0, %0\n v_fma_f32 %1, %1, %1, %1\n v_fma_f32 %1, %1, %1, %1", float)
+KERNEL(k_logand2, "v_log_f32 %0, %0\n v_and_b32 %1, %1, %1\n v_and_b32 %1, %1, %1", float)
+__global__ void __launch_bounds__(256) k_lshl64(uint32_t* out, uint32_t seed) {
+    uint64_t a0 = threadIdx.x + seed, a1 = a0 + 1, a2 = a0 + 2, a3 = a0 + 3, a4 = a0+4, a5=a0+5, a6=a0+6, a7=a0+7;
+    uint32_t b = seed & 3;
+    for (int i = 0; i < ITERS; ++i) {
+        asm volatile("v_lshlrev_b64 %0, %1, %0" : "+v"(a0) : "v"(b));
+        asm volatile("v_lshlrev_b64 %0, %1, %0" : "+v"(a1) : "v"(b));
+        asm volatile("v_lshlrev_b64 %0, %1, %0" : "+v"(a2) : "v"(b));
+        asm volatile("v_lshlrev_b64 %0, %1, %0" : "+v"(a3) : "v"(b));
+        asm volatile("v_lshlrev_b64 %0, %1, %0" : "+v"(a4) : "v"(b));
+        asm volatile("v_lshlrev_b64 %0, %1, %0" : "+v"(a5) : "v"(b));
+        asm volatile("v_lshlrev_b64 %0, %1, %0" : "+v"(a6) : "v"(b));
+        asm volatile("v_lshlrev_b64 %0, %1, %0" : "+v"(a7) : "v"(b));
+    }
+    uint64_t s = a0+a1+a2+a3+a4+a5+a6+a7;
+    if (s == 12345) out[0] = 1;
+}
+__global__ void __launch_bounds__(256) k_mad64(uint32_t* out, uint32_t seed) {
+    uint64_t a0 = threadIdx.x + seed, a1 = a0 + 1, a2 = a0 + 2, a3 = a0 + 3, a4 = a0+4, a5=a0+5, a6=a0+6, a7=a0+7;
+    uint32_t b = seed | 3;
+    for (int i = 0; i < ITERS; ++i) {
+        asm volatile("v_mad_u64_u32 %0, vcc, %1, %1, %0" : "+v"(a0) : "v"(b) : "vcc");
+        asm volatile("v_mad_u64_u32 %0, vcc, %1, %1, %0" : "+v"(a1) : "v"(b) : "vcc");
+        asm volatile("v_mad_u64_u32 %0, vcc, %1, %1, %0" : "+v"(a2) : "v"(b) : "vcc");
+        asm volatile("v_mad_u64_u32 %0, vcc, %1, %1, %0" : "+v"(a3) : "v"(b) : "vcc");
+        asm volatile("v_mad_u64_u32 %0, vcc, %1, %1, %0" : "+v"(a4) : "v"(b) : "vcc");
+        asm volatile("v_mad_u64_u32 %0, vcc, %1, %1, %0" : "+v"(a5) : "v"(b) : "vcc");
+        asm volatile("v_mad_u64_u32 %0, vcc, %1, %1, %0" : "+v"(a6) : "v"(b) : "vcc");
+        asm volatile("v_mad_u64_u32 %0, vcc, %1, %1, %0" : "+v"(a7) : "v"(b) : "vcc");
+    }
+    uint64_t s = a0+a1+a2+a3+a4+a5+a6+a7;
+    if (s == 12345) out[0] = 1;
+}
+// mad64 with a zero addend (as the Philox round uses it): "v_mad_u64_u32 d, vcc, a, b, 0"
+__global__ void __launch_bounds__(256) k_mad64z(uint32_t* out, uint32_t seed) {
+    uint32_t x0 = threadIdx.x + seed, x1 = x0+1, x2=x0+2, x3=x0+3, x4=x0+4,x5=x0+5,x6=x0+6,x7=x0+7;
+    uint32_t b = seed | 3;
+    for (int i = 0; i < ITERS; ++i) {
+        uint64_t t;
+#define ONE(X) asm volatile("v_mad_u64_u32 %0, vcc, %1, %2, 0" : "=v"(t) : "v"(X), "v"(b) : "vcc"); X = (uint32_t)(t >> 32) ^ (uint32_t)t;
+        ONE(x0) ONE(x1) ONE(x2) ONE(x3) ONE(x4) ONE(x5) ONE(x6) ONE(x7)
+    }
+    uint32_t s = x0+x1+x2+x3+x4+x5+x6+x7;
+    if (s == 12345) out[0] = 1;
+}
+__global__ void __launch_bounds__(256) k_ldsw8(uint32_t* out, uint32_t seed) {
+    __shared__ unsigned char buf[256*68];
+    uint32_t a = threadIdx.x * 68;
+    for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { asm volatile("ds_write_b8 %0, %1 offset:%2" :: "v"(a), "v"(seed), "n"(u)); }
+    }
+    __syncthreads();
+    if (buf[threadIdx.x*68] == 77 && seed == 99999) out[0] = 1;
+}
+
+template <typename K> int run(const char* name, K kern, double ops_per_thread_iter, uint32_t* out) {
+    const int blocks = 256 * 8, threads = 256;  // 8 WG/CU -> 8 waves per SIMD
+    hipEvent_t e0, e1; CHK(hipEventCreate(&e0)); CHK(hipEventCreate(&e1));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, out, 1u);
+    CHK(hipDeviceSynchronize());
+    CHK(hipEventRecord(e0));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, out, 1u);
+    CHK(hipEventRecord(e1)); CHK(hipEventSynchronize(e1));
+    float ms; CHK(hipEventElapsedTime(&ms, e0, e1));
+    double ops = (double)blocks * threads * ITERS * ops_per_thread_iter;
+    printf("%-10s %8.3f ms  %8.2f Tlane-op/s  (%.3f of 39.3)\n", name, ms, ops / ms / 1e9, ops / ms / 1e9 / 39.32);
+    fflush(stdout);
+    return 0;
+}
+int main() {
+    uint32_t* out; CHK(hipMalloc(&out, 64));
+    hipDeviceProp_t p; CHK(hipGetDeviceProperties(&p, 0));
+    printf("%s CUs=%d clock=%d kHz lds/block=%zu\n", p.name, p.multiProcessorCount, p.clockRate, p.sharedMemPerBlock);
+    run("v_and", k_and, 8, out); run("v_add", k_add, 8, out); run("v_bcnt", k_bcnt, 8, out);
+    run("v_mul_lo", k_mul_lo, 8, out); run("v_mul_hi", k_mul_hi, 8, out); run("v_mul24", k_mul24, 8, out);
+    run("v_mad64", k_mad64, 8, out); run("v_mad64z+2", k_mad64z, 8, out);
+    run("v_bitop3", k_bitop3, 8, out); run("v_cndmask", k_cndmask, 8, out); run("v_bfi", k_bfi, 8, out);
+    run("v_fma", k_fma, 8, out); run("v_mul_f32", k_mulf, 8, out); run("v_med3", k_med3, 8, out);
+    run("v_log", k_log, 8, out); run("v_sin", k_sin, 8, out); run("v_sqrt", k_sqrt, 8, out); run("v_rcp", k_rcp, 8, out);
+    run("v_cvt", k_cvt, 8, out); run("v_lshr", k_lshr, 8, out); run("v_cmp", k_cmp, 8, out); run("v_addc", k_addc, 8, out);
+    run("ds_write8", k_ldsw8, 8, out);
+    run("v_bfm", k_bfm, 8, out); run("v_and_or", k_andor, 8, out); run("v_bfe_i32", k_bfei, 8, out);
+    run("v_lshl_add", k_lshladd, 8, out); run("v_max3_u32", k_max3, 8, out); run("v_ashr", k_ashr, 8, out);
+    run("v_xor", k_xor, 8, out); run("v_or", k_or, 8, out); run("v_sub", k_sub, 8, out); run("v_max_f32", k_maxf, 8, out);
+    run("v_cmp_gt", k_cmpgt, 8, out); run("v_cnd_e64", k_cnd64, 8, out); run("v_alignbit", k_alignbit, 8, out);
+    run("v_lshl_b64", k_lshl64, 8, out);
+    run("log+fma", k_logfma, 16, out); run("log+2fma", k_logfma2, 24, out); run("log+2and", k_logand2, 24, out);
+    return 0;
+}

@@ -199,9 +199,8 @@ int choose_rpl(const aht_tile* t)
     const int forced = env_int("AHT_RPL", 0);
     if (forced == 1 || forced == 2 || forced == 4) return forced;
     const size_t cells = (size_t)t->rows * t->cols;
-    const size_t want_waves = 8192;
-    if (cells / (64 * 4) >= want_waves) return 4;
-    if (cells / (64 * 2) >= want_waves) return 2;
+    if (cells / (64 * 4) >= 16384) return 4;      // measured: 4 rows per lane pay from ~4 M cells on
+    if (cells / (64 * 2) >= 2048) return 2;
     return 1;
 }
 
@@ -212,6 +211,7 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s)
     // stream storage per cell: 12 words hold 320 pulses before an early drain is needed
     int qwords = env_int("AHT_QWORDS", 0);
     if (qwords < 5 || qwords > 160) qwords = 12;
+    while (qwords > 5 && (size_t)4 * rpl * 64 * qwords * 4 > 160 * 1024) --qwords;   // LDS of one CU
     CellPtrs p{};
     p.W = t->W;
     p.dw_up = t->planes[AHT_PLANE_DW_UP];

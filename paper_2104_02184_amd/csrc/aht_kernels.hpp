@@ -10,7 +10,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "aht_rng.hpp"
+
+#ifndef AHT_GROUP
+#define AHT_GROUP 4
+#endif
 
 namespace aht {
 
@@ -317,7 +323,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
     constexpr int kSign = WordTraits<WordT>::kSignBit;
     constexpr WordT kBits = (WordT)(~((WordT)1 << kSign));
-    constexpr int G = 4;                          // samples per group (one stream flush per group)
+    // samples per group (one stream flush per group); sparse 32-bit words take longer groups
+    constexpr int G = (sizeof(WordT) == 4) ? 2 * AHT_GROUP : AHT_GROUP;
     constexpr uint32_t kWordStride = 64 * 4;      // bytes between consecutive words of one stream
 
     // XCD-aware tile mapping.  Consecutive workgroup ids go round-robin to the 8 XCDs, so each
@@ -398,7 +405,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     // ---- phase B: drain the streams ---------------------------------------------------
     auto drain = [&]() __attribute__((always_inline)) {
         uint32_t endpos[RPL], start[RPL], blk0[RPL], D[RPL];
-        uint32_t longest = 0;
+        int row_iters[RPL];                       // wave-uniform: iterations the lanes' c-th cells need
+        int niter = 0;
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
             lds_store_u32(wp[c], acc_lo[c] << ((32u - fill[c]) & 31u));      // left-aligned partial word
@@ -406,30 +414,50 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             start[c] = q[c] & 31u;
             blk0[c] = (q[c] >> 5) << 3;
             D[c] = 0;
-            longest = longest > endpos[c] ? longest : endpos[c];
+            row_iters[c] = (int)((wave_max_u32(endpos[c]) + 3u) >> 2);
+            niter = niter > row_iters[c] ? niter : row_iters[c];
         }
-        const int niter = (int)((wave_max_u32(longest) + 3u) >> 2);
-        for (int i = 0; i < niter; ++i) {
+        // Iterations in which every cell of the wave has four valid pulses need no masks: from the
+        // last stream start (rounded up) to the first stream end (rounded down).
+        uint32_t first_end = 0xFFFFFFFFu, last_start = 0;
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) {
+            first_end = first_end < endpos[c] ? first_end : endpos[c];
+            last_start = last_start > start[c] ? last_start : start[c];
+        }
+        const int plain_begin = (int)((wave_max_u32(last_start) + 3u) >> 2);
+        const int plain_end = (int)(~wave_max_u32(~first_end) >> 2);          // wave minimum, rounded down
+        auto iteration = [&](int i, auto masked) __attribute__((always_inline)) {
             if ((i & 7) == 0) {
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) D[c] = lds_load_u32(qb[c] + (uint32_t)(i >> 3) * kWordStride);
             }
 #pragma unroll
             for (int c = 0; c < RPL; ++c) {
+                if (decltype(masked)::value && i >= row_iters[c]) continue;   // all 64 cells of this row are done
                 float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (NOISE) gauss4_fast(a.k0, a.k1, cellid[c], blk0[c] + (uint32_t)i, a.t, kTagC2C, z);
                 const int lo = (int)start[c] - 4 * i, hi = (int)endpos[c] - 4 * i;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const bool act = (k >= lo) & (k < hi);
                     const uint32_t dmask = (uint32_t)__builtin_amdgcn_sbfe((int)D[c], 31 - k, 1);
                     const float wn = device_step<KIND, NOISE>(w[c], dmask, z[k], a.c2c, s_up[c], s_dn_neg[c],
                                                               bmax[c], bmin[c], sl_up[c], sl_dn[c]);
-                    w[c] = act ? wn : w[c];
+                    if (decltype(masked)::value) {
+                        const bool act = (k >= lo) & (k < hi);
+                        w[c] = act ? wn : w[c];
+                    } else {
+                        w[c] = wn;
+                    }
                 }
                 D[c] <<= 4;
             }
-        }
+        };
+        int i = 0;
+        const int head_end = plain_begin < niter ? plain_begin : niter;
+        for (; i < head_end; ++i) iteration(i, std::true_type{});
+        for (; i < plain_end; ++i) iteration(i, std::false_type{});
+        for (; i < niter; ++i) iteration(i, std::true_type{});
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31
             q[c] += endpos[c] - start[c];
@@ -442,7 +470,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 
     // ---- phase A ----------------------------------------------------------------------
     const WordT* __restrict__ xcur = xp;          // column words of sample b
-    const WordT* __restrict__ dcur = dp;          // row words of sample b (wave-uniform)
+    size_t doff = (size_t)i0;                     // dw[doff + c]: row words of sample b (wave-uniform,
+                                                  // indexed off the kernel argument so that they stay scalar loads)
     auto load_x = [&](const WordT* __restrict__ p0, WordT (&xg)[G]) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < G; ++u) xg[u] = p0[(size_t)u * xstride];
@@ -493,7 +522,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 #pragma unroll
                 for (int u = 0; u < G; ++u)
 #pragma unroll
-                    for (int c = 0; c < RPL; ++c) dg[u][c] = dcur[(size_t)u * dstride + c];
+                    for (int c = 0; c < RPL; ++c) dg[u][c] = dw[doff + (size_t)u * dstride + c];
                 WordT xn[G];
                 const bool more = b + 2 * G <= B;
                 if (more) load_x(xcur + (size_t)G * xstride, xn);    // next group in flight meanwhile
@@ -502,7 +531,12 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                 for (int u = 0; u < G; ++u) count(xg[u], dg[u], n[u], m[u]);
                 bool big = false;
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) big |= (n[0][c] + n[1][c] + n[2][c] + n[3][c]) > 31u;
+                for (int c = 0; c < RPL; ++c) {
+                    uint32_t sum = 0;
+#pragma unroll
+                    for (int u = 0; u < G; ++u) sum += n[u][c];
+                    big |= sum > 31u;
+                }
                 if (!__any(big)) {                // usual case: the group adds < 32 bits per cell
 #pragma unroll
                     for (int c = 0; c < RPL; ++c) {
@@ -512,29 +546,38 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                     }
                     b += G;
                     xcur += (size_t)G * xstride;
-                    dcur += (size_t)G * dstride;
+                    doff += (size_t)G * dstride;
                     have_x = more;
                     if (more) {
 #pragma unroll
                         for (int u = 0; u < G; ++u) xg[u] = xn[u];
                     }
-                } else {                          // a large count somewhere: one sample at a time
-                    append_slow(n[0], m[0]);
-                    b += 1;
-                    xcur += xstride;
-                    dcur += dstride;
+                } else {                          // a large count somewhere: sample by sample while room lasts
                     have_x = false;
+#pragma unroll
+                    for (int u = 0; u < G; ++u) {
+                        append_slow(n[u], m[u]);
+                        b += 1;
+                        xcur += xstride;
+                        doff += dstride;
+                        if (u + 1 < G) {
+                            bool nf = false;
+#pragma unroll
+                            for (int c = 0; c < RPL; ++c) nf |= (wp[c] - qb[c]) > last_ok;
+                            if (__any(nf)) break;
+                        }
+                    }
                 }
             } else {                              // fewer than G samples left
                 WordT dv[RPL];
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) dv[c] = dcur[c];
+                for (int c = 0; c < RPL; ++c) dv[c] = dw[doff + c];
                 uint32_t n1[RPL], m1[RPL];
                 count(*xcur, dv, n1, m1);
                 append_slow(n1, m1);
                 b += 1;
                 xcur += xstride;
-                dcur += dstride;
+                doff += dstride;
             }
             bool nearly_full = false;
 #pragma unroll

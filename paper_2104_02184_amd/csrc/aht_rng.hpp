@@ -51,7 +51,7 @@ __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c
 // v_sin_f32 / v_cos_f32, whose argument is in revolutions -- exactly u2.
 __device__ __forceinline__ void box_muller_fast(uint32_t ra, uint32_t rb, float& z_even, float& z_odd)
 {
-    const float u1 = (float)((ra >> 8) + 1u) * 0x1p-24f;             // (0, 1], exact
+    const float u1 = fmaf((float)(ra >> 8), 0x1p-24f, 0x1p-24f);     // ((ra>>8)+1) 2^-24 in (0, 1], exact
     const float u2 = (float)(rb >> 8) * 0x1p-24f;                    // [0, 1), exact
     const float rad2 = __builtin_amdgcn_logf(u1) * -1.3862943611198906f;  // -2 ln u1 = -2 ln2 log2 u1
     const float rad = __builtin_amdgcn_sqrtf(rad2);

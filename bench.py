@@ -74,6 +74,40 @@ def cpu_baseline(w, target_rows):
     }
 
 
+def bench_decay_diffuse(args):
+    """Side benchmark: the once-per-mini-batch decay + diffusion pass on the headline tile
+    (HBM bound: 20 bytes read and 4 written per cell)."""
+    import torch
+
+    import paper_2104_02184_amd as aht
+    from paper_2104_02184_amd import workloads as wl
+
+    w = wl.WORKLOADS[args.workload or wl.HEADLINE]
+    tile = aht.Tile(w.rows, w.cols, aht.DeviceParams(**w.device), w.bl, w.update_management, w.seed)
+    tile.set_temporal(decay_rate=0.001, decay_rate_dtod=0.1, diffusion=0.0005, diffusion_dtod=0.3)
+    tile.set_weights(torch.from_numpy(wl.initial_weights(w)).cuda())
+    for _ in range(args.warmup):
+        tile.decay_diffuse()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        tile.decay_diffuse()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    tile.close()
+    cells = w.rows * w.cols
+    bytes_alg = cells * 24.0
+    print(json.dumps({
+        "metric": "Gcell/s of decay_diffuse", "value": cells / (ms * 1e-3) / 1e9, "unit": "Gcell/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "f32",
+        "data": "synthetic", "config": {"workload": w.name + " decay_diffuse"},
+        "roofline": {"bound": "hbm", "achieved": bytes_alg / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                     "frac": bytes_alg / (ms * 1e-3) / 8e12, "traffic": None},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,6 +116,8 @@ def main():
     ap.add_argument("--workload", default=None, help="workload name (default: the headline one)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-rows", type=int, default=512)
+    ap.add_argument("--op", default="pulsed_update", choices=["pulsed_update", "decay_diffuse"],
+                    help="side benchmarks of other operations; the default is the headline metric")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the pulsed update of one tile runs on a single MI355X "
@@ -97,6 +133,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     aht.load_library()
+    if args.op == "decay_diffuse":
+        bench_decay_diffuse(args)
+        return
     w = wl.WORKLOADS[args.workload or wl.HEADLINE]
     K, Wm = args.steps, args.warmup
 

@@ -156,6 +156,35 @@ aht_status aht_debug_philox(const uint32_t* ctr_dev, const uint32_t* key_dev, in
 aht_status aht_debug_gauss(uint64_t seed, uint32_t index, uint32_t t, uint32_t tag, uint32_t q0,
                            int32_t n, int32_t fast, float* gauss_dev, void* stream);
 
+/* Once-per-mini-batch temporal processes with device-to-device variability (Sec. 4, last
+ * paragraph: conductance decay, reset and diffusion).  Per-cell planes are drawn at
+ * aht_set_temporal from the tile's seed:
+ *   decay_ij = clamp(decay_rate (1 + decay_rate_dtod g), 0, 1),  diffusion_ij = diffusion |1 + diffusion_dtod g|,
+ *   reset_ij = reset + reset_dtod g.
+ * aht_decay_diffuse: w <- clamp(w (1 - decay_ij) + diffusion_ij xi, b_min, b_max) for every cell,
+ *   xi fresh per cell and temporal step; uses the temporal step counter, then increments it.
+ * aht_reset_columns: w <- clamp(reset_ij + reset_std xi, b_min, b_max) for the cells of columns
+ *   [c0, c0 + ncols) (clipped to the tile); uses the current temporal step, does not advance it.
+ * aht_set_temporal allocates three planes and may synchronise; the other calls are asynchronous
+ * on `stream`.  Errors: INVALID_ARG (null, negative or non-finite rates, c0 < 0, ncols < 0,
+ * processes used before aht_set_temporal), OOM, DEVICE. */
+typedef struct {
+    float decay_rate;       /* fraction of the weight lost per mini-batch, 0..1 */
+    float decay_rate_dtod;  /* relative std */
+    float diffusion;        /* std of the per-mini-batch Gaussian step */
+    float diffusion_dtod;   /* relative std */
+    float reset;            /* mean reset value */
+    float reset_dtod;       /* absolute std of the per-cell reset value */
+    float reset_std;        /* std of the reset noise of every reset event */
+} aht_temporal_params;
+enum { AHT_TPLANE_DECAY = 0, AHT_TPLANE_DIFFUSION = 1, AHT_TPLANE_RESET = 2, AHT_NUM_TPLANES = 3 };
+aht_status aht_set_temporal(aht_tile* tile, const aht_temporal_params* params);
+aht_status aht_decay_diffuse(aht_tile* tile, void* stream);
+aht_status aht_reset_columns(aht_tile* tile, int32_t c0, int32_t ncols, void* stream);
+aht_status aht_get_temporal_plane(const aht_tile* tile, int32_t which, float* dev_out, void* stream);
+aht_status aht_get_temporal_step(const aht_tile* tile, uint32_t* step);
+aht_status aht_set_temporal_step(aht_tile* tile, uint32_t step);
+
 /* Measurement hook.  While enabled, every aht_pulsed_update records HIP events on its stream
  * before the pulse-train kernels, between them and the cell-update kernel, and after it.
  * aht_profile_read waits for the recorded events, returns the summed durations in

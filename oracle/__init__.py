@@ -83,6 +83,12 @@ def _declare(L):
     L.orc_pulsed_update.argtypes = ([_f32p] * 7 + [_i, _f, _f, _i, _i, _f32p, _f32p, _i, _i, _i, _f,
                                                    _u64, _u32, _i64p, ctypes.c_int64])
     L.orc_pulsed_update.restype = ctypes.c_int64
+    L.orc_temporal_planes.argtypes = [_f] * 6 + [_u64, _i, _i] + [_f32p] * 3
+    L.orc_temporal_planes.restype = None
+    L.orc_decay_diffuse.argtypes = [_f32p] * 5 + [_u64, _u32, _i, _i]
+    L.orc_decay_diffuse.restype = None
+    L.orc_reset_columns.argtypes = [_f32p, _f32p, _f, _f32p, _f32p, _u64, _u32, _i, _i, _i, _i]
+    L.orc_reset_columns.restype = None
     L.orc_num_threads.argtypes = []
     L.orc_num_threads.restype = _i
     L.orc_set_num_threads.argtypes = [_i]
@@ -233,6 +239,44 @@ def pulsed_update(W, planes, p: DeviceParams, BL, update_management, x, d, lr, s
     return int(lib().orc_pulsed_update(_p(W, _f32p), *ptrs, p.kind, p.dw_min_std, p.dw_min, BL,
                                        int(update_management), _p(x, _f32p), _p(d, _f32p), B, R, C,
                                        lr, seed, t, cptr, nc))
+
+
+@dataclass
+class TemporalParams:
+    """Once-per-mini-batch processes: decay toward 0, diffusion, reset (normalised units)."""
+    decay_rate: float = 0.0
+    decay_rate_dtod: float = 0.0
+    diffusion: float = 0.0
+    diffusion_dtod: float = 0.0
+    reset: float = 0.0
+    reset_dtod: float = 0.0
+    reset_std: float = 0.0
+
+
+TEMPORAL_PLANE_NAMES = ("decay", "diffusion", "reset")
+
+
+def temporal_planes(tp: TemporalParams, seed: int, R: int, C: int):
+    planes = {n: np.zeros((R, C), dtype=np.float32) for n in TEMPORAL_PLANE_NAMES}
+    lib().orc_temporal_planes(tp.decay_rate, tp.decay_rate_dtod, tp.diffusion, tp.diffusion_dtod, tp.reset,
+                              tp.reset_dtod, seed, R, C, *[_p(planes[n], _f32p) for n in TEMPORAL_PLANE_NAMES])
+    return planes
+
+
+def decay_diffuse(W, tplanes, planes, seed, tau):
+    """One application (temporal step tau) in place on W."""
+    assert W.dtype == np.float32 and W.flags.c_contiguous
+    R, C = W.shape
+    arrs = [_f32(tplanes["decay"]), _f32(tplanes["diffusion"]), _f32(planes["b_max"]), _f32(planes["b_min"])]
+    lib().orc_decay_diffuse(_p(W, _f32p), *[_p(a, _f32p) for a in arrs], seed, tau, R, C)
+
+
+def reset_columns(W, tplanes, reset_std, planes, seed, tau, c0, ncols):
+    assert W.dtype == np.float32 and W.flags.c_contiguous
+    R, C = W.shape
+    arrs = [_f32(tplanes["reset"]), _f32(planes["b_max"]), _f32(planes["b_min"])]
+    lib().orc_reset_columns(_p(W, _f32p), _p(arrs[0], _f32p), reset_std, _p(arrs[1], _f32p), _p(arrs[2], _f32p),
+                            seed, tau, R, C, c0, ncols)
 
 
 def num_threads():

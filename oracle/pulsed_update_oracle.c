@@ -383,3 +383,82 @@ void orc_gauss_fill(uint64_t seed, uint32_t index0, int n_index, uint32_t t, int
         for (int q = 0; q < nq; ++q)
             out[(size_t)k * nq + q] = orc_gauss(seed, index0 + (uint32_t)k, t, (uint32_t)q, tag);
 }
+
+/* ------------------------------------------------------------------------
+ * Temporal processes (Sec. 4 of the paper, last paragraph: conductance
+ * decay, reset and diffusion with systematic device-to-device variability,
+ * applied once per mini-batch).  The paper names them only; readings:
+ *   planes (fixed at set-up; Gaussians 6, 7, 8 of stream (cell, t=0, tag 4)):
+ *     lambda_ij = clamp(decay_rate * (1 + decay_rate_dtod*g7), 0, 1)
+ *     sdiff_ij  = diffusion * |1 + diffusion_dtod*g8|
+ *     reset_ij  = reset + reset_dtod*g9
+ *   once per mini-batch (temporal step tau):
+ *     w <- w * (1 - lambda_ij)                      (decay toward 0)
+ *     w <- w + sdiff_ij * xi,  xi = Gaussian (cell & 3) of block
+ *          (index = cell >> 2, blk = 0, t = tau, tag 5)   (four neighbours share a block)
+ *     w <- clamp(w, b_min, b_max)
+ *   reset of columns [c0, c0+n): w <- clamp(reset_ij + reset_std * xi', ...),
+ *     xi' from the same keying with tag 6.
+ * fp32 arithmetic, every operation rounded separately.
+ * ---------------------------------------------------------------------- */
+enum { ORC_TAG_DIFFUSION = 5, ORC_TAG_RESET = 6 };
+
+void orc_temporal_planes(float decay_rate, float decay_rate_dtod, float diffusion, float diffusion_dtod,
+                         float reset, float reset_dtod, uint64_t seed, int R, int C, float *lambda,
+                         float *sdiff, float *reset_plane)
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < R; ++i)
+        for (int j = 0; j < C; ++j) {
+            uint32_t cell = (uint32_t)i * (uint32_t)C + (uint32_t)j;
+            float g7 = orc_gauss(seed, cell, 0u, 6u, ORC_TAG_D2D);
+            float g8 = orc_gauss(seed, cell, 0u, 7u, ORC_TAG_D2D);
+            float g9 = orc_gauss(seed, cell, 0u, 8u, ORC_TAG_D2D);
+            float lam = decay_rate * (1.0f + decay_rate_dtod * g7);
+            lam = fminf(fmaxf(lam, 0.0f), 1.0f);
+            size_t k = (size_t)i * C + j;
+            lambda[k] = lam;
+            sdiff[k] = diffusion * fabsf(1.0f + diffusion_dtod * g8);
+            reset_plane[k] = reset + reset_dtod * g9;
+        }
+}
+
+static float temporal_gauss(uint64_t seed, uint32_t cell, uint32_t tau, uint32_t tag)
+{
+    double z[4];
+    orc_gauss_block_f64(seed, cell >> 2, tau, 0u, tag, z);
+    return (float)z[cell & 3];
+}
+
+void orc_decay_diffuse(float *W, const float *lambda, const float *sdiff, const float *b_max,
+                       const float *b_min, uint64_t seed, uint32_t tau, int R, int C)
+{
+    size_t n = (size_t)R * C;
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < (int64_t)n; ++k) {
+        float w = W[k];
+        float keep = 1.0f - lambda[k];
+        w = w * keep;
+        float xi = temporal_gauss(seed, (uint32_t)k, tau, ORC_TAG_DIFFUSION);
+        float dz = sdiff[k] * xi;
+        w = w + dz;
+        w = fmaxf(w, b_min[k]);
+        w = fminf(w, b_max[k]);
+        W[k] = w;
+    }
+}
+
+void orc_reset_columns(float *W, const float *reset_plane, float reset_std, const float *b_max,
+                       const float *b_min, uint64_t seed, uint32_t tau, int R, int C, int c0, int ncols)
+{
+    for (int i = 0; i < R; ++i)
+        for (int j = c0; j < c0 + ncols && j < C; ++j) {
+            size_t k = (size_t)i * C + j;
+            float xi = temporal_gauss(seed, (uint32_t)k, tau, ORC_TAG_RESET);
+            float dz = reset_std * xi;
+            float w = reset_plane[k] + dz;
+            w = fmaxf(w, b_min[k]);
+            w = fminf(w, b_max[k]);
+            W[k] = w;
+        }
+}

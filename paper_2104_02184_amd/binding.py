@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(HERE, "libaht.so")
 
 CONSTANT_STEP, LINEAR_STEP, SOFT_BOUNDS = 0, 1, 2
 PLANE_NAMES = ("dw_up", "dw_down", "b_max", "b_min", "slope_up", "slope_down")
+TEMPORAL_PLANE_NAMES = ("decay", "diffusion", "reset")
 
 # every symbol include/aht.h declares
 EXPORTS = (
@@ -22,6 +23,8 @@ EXPORTS = (
     "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
     "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
     "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
+    "aht_set_temporal", "aht_decay_diffuse", "aht_reset_columns", "aht_get_temporal_plane",
+    "aht_get_temporal_step", "aht_set_temporal_step",
     "aht_status_string", "aht_last_error", "aht_version",
 )
 
@@ -39,6 +42,11 @@ class aht_device_params(ctypes.Structure):
                 ("w_max", ctypes.c_float), ("w_max_dtod", ctypes.c_float), ("w_min", ctypes.c_float),
                 ("w_min_dtod", ctypes.c_float), ("gamma_up", ctypes.c_float), ("gamma_down", ctypes.c_float),
                 ("gamma_dtod", ctypes.c_float)]
+
+
+class aht_temporal_params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_float) for n in ("decay_rate", "decay_rate_dtod", "diffusion", "diffusion_dtod",
+                                               "reset", "reset_dtod", "reset_std")]
 
 
 class aht_update_params(ctypes.Structure):
@@ -77,6 +85,12 @@ def load_library() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime under the same SONAME; load it first so that the tensors
+    # torch allocates and the kernels this library launches share one runtime.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2104_02184_amd.build` "
                           "(hipcc, gfx950); there is no CPU fallback")
@@ -98,6 +112,12 @@ def load_library() -> ctypes.CDLL:
     L.aht_debug_apply_words.argtypes = [vp, vp, vp, i32, u32, vp]
     L.aht_debug_philox.argtypes = [vp, vp, i32, vp, vp]
     L.aht_debug_gauss.argtypes = [u64, u32, u32, u32, u32, i32, i32, vp, vp]
+    L.aht_set_temporal.argtypes = [vp, ctypes.POINTER(aht_temporal_params)]
+    L.aht_decay_diffuse.argtypes = [vp, vp]
+    L.aht_reset_columns.argtypes = [vp, i32, i32, vp]
+    L.aht_get_temporal_plane.argtypes = [vp, i32, vp, vp]
+    L.aht_get_temporal_step.argtypes = [vp, ctypes.POINTER(u32)]
+    L.aht_set_temporal_step.argtypes = [vp, u32]
     L.aht_profile_enable.argtypes = [vp, i32]
     L.aht_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                    ctypes.POINTER(i32)]
@@ -216,6 +236,35 @@ class Tile:
         idx = PLANE_NAMES.index(name) if isinstance(name, str) else int(name)
         _check(self._lib.aht_set_device_planes(self._h, idx, _ptr(values, torch.float32, (self.rows, self.cols)),
                                                _stream()))
+
+    # -- temporal processes ----------------------------------------------------------------
+    def set_temporal(self, decay_rate=0.0, decay_rate_dtod=0.0, diffusion=0.0, diffusion_dtod=0.0, reset=0.0,
+                     reset_dtod=0.0, reset_std=0.0):
+        p = aht_temporal_params(decay_rate, decay_rate_dtod, diffusion, diffusion_dtod, reset, reset_dtod, reset_std)
+        _check(self._lib.aht_set_temporal(self._h, ctypes.byref(p)))
+
+    def decay_diffuse(self):
+        _check(self._lib.aht_decay_diffuse(self._h, _stream()))
+
+    def reset_columns(self, c0: int, ncols: int):
+        _check(self._lib.aht_reset_columns(self._h, c0, ncols, _stream()))
+
+    def get_temporal_plane(self, name):
+        import torch
+        idx = TEMPORAL_PLANE_NAMES.index(name) if isinstance(name, str) else int(name)
+        out = torch.empty((self.rows, self.cols), dtype=torch.float32, device="cuda")
+        _check(self._lib.aht_get_temporal_plane(self._h, idx, _ptr(out, torch.float32), _stream()))
+        return out
+
+    @property
+    def temporal_step(self) -> int:
+        v = ctypes.c_uint32()
+        _check(self._lib.aht_get_temporal_step(self._h, ctypes.byref(v)))
+        return v.value
+
+    @temporal_step.setter
+    def temporal_step(self, value: int):
+        _check(self._lib.aht_set_temporal_step(self._h, ctypes.c_uint32(value)))
 
     # -- measurement hook ------------------------------------------------------------------
     def profile_enable(self, enable: bool = True):

@@ -35,6 +35,11 @@ struct aht_tile {
     double* a_d = nullptr;
     int a_cap = 0;
     unsigned long long* pulse_count = nullptr;
+    // temporal processes
+    bool has_temporal = false;
+    aht_temporal_params temporal{};
+    float* tplanes[AHT_NUM_TPLANES] = {nullptr, nullptr, nullptr};
+    uint32_t tstep = 0;
     // measurement hook: three events per recorded call
     bool profiling = false;
     std::vector<hipEvent_t> events;
@@ -348,6 +353,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     rel(t->W);
     for (auto* p : t->planes) rel(p);
     rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->pulse_count);
+    for (auto* p : t->tplanes) rel(p);
     for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
     delete t;
     if (first != hipSuccess) return hip_fail(first, "aht_tile_destroy");
@@ -404,6 +410,87 @@ aht_status aht_pulsed_update(aht_tile* t, const float* x_dev, const float* d_dev
         }
     }
     t->step += 1;
+    return AHT_OK;
+}
+
+aht_status aht_set_temporal(aht_tile* t, const aht_temporal_params* p)
+{
+    if (!t || !p) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (!(p->decay_rate >= 0.0f && p->decay_rate <= 1.0f)) return fail(AHT_ERR_INVALID_ARG, "decay_rate must be in 0..1");
+    if (!finite_nonneg(p->decay_rate_dtod) || !finite_nonneg(p->diffusion) || !finite_nonneg(p->diffusion_dtod) ||
+        !finite_nonneg(p->reset_dtod) || !finite_nonneg(p->reset_std) || !std::isfinite(p->reset))
+        return fail(AHT_ERR_INVALID_ARG, "temporal parameters must be finite, spreads >= 0");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    const size_t n = (size_t)t->rows * t->cols;
+    for (auto*& pl : t->tplanes)
+        if (!pl) AHT_HIP(hipMalloc((void**)&pl, n * sizeof(float)));
+    unsigned nb = blocks_for(n);
+    if (nb > 65536u) nb = 65536u;
+    hipLaunchKernelGGL(k_gen_temporal_planes, dim3(nb), dim3(256), 0, 0, p->decay_rate, p->decay_rate_dtod, p->diffusion,
+                       p->diffusion_dtod, p->reset, p->reset_dtod, (uint32_t)t->seed, (uint32_t)(t->seed >> 32), n,
+                       t->tplanes[0], t->tplanes[1], t->tplanes[2]);
+    AHT_HIP(hipGetLastError());
+    AHT_HIP(hipDeviceSynchronize());
+    t->temporal = *p;
+    t->has_temporal = true;
+    return AHT_OK;
+}
+
+aht_status aht_decay_diffuse(aht_tile* t, void* stream)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    if (!t->has_temporal) return fail(AHT_ERR_INVALID_ARG, "aht_set_temporal has not been called");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    const size_t n = (size_t)t->rows * t->cols;
+    hipLaunchKernelGGL(k_decay_diffuse, dim3(blocks_for((n + 3) / 4)), dim3(256), 0, (hipStream_t)stream, t->W,
+                       t->tplanes[0], t->tplanes[1], t->planes[AHT_PLANE_B_MAX], t->planes[AHT_PLANE_B_MIN], n,
+                       (uint32_t)t->seed, (uint32_t)(t->seed >> 32), t->tstep, t->temporal.diffusion > 0.0f ? 1 : 0);
+    AHT_HIP(hipGetLastError());
+    t->tstep += 1;
+    return AHT_OK;
+}
+
+aht_status aht_reset_columns(aht_tile* t, int32_t c0, int32_t ncols, void* stream)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    if (!t->has_temporal) return fail(AHT_ERR_INVALID_ARG, "aht_set_temporal has not been called");
+    if (c0 < 0 || ncols < 0) return fail(AHT_ERR_INVALID_ARG, "c0 and ncols must be >= 0");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    if (c0 >= t->cols || ncols == 0) return AHT_OK;
+    if (ncols > t->cols - c0) ncols = t->cols - c0;
+    hipLaunchKernelGGL(k_reset_columns, dim3(blocks_for((size_t)t->rows * ncols)), dim3(256), 0, (hipStream_t)stream, t->W,
+                       t->tplanes[2], t->temporal.reset_std, t->planes[AHT_PLANE_B_MAX], t->planes[AHT_PLANE_B_MIN],
+                       t->rows, t->cols, c0, ncols, (uint32_t)t->seed, (uint32_t)(t->seed >> 32), t->tstep);
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+aht_status aht_get_temporal_plane(const aht_tile* t, int32_t which, float* dev_out, void* stream)
+{
+    if (!t || !dev_out) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (which < 0 || which >= AHT_NUM_TPLANES) return fail(AHT_ERR_INVALID_ARG, "plane index %d out of range", which);
+    if (!t->has_temporal) return fail(AHT_ERR_INVALID_ARG, "aht_set_temporal has not been called");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    AHT_HIP(hipMemcpyAsync(dev_out, t->tplanes[which], (size_t)t->rows * t->cols * sizeof(float),
+                           hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return AHT_OK;
+}
+
+aht_status aht_get_temporal_step(const aht_tile* t, uint32_t* step)
+{
+    if (!t || !step) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    *step = t->tstep;
+    return AHT_OK;
+}
+
+aht_status aht_set_temporal_step(aht_tile* t, uint32_t step)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    t->tstep = step;
     return AHT_OK;
 }
 

@@ -86,6 +86,72 @@ __global__ void __launch_bounds__(256) k_derived_slope(const float* bound, float
 }
 
 // ------------------------------------------------------------------------------------------
+// Temporal processes, once per mini-batch (Sec. 4, last paragraph of the paper): decay,
+// diffusion and reset with per-cell parameters.  The planes use Gaussians 6, 7, 8 of the
+// device-to-device stream; the per-step Gaussians of four neighbouring cells share one Philox
+// block (index = cell >> 2, t = temporal step, tag 5 for diffusion, 6 for reset).
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kTagDiffusion = 5u, kTagReset = 6u;
+
+__global__ void __launch_bounds__(256)
+k_gen_temporal_planes(float decay_rate, float decay_rate_dtod, float diffusion, float diffusion_dtod, float reset,
+                      float reset_dtod, uint32_t k0, uint32_t k1, size_t n, float* decay, float* sdiff, float* rplane)
+{
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x) {
+        float g1[4], g2[4];
+        gauss4_accurate(k0, k1, (uint32_t)k, 1u, 0u, kTagD2D, g1);     // numbers 4..7
+        gauss4_accurate(k0, k1, (uint32_t)k, 2u, 0u, kTagD2D, g2);     // numbers 8..11
+        float lam = decay_rate * (1.0f + decay_rate_dtod * g1[2]);
+        lam = fminf(fmaxf(lam, 0.0f), 1.0f);
+        decay[k] = lam;
+        sdiff[k] = diffusion * fabsf(1.0f + diffusion_dtod * g1[3]);
+        rplane[k] = reset + reset_dtod * g2[0];
+    }
+}
+
+// HBM bound: 20 bytes read and 4 written per cell.  One thread per four consecutive cells.
+__global__ void __launch_bounds__(256)
+k_decay_diffuse(float* __restrict__ W, const float* __restrict__ decay, const float* __restrict__ sdiff,
+                const float* __restrict__ b_max, const float* __restrict__ b_min, size_t n, uint32_t k0,
+                uint32_t k1, uint32_t tau, int with_diffusion)
+{
+    const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t k = g * 4;
+    if (k >= n) return;
+    float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (with_diffusion) gauss4_fast(k0, k1, (uint32_t)g, 0u, tau, kTagDiffusion, z);
+    if (k + 4 <= n) {
+        float4 w = *(const float4*)(W + k);
+        const float4 la = *(const float4*)(decay + k), sd = *(const float4*)(sdiff + k);
+        const float4 hi = *(const float4*)(b_max + k), lo = *(const float4*)(b_min + k);
+        w.x = fminf(fmaxf(w.x * (1.0f - la.x) + sd.x * z[0], lo.x), hi.x);
+        w.y = fminf(fmaxf(w.y * (1.0f - la.y) + sd.y * z[1], lo.y), hi.y);
+        w.z = fminf(fmaxf(w.z * (1.0f - la.z) + sd.z * z[2], lo.z), hi.z);
+        w.w = fminf(fmaxf(w.w * (1.0f - la.w) + sd.w * z[3], lo.w), hi.w);
+        *(float4*)(W + k) = w;
+    } else {
+        for (int e = 0; e < 4 && k + e < n; ++e)
+            W[k + e] = fminf(fmaxf(W[k + e] * (1.0f - decay[k + e]) + sdiff[k + e] * z[e], b_min[k + e]), b_max[k + e]);
+    }
+}
+
+__global__ void __launch_bounds__(256)
+k_reset_columns(float* __restrict__ W, const float* __restrict__ rplane, float reset_std,
+                const float* __restrict__ b_max, const float* __restrict__ b_min, int R, int C, int c0, int ncols,
+                uint32_t k0, uint32_t k1, uint32_t tau)
+{
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (size_t)R * ncols) return;
+    const int i = (int)(t / (size_t)ncols), j = c0 + (int)(t % (size_t)ncols);
+    const size_t k = (size_t)i * C + j;
+    float z[4];
+    gauss4_fast(k0, k1, (uint32_t)(k >> 2), 0u, tau, kTagReset, z);
+    const uint32_t e = (uint32_t)k & 3u;
+    const float xi = e == 0 ? z[0] : e == 1 ? z[1] : e == 2 ? z[2] : z[3];
+    W[k] = fminf(fmaxf(rplane[k] + reset_std * xi, b_min[k]), b_max[k]);
+}
+
+// ------------------------------------------------------------------------------------------
 // Line scaling with update management: one workgroup per update vector.
 // a_x = A sqrt(m_d/m_x), a_d = A sqrt(m_x/m_d); both 0 when a maximum is 0 (sample skipped).
 // ------------------------------------------------------------------------------------------

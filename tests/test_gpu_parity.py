@@ -359,3 +359,45 @@ def test_setting_planes_overrides_the_drawn_ones():
         assert np.allclose(sb.get_plane("slope_down").cpu().numpy(), -4.0)
         with pytest.raises(aht.AhtError):
             sb.set_plane("slope_up", torch.zeros((8, 8), device="cuda"))
+
+
+def test_more_samples_than_one_grid_dimension_holds():
+    # B above 32768 makes the pulse-word kernel loop over samples inside one launch
+    R, C, B, bl = 5, 70, 40_000, 31
+    dev = dict(kind=aht.CONSTANT_STEP, dw_min=0.0005, dw_min_std=0.3, w_max=0.6, w_min=-0.6)
+    g = np.random.default_rng(7)
+    x = g.normal(size=(B, C)).astype(np.float32)
+    d = (g.normal(size=(B, R)) * 0.05).astype(np.float32)
+    oplanes = oracle.device_planes(oracle_params(dev), 11, R, C)
+    Wo = np.zeros((R, C), dtype=np.float32)
+    po = oracle.pulsed_update(Wo, oplanes, oracle_params(dev), bl, False, x, d, 0.01, 11, 0)
+    with aht.Tile(R, C, gpu_params(dev), bl, False, 11) as tile:
+        xw, dw = tile.debug_pulse_words(to_dev(x), to_dev(d), 0.01)
+        oxw, odw = oracle.pulse_words(x, d, 0.01, 0.0005, bl, False, 11, 0)
+        assert (words_to_np(xw) == oxw).all() and (words_to_np(dw) == odw).all()
+        tile.pulsed_update(to_dev(x), to_dev(d), 0.01)
+        Wg = tile.get_weights().cpu().numpy()
+        assert tile.pulse_count() == po
+    assert np.abs(Wg - Wo).max() / 0.6 <= WEIGHT_TOL
+
+
+def test_two_tiles_on_two_streams():
+    import torch
+    w = wl.scaled(wl.WORKLOADS["cfg3_1024x1024_softbounds"], rows=128, cols=192, batch=32, steps=3)
+    W0 = wl.initial_weights(w)
+    ref, _ = run_gpu(w, W0)
+    tiles = [make_tile(w), make_tile(w)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    inputs = [(to_dev(x), to_dev(d)) for _, x, d in wl.input_stream(w)]
+    torch.cuda.synchronize()
+    for tile, s in zip(tiles, streams):
+        with torch.cuda.stream(s):
+            tile.set_weights(to_dev(W0))
+    for xd, dd in inputs:
+        for tile, s in zip(tiles, streams):
+            with torch.cuda.stream(s):
+                tile.pulsed_update(xd, dd, w.lr)
+    torch.cuda.synchronize()
+    for tile in tiles:
+        assert (tile.get_weights().cpu().numpy() == ref).all()
+        tile.close()

@@ -118,6 +118,20 @@ aht_status aht_get_weights(const aht_tile* tile, float* w_dev_out, void* stream)
 aht_status aht_pulsed_update(aht_tile* tile, const float* x_dev, const float* d_dev, int32_t B,
                              float lr, void* stream);
 
+/* Alternative pulse-train generators (Sec. 3: "stochastic (or deterministic) pulse trains",
+ * "pulse sequences of variable or fixed length").
+ *   train_kind  AHT_TRAIN_STOCHASTIC (default): Bernoulli pulses from the counter-based stream.
+ *               AHT_TRAIN_DETERMINISTIC: no random numbers; a column line with probability p
+ *               fires its first round(bl p) pulses ((n + 1/2)/bl < p), a row line fires pulse n
+ *               iff (bit-reversed n xor 0xAAAAAAAA) / 2^32 < p, so that coincidences number
+ *               bl p_x p_d up to the discrepancy of that point set (at most 2 for bl <= 63).
+ *   dynamic_bl  0 (default): every update vector uses `bl` pulses.  1: vector b uses
+ *               bl_b = clamp(ceil(lr max|x_b| max|d_b| / dw_min), 1, bl) pulses, the shortest
+ *               train whose probabilities need no clipping; the probability factor uses bl_b.
+ * Takes effect from the next aht_pulsed_update.  Errors: INVALID_ARG. */
+enum { AHT_TRAIN_STOCHASTIC = 0, AHT_TRAIN_DETERMINISTIC = 1 };
+aht_status aht_set_pulse_mode(aht_tile* tile, int32_t train_kind, int32_t dynamic_bl);
+
 /* Step counter (number of aht_pulsed_update calls so far); together with the weights, the
  * planes and the seed it makes a run resumable bit for bit. */
 aht_status aht_get_step(const aht_tile* tile, uint32_t* step);

@@ -83,6 +83,16 @@ def _declare(L):
     L.orc_pulsed_update.argtypes = ([_f32p] * 7 + [_i, _f, _f, _i, _i, _f32p, _f32p, _i, _i, _i, _f,
                                                    _u64, _u32, _i64p, ctypes.c_int64])
     L.orc_pulsed_update.restype = ctypes.c_int64
+    L.orc_line_scale_ex.argtypes = [_f32p, _f32p, _i, _i, _i, _f, _f, _i, _i, _i, _f64p, _f64p,
+                                    ctypes.POINTER(ctypes.c_int32)]
+    L.orc_line_scale_ex.restype = None
+    L.orc_pulse_word_deterministic.argtypes = [_u32, ctypes.c_double, _f, _i]
+    L.orc_pulse_word_deterministic.restype = _u64
+    L.orc_pulse_words_ex.argtypes = [_f32p, _f32p, _i, _i, _i, _f, _f, _i, _i, _i, _i, _u64, _u32, _u64p, _u64p]
+    L.orc_pulse_words_ex.restype = None
+    L.orc_pulsed_update_ex.argtypes = ([_f32p] * 7 + [_i, _f, _f, _i, _i, _i, _i, _f32p, _f32p, _i, _i, _i, _f,
+                                                      _u64, _u32, _i64p, ctypes.c_int64])
+    L.orc_pulsed_update_ex.restype = ctypes.c_int64
     L.orc_temporal_planes.argtypes = [_f] * 6 + [_u64, _i, _i] + [_f32p] * 3
     L.orc_temporal_planes.restype = None
     L.orc_decay_diffuse.argtypes = [_f32p] * 5 + [_u64, _u32, _i, _i]
@@ -163,6 +173,27 @@ def line_scale(x, d, lr, dw_min, BL, update_management):
     return a_x, a_d
 
 
+STOCHASTIC, DETERMINISTIC = 0, 1
+
+
+def line_scale_ex(x, d, lr, dw_min, BL, update_management, dynamic_bl):
+    """(a_x, a_d, bl_b): per-sample probability factors and train lengths."""
+    x, d = _f32(x), _f32(d)
+    B, C = x.shape
+    R = d.shape[1]
+    a_x = np.zeros(B, dtype=np.float64)
+    a_d = np.zeros(B, dtype=np.float64)
+    bl = np.zeros(B, dtype=np.int32)
+    lib().orc_line_scale_ex(_p(x, _f32p), _p(d, _f32p), B, R, C, lr, dw_min, BL, int(update_management),
+                            int(dynamic_bl), _p(a_x, _f64p), _p(a_d, _f64p),
+                            bl.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    return a_x, a_d, bl
+
+
+def pulse_word_deterministic(tag, a, v, BL):
+    return int(lib().orc_pulse_word_deterministic(tag, float(a), float(np.float32(v)), BL))
+
+
 def threshold(a, v):
     return int(lib().orc_threshold(float(a), float(np.float32(v))))
 
@@ -171,7 +202,7 @@ def pulse_word(seed, t, tag, index, b, a, v, BL):
     return int(lib().orc_pulse_word(seed, t, tag, index, b, float(a), float(np.float32(v)), BL))
 
 
-def pulse_words(x, d, lr, dw_min, BL, update_management, seed, t):
+def pulse_words(x, d, lr, dw_min, BL, update_management, seed, t, train_kind=STOCHASTIC, dynamic_bl=False):
     """(xw[B][C], dw[B][R]) uint64 pulse words of the call at step t."""
     x, d = _f32(x), _f32(d)
     B, C = x.shape
@@ -179,8 +210,12 @@ def pulse_words(x, d, lr, dw_min, BL, update_management, seed, t):
     assert d.shape[0] == B
     xw = np.zeros((B, C), dtype=np.uint64)
     dw = np.zeros((B, R), dtype=np.uint64)
-    lib().orc_pulse_words(_p(x, _f32p), _p(d, _f32p), B, R, C, lr, dw_min, BL,
-                          int(update_management), seed, t, _p(xw, _u64p), _p(dw, _u64p))
+    if train_kind == STOCHASTIC and not dynamic_bl:
+        lib().orc_pulse_words(_p(x, _f32p), _p(d, _f32p), B, R, C, lr, dw_min, BL,
+                              int(update_management), seed, t, _p(xw, _u64p), _p(dw, _u64p))
+    else:
+        lib().orc_pulse_words_ex(_p(x, _f32p), _p(d, _f32p), B, R, C, lr, dw_min, BL, int(update_management),
+                                 int(train_kind), int(dynamic_bl), seed, t, _p(xw, _u64p), _p(dw, _u64p))
     return xw, dw
 
 
@@ -226,7 +261,7 @@ def apply_words(W, planes, kind, c2c, xw, dw, BL, seed, t, cells=None):
 
 
 def pulsed_update(W, planes, p: DeviceParams, BL, update_management, x, d, lr, seed, t,
-                  cells=None):
+                  cells=None, train_kind=STOCHASTIC, dynamic_bl=False):
     """One whole update call at step t, in place on W; returns pulses applied.
     With ``cells`` (flat indices) only those cells are updated."""
     assert W.dtype == np.float32 and W.flags.c_contiguous
@@ -236,9 +271,13 @@ def pulsed_update(W, planes, p: DeviceParams, BL, update_management, x, d, lr, s
     assert x.shape == (B, C) and d.shape == (B, R)
     keep, ptrs = _plane_ptrs(planes)
     ckeep, cptr, nc = _cells_arg(cells)
-    return int(lib().orc_pulsed_update(_p(W, _f32p), *ptrs, p.kind, p.dw_min_std, p.dw_min, BL,
-                                       int(update_management), _p(x, _f32p), _p(d, _f32p), B, R, C,
-                                       lr, seed, t, cptr, nc))
+    if train_kind == STOCHASTIC and not dynamic_bl:
+        return int(lib().orc_pulsed_update(_p(W, _f32p), *ptrs, p.kind, p.dw_min_std, p.dw_min, BL,
+                                           int(update_management), _p(x, _f32p), _p(d, _f32p), B, R, C,
+                                           lr, seed, t, cptr, nc))
+    return int(lib().orc_pulsed_update_ex(_p(W, _f32p), *ptrs, p.kind, p.dw_min_std, p.dw_min, BL,
+                                          int(update_management), int(train_kind), int(dynamic_bl),
+                                          _p(x, _f32p), _p(d, _f32p), B, R, C, lr, seed, t, cptr, nc))
 
 
 @dataclass

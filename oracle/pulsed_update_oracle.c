@@ -44,6 +44,8 @@
  *   R8  Gaussian = Box-Muller on 24-bit uniforms, evaluated in fp64, rounded
  *       once to fp32.
  *   R9  device step in fp32, clip after every pulse.
+ *   R14 variable-length trains: the length is chosen per sample (orc_line_scale_ex).
+ *   R15 deterministic trains: evenly spaced / bit-reversed pulses (orc_pulse_word_deterministic).
  *
  * Parity pins: see tests/test_oracle_*.py.  The SHAPE of the response curves
  * against measured ReRAM data (the paper's Fig. 2B) is "parity unpinned": the
@@ -179,25 +181,54 @@ void orc_device_planes(int kind, float dw_min, float dw_min_dtod, float up_down,
  * ---------------------------------------------------------------------- */
 static int is_active(float v) { return isfinite(v) && v != 0.0f; }
 
+/* Extended form: dynamic_bl != 0 chooses the train length per sample (reading R14 of the
+ * paper's "variable or fixed length"): BL_b = clamp(ceil(lr*m_x*m_d/dw_min), 1, BL), the
+ * shortest train whose largest pulse probabilities stay <= 1 under update management; the
+ * factor A uses BL_b.  bl_b may be NULL when dynamic_bl == 0. */
+void orc_line_scale_ex(const float *x, const float *d, int B, int R, int C, float lr, float dw_min,
+                       int BL, int update_management, int dynamic_bl, double *a_x, double *a_d,
+                       int32_t *bl_b)
+{
+    for (int b = 0; b < B; ++b) {
+        int bl = BL;
+        double m_x = 0.0, m_d = 0.0;
+        if (update_management || dynamic_bl) {
+            for (int j = 0; j < C; ++j) {
+                float v = x[(size_t)b * C + j];
+                if (is_active(v) && fabs((double)v) > m_x) m_x = fabs((double)v);
+            }
+            for (int i = 0; i < R; ++i) {
+                float v = d[(size_t)b * R + i];
+                if (is_active(v) && fabs((double)v) > m_d) m_d = fabs((double)v);
+            }
+            if (m_x == 0.0 || m_d == 0.0) {
+                a_x[b] = 0.0; a_d[b] = 0.0;
+                if (bl_b) bl_b[b] = BL;
+                continue;
+            }
+        }
+        if (dynamic_bl) {
+            double need = ceil((double)lr * m_x * m_d / (double)dw_min);
+            if (!(need >= 1.0)) need = 1.0;
+            if (need > (double)BL) need = (double)BL;
+            bl = (int)need;
+        }
+        if (bl_b) bl_b[b] = bl;
+        double A = sqrt((double)lr / ((double)dw_min * (double)bl));
+        if (update_management) {
+            a_x[b] = A * sqrt(m_d / m_x);
+            a_d[b] = A * sqrt(m_x / m_d);
+        } else {
+            a_x[b] = A;
+            a_d[b] = A;
+        }
+    }
+}
+
 void orc_line_scale(const float *x, const float *d, int B, int R, int C, float lr,
                     float dw_min, int BL, int update_management, double *a_x, double *a_d)
 {
-    double A = sqrt((double)lr / ((double)dw_min * (double)BL));
-    for (int b = 0; b < B; ++b) {
-        if (!update_management) { a_x[b] = A; a_d[b] = A; continue; }
-        double m_x = 0.0, m_d = 0.0;
-        for (int j = 0; j < C; ++j) {
-            float v = x[(size_t)b * C + j];
-            if (is_active(v) && fabs((double)v) > m_x) m_x = fabs((double)v);
-        }
-        for (int i = 0; i < R; ++i) {
-            float v = d[(size_t)b * R + i];
-            if (is_active(v) && fabs((double)v) > m_d) m_d = fabs((double)v);
-        }
-        if (m_x == 0.0 || m_d == 0.0) { a_x[b] = 0.0; a_d[b] = 0.0; continue; }
-        a_x[b] = A * sqrt(m_d / m_x);
-        a_d[b] = A * sqrt(m_x / m_d);
-    }
+    orc_line_scale_ex(x, d, B, R, C, lr, dw_min, BL, update_management, 0, a_x, a_d, NULL);
 }
 
 /* 33-bit threshold (R5): 0 .. 2^32 inclusive. */
@@ -227,25 +258,71 @@ uint64_t orc_pulse_word(uint64_t seed, uint32_t t, uint32_t tag, uint32_t index,
     return word;
 }
 
-/* All pulse words of one call: xw[B][C], dw[B][R]. */
+/* Deterministic train (reading R15 of the paper's "stochastic (or deterministic) pulse
+ * trains"): no random numbers; pulse n of a line is set iff u_n < T/2^32 with
+ *   column lines:  u_n = (n + 1/2) / BL        (evenly spaced pulses)
+ *   row lines:     u_n = (bit-reversal of n  XOR  0xAAAAAAAA) / 2^32
+ *                  (van der Corput sequence with an alternating digital shift)
+ * so that the pairs (u_n^x, u_n^d), n < BL, form a digitally shifted Hammersley point set: the
+ * number of coincidences is BL*p_x*p_d up to its discrepancy, and the alternating shift removes
+ * the positive mean error (log2(BL)/8) of the unshifted set.  All in integer arithmetic. */
+static uint32_t bit_reverse32(uint32_t v)
+{
+    uint32_t r = 0;
+    for (int k = 0; k < 32; ++k) { r = (r << 1) | (v & 1u); v >>= 1; }
+    return r;
+}
+
+uint64_t orc_pulse_word_deterministic(uint32_t tag, double a, float v, int BL)
+{
+    if (!is_active(v) || !(a > 0.0)) return 0;
+    uint64_t T = orc_threshold(a, v);
+    uint64_t word = 0;
+    for (int n = 0; n < BL; ++n) {
+        int set;
+        if (tag == ORC_TAG_X) set = (((uint64_t)(2 * n + 1)) << 32) < 2u * (uint64_t)BL * T;
+        else set = (uint64_t)(bit_reverse32((uint32_t)n) ^ 0xAAAAAAAAu) < T;
+        if (set) word |= (uint64_t)1 << n;
+    }
+    if (v < 0.0f) word |= (uint64_t)1 << 63;
+    return word;
+}
+
+/* All pulse words of one call: xw[B][C], dw[B][R].
+ * train_kind 0 = stochastic, 1 = deterministic; dynamic_bl as in orc_line_scale_ex. */
+void orc_pulse_words_ex(const float *x, const float *d, int B, int R, int C, float lr, float dw_min,
+                        int BL, int update_management, int train_kind, int dynamic_bl, uint64_t seed,
+                        uint32_t t, uint64_t *xw, uint64_t *dw)
+{
+    double *a_x = (double *)malloc(sizeof(double) * (size_t)(B > 0 ? B : 1));
+    double *a_d = (double *)malloc(sizeof(double) * (size_t)(B > 0 ? B : 1));
+    int32_t *bl_b = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B > 0 ? B : 1));
+    orc_line_scale_ex(x, d, B, R, C, lr, dw_min, BL, update_management, dynamic_bl, a_x, a_d, bl_b);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int j = 0; j < C; ++j) {
+            float v = x[(size_t)b * C + j];
+            xw[(size_t)b * C + j] = train_kind
+                ? orc_pulse_word_deterministic(ORC_TAG_X, a_x[b], v, bl_b[b])
+                : orc_pulse_word(seed, t, ORC_TAG_X, (uint32_t)j, (uint32_t)b, a_x[b], v, bl_b[b]);
+        }
+        for (int i = 0; i < R; ++i) {
+            float v = d[(size_t)b * R + i];
+            dw[(size_t)b * R + i] = train_kind
+                ? orc_pulse_word_deterministic(ORC_TAG_D, a_d[b], v, bl_b[b])
+                : orc_pulse_word(seed, t, ORC_TAG_D, (uint32_t)i, (uint32_t)b, a_d[b], v, bl_b[b]);
+        }
+    }
+    free(a_x);
+    free(a_d);
+    free(bl_b);
+}
+
 void orc_pulse_words(const float *x, const float *d, int B, int R, int C, float lr, float dw_min,
                      int BL, int update_management, uint64_t seed, uint32_t t, uint64_t *xw,
                      uint64_t *dw)
 {
-    double *a_x = (double *)malloc(sizeof(double) * (size_t)(B > 0 ? B : 1));
-    double *a_d = (double *)malloc(sizeof(double) * (size_t)(B > 0 ? B : 1));
-    orc_line_scale(x, d, B, R, C, lr, dw_min, BL, update_management, a_x, a_d);
-#pragma omp parallel for schedule(dynamic, 1)
-    for (int b = 0; b < B; ++b) {
-        for (int j = 0; j < C; ++j)
-            xw[(size_t)b * C + j] = orc_pulse_word(seed, t, ORC_TAG_X, (uint32_t)j, (uint32_t)b,
-                                                   a_x[b], x[(size_t)b * C + j], BL);
-        for (int i = 0; i < R; ++i)
-            dw[(size_t)b * R + i] = orc_pulse_word(seed, t, ORC_TAG_D, (uint32_t)i, (uint32_t)b,
-                                                   a_d[b], d[(size_t)b * R + i], BL);
-    }
-    free(a_x);
-    free(a_d);
+    orc_pulse_words_ex(x, d, B, R, C, lr, dw_min, BL, update_management, 0, 0, seed, t, xw, dw);
 }
 
 /* Coincidences of cell (i,j) in one sample: count and direction. */
@@ -340,21 +417,33 @@ int64_t orc_apply_words(float *W, const float *dw_up, const float *dw_down, cons
 }
 
 /* The whole update call at step t: words, then cells.  Returns applied pulses. */
+int64_t orc_pulsed_update_ex(float *W, const float *dw_up, const float *dw_down, const float *b_max,
+                             const float *b_min, const float *slope_up, const float *slope_down,
+                             int kind, float c2c, float dw_min, int BL, int update_management,
+                             int train_kind, int dynamic_bl, const float *x, const float *d, int B,
+                             int R, int C, float lr, uint64_t seed, uint32_t t, const int64_t *cells,
+                             int64_t n_cells)
+{
+    if (B <= 0 || !(lr > 0.0f)) return 0;
+    uint64_t *xw = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)B * C);
+    uint64_t *dw = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)B * R);
+    orc_pulse_words_ex(x, d, B, R, C, lr, dw_min, BL, update_management, train_kind, dynamic_bl, seed,
+                       t, xw, dw);
+    int64_t pulses = orc_apply_words(W, dw_up, dw_down, b_max, b_min, slope_up, slope_down, kind,
+                                     c2c, xw, dw, B, R, C, BL, seed, t, cells, n_cells);
+    free(xw);
+    free(dw);
+    return pulses;
+}
+
 int64_t orc_pulsed_update(float *W, const float *dw_up, const float *dw_down, const float *b_max,
                           const float *b_min, const float *slope_up, const float *slope_down,
                           int kind, float c2c, float dw_min, int BL, int update_management,
                           const float *x, const float *d, int B, int R, int C, float lr,
                           uint64_t seed, uint32_t t, const int64_t *cells, int64_t n_cells)
 {
-    if (B <= 0 || !(lr > 0.0f)) return 0;
-    uint64_t *xw = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)B * C);
-    uint64_t *dw = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)B * R);
-    orc_pulse_words(x, d, B, R, C, lr, dw_min, BL, update_management, seed, t, xw, dw);
-    int64_t pulses = orc_apply_words(W, dw_up, dw_down, b_max, b_min, slope_up, slope_down, kind,
-                                     c2c, xw, dw, B, R, C, BL, seed, t, cells, n_cells);
-    free(xw);
-    free(dw);
-    return pulses;
+    return orc_pulsed_update_ex(W, dw_up, dw_down, b_max, b_min, slope_up, slope_down, kind, c2c, dw_min,
+                                BL, update_management, 0, 0, x, d, B, R, C, lr, seed, t, cells, n_cells);
 }
 
 int orc_num_threads(void)

@@ -23,7 +23,7 @@ EXPORTS = (
     "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
     "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
     "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
-    "aht_set_temporal", "aht_decay_diffuse", "aht_reset_columns", "aht_get_temporal_plane",
+    "aht_set_pulse_mode", "aht_set_temporal", "aht_decay_diffuse", "aht_reset_columns", "aht_get_temporal_plane",
     "aht_get_temporal_step", "aht_set_temporal_step",
     "aht_status_string", "aht_last_error", "aht_version",
 )
@@ -112,6 +112,7 @@ def load_library() -> ctypes.CDLL:
     L.aht_debug_apply_words.argtypes = [vp, vp, vp, i32, u32, vp]
     L.aht_debug_philox.argtypes = [vp, vp, i32, vp, vp]
     L.aht_debug_gauss.argtypes = [u64, u32, u32, u32, u32, i32, i32, vp, vp]
+    L.aht_set_pulse_mode.argtypes = [vp, i32, i32]
     L.aht_set_temporal.argtypes = [vp, ctypes.POINTER(aht_temporal_params)]
     L.aht_decay_diffuse.argtypes = [vp, vp]
     L.aht_reset_columns.argtypes = [vp, i32, i32, vp]
@@ -207,6 +208,9 @@ class Tile:
         else:
             xp = dp = ctypes.c_void_p()
         _check(self._lib.aht_pulsed_update(self._h, xp, dp, B, ctypes.c_float(lr), _stream()))
+
+    def set_pulse_mode(self, deterministic: bool = False, dynamic_bl: bool = False):
+        _check(self._lib.aht_set_pulse_mode(self._h, int(bool(deterministic)), int(bool(dynamic_bl))))
 
     # -- state -----------------------------------------------------------------------------
     @property

@@ -34,6 +34,10 @@ struct aht_tile {
     double* a_x = nullptr;
     double* a_d = nullptr;
     int a_cap = 0;
+    int32_t* bl_b = nullptr;
+    int bl_cap = 0;
+    int train_kind = AHT_TRAIN_STOCHASTIC;
+    int dynamic_bl = 0;
     unsigned long long* pulse_count = nullptr;
     // temporal processes
     bool has_temporal = false;
@@ -111,7 +115,13 @@ aht_status ensure_scratch(aht_tile* t, int B)
         AHT_HIP(hipMalloc(&t->dw, need_d));
         t->dw_bytes = need_d;
     }
-    if (t->upd.update_management && B > t->a_cap) {
+    if (t->dynamic_bl && B > t->bl_cap) {
+        if (t->bl_b) AHT_HIP(hipFree(t->bl_b));
+        t->bl_b = nullptr; t->bl_cap = 0;
+        AHT_HIP(hipMalloc((void**)&t->bl_b, sizeof(int32_t) * (size_t)B));
+        t->bl_cap = B;
+    }
+    if ((t->upd.update_management || t->dynamic_bl) && B > t->a_cap) {
         if (t->a_x) AHT_HIP(hipFree(t->a_x));
         if (t->a_d) AHT_HIP(hipFree(t->a_d));
         t->a_x = t->a_d = nullptr; t->a_cap = 0;
@@ -128,20 +138,24 @@ aht_status launch_words(aht_tile* t, const float* x, const float* d, int B, floa
 {
     const double A = std::sqrt((double)lr / ((double)t->dev.dw_min * (double)t->upd.bl));
     const double *ax = nullptr, *ad = nullptr;
-    if (t->upd.update_management) {
-        hipLaunchKernelGGL(k_line_scale, dim3((unsigned)B), dim3(256), 0, s, x, d, t->rows, t->cols, A, t->a_x, t->a_d);
+    const int32_t* blb = nullptr;
+    if (t->upd.update_management || t->dynamic_bl) {
+        hipLaunchKernelGGL(k_line_scale, dim3((unsigned)B), dim3(256), 0, s, x, d, t->rows, t->cols, (double)lr,
+                           (double)t->dev.dw_min, t->upd.bl, t->upd.update_management, t->dynamic_bl, t->a_x, t->a_d,
+                           t->dynamic_bl ? t->bl_b : nullptr);
         ax = t->a_x;
         ad = t->a_d;
+        blb = t->dynamic_bl ? t->bl_b : nullptr;
     }
     const uint32_t k0 = (uint32_t)t->seed, k1 = (uint32_t)(t->seed >> 32);
     const int Cp = cpad(t), Rp = rpad(t);
     const dim3 grid(blocks_for((size_t)Cp + Rp), (unsigned)(B < 32768 ? B : 32768));
     if (use_u32(t))
         hipLaunchKernelGGL(k_pulse_words<uint32_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp,
-                           t->upd.bl, A, ax, ad, k0, k1, step, (uint32_t*)t->xw, (uint32_t*)t->dw);
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint32_t*)t->xw, (uint32_t*)t->dw);
     else
         hipLaunchKernelGGL(k_pulse_words<uint64_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp,
-                           t->upd.bl, A, ax, ad, k0, k1, step, (uint64_t*)t->xw, (uint64_t*)t->dw);
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint64_t*)t->xw, (uint64_t*)t->dw);
     AHT_HIP(hipGetLastError());
     return AHT_OK;
 }
@@ -352,7 +366,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     };
     rel(t->W);
     for (auto* p : t->planes) rel(p);
-    rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->pulse_count);
+    rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->bl_b); rel(t->pulse_count);
     for (auto* p : t->tplanes) rel(p);
     for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
     delete t;
@@ -517,6 +531,16 @@ aht_status aht_profile_read(aht_tile* t, double* ms_words, double* ms_cells, int
     *ms_cells = c;
     *calls = (int32_t)(t->events_used / 3);
     t->events_used = 0;
+    return AHT_OK;
+}
+
+aht_status aht_set_pulse_mode(aht_tile* t, int32_t train_kind, int32_t dynamic_bl)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    if (train_kind != AHT_TRAIN_STOCHASTIC && train_kind != AHT_TRAIN_DETERMINISTIC)
+        return fail(AHT_ERR_INVALID_ARG, "unknown train kind %d", train_kind);
+    t->train_kind = train_kind;
+    t->dynamic_bl = dynamic_bl ? 1 : 0;
     return AHT_OK;
 }
 

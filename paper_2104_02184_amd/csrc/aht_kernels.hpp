@@ -154,6 +154,7 @@ k_reset_columns(float* __restrict__ W, const float* __restrict__ rplane, float r
 // ------------------------------------------------------------------------------------------
 // Line scaling with update management: one workgroup per update vector.
 // a_x = A sqrt(m_d/m_x), a_d = A sqrt(m_x/m_d); both 0 when a maximum is 0 (sample skipped).
+// With a per-sample train length BL_b = clamp(ceil(lr m_x m_d / dw_min), 1, BL), A uses BL_b.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ float finite_abs_or_zero(float v)
 {
@@ -163,8 +164,9 @@ __device__ __forceinline__ float finite_abs_or_zero(float v)
 
 __global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
                                                     const float* __restrict__ d, int R, int C,
-                                                    double A, double* __restrict__ a_x,
-                                                    double* __restrict__ a_d)
+                                                    double lr, double dw_min, int BL, int update_management,
+                                                    int dynamic_bl, double* __restrict__ a_x,
+                                                    double* __restrict__ a_d, int32_t* __restrict__ bl_b)
 {
     __shared__ float red_x[4], red_d[4];
     const int b = blockIdx.x;
@@ -185,12 +187,26 @@ __global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
         const double m_x = (double)fmaxf(fmaxf(red_x[0], red_x[1]), fmaxf(red_x[2], red_x[3]));
         const double m_d = (double)fmaxf(fmaxf(red_d[0], red_d[1]), fmaxf(red_d[2], red_d[3]));
         double ax = 0.0, ad = 0.0;
+        int bl = BL;
         if (m_x != 0.0 && m_d != 0.0) {
-            ax = A * sqrt(m_d / m_x);
-            ad = A * sqrt(m_x / m_d);
+            if (dynamic_bl) {                     // shortest train that keeps the probabilities <= 1
+                double need = ceil(lr * m_x * m_d / dw_min);
+                if (!(need >= 1.0)) need = 1.0;
+                if (need > (double)BL) need = (double)BL;
+                bl = (int)need;
+            }
+            const double A = sqrt(lr / (dw_min * (double)bl));
+            if (update_management) {
+                ax = A * sqrt(m_d / m_x);
+                ad = A * sqrt(m_x / m_d);
+            } else {
+                ax = A;
+                ad = A;
+            }
         }
         a_x[b] = ax;
         a_d[b] = ad;
+        if (bl_b) bl_b[b] = bl;
     }
 }
 
@@ -201,10 +217,14 @@ __global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
 // up to 16, the padding filled with zero words so that the cell kernel needs no edge masks.
 // grid.x covers the Cpad + Rpad lines of one sample, grid.y strides over the samples.
 // ------------------------------------------------------------------------------------------
+// Deterministic trains use no random numbers: pulse n is set iff u_n < T / 2^32 with
+// u_n = (n + 1/2) / BL for column lines and the bit-reversed, digitally shifted pulse number
+// (brev(n) xor 0xAAAAAAAA) / 2^32 for row lines (a shifted Hammersley point set).
 template <typename WordT>
 __global__ void __launch_bounds__(256)
 k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int Rpad, int Cpad,
               int BL, double A, const double* __restrict__ a_x, const double* __restrict__ a_d,
+              const int32_t* __restrict__ bl_b, int deterministic,
               uint32_t k0, uint32_t k1, uint32_t t, WordT* __restrict__ xw, WordT* __restrict__ dw)
 {
     const int l = (int)(blockIdx.x * 256 + threadIdx.x);
@@ -213,27 +233,37 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
     const int idx = is_x ? l : l - Cpad;
     const int len = is_x ? C : R;
     const uint32_t tagw = (is_x ? kTagX : kTagD) << 24;
-    const int nblk = (BL + 3) >> 2;
     for (uint32_t b = blockIdx.y; b < (uint32_t)B; b += gridDim.y) {
         WordT word = 0;
         if (idx < len) {
             const float v = is_x ? x[(size_t)b * C + idx] : d[(size_t)b * R + idx];
             const double a = a_x ? (is_x ? a_x[b] : a_d[b]) : A;
+            const int bl = bl_b ? bl_b[b] : BL;
             const float av = fabsf(v);
             if (av > 0.0f && av < __builtin_inff() && a > 0.0) {
                 double p = a * (double)av;
                 if (!(p < 1.0)) p = 1.0;
                 const uint64_t T = (uint64_t)(p * 4294967296.0);      // 0 .. 2^32
                 if (T != 0) {
-                    const bool sat = (T >> 32) != 0;
-                    const uint32_t Tlo = (uint32_t)T;
-                    for (int blk = 0; blk < nblk; ++blk) {
-                        const U4 r = philox4x32_10((uint32_t)idx, b, t, tagw | (uint32_t)blk, k0, k1);
-                        const uint32_t bits = (uint32_t)(sat | (r.x < Tlo)) | ((uint32_t)(sat | (r.y < Tlo)) << 1) |
-                                              ((uint32_t)(sat | (r.z < Tlo)) << 2) | ((uint32_t)(sat | (r.w < Tlo)) << 3);
-                        word |= (WordT)bits << (4 * blk);
+                    if (deterministic) {
+                        const uint64_t lim = 2ull * (uint64_t)bl * T;
+                        for (int n = 0; n < bl; ++n) {
+                            const bool set = is_x ? (((uint64_t)(2 * n + 1)) << 32) < lim
+                                                  : (uint64_t)(__brev((uint32_t)n) ^ 0xAAAAAAAAu) < T;
+                            word |= (WordT)(set ? 1u : 0u) << n;
+                        }
+                    } else {
+                        const bool sat = (T >> 32) != 0;
+                        const uint32_t Tlo = (uint32_t)T;
+                        const int nblk = (bl + 3) >> 2;
+                        for (int blk = 0; blk < nblk; ++blk) {
+                            const U4 r = philox4x32_10((uint32_t)idx, b, t, tagw | (uint32_t)blk, k0, k1);
+                            const uint32_t bits = (uint32_t)(sat | (r.x < Tlo)) | ((uint32_t)(sat | (r.y < Tlo)) << 1) |
+                                                  ((uint32_t)(sat | (r.z < Tlo)) << 2) | ((uint32_t)(sat | (r.w < Tlo)) << 3);
+                            word |= (WordT)bits << (4 * blk);
+                        }
+                        word &= (((WordT)1 << bl) - 1);
                     }
-                    word &= (((WordT)1 << BL) - 1);
                 }
                 if (v < 0.0f) word |= (WordT)1 << WordTraits<WordT>::kSignBit;
             }

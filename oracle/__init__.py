@@ -93,6 +93,8 @@ def _declare(L):
     L.orc_pulsed_update_ex.argtypes = ([_f32p] * 7 + [_i, _f, _f, _i, _i, _i, _i, _f32p, _f32p, _i, _i, _i, _f,
                                                       _u64, _u32, _i64p, ctypes.c_int64])
     L.orc_pulsed_update_ex.restype = ctypes.c_int64
+    L.orc_analog_mvm.argtypes = [_f32p, _i, _i, _i, _f32p, _i] + [_f] * 7 + [_i, _u64, _u32, _f32p, _f32p]
+    L.orc_analog_mvm.restype = None
     L.orc_temporal_planes.argtypes = [_f] * 6 + [_u64, _i, _i] + [_f32p] * 3
     L.orc_temporal_planes.restype = None
     L.orc_decay_diffuse.argtypes = [_f32p] * 5 + [_u64, _u32, _i, _i]
@@ -278,6 +280,35 @@ def pulsed_update(W, planes, p: DeviceParams, BL, update_management, x, d, lr, s
     return int(lib().orc_pulsed_update_ex(_p(W, _f32p), *ptrs, p.kind, p.dw_min_std, p.dw_min, BL,
                                           int(update_management), int(train_kind), int(dynamic_bl),
                                           _p(x, _f32p), _p(d, _f32p), B, R, C, lr, seed, t, cptr, nc))
+
+
+@dataclass
+class IOParams:
+    """Non-idealities of the analog matrix-vector product (Eq. (1) of the paper)."""
+    inp_res: float = 1.0 / 126.0      # DAC step of the scaled input (0: no quantisation)
+    inp_bound: float = 1.0
+    inp_noise: float = 0.0
+    w_noise: float = 0.0
+    out_noise: float = 0.06
+    out_res: float = 12.0 / 254.0     # ADC step (0: no quantisation)
+    out_bound: float = 12.0
+    noise_management: bool = True
+
+
+def analog_mvm(W, x, io: IOParams, seed, t, transposed=False, return_pre=False):
+    """y[B][R] = analog product of x[B][C] with W[R][C] (transposed: x[B][R] -> y[B][C])."""
+    W = _f32(W)
+    x = _f32(x)
+    R, C = W.shape
+    B = x.shape[0]
+    N = C if transposed else R
+    assert x.shape[1] == (R if transposed else C)
+    y = np.zeros((B, N), dtype=np.float32)
+    pre = np.zeros((B, N), dtype=np.float32)
+    lib().orc_analog_mvm(_p(W, _f32p), R, C, int(transposed), _p(x, _f32p), B, io.inp_res, io.inp_bound,
+                         io.inp_noise, io.w_noise, io.out_noise, io.out_res, io.out_bound,
+                         int(io.noise_management), seed, t, _p(y, _f32p), _p(pre, _f32p))
+    return (y, pre) if return_pre else y
 
 
 @dataclass

@@ -551,3 +551,92 @@ void orc_reset_columns(float *W, const float *reset_plane, float reset_std, cons
             W[k] = w;
         }
 }
+
+/* ------------------------------------------------------------------------
+ * Analog matrix-vector product, Eq. (1) of the paper:
+ *   y_i = f_adc( sum_j (w_ij + s_w xi_ij)(f_dac(x_j) + s_inp xi_j) + s_out xi_i )
+ * and its transposed form for the backward pass (Sec. 3, paragraph on the backward
+ * pass).  The paper leaves f_dac, f_adc ("discretization ... dynamic scaling and
+ * clipping") and the noise bookkeeping open; readings (F1..F7):
+ *   F1 dynamic scaling: alpha = max |x| over the finite entries of the vector
+ *      (non-finite entries count as 0); alpha == 0 gives the zero vector.
+ *   F2 f_dac: xh = x/alpha clipped to +-inp_bound; with inp_res > 0
+ *      xq = rint(xh / inp_res) * inp_res (round half to even), all fp32.
+ *   F3 input noise: xq_j += s_inp * Gaussian (j & 3) of block (index j>>2, word b,
+ *      t = call counter, tag 7 forward / 9 backward).
+ *   F4 weight noise, output referred: the sum over j of s_w xi_ij xq_j of fresh
+ *      independent xi_ij is N(0, s_w^2 |xq|^2) and independent across i, so it is
+ *      drawn as s_w * |xq|_2 * one Gaussian per output.
+ *   F5 output noise: s_out * one Gaussian per output.  Output i takes Gaussians
+ *      2(i&1) (output noise) and 2(i&1)+1 (weight noise) of block (index i>>1,
+ *      word b, t, tag 8 forward / 10 backward).
+ *   F6 f_adc: z clipped to +-out_bound; with out_res > 0 rint(z/out_res)*out_res;
+ *      y = alpha * that.
+ *   F7 the product itself is accumulated in fp64 and rounded once to fp32; the
+ *      noise terms are added in fp32 in the order product, weight noise, output noise.
+ * transposed == 0: x[B][C] -> y[B][R] with W[R][C];  != 0: x[B][R] -> y[B][C].
+ * pre (optional) receives the value entering f_adc.
+ * ---------------------------------------------------------------------- */
+void orc_analog_mvm(const float *W, int R, int C, int transposed, const float *x, int B, float inp_res,
+                    float inp_bound, float inp_noise, float w_noise, float out_noise, float out_res,
+                    float out_bound, int noise_management, uint64_t seed, uint32_t t, float *y, float *pre)
+{
+    const int K = transposed ? R : C;      /* input length */
+    const int N = transposed ? C : R;      /* output length */
+    const uint32_t tag_in = transposed ? 9u : 7u, tag_out = transposed ? 10u : 8u;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        float *xq = (float *)malloc(sizeof(float) * (size_t)K);
+        float alpha = 1.0f;
+        if (noise_management) {
+            alpha = 0.0f;
+            for (int j = 0; j < K; ++j) {
+                float v = x[(size_t)b * K + j];
+                if (isfinite(v) && fabsf(v) > alpha) alpha = fabsf(v);
+            }
+        }
+        double norm2 = 0.0;
+        for (int j = 0; j < K; ++j) {
+            float v = x[(size_t)b * K + j];
+            if (!isfinite(v) || alpha == 0.0f) v = 0.0f;
+            float xh = (alpha != 0.0f) ? v / alpha : 0.0f;
+            xh = fminf(fmaxf(xh, -inp_bound), inp_bound);
+            if (inp_res > 0.0f) xh = rintf(xh / inp_res) * inp_res;
+            xq[j] = xh;
+        }
+        if (inp_noise > 0.0f) {
+            for (int j = 0; j < K; ++j) {
+                double zb[4];                     /* counter (j>>2, b, t, tag): the sample is word 1 */
+                orc_gauss_block_f64(seed, (uint32_t)j >> 2, t, (uint32_t)b, tag_in, zb);
+                float xi = (float)zb[j & 3];
+                float nz = inp_noise * xi;
+                xq[j] = xq[j] + nz;
+            }
+        }
+        for (int j = 0; j < K; ++j) norm2 += (double)xq[j] * (double)xq[j];
+        float norm = (float)sqrt(norm2);
+        for (int i = 0; i < N; ++i) {
+            double acc = 0.0;
+            for (int j = 0; j < K; ++j) {
+                float w = transposed ? W[(size_t)j * C + i] : W[(size_t)i * C + j];
+                acc += (double)w * (double)xq[j];
+            }
+            float z = (float)acc;
+            if (w_noise > 0.0f || out_noise > 0.0f) {
+                double zb[4];                     /* counter (i>>1, b, t, tag) */
+                orc_gauss_block_f64(seed, (uint32_t)i >> 1, t, (uint32_t)b, tag_out, zb);
+                float g_out = (float)zb[2 * (i & 1)], g_w = (float)zb[2 * (i & 1) + 1];
+                float wn = w_noise * norm;
+                wn = wn * g_w;
+                z = z + wn;
+                float on = out_noise * g_out;
+                z = z + on;
+            }
+            if (pre) pre[(size_t)b * N + i] = z;
+            float q = fminf(fmaxf(z, -out_bound), out_bound);
+            if (out_res > 0.0f) q = rintf(q / out_res) * out_res;
+            y[(size_t)b * N + i] = alpha * q;
+        }
+        free(xq);
+    }
+}

@@ -108,6 +108,44 @@ def bench_decay_diffuse(args):
     }), flush=True)
 
 
+def bench_mvm(args, transposed):
+    """Side benchmark: the analog matrix-vector product of a batch (Eq. (1)) on the headline tile,
+    bound by the fp32 matrix cores (2*B*R*C flops per call)."""
+    import torch
+
+    import paper_2104_02184_amd as aht
+    from paper_2104_02184_amd import workloads as wl
+
+    w = wl.WORKLOADS[args.workload or wl.HEADLINE]
+    tile = aht.Tile(w.rows, w.cols, aht.DeviceParams(**w.device), w.bl, w.update_management, w.seed)
+    tile.set_weights(torch.from_numpy(wl.initial_weights(w)).cuda())
+    g = wl.rng_for(w, 3)
+    n_in = w.rows if transposed else w.cols
+    x = torch.from_numpy(g.standard_normal((w.batch, n_in), dtype="float32")).cuda()
+    io = aht.IOParams(inp_noise=0.01, w_noise=0.02)
+    fn = tile.backward if transposed else tile.forward
+    for _ in range(args.warmup):
+        fn(x, io)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        fn(x, io)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    tile.close()
+    flops = 2.0 * w.batch * w.rows * w.cols
+    print(json.dumps({
+        "metric": "TFLOP/s of analog " + ("backward" if transposed else "forward"), "value": flops / (ms * 1e-3) / 1e12,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name} analog MVM, B={w.batch}"},
+        "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s",
+                     "frac": flops / (ms * 1e-3) / 157.3e12, "traffic": None},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -116,7 +154,7 @@ def main():
     ap.add_argument("--workload", default=None, help="workload name (default: the headline one)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-rows", type=int, default=512)
-    ap.add_argument("--op", default="pulsed_update", choices=["pulsed_update", "decay_diffuse"],
+    ap.add_argument("--op", default="pulsed_update", choices=["pulsed_update", "decay_diffuse", "forward", "backward"],
                     help="side benchmarks of other operations; the default is the headline metric")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -135,6 +173,9 @@ def main():
     aht.load_library()
     if args.op == "decay_diffuse":
         bench_decay_diffuse(args)
+        return
+    if args.op in ("forward", "backward"):
+        bench_mvm(args, args.op == "backward")
         return
     w = wl.WORKLOADS[args.workload or wl.HEADLINE]
     K, Wm = args.steps, args.warmup

@@ -170,6 +170,32 @@ aht_status aht_debug_philox(const uint32_t* ctr_dev, const uint32_t* key_dev, in
 aht_status aht_debug_gauss(uint64_t seed, uint32_t index, uint32_t t, uint32_t tag, uint32_t q0,
                            int32_t n, int32_t fast, float* gauss_dev, void* stream);
 
+/* Analog matrix-vector product, Eq. (1) of the paper, and its transposed form for the backward
+ * pass (Sec. 3):  y_i = f_adc( sum_j (w_ij + s_w xi_ij)(f_dac(x_j) + s_inp xi_j) + s_out xi_i ).
+ *   f_dac: with noise_management the vector is divided by alpha = max|x| (finite entries only;
+ *          alpha == 0 gives y == 0), clipped to +-inp_bound and rounded (half to even) to
+ *          multiples of inp_res (0 = no rounding); input noise s_inp is added after it.
+ *   weight noise is drawn output-referred: s_w |f_dac(x)|_2 times one Gaussian per output
+ *          (equal in law to fresh independent xi_ij).
+ *   f_adc: clipped to +-out_bound, rounded to multiples of out_res (0 = none), times alpha.
+ * aht_forward:  x_dev [B][cols] -> y_dev [B][rows];  aht_backward: d_dev [B][rows] -> g_dev [B][cols].
+ * pre_dev (nullable, test hook) receives the values entering f_adc.  Each call uses the tile's
+ * forward (backward) call counter for its random stream and increments it.  fp32 product on the
+ * matrix cores; asynchronous on `stream`.  Errors: INVALID_ARG (null pointers, B <= 0, negative
+ * or non-finite parameters), OOM (scratch), DEVICE. */
+typedef struct {
+    float inp_res, inp_bound, inp_noise;
+    float w_noise;
+    float out_noise, out_res, out_bound;
+    int32_t noise_management;
+} aht_io_params;
+aht_status aht_forward(aht_tile* tile, const aht_io_params* io, const float* x_dev, float* y_dev,
+                       float* pre_dev, int32_t B, void* stream);
+aht_status aht_backward(aht_tile* tile, const aht_io_params* io, const float* d_dev, float* g_dev,
+                        float* pre_dev, int32_t B, void* stream);
+aht_status aht_get_mvm_steps(const aht_tile* tile, uint32_t* forward_calls, uint32_t* backward_calls);
+aht_status aht_set_mvm_steps(aht_tile* tile, uint32_t forward_calls, uint32_t backward_calls);
+
 /* Once-per-mini-batch temporal processes with device-to-device variability (Sec. 4, last
  * paragraph: conductance decay, reset and diffusion).  Per-cell planes are drawn at
  * aht_set_temporal from the tile's seed:

@@ -23,6 +23,7 @@ EXPORTS = (
     "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
     "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
     "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
+    "aht_forward", "aht_backward", "aht_get_mvm_steps", "aht_set_mvm_steps",
     "aht_set_pulse_mode", "aht_set_temporal", "aht_decay_diffuse", "aht_reset_columns", "aht_get_temporal_plane",
     "aht_get_temporal_step", "aht_set_temporal_step",
     "aht_status_string", "aht_last_error", "aht_version",
@@ -42,6 +43,27 @@ class aht_device_params(ctypes.Structure):
                 ("w_max", ctypes.c_float), ("w_max_dtod", ctypes.c_float), ("w_min", ctypes.c_float),
                 ("w_min_dtod", ctypes.c_float), ("gamma_up", ctypes.c_float), ("gamma_down", ctypes.c_float),
                 ("gamma_dtod", ctypes.c_float)]
+
+
+class aht_io_params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_float) for n in ("inp_res", "inp_bound", "inp_noise", "w_noise", "out_noise",
+                                               "out_res", "out_bound")] + [("noise_management", ctypes.c_int32)]
+
+
+@dataclass
+class IOParams:
+    inp_res: float = 1.0 / 126.0
+    inp_bound: float = 1.0
+    inp_noise: float = 0.0
+    w_noise: float = 0.0
+    out_noise: float = 0.06
+    out_res: float = 12.0 / 254.0
+    out_bound: float = 12.0
+    noise_management: bool = True
+
+    def to_c(self) -> "aht_io_params":
+        return aht_io_params(self.inp_res, self.inp_bound, self.inp_noise, self.w_noise, self.out_noise,
+                             self.out_res, self.out_bound, int(bool(self.noise_management)))
 
 
 class aht_temporal_params(ctypes.Structure):
@@ -112,6 +134,10 @@ def load_library() -> ctypes.CDLL:
     L.aht_debug_apply_words.argtypes = [vp, vp, vp, i32, u32, vp]
     L.aht_debug_philox.argtypes = [vp, vp, i32, vp, vp]
     L.aht_debug_gauss.argtypes = [u64, u32, u32, u32, u32, i32, i32, vp, vp]
+    L.aht_forward.argtypes = [vp, ctypes.POINTER(aht_io_params), vp, vp, vp, i32, vp]
+    L.aht_backward.argtypes = [vp, ctypes.POINTER(aht_io_params), vp, vp, vp, i32, vp]
+    L.aht_get_mvm_steps.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(u32)]
+    L.aht_set_mvm_steps.argtypes = [vp, u32, u32]
     L.aht_set_pulse_mode.argtypes = [vp, i32, i32]
     L.aht_set_temporal.argtypes = [vp, ctypes.POINTER(aht_temporal_params)]
     L.aht_decay_diffuse.argtypes = [vp, vp]
@@ -208,6 +234,33 @@ class Tile:
         else:
             xp = dp = ctypes.c_void_p()
         _check(self._lib.aht_pulsed_update(self._h, xp, dp, B, ctypes.c_float(lr), _stream()))
+
+    # -- analog matrix-vector product ------------------------------------------------------
+    def _mvm(self, fn, io, x, n_in, n_out, with_pre):
+        import torch
+        B = int(x.shape[0])
+        y = torch.empty((B, n_out), dtype=torch.float32, device="cuda")
+        pre = torch.empty((B, n_out), dtype=torch.float32, device="cuda") if with_pre else None
+        c = io.to_c()
+        _check(fn(self._h, ctypes.byref(c), _ptr(x, torch.float32, (B, n_in)), _ptr(y, torch.float32),
+                  _ptr(pre, torch.float32) if with_pre else ctypes.c_void_p(), B, _stream()))
+        return (y, pre) if with_pre else y
+
+    def forward(self, x, io: "IOParams", with_pre: bool = False):
+        return self._mvm(self._lib.aht_forward, io, x, self.cols, self.rows, with_pre)
+
+    def backward(self, d, io: "IOParams", with_pre: bool = False):
+        return self._mvm(self._lib.aht_backward, io, d, self.rows, self.cols, with_pre)
+
+    @property
+    def mvm_steps(self):
+        f, b = ctypes.c_uint32(), ctypes.c_uint32()
+        _check(self._lib.aht_get_mvm_steps(self._h, ctypes.byref(f), ctypes.byref(b)))
+        return f.value, b.value
+
+    @mvm_steps.setter
+    def mvm_steps(self, fb):
+        _check(self._lib.aht_set_mvm_steps(self._h, ctypes.c_uint32(fb[0]), ctypes.c_uint32(fb[1])))
 
     def set_pulse_mode(self, deterministic: bool = False, dynamic_bl: bool = False):
         _check(self._lib.aht_set_pulse_mode(self._h, int(bool(deterministic)), int(bool(dynamic_bl))))

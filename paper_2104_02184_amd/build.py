@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaht.so")
 SOURCES = [os.path.join(CSRC, "aht.hip")]
-DEPS = SOURCES + [os.path.join(CSRC, "aht_kernels.hpp"), os.path.join(CSRC, "aht_rng.hpp"),
+DEPS = SOURCES + [os.path.join(CSRC, "aht_kernels.hpp"), os.path.join(CSRC, "aht_rng.hpp"), os.path.join(CSRC, "aht_mvm.hpp"),
                   os.path.join(os.path.dirname(HERE), "include", "aht.h")]
 
 FLAGS = [

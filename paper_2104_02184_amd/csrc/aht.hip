@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "aht_kernels.hpp"
+#include "aht_mvm.hpp"
 
 using namespace aht;
 
@@ -39,6 +40,13 @@ struct aht_tile {
     int train_kind = AHT_TRAIN_STOCHASTIC;
     int dynamic_bl = 0;
     unsigned long long* pulse_count = nullptr;
+    // analog matrix-vector product: scratch and call counters
+    float* mvm_xq = nullptr;
+    float* mvm_alpha = nullptr;
+    float* mvm_norm = nullptr;
+    size_t mvm_xq_floats = 0;
+    int mvm_b_cap = 0;
+    uint32_t fwd_step = 0, bwd_step = 0;
     // temporal processes
     bool has_temporal = false;
     aht_temporal_params temporal{};
@@ -368,6 +376,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     for (auto* p : t->planes) rel(p);
     rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->bl_b); rel(t->pulse_count);
     for (auto* p : t->tplanes) rel(p);
+    rel(t->mvm_xq); rel(t->mvm_alpha); rel(t->mvm_norm);
     for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
     delete t;
     if (first != hipSuccess) return hip_fail(first, "aht_tile_destroy");
@@ -424,6 +433,80 @@ aht_status aht_pulsed_update(aht_tile* t, const float* x_dev, const float* d_dev
         }
     }
     t->step += 1;
+    return AHT_OK;
+}
+
+static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* x, float* y, float* pre, int32_t B,
+                             bool transposed, hipStream_t s)
+{
+    if (!t || !io || !x || !y) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (B <= 0) return fail(AHT_ERR_INVALID_ARG, "B must be > 0");
+    if (!finite_nonneg(io->inp_res) || !finite_nonneg(io->inp_noise) || !finite_nonneg(io->w_noise) ||
+        !finite_nonneg(io->out_noise) || !finite_nonneg(io->out_res) || !(io->inp_bound > 0.0f) ||
+        !(io->out_bound > 0.0f))
+        return fail(AHT_ERR_INVALID_ARG, "io parameters must be finite and >= 0, bounds > 0");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    const int K = transposed ? t->rows : t->cols, N = transposed ? t->cols : t->rows;
+    const size_t need = (size_t)B * K;
+    if (need > t->mvm_xq_floats) {
+        if (t->mvm_xq) AHT_HIP(hipFree(t->mvm_xq));
+        t->mvm_xq = nullptr; t->mvm_xq_floats = 0;
+        AHT_HIP(hipMalloc((void**)&t->mvm_xq, need * sizeof(float)));
+        t->mvm_xq_floats = need;
+    }
+    if (B > t->mvm_b_cap) {
+        if (t->mvm_alpha) AHT_HIP(hipFree(t->mvm_alpha));
+        if (t->mvm_norm) AHT_HIP(hipFree(t->mvm_norm));
+        t->mvm_alpha = t->mvm_norm = nullptr; t->mvm_b_cap = 0;
+        AHT_HIP(hipMalloc((void**)&t->mvm_alpha, sizeof(float) * (size_t)B));
+        AHT_HIP(hipMalloc((void**)&t->mvm_norm, sizeof(float) * (size_t)B));
+        t->mvm_b_cap = B;
+    }
+    IoArgs a{io->inp_res, io->inp_bound, io->inp_noise, io->w_noise, io->out_noise, io->out_res, io->out_bound,
+             io->noise_management ? 1 : 0};
+    const uint32_t k0 = (uint32_t)t->seed, k1 = (uint32_t)(t->seed >> 32);
+    const uint32_t step = transposed ? t->bwd_step : t->fwd_step;
+    const uint32_t tag_in = transposed ? 9u : 7u, tag_out = transposed ? 10u : 8u;
+    hipLaunchKernelGGL(k_mvm_prepare, dim3((unsigned)B), dim3(256), 0, s, x, K, a, k0, k1, step, tag_in, t->mvm_xq,
+                       t->mvm_alpha, t->mvm_norm);
+    const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((B + 63) / 64));
+    if (transposed)
+        hipLaunchKernelGGL(k_mvm_gemm<true>, grid, dim3(256), 0, s, t->mvm_xq, t->W, B, N, K, t->cols, t->mvm_alpha,
+                           t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
+    else
+        hipLaunchKernelGGL(k_mvm_gemm<false>, grid, dim3(256), 0, s, t->mvm_xq, t->W, B, N, K, t->cols, t->mvm_alpha,
+                           t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
+    AHT_HIP(hipGetLastError());
+    if (transposed) t->bwd_step += 1; else t->fwd_step += 1;
+    return AHT_OK;
+}
+
+aht_status aht_forward(aht_tile* t, const aht_io_params* io, const float* x_dev, float* y_dev, float* pre_dev,
+                       int32_t B, void* stream)
+{
+    return analog_mvm(t, io, x_dev, y_dev, pre_dev, B, false, (hipStream_t)stream);
+}
+
+aht_status aht_backward(aht_tile* t, const aht_io_params* io, const float* d_dev, float* g_dev, float* pre_dev,
+                        int32_t B, void* stream)
+{
+    return analog_mvm(t, io, d_dev, g_dev, pre_dev, B, true, (hipStream_t)stream);
+}
+
+aht_status aht_get_mvm_steps(const aht_tile* t, uint32_t* f, uint32_t* b)
+{
+    if (!t || !f || !b) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    *f = t->fwd_step;
+    *b = t->bwd_step;
+    return AHT_OK;
+}
+
+aht_status aht_set_mvm_steps(aht_tile* t, uint32_t f, uint32_t b)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    t->fwd_step = f;
+    t->bwd_step = b;
     return AHT_OK;
 }
 

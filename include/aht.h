@@ -118,6 +118,23 @@ aht_status aht_get_weights(const aht_tile* tile, float* w_dev_out, void* stream)
 aht_status aht_pulsed_update(aht_tile* tile, const float* x_dev, const float* d_dev, int32_t B,
                              float lr, void* stream);
 
+/* The pulsed update of a convolution layer mapped on the tile (Sec. 3: convolutions accumulate
+ * their rank-1 updates in analog memory): rows = output channels, cols = Cin * kh * kw, and
+ * every output position of every image is one update vector, applied in the order
+ * b = (n * OH + oy) * OW + ox.  The patches are gathered inside the pulse-train kernel; no
+ * [B][cols] matrix is materialised.
+ *   img_dev  [N][Cin][H][W] fp32 (zero padding `pad` on both sides of H and W)
+ *   grad_dev [N][rows][OH][OW] fp32, OH = (H + 2 pad - kh) / stride + 1, OW likewise
+ * Same semantics, counters and errors as aht_pulsed_update with B = N * OH * OW; additionally
+ * INVALID_ARG if Cin * kh * kw != cols, a size is <= 0, pad < 0, or OH, OW <= 0.
+ * aht_debug_pulse_words_conv2d is the test hook corresponding to aht_debug_pulse_words. */
+aht_status aht_pulsed_update_conv2d(aht_tile* tile, const float* img_dev, const float* grad_dev, int32_t N,
+                                    int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t stride,
+                                    int32_t pad, float lr, void* stream);
+aht_status aht_debug_pulse_words_conv2d(aht_tile* tile, const float* img_dev, const float* grad_dev, int32_t N,
+                                        int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t stride,
+                                        int32_t pad, float lr, uint64_t* xw_dev, uint64_t* dw_dev, void* stream);
+
 /* Alternative pulse-train generators (Sec. 3: "stochastic (or deterministic) pulse trains",
  * "pulse sequences of variable or fixed length").
  *   train_kind  AHT_TRAIN_STOCHASTIC (default): Bernoulli pulses from the counter-based stream.

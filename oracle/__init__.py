@@ -95,6 +95,10 @@ def _declare(L):
     L.orc_pulsed_update_ex.restype = ctypes.c_int64
     L.orc_analog_mvm.argtypes = [_f32p, _i, _i, _i, _f32p, _i] + [_f] * 7 + [_i, _u64, _u32, _f32p, _f32p]
     L.orc_analog_mvm.restype = None
+    L.orc_conv_patches.argtypes = [_f32p] + [_i] * 8 + [_f32p]
+    L.orc_conv_patches.restype = None
+    L.orc_conv_rows.argtypes = [_f32p, _i, _i, _i, _i, _f32p]
+    L.orc_conv_rows.restype = None
     L.orc_temporal_planes.argtypes = [_f] * 6 + [_u64, _i, _i] + [_f32p] * 3
     L.orc_temporal_planes.restype = None
     L.orc_decay_diffuse.argtypes = [_f32p] * 5 + [_u64, _u32, _i, _i]
@@ -309,6 +313,21 @@ def analog_mvm(W, x, io: IOParams, seed, t, transposed=False, return_pre=False):
                          io.inp_noise, io.w_noise, io.out_noise, io.out_res, io.out_bound,
                          int(io.noise_management), seed, t, _p(y, _f32p), _p(pre, _f32p))
     return (y, pre) if return_pre else y
+
+
+def conv_update_vectors(img, dgrad, kh, kw, stride=1, pad=0):
+    """(x[B][Cin*kh*kw], d[B][Cout]) of a convolution layer's update: one update vector per image
+    and output position.  img [N][Cin][H][W], dgrad [N][Cout][OH][OW]."""
+    img, dgrad = _f32(img), _f32(dgrad)
+    N, Cin, H, Wd = img.shape
+    OH, OW = (H + 2 * pad - kh) // stride + 1, (Wd + 2 * pad - kw) // stride + 1
+    assert dgrad.shape[0] == N and dgrad.shape[2:] == (OH, OW)
+    Cout = dgrad.shape[1]
+    x = np.zeros((N * OH * OW, Cin * kh * kw), dtype=np.float32)
+    d = np.zeros((N * OH * OW, Cout), dtype=np.float32)
+    lib().orc_conv_patches(_p(img, _f32p), N, Cin, H, Wd, kh, kw, stride, pad, _p(x, _f32p))
+    lib().orc_conv_rows(_p(dgrad, _f32p), N, Cout, OH, OW, _p(d, _f32p))
+    return x, d
 
 
 @dataclass

@@ -640,3 +640,46 @@ void orc_analog_mvm(const float *W, int R, int C, int transposed, const float *x
         free(xq);
     }
 }
+
+/* ------------------------------------------------------------------------
+ * Convolution layers (Sec. 3: "gradient accumulation happens using parallel update in
+ * analog memory even for batch sizes larger than 1 or in case of convolutions").  A
+ * convolution maps on a tile with one row per output channel and one column per
+ * (input channel, kernel row, kernel column); every output position of every image is one
+ * update vector.  These two functions write the update vectors out explicitly:
+ *   x[b][j],  b = (n*OH + oy)*OW + ox,  j = (c*kh + ky)*kw + kx
+ *           = img[n][c][oy*stride - pad + ky][ox*stride - pad + kx]   (0 outside the image)
+ *   d[b][i] = dgrad[n][i][oy][ox]
+ * with OH = (H + 2 pad - kh)/stride + 1, OW likewise.  The update itself is the ordinary one.
+ * ---------------------------------------------------------------------- */
+void orc_conv_patches(const float *img, int N, int Cin, int H, int Wd, int kh, int kw, int stride,
+                      int pad, float *x)
+{
+    int OH = (H + 2 * pad - kh) / stride + 1, OW = (Wd + 2 * pad - kw) / stride + 1;
+    int J = Cin * kh * kw;
+    for (int n = 0; n < N; ++n)
+        for (int oy = 0; oy < OH; ++oy)
+            for (int ox = 0; ox < OW; ++ox) {
+                size_t b = ((size_t)n * OH + oy) * OW + ox;
+                for (int c = 0; c < Cin; ++c)
+                    for (int ky = 0; ky < kh; ++ky)
+                        for (int kx = 0; kx < kw; ++kx) {
+                            int iy = oy * stride - pad + ky, ix = ox * stride - pad + kx;
+                            float v = 0.0f;
+                            if (iy >= 0 && iy < H && ix >= 0 && ix < Wd)
+                                v = img[(((size_t)n * Cin + c) * H + iy) * Wd + ix];
+                            x[b * J + ((size_t)c * kh + ky) * kw + kx] = v;
+                        }
+            }
+}
+
+void orc_conv_rows(const float *dgrad, int N, int Cout, int OH, int OW, float *d)
+{
+    for (int n = 0; n < N; ++n)
+        for (int i = 0; i < Cout; ++i)
+            for (int oy = 0; oy < OH; ++oy)
+                for (int ox = 0; ox < OW; ++ox) {
+                    size_t b = ((size_t)n * OH + oy) * OW + ox;
+                    d[b * Cout + i] = dgrad[(((size_t)n * Cout + i) * OH + oy) * OW + ox];
+                }
+}

@@ -23,7 +23,7 @@ EXPORTS = (
     "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
     "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
     "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
-    "aht_forward", "aht_backward", "aht_get_mvm_steps", "aht_set_mvm_steps",
+    "aht_pulsed_update_conv2d", "aht_debug_pulse_words_conv2d", "aht_forward", "aht_backward", "aht_get_mvm_steps", "aht_set_mvm_steps",
     "aht_set_pulse_mode", "aht_set_temporal", "aht_decay_diffuse", "aht_reset_columns", "aht_get_temporal_plane",
     "aht_get_temporal_step", "aht_set_temporal_step",
     "aht_status_string", "aht_last_error", "aht_version",
@@ -134,6 +134,8 @@ def load_library() -> ctypes.CDLL:
     L.aht_debug_apply_words.argtypes = [vp, vp, vp, i32, u32, vp]
     L.aht_debug_philox.argtypes = [vp, vp, i32, vp, vp]
     L.aht_debug_gauss.argtypes = [u64, u32, u32, u32, u32, i32, i32, vp, vp]
+    L.aht_pulsed_update_conv2d.argtypes = [vp, vp, vp] + [i32] * 8 + [f32, vp]
+    L.aht_debug_pulse_words_conv2d.argtypes = [vp, vp, vp] + [i32] * 8 + [f32, vp, vp, vp]
     L.aht_forward.argtypes = [vp, ctypes.POINTER(aht_io_params), vp, vp, vp, i32, vp]
     L.aht_backward.argtypes = [vp, ctypes.POINTER(aht_io_params), vp, vp, vp, i32, vp]
     L.aht_get_mvm_steps.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(u32)]
@@ -264,6 +266,31 @@ class Tile:
 
     def set_pulse_mode(self, deterministic: bool = False, dynamic_bl: bool = False):
         _check(self._lib.aht_set_pulse_mode(self._h, int(bool(deterministic)), int(bool(dynamic_bl))))
+
+    def _conv_geometry(self, img, grad, kh, kw, stride, pad):
+        import torch
+        N, Cin, H, W = (int(v) for v in img.shape)
+        OH, OW = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+        ip = _ptr(img, torch.float32, (N, Cin, H, W))
+        gp = _ptr(grad, torch.float32, (N, self.rows, OH, OW))
+        return ip, gp, N, Cin, H, W, OH, OW
+
+    def pulsed_update_conv2d(self, img, grad, kh: int, kw: int, stride: int, pad: int, lr: float):
+        """img [N][Cin][H][W], grad [N][rows][OH][OW]; one update vector per output position."""
+        ip, gp, N, Cin, H, W, _, _ = self._conv_geometry(img, grad, kh, kw, stride, pad)
+        _check(self._lib.aht_pulsed_update_conv2d(self._h, ip, gp, N, Cin, H, W, kh, kw, stride, pad,
+                                                  ctypes.c_float(lr), _stream()))
+
+    def debug_pulse_words_conv2d(self, img, grad, kh: int, kw: int, stride: int, pad: int, lr: float):
+        import torch
+        ip, gp, N, Cin, H, W, OH, OW = self._conv_geometry(img, grad, kh, kw, stride, pad)
+        B = N * OH * OW
+        xw = torch.empty((B, self.cols), dtype=torch.int64, device="cuda")
+        dw = torch.empty((B, self.rows), dtype=torch.int64, device="cuda")
+        _check(self._lib.aht_debug_pulse_words_conv2d(self._h, ip, gp, N, Cin, H, W, kh, kw, stride, pad,
+                                                      ctypes.c_float(lr), _ptr(xw, torch.int64), _ptr(dw, torch.int64),
+                                                      _stream()))
+        return xw, dw
 
     # -- state -----------------------------------------------------------------------------
     @property

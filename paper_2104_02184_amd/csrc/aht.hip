@@ -142,7 +142,7 @@ aht_status ensure_scratch(aht_tile* t, int B)
 
 // pulse trains of the call at step `step` into the tile's scratch
 aht_status launch_words(aht_tile* t, const float* x, const float* d, int B, float lr, uint32_t step,
-                        hipStream_t s)
+                        hipStream_t s, const ConvView& conv = ConvView{})
 {
     const double A = std::sqrt((double)lr / ((double)t->dev.dw_min * (double)t->upd.bl));
     const double *ax = nullptr, *ad = nullptr;
@@ -150,7 +150,7 @@ aht_status launch_words(aht_tile* t, const float* x, const float* d, int B, floa
     if (t->upd.update_management || t->dynamic_bl) {
         hipLaunchKernelGGL(k_line_scale, dim3((unsigned)B), dim3(256), 0, s, x, d, t->rows, t->cols, (double)lr,
                            (double)t->dev.dw_min, t->upd.bl, t->upd.update_management, t->dynamic_bl, t->a_x, t->a_d,
-                           t->dynamic_bl ? t->bl_b : nullptr);
+                           t->dynamic_bl ? t->bl_b : nullptr, conv);
         ax = t->a_x;
         ad = t->a_d;
         blb = t->dynamic_bl ? t->bl_b : nullptr;
@@ -160,10 +160,10 @@ aht_status launch_words(aht_tile* t, const float* x, const float* d, int B, floa
     const dim3 grid(blocks_for((size_t)Cp + Rp), (unsigned)(B < 32768 ? B : 32768));
     if (use_u32(t))
         hipLaunchKernelGGL(k_pulse_words<uint32_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp,
-                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint32_t*)t->xw, (uint32_t*)t->dw);
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint32_t*)t->xw, (uint32_t*)t->dw, conv);
     else
         hipLaunchKernelGGL(k_pulse_words<uint64_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp,
-                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint64_t*)t->xw, (uint64_t*)t->dw);
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint64_t*)t->xw, (uint64_t*)t->dw, conv);
     AHT_HIP(hipGetLastError());
     return AHT_OK;
 }
@@ -403,10 +403,13 @@ aht_status aht_get_weights(const aht_tile* t, float* w_dev_out, void* stream)
     return AHT_OK;
 }
 
-aht_status aht_pulsed_update(aht_tile* t, const float* x_dev, const float* d_dev, int32_t B, float lr, void* stream)
+static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const float* d_dev, int64_t B64, float lr,
+                                     void* stream, const ConvView& conv)
 {
     if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
-    if (B < 0) return fail(AHT_ERR_INVALID_ARG, "B must be >= 0");
+    if (B64 < 0) return fail(AHT_ERR_INVALID_ARG, "B must be >= 0");
+    if (B64 > 0x7FFFFFFF) return fail(AHT_ERR_INVALID_ARG, "too many update vectors for one call");
+    const int B = (int)B64;
     if (!(lr >= 0.0f) || !std::isfinite(lr)) return fail(AHT_ERR_INVALID_ARG, "lr must be finite and >= 0");
     if (B > 0 && (!x_dev || !d_dev)) return fail(AHT_ERR_INVALID_ARG, "null x or d");
     aht_status st = check_device(t);
@@ -424,7 +427,7 @@ aht_status aht_pulsed_update(aht_tile* t, const float* x_dev, const float* d_dev
             ev = &t->events[t->events_used];
         }
         if (ev) AHT_HIP(hipEventRecord(ev[0], s));
-        if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s)) != AHT_OK) return st;
+        if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
         if (ev) AHT_HIP(hipEventRecord(ev[1], s));
         if ((st = launch_cells(t, B, t->step, s)) != AHT_OK) return st;
         if (ev) {
@@ -434,6 +437,40 @@ aht_status aht_pulsed_update(aht_tile* t, const float* x_dev, const float* d_dev
     }
     t->step += 1;
     return AHT_OK;
+}
+
+aht_status aht_pulsed_update(aht_tile* t, const float* x_dev, const float* d_dev, int32_t B, float lr, void* stream)
+{
+    return pulsed_update_impl(t, x_dev, d_dev, B, lr, stream, ConvView{});
+}
+
+// checks the convolution geometry against the tile and fills the view; B = number of update vectors
+static aht_status make_conv_view(const aht_tile* t, int32_t N, int32_t Cin, int32_t H, int32_t W, int32_t kh,
+                                 int32_t kw, int32_t stride, int32_t pad, ConvView* v, int64_t* B)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    if (N < 0 || Cin <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0)
+        return fail(AHT_ERR_INVALID_ARG, "convolution sizes must be positive (pad >= 0)");
+    if ((int64_t)Cin * kh * kw != t->cols)
+        return fail(AHT_ERR_INVALID_ARG, "Cin*kh*kw = %lld does not match the tile's %d columns",
+                    (long long)Cin * kh * kw, t->cols);
+    const int OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1;
+    if (H + 2 * pad < kh || W + 2 * pad < kw || OH <= 0 || OW <= 0)
+        return fail(AHT_ERR_INVALID_ARG, "kernel larger than the padded image");
+    *v = ConvView{1, Cin, H, W, kh, kw, stride, pad, OH, OW, t->rows};
+    *B = (int64_t)N * OH * OW;
+    return AHT_OK;
+}
+
+aht_status aht_pulsed_update_conv2d(aht_tile* t, const float* img_dev, const float* grad_dev, int32_t N, int32_t Cin,
+                                    int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                    float lr, void* stream)
+{
+    ConvView v{};
+    int64_t B = 0;
+    aht_status st = make_conv_view(t, N, Cin, H, W, kh, kw, stride, pad, &v, &B);
+    if (st != AHT_OK) return st;
+    return pulsed_update_impl(t, img_dev, grad_dev, B, lr, stream, v);
 }
 
 static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* x, float* y, float* pre, int32_t B,
@@ -689,17 +726,18 @@ aht_status aht_set_device_planes(aht_tile* t, int32_t plane, const float* dev_in
     return AHT_OK;
 }
 
-aht_status aht_debug_pulse_words(aht_tile* t, const float* x_dev, const float* d_dev, int32_t B, float lr,
-                                 uint64_t* xw_dev, uint64_t* dw_dev, void* stream)
+static aht_status debug_pulse_words_impl(aht_tile* t, const float* x_dev, const float* d_dev, int64_t B64, float lr,
+                                         uint64_t* xw_dev, uint64_t* dw_dev, void* stream, const ConvView& conv)
 {
     if (!t || !x_dev || !d_dev || !xw_dev || !dw_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
-    if (B <= 0) return fail(AHT_ERR_INVALID_ARG, "B must be > 0");
+    if (B64 <= 0 || B64 > 0x7FFFFFFF) return fail(AHT_ERR_INVALID_ARG, "B must be > 0");
+    const int B = (int)B64;
     if (!(lr >= 0.0f) || !std::isfinite(lr)) return fail(AHT_ERR_INVALID_ARG, "lr must be finite and >= 0");
     aht_status st = check_device(t);
     if (st != AHT_OK) return st;
     if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
     hipStream_t s = (hipStream_t)stream;
-    if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s)) != AHT_OK) return st;
+    if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
     const size_t nx = (size_t)B * t->cols, nd = (size_t)B * t->rows;
     if (use_u32(t)) {
         hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint32_t*)t->xw, xw_dev, B, t->cols, cpad(t));
@@ -710,6 +748,23 @@ aht_status aht_debug_pulse_words(aht_tile* t, const float* x_dev, const float* d
     }
     AHT_HIP(hipGetLastError());
     return AHT_OK;
+}
+
+aht_status aht_debug_pulse_words(aht_tile* t, const float* x_dev, const float* d_dev, int32_t B, float lr,
+                                 uint64_t* xw_dev, uint64_t* dw_dev, void* stream)
+{
+    return debug_pulse_words_impl(t, x_dev, d_dev, B, lr, xw_dev, dw_dev, stream, ConvView{});
+}
+
+aht_status aht_debug_pulse_words_conv2d(aht_tile* t, const float* img_dev, const float* grad_dev, int32_t N, int32_t Cin,
+                                        int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                        float lr, uint64_t* xw_dev, uint64_t* dw_dev, void* stream)
+{
+    ConvView v{};
+    int64_t B = 0;
+    aht_status st = make_conv_view(t, N, Cin, H, W, kh, kw, stride, pad, &v, &B);
+    if (st != AHT_OK) return st;
+    return debug_pulse_words_impl(t, img_dev, grad_dev, B, lr, xw_dev, dw_dev, stream, v);
 }
 
 aht_status aht_debug_counts(aht_tile* t, const uint64_t* xw_dev, const uint64_t* dw_dev, int32_t B, int32_t b,

@@ -152,6 +152,49 @@ k_reset_columns(float* __restrict__ W, const float* __restrict__ rplane, float r
 }
 
 // ------------------------------------------------------------------------------------------
+// Update vectors of a convolution layer, gathered on the fly (Sec. 3: convolutions accumulate
+// their positions' rank-1 updates in analog memory).  With conv.enabled the "x" buffer is the
+// input image [N][Cin][H][W] and the "d" buffer the output gradient [N][Cout][OH][OW]; update
+// vector b = (n*OH + oy)*OW + ox has x_b[(c*kh + ky)*kw + kx] = img[n][c][oy*stride-pad+ky][ox*stride-pad+kx]
+// (0 outside the image) and d_b[i] = grad[n][i][oy][ox].  Otherwise x is [B][C] and d is [B][R].
+// ------------------------------------------------------------------------------------------
+struct ConvView {
+    int enabled;
+    int Cin, H, W, kh, kw, stride, pad, OH, OW, Cout;
+};
+
+struct ConvPos {
+    int n, oy, ox;
+};
+
+__device__ __forceinline__ ConvPos conv_pos(const ConvView& v, uint32_t b)
+{
+    ConvPos p;
+    p.ox = (int)(b % (uint32_t)v.OW);
+    const uint32_t t = b / (uint32_t)v.OW;
+    p.oy = (int)(t % (uint32_t)v.OH);
+    p.n = (int)(t / (uint32_t)v.OH);
+    return p;
+}
+
+__device__ __forceinline__ float view_x(const float* __restrict__ x, const ConvView& v, uint32_t b, int j, int C)
+{
+    if (!v.enabled) return x[(size_t)b * C + j];
+    const int kx = j % v.kw, t = j / v.kw, ky = t % v.kh, c = t / v.kh;
+    const ConvPos p = conv_pos(v, b);
+    const int iy = p.oy * v.stride - v.pad + ky, ix = p.ox * v.stride - v.pad + kx;
+    if (iy < 0 || iy >= v.H || ix < 0 || ix >= v.W) return 0.0f;
+    return x[(((size_t)p.n * v.Cin + c) * v.H + iy) * v.W + ix];
+}
+
+__device__ __forceinline__ float view_d(const float* __restrict__ d, const ConvView& v, uint32_t b, int i, int R)
+{
+    if (!v.enabled) return d[(size_t)b * R + i];
+    const ConvPos p = conv_pos(v, b);
+    return d[(((size_t)p.n * v.Cout + i) * v.OH + p.oy) * v.OW + p.ox];
+}
+
+// ------------------------------------------------------------------------------------------
 // Line scaling with update management: one workgroup per update vector.
 // a_x = A sqrt(m_d/m_x), a_d = A sqrt(m_x/m_d); both 0 when a maximum is 0 (sample skipped).
 // With a per-sample train length BL_b = clamp(ceil(lr m_x m_d / dw_min), 1, BL), A uses BL_b.
@@ -166,13 +209,14 @@ __global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
                                                     const float* __restrict__ d, int R, int C,
                                                     double lr, double dw_min, int BL, int update_management,
                                                     int dynamic_bl, double* __restrict__ a_x,
-                                                    double* __restrict__ a_d, int32_t* __restrict__ bl_b)
+                                                    double* __restrict__ a_d, int32_t* __restrict__ bl_b,
+                                                    ConvView conv)
 {
     __shared__ float red_x[4], red_d[4];
     const int b = blockIdx.x;
     float mx = 0.0f, md = 0.0f;
-    for (int j = threadIdx.x; j < C; j += 256) mx = fmaxf(mx, finite_abs_or_zero(x[(size_t)b * C + j]));
-    for (int i = threadIdx.x; i < R; i += 256) md = fmaxf(md, finite_abs_or_zero(d[(size_t)b * R + i]));
+    for (int j = threadIdx.x; j < C; j += 256) mx = fmaxf(mx, finite_abs_or_zero(view_x(x, conv, (uint32_t)b, j, C)));
+    for (int i = threadIdx.x; i < R; i += 256) md = fmaxf(md, finite_abs_or_zero(view_d(d, conv, (uint32_t)b, i, R)));
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         mx = fmaxf(mx, __shfl_xor(mx, off, 64));
@@ -225,7 +269,7 @@ __global__ void __launch_bounds__(256)
 k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int Rpad, int Cpad,
               int BL, double A, const double* __restrict__ a_x, const double* __restrict__ a_d,
               const int32_t* __restrict__ bl_b, int deterministic,
-              uint32_t k0, uint32_t k1, uint32_t t, WordT* __restrict__ xw, WordT* __restrict__ dw)
+              uint32_t k0, uint32_t k1, uint32_t t, WordT* __restrict__ xw, WordT* __restrict__ dw, ConvView conv)
 {
     const int l = (int)(blockIdx.x * 256 + threadIdx.x);
     if (l >= Cpad + Rpad) return;
@@ -236,7 +280,7 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
     for (uint32_t b = blockIdx.y; b < (uint32_t)B; b += gridDim.y) {
         WordT word = 0;
         if (idx < len) {
-            const float v = is_x ? x[(size_t)b * C + idx] : d[(size_t)b * R + idx];
+            const float v = is_x ? view_x(x, conv, b, idx, C) : view_d(d, conv, b, idx, R);
             const double a = a_x ? (is_x ? a_x[b] : a_d[b]) : A;
             const int bl = bl_b ? bl_b[b] : BL;
             const float av = fabsf(v);

@@ -20,7 +20,7 @@ def _lib():
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "aht.h")).read()
-    declared = set(re.findall(r"\b(aht_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(aht_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     L = _lib()
     for name in declared:

@@ -213,6 +213,18 @@ aht_status aht_backward(aht_tile* tile, const aht_io_params* io, const float* d_
 aht_status aht_get_mvm_steps(const aht_tile* tile, uint32_t* forward_calls, uint32_t* backward_calls);
 aht_status aht_set_mvm_steps(aht_tile* tile, uint32_t forward_calls, uint32_t backward_calls);
 
+/* Transfer between two coupled tiles (Sec. 4: "each analog tile of SGD is replaced with two
+ * analog tiles to create a coupled system by exchanging information between the two", the
+ * Tiki-Taka rule of the paper's second listing).  One transfer event reads column `col` of the
+ * fast tile `src` with an analog forward pass of the one-hot vector e_col (non-idealities `io`)
+ * and writes it onto the slow tile `dst` with one pulsed update: dst[:, col] += lr * read, in
+ * the mean, through dst's own device model.  Both tiles must have the same shape and live on
+ * the same device.  Uses and advances src's forward counter and dst's step counter; asynchronous
+ * on `stream`; scratch is owned by `dst`.  Errors: INVALID_ARG (null, shape mismatch, col out
+ * of range, lr < 0), OOM, DEVICE. */
+aht_status aht_transfer_column(aht_tile* src, aht_tile* dst, int32_t col, float lr, const aht_io_params* io,
+                               void* stream);
+
 /* Once-per-mini-batch temporal processes with device-to-device variability (Sec. 4, last
  * paragraph: conductance decay, reset and diffusion).  Per-cell planes are drawn at
  * aht_set_temporal from the tile's seed:

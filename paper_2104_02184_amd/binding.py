@@ -138,6 +138,7 @@ def load_library() -> ctypes.CDLL:
     L.aht_debug_pulse_words_conv2d.argtypes = [vp, vp, vp] + [i32] * 8 + [f32, vp, vp, vp]
     L.aht_forward.argtypes = [vp, ctypes.POINTER(aht_io_params), vp, vp, vp, i32, vp]
     L.aht_backward.argtypes = [vp, ctypes.POINTER(aht_io_params), vp, vp, vp, i32, vp]
+    L.aht_transfer_column.argtypes = [vp, vp, i32, f32, ctypes.POINTER(aht_io_params), vp]
     L.aht_get_mvm_steps.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(u32)]
     L.aht_set_mvm_steps.argtypes = [vp, u32, u32]
     L.aht_set_pulse_mode.argtypes = [vp, i32, i32]
@@ -253,6 +254,11 @@ class Tile:
 
     def backward(self, d, io: "IOParams", with_pre: bool = False):
         return self._mvm(self._lib.aht_backward, io, d, self.rows, self.cols, with_pre)
+
+    def transfer_column_to(self, dst: "Tile", col: int, lr: float, io: "IOParams"):
+        """One Tiki-Taka transfer event: read column `col` of this tile, pulse it onto `dst`."""
+        c = io.to_c()
+        _check(self._lib.aht_transfer_column(self._h, dst._h, col, ctypes.c_float(lr), ctypes.byref(c), _stream()))
 
     @property
     def mvm_steps(self):

@@ -47,6 +47,8 @@ struct aht_tile {
     size_t mvm_xq_floats = 0;
     int mvm_b_cap = 0;
     uint32_t fwd_step = 0, bwd_step = 0;
+    // transfer scratch: one-hot input, read-out, negated read-out
+    float* xfer = nullptr;
     // temporal processes
     bool has_temporal = false;
     aht_temporal_params temporal{};
@@ -376,7 +378,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     for (auto* p : t->planes) rel(p);
     rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->bl_b); rel(t->pulse_count);
     for (auto* p : t->tplanes) rel(p);
-    rel(t->mvm_xq); rel(t->mvm_alpha); rel(t->mvm_norm);
+    rel(t->mvm_xq); rel(t->mvm_alpha); rel(t->mvm_norm); rel(t->xfer);
     for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
     delete t;
     if (first != hipSuccess) return hip_fail(first, "aht_tile_destroy");
@@ -529,6 +531,30 @@ aht_status aht_backward(aht_tile* t, const aht_io_params* io, const float* d_dev
                         int32_t B, void* stream)
 {
     return analog_mvm(t, io, d_dev, g_dev, pre_dev, B, true, (hipStream_t)stream);
+}
+
+aht_status aht_transfer_column(aht_tile* src, aht_tile* dst, int32_t col, float lr, const aht_io_params* io, void* stream)
+{
+    if (!src || !dst || !io) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    if (src == dst) return fail(AHT_ERR_INVALID_ARG, "source and destination must be different tiles");
+    if (src->rows != dst->rows || src->cols != dst->cols || src->device != dst->device)
+        return fail(AHT_ERR_INVALID_ARG, "tiles must have the same shape and device");
+    if (col < 0 || col >= src->cols) return fail(AHT_ERR_INVALID_ARG, "column %d out of range", col);
+    if (!(lr >= 0.0f) || !std::isfinite(lr)) return fail(AHT_ERR_INVALID_ARG, "lr must be finite and >= 0");
+    aht_status st = check_device(dst);
+    if (st != AHT_OK) return st;
+    const int R = dst->rows, C = dst->cols;
+    if (!dst->xfer) AHT_HIP(hipMalloc((void**)&dst->xfer, sizeof(float) * ((size_t)C + 2 * (size_t)R)));
+    float* onehot = dst->xfer;
+    float* read = dst->xfer + C;
+    float* neg = read + R;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_one_hot, dim3(blocks_for((size_t)C)), dim3(256), 0, s, onehot, C, col);
+    AHT_HIP(hipGetLastError());
+    if ((st = analog_mvm(src, io, onehot, read, nullptr, 1, false, s)) != AHT_OK) return st;
+    hipLaunchKernelGGL(k_negate, dim3(blocks_for((size_t)R)), dim3(256), 0, s, read, neg, R);
+    AHT_HIP(hipGetLastError());
+    return pulsed_update_impl(dst, onehot, neg, 1, lr, stream, ConvView{});   // dst -= lr * (-read) e_col^T
 }
 
 aht_status aht_get_mvm_steps(const aht_tile* t, uint32_t* f, uint32_t* b)

@@ -85,6 +85,19 @@ __global__ void __launch_bounds__(256) k_derived_slope(const float* bound, float
     }
 }
 
+// transfer between coupled tiles: the one-hot read vector and the negated read-out
+__global__ void __launch_bounds__(256) k_one_hot(float* x, int n, int hot)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k < n) x[k] = (k == hot) ? 1.0f : 0.0f;
+}
+
+__global__ void __launch_bounds__(256) k_negate(const float* in, float* out, int n)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k < n) out[k] = -in[k];
+}
+
 // ------------------------------------------------------------------------------------------
 // Temporal processes, once per mini-batch (Sec. 4, last paragraph of the paper): decay,
 // diffusion and reset with per-cell parameters.  The planes use Gaussians 6, 7, 8 of the

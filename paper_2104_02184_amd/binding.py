@@ -23,7 +23,8 @@ EXPORTS = (
     "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
     "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
     "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
-    "aht_pulsed_update_conv2d", "aht_debug_pulse_words_conv2d", "aht_forward", "aht_backward", "aht_get_mvm_steps", "aht_set_mvm_steps",
+    "aht_pulsed_update_conv2d", "aht_debug_pulse_words_conv2d", "aht_forward", "aht_backward",
+    "aht_transfer_column", "aht_get_mvm_steps", "aht_set_mvm_steps",
     "aht_set_pulse_mode", "aht_set_temporal", "aht_decay_diffuse", "aht_reset_columns", "aht_get_temporal_plane",
     "aht_get_temporal_step", "aht_set_temporal_step",
     "aht_status_string", "aht_last_error", "aht_version",

@@ -135,8 +135,8 @@ aht_status aht_debug_pulse_words_conv2d(aht_tile* tile, const float* img_dev, co
                                         int32_t Cin, int32_t H, int32_t W, int32_t kh, int32_t kw, int32_t stride,
                                         int32_t pad, float lr, uint64_t* xw_dev, uint64_t* dw_dev, void* stream);
 
-/* Alternative pulse-train generators (Sec. 3: "stochastic (or deterministic) pulse trains",
- * "pulse sequences of variable or fixed length").
+/* Alternative pulse-train generators (Sec. 3 mentions deterministic trains and trains of
+ * variable length beside the stochastic fixed-length ones, without giving their rules).
  *   train_kind  AHT_TRAIN_STOCHASTIC (default): Bernoulli pulses from the counter-based stream.
  *               AHT_TRAIN_DETERMINISTIC: no random numbers; a column line with probability p
  *               fires its first round(bl p) pulses ((n + 1/2)/bl < p), a row line fires pulse n
@@ -213,9 +213,9 @@ aht_status aht_backward(aht_tile* tile, const aht_io_params* io, const float* d_
 aht_status aht_get_mvm_steps(const aht_tile* tile, uint32_t* forward_calls, uint32_t* backward_calls);
 aht_status aht_set_mvm_steps(aht_tile* tile, uint32_t forward_calls, uint32_t backward_calls);
 
-/* Transfer between two coupled tiles (Sec. 4: "each analog tile of SGD is replaced with two
- * analog tiles to create a coupled system by exchanging information between the two", the
- * Tiki-Taka rule of the paper's second listing).  One transfer event reads column `col` of the
+/* Transfer between two coupled tiles (Sec. 4, the Tiki-Taka compound that the paper's second
+ * listing configures: a fast tile takes the gradient updates and hands its content, column by
+ * column, to a slow tile).  One transfer event reads column `col` of the
  * fast tile `src` with an analog forward pass of the one-hot vector e_col (non-idealities `io`)
  * and writes it onto the slow tile `dst` with one pulsed update: dst[:, col] += lr * read, in
  * the mean, through dst's own device model.  Both tiles must have the same shape and live on

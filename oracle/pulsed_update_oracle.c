@@ -181,8 +181,8 @@ void orc_device_planes(int kind, float dw_min, float dw_min_dtod, float up_down,
  * ---------------------------------------------------------------------- */
 static int is_active(float v) { return isfinite(v) && v != 0.0f; }
 
-/* Extended form: dynamic_bl != 0 chooses the train length per sample (reading R14 of the
- * paper's "variable or fixed length"): BL_b = clamp(ceil(lr*m_x*m_d/dw_min), 1, BL), the
+/* Extended form: dynamic_bl != 0 chooses the train length per sample (the paper names
+ * variable-length trains without a rule): BL_b = clamp(ceil(lr*m_x*m_d/dw_min), 1, BL), the
  * shortest train whose largest pulse probabilities stay <= 1 under update management; the
  * factor A uses BL_b.  bl_b may be NULL when dynamic_bl == 0. */
 void orc_line_scale_ex(const float *x, const float *d, int B, int R, int C, float lr, float dw_min,

@@ -262,6 +262,13 @@ aht_status aht_set_temporal_step(aht_tile* tile, uint32_t step);
 aht_status aht_profile_enable(aht_tile* tile, int32_t enable);
 aht_status aht_profile_read(aht_tile* tile, double* ms_words, double* ms_cells, int32_t* calls);
 
+/* Tuning overrides, read from the environment at every call (measurement aids; results do not
+ * depend on them beyond the summation order of the analog product):
+ *   AHT_RPL         rows per lane of the cell-update kernel (1, 2 or 4)
+ *   AHT_QWORDS      32-bit words of pulse-stream storage per cell in LDS
+ *   AHT_MVM_BM      block height of the analog product (64 or 128 input vectors)
+ *   AHT_MVM_SPLITS  number of slices the product's inner dimension is cut into (1..16) */
+
 const char* aht_status_string(aht_status s);
 const char* aht_last_error(void);
 /* Library version string; also tells which architecture the kernels were built for. */

@@ -45,6 +45,8 @@ struct aht_tile {
     float* mvm_alpha = nullptr;
     float* mvm_norm = nullptr;
     size_t mvm_xq_floats = 0;
+    float* mvm_part = nullptr;    // partial sums of a K-split product [splits][B][N]
+    size_t mvm_part_floats = 0;
     int mvm_b_cap = 0;
     uint32_t fwd_step = 0, bwd_step = 0;
     // transfer scratch: one-hot input, read-out, negated read-out
@@ -378,7 +380,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     for (auto* p : t->planes) rel(p);
     rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->bl_b); rel(t->pulse_count);
     for (auto* p : t->tplanes) rel(p);
-    rel(t->mvm_xq); rel(t->mvm_alpha); rel(t->mvm_norm); rel(t->xfer);
+    rel(t->mvm_xq); rel(t->mvm_part); rel(t->mvm_alpha); rel(t->mvm_norm); rel(t->xfer);
     for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
     delete t;
     if (first != hipSuccess) return hip_fail(first, "aht_tile_destroy");
@@ -507,15 +509,54 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     const uint32_t k0 = (uint32_t)t->seed, k1 = (uint32_t)(t->seed >> 32);
     const uint32_t step = transposed ? t->bwd_step : t->fwd_step;
     const uint32_t tag_in = transposed ? 9u : 7u, tag_out = transposed ? 10u : 8u;
-    hipLaunchKernelGGL(k_mvm_prepare, dim3((unsigned)B), dim3(256), 0, s, x, K, a, k0, k1, step, tag_in, t->mvm_xq,
-                       t->mvm_alpha, t->mvm_norm);
-    const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((B + 63) / 64));
-    if (transposed)
-        hipLaunchKernelGGL(k_mvm_gemm<true>, grid, dim3(256), 0, s, t->mvm_xq, t->W, B, N, K, t->cols, t->mvm_alpha,
-                           t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
-    else
-        hipLaunchKernelGGL(k_mvm_gemm<false>, grid, dim3(256), 0, s, t->mvm_xq, t->W, B, N, K, t->cols, t->mvm_alpha,
-                           t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
+    const int vec_in = (K % 4 == 0) && (((uintptr_t)x | (uintptr_t)t->mvm_xq) % 16 == 0);
+    hipLaunchKernelGGL(k_mvm_prepare, dim3((unsigned)B), dim3(1024), 0, s, x, K, vec_in, a, k0, k1, step, tag_in,
+                       t->mvm_xq, t->mvm_alpha, t->mvm_norm);
+    // Block height 128 when the batch fills it; K split aiming at two workgroups of 64 rows per
+    // compute unit or one of 128 rows (measured optimum: more slices only add partial-sum
+    // traffic), at least four K steps per slice.
+    int bm = (B > 64) ? 128 : 64;
+    if (const int e = env_int("AHT_MVM_BM", 0)) bm = (e == 128) ? 128 : 64;
+    const int mb = (B + bm - 1) / bm, nb = (N + 63) / 64, nchunks = (K + 31) / 32;
+    int splits = env_int("AHT_MVM_SPLITS", 0);
+    if (splits <= 0) {
+        const long tiles = (long)mb * nb, want = (bm == 128) ? 256 : 512;
+        splits = (int)((want + tiles - 1) / tiles);
+        if (splits > nchunks / 4) splits = nchunks / 4;
+    }
+    if (splits > 16) splits = 16;
+    if (splits < 1) splits = 1;
+    if (splits > 1) {
+        const size_t pneed = (size_t)splits * (size_t)B * (size_t)N;
+        if (pneed > t->mvm_part_floats) {
+            if (t->mvm_part) AHT_HIP(hipFree(t->mvm_part));
+            t->mvm_part = nullptr; t->mvm_part_floats = 0;
+            AHT_HIP(hipMalloc((void**)&t->mvm_part, pneed * sizeof(float)));
+            t->mvm_part_floats = pneed;
+        }
+    }
+    const unsigned total = (unsigned)mb * (unsigned)nb * (unsigned)splits;
+    const dim3 grid(((total + 7u) / 8u) * 8u);
+    // 16-byte accesses need aligned rows and whole groups; the tile's weights start 256-byte aligned
+    const bool aligned = (K % 32 == 0) && (t->cols % 4 == 0) && (N % 4 == 0) &&
+                         (((uintptr_t)t->mvm_xq | (uintptr_t)t->W) % 16 == 0);
+#define AHT_MVM_LAUNCH(TR, BMV, AL)                                                                              \
+    hipLaunchKernelGGL((k_mvm_gemm<TR, BMV, AL>), grid, dim3(256), 0, s, t->mvm_xq, t->W, B, N, K, t->cols,       \
+                       t->mvm_alpha, t->mvm_norm, a, k0, k1, step, tag_out, y, pre, t->mvm_part, splits, mb, nb)
+#define AHT_MVM_PICK(TR)                                                                                         \
+    do {                                                                                                         \
+        if (bm == 128) { if (aligned) AHT_MVM_LAUNCH(TR, 128, true); else AHT_MVM_LAUNCH(TR, 128, false); }      \
+        else { if (aligned) AHT_MVM_LAUNCH(TR, 64, true); else AHT_MVM_LAUNCH(TR, 64, false); }                  \
+    } while (0)
+    if (transposed) AHT_MVM_PICK(true); else AHT_MVM_PICK(false);
+#undef AHT_MVM_PICK
+#undef AHT_MVM_LAUNCH
+    if (splits > 1) {
+        AHT_HIP(hipGetLastError());
+        const size_t pairs = (size_t)B * (size_t)((N + 1) / 2);
+        hipLaunchKernelGGL(k_mvm_epilogue, dim3(blocks_for(pairs)), dim3(256), 0, s, t->mvm_part, splits, B, N,
+                           t->mvm_alpha, t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
+    }
     AHT_HIP(hipGetLastError());
     if (transposed) t->bwd_step += 1; else t->fwd_step += 1;
     return AHT_OK;

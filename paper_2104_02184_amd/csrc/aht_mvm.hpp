@@ -4,9 +4,10 @@
 //   k_mvm_prepare  per input vector: dynamic scaling alpha = max|x|, DAC (clip, round to the
 //                  input grid), input noise, and |xq|_2 for the output-referred weight noise
 //   k_mvm_gemm     Z = Xq * W^T (forward) or Xq * W (backward) on the fp32 matrix cores
-//                  (v_mfma_f32_32x32x2_f32, 64x64 block tiles staged through LDS), with the
-//                  epilogue fused: weight noise, output noise, ADC (clip, round to the output
-//                  grid), rescale by alpha.
+//                  (v_mfma_f32_32x32x2_f32, 64x64 block tiles staged through LDS, the K range
+//                  split over several workgroups when there are few tiles)
+//   epilogue       weight noise, output noise, ADC (clip, round to the output grid), rescale
+//                  by alpha: fused into k_mvm_gemm, or k_mvm_epilogue after a K-split product
 // Random numbers: input j of vector b takes Gaussian (j & 3) of block (j >> 2, b, call counter,
 // tag 7 forward / 9 backward); output i takes Gaussians 2(i & 1) (output noise) and 2(i & 1) + 1
 // (weight noise) of block (i >> 1, b, call counter, tag 8 / 10).
@@ -23,181 +24,316 @@ struct IoArgs {
     int noise_management;
 };
 
-// one workgroup per input vector
-__global__ void __launch_bounds__(256)
-k_mvm_prepare(const float* __restrict__ x, int K, IoArgs io, uint32_t k0, uint32_t k1, uint32_t t, uint32_t tag,
-              float* __restrict__ xq, float* __restrict__ alpha_out, float* __restrict__ norm_out)
+// one workgroup of 1024 lanes per input vector; a lane handles groups of four neighbouring
+// inputs (one Philox block each), with 16-byte accesses when `vec` (K a multiple of 4, aligned)
+__global__ void __launch_bounds__(1024)
+k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k0, uint32_t k1, uint32_t t,
+              uint32_t tag, float* __restrict__ xq, float* __restrict__ alpha_out, float* __restrict__ norm_out)
 {
-    __shared__ float red[4];
-    __shared__ double redd[4];
-    const int b = blockIdx.x;
+    __shared__ float red[16];
+    __shared__ double redd[16];
+    const int b = blockIdx.x, tid = threadIdx.x;
     const float* xr = x + (size_t)b * K;
+    float* qr = xq + (size_t)b * K;
+    const int groups = (K + 3) >> 2;
+    auto load_group = [&](int g, float (&v)[4]) __attribute__((always_inline)) {
+        if (vec) {
+            const float4 q = *(const float4*)(xr + 4 * (size_t)g);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (4 * g + e < K) ? xr[4 * (size_t)g + e] : 0.0f;
+        }
+    };
     float alpha = 1.0f;
     if (io.noise_management) {
         float m = 0.0f;
-        for (int j = threadIdx.x; j < K; j += 256) {
-            const float a = fabsf(xr[j]);
-            m = fmaxf(m, (a < __builtin_inff()) ? a : 0.0f);
+        for (int g = tid; g < groups; g += 1024) {
+            float v[4];
+            load_group(g, v);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a = fabsf(v[e]);
+                m = fmaxf(m, (a < __builtin_inff()) ? a : 0.0f);
+            }
         }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+        if ((tid & 63) == 0) red[tid >> 6] = m;
         __syncthreads();
-        alpha = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        alpha = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) alpha = fmaxf(alpha, red[w]);
     }
     double part = 0.0;
-    for (int g = threadIdx.x; g * 4 < K; g += 256) {      // four inputs share one Philox block
+    for (int g = tid; g < groups; g += 1024) {            // four inputs share one Philox block
         float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         if (io.inp_noise > 0.0f) gauss4_fast(k0, k1, (uint32_t)g, (uint32_t)b, t, tag, z);
+        float v[4], o[4];
+        load_group(g, v);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int j = g * 4 + e;
-            if (j < K) {
-                float v = xr[j];
-                if (!(fabsf(v) < __builtin_inff()) || alpha == 0.0f) v = 0.0f;
-                float xh = (alpha != 0.0f) ? v / alpha : 0.0f;
-                xh = fminf(fmaxf(xh, -io.inp_bound), io.inp_bound);
-                if (io.inp_res > 0.0f) xh = rintf(xh / io.inp_res) * io.inp_res;
-                if (io.inp_noise > 0.0f) {
-                    const float nz = io.inp_noise * z[e];
-                    xh = xh + nz;
-                }
-                xq[(size_t)b * K + j] = xh;
-                part += (double)xh * (double)xh;
+            float u = v[e];
+            if (!(fabsf(u) < __builtin_inff()) || alpha == 0.0f) u = 0.0f;
+            float xh = (alpha != 0.0f) ? u / alpha : 0.0f;
+            xh = fminf(fmaxf(xh, -io.inp_bound), io.inp_bound);
+            if (io.inp_res > 0.0f) xh = rintf(xh / io.inp_res) * io.inp_res;
+            if (io.inp_noise > 0.0f) {
+                const float nz = io.inp_noise * z[e];
+                xh = xh + nz;
             }
+            o[e] = xh;
+            if (4 * g + e < K) part += (double)xh * (double)xh;
+        }
+        if (vec) {
+            *(float4*)(qr + 4 * (size_t)g) = make_float4(o[0], o[1], o[2], o[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * g + e < K) qr[4 * (size_t)g + e] = o[e];
         }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
-    if ((threadIdx.x & 63) == 0) redd[threadIdx.x >> 6] = part;
+    if ((tid & 63) == 0) redd[tid >> 6] = part;
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (tid == 0) {
+        double sum = 0.0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) sum += redd[w];
         alpha_out[b] = alpha;
-        norm_out[b] = (float)sqrt(redd[0] + redd[1] + redd[2] + redd[3]);
+        norm_out[b] = (float)sqrt(sum);
     }
 }
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-// Z[M][N] = A[M][K] * Bm, Bm[k][n] = TRANS ? Wm[k*ldw + n] : Wm[n*ldw + k]; fused analog epilogue.
-// Block tile 64 x 64, K step 32; four waves, each a 32 x 32 tile of v_mfma_f32_32x32x2_f32.
-template <bool TRANS>
+// Noise, ADC and rescaling of one pre-activation z = (Xq W^T)[m][n]; g_out / g_w are the output's
+// two Gaussians.
+__device__ __forceinline__ void mvm_finish(float z, float g_out, float g_w, bool noisy, const IoArgs& io, float norm_m,
+                                           float alpha_m, size_t at, float* __restrict__ y, float* __restrict__ pre)
+{
+    if (noisy) {
+        float wn_ = io.w_noise * norm_m;
+        wn_ = wn_ * g_w;
+        z = z + wn_;
+        const float on = io.out_noise * g_out;
+        z = z + on;
+    }
+    if (pre) pre[at] = z;
+    float q = fminf(fmaxf(z, -io.out_bound), io.out_bound);
+    if (io.out_res > 0.0f) q = rintf(q / io.out_res) * io.out_res;
+    y[at] = alpha_m * q;
+}
+
+// Z[M][N] = A[M][K] * Bm, Bm[k][n] = TRANS ? Wm[k*ldw + n] : Wm[n*ldw + k].
+// Block tile BM x 64 (BM = 64 or 128), K step 32; four waves, each BM/2 x 32 outputs as one or
+// two 32 x 32 tiles of v_mfma_f32_32x32x2_f32.
+//
+// Operand order inside a K step.  One matrix instruction multiplies, per lane half h = lane/32,
+// one k index.  Which of the step's 32 k values a half takes is free as long as both operands
+// agree, so half h takes k = 16 h + s at instruction s: a lane then needs 16 consecutive k of
+// its row, which are four 16-byte LDS reads from a tile kept in the matrix' own k-contiguous
+// order (rows padded to 36 floats: conflict-free for 16-byte accesses).  No transposition on
+// the way into LDS either: 16-byte global loads, 16-byte LDS stores.  In the transposed product
+// the weights are n-contiguous; their tile is [k][n] (rows of 68 floats) and a lane reads its 16
+// k values one by one, 32 lanes side by side.
+//
+// K split.  The K range is cut into `splits` slices, one workgroup per (tile, slice), so that a
+// product with few output tiles (a batch of 256 vectors against 4096 rows gives one 64 x 64 tile
+// per compute unit) still puts several workgroups on every compute unit, whose loads, barriers
+// and matrix instructions overlap.  splits == 1: the analog epilogue is fused.  splits > 1:
+// slice z writes its partial sums to part[z][M][N] and k_mvm_epilogue adds them in slice order.
+//
+// Workgroup ids go round-robin to the 8 XCDs; the id -> (tile, slice) map gives each XCD a
+// contiguous range with the row blocks of A fastest, so that the workgroups sharing a tile of
+// the weights run together on one L2.
+//
+// ALIGNED: K is a multiple of 32 and every 16-byte group is aligned and inside its row.  Rows
+// m >= M and n >= N of a ragged edge tile are read from the last valid row instead (their
+// outputs are never stored).  Otherwise elements are loaded one by one with k >= K as zero.
+template <bool TRANS, int BM, bool ALIGNED>
 __global__ void __launch_bounds__(256)
 k_mvm_gemm(const float* __restrict__ A, const float* __restrict__ Wm, int M, int N, int K, int ldw,
            const float* __restrict__ alpha, const float* __restrict__ norm, IoArgs io, uint32_t k0, uint32_t k1,
-           uint32_t t, uint32_t tag, float* __restrict__ y, float* __restrict__ pre)
+           uint32_t t, uint32_t tag, float* __restrict__ y, float* __restrict__ pre, float* __restrict__ part,
+           int splits, int mb, int nb)
 {
-    constexpr int BM = 64, BN = 64, BK = 32, LD = 65;      // LD: padded row length of the k-major LDS tiles
-    __shared__ float As[2][BK][LD];
-    __shared__ float Bs[2][BK][LD];
+    constexpr int BN = 64, BK = 32, LDK = 36, LDN = 68;
+    constexpr int AH = BM / 32;                   // 16-byte groups of A per thread and K step (2 or 4)
+    constexpr int NACC = BM / 64;                 // 32 x 32 tiles per wave
+    constexpr int kBsFloats = TRANS ? BK * LDN : BN * LDK;
+    __shared__ __align__(16) float As[2][BM * LDK];
+    __shared__ __align__(16) float Bs[2][kBsFloats];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
 
-    // staging: every thread moves two groups of four consecutive k (or n) values per operand
-    float ra[2][4], rb[2][4];
-    // 16-byte loads when every row start and every group of four is aligned and inside the matrix
-    const bool vec_a = (K & 3) == 0, vec_w = (ldw & 3) == 0 && (TRANS ? (N & 3) == 0 : (K & 3) == 0);
+    const uint32_t total = (uint32_t)mb * (uint32_t)nb * (uint32_t)splits;
+    const uint32_t per = (total + 7u) >> 3;
+    const uint32_t seq = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
+    if (seq >= total) return;
+    const uint32_t mblk = seq % (uint32_t)mb, rest = seq / (uint32_t)mb;
+    const uint32_t z = rest % (uint32_t)splits, nblk = rest / (uint32_t)splits;
+    const int m0 = (int)mblk * BM, n0 = (int)nblk * BN;
+    const int nchunks = (K + BK - 1) / BK;
+    const int cps = (nchunks + splits - 1) / splits;
+    const int c_begin = (int)z * cps, c_end = (c_begin + cps < nchunks) ? c_begin + cps : nchunks;
+
+    // element (row, k) of a k-contiguous matrix with `rows` rows of length `ld`; rows are clamped
+    auto load4 = [&](const float* __restrict__ base, int row, int rows, int ld, int kk) __attribute__((always_inline)) {
+        const int r = row < rows ? row : rows - 1;
+        if (ALIGNED) return *(const float4*)(base + (size_t)r * ld + kk);
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool ok = kk + e < K;
+            const float x = base[(size_t)r * ld + (ok ? kk + e : 0)];
+            v[e] = ok ? x : 0.0f;
+        }
+        return make_float4(v[0], v[1], v[2], v[3]);
+    };
+    // 16-byte group of the transposed product's weights W[k][n] (n contiguous)
+    auto load4_t = [&](int kr, int nn) __attribute__((always_inline)) {
+        if (ALIGNED) {
+            const int nc = nn + 3 < N ? nn : N - 4;                  // N is a multiple of 4 here
+            return *(const float4*)(Wm + (size_t)kr * ldw + nc);
+        }
+        const bool kok = kr < K;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int nc = nn + e < N ? nn + e : N - 1;
+            const float x = Wm[(size_t)(kok ? kr : 0) * ldw + nc];
+            v[e] = kok ? x : 0.0f;
+        }
+        return make_float4(v[0], v[1], v[2], v[3]);
+    };
+    float4 ra0, ra1, ra2 = {}, ra3 = {}, rb0, rb1;
     auto fetch = [&](int kc) __attribute__((always_inline)) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            {   // A: rows m, k contiguous
-                const int row = (tid >> 3) + 32 * h, kk = kc + (tid & 7) * 4;
-                const int m = m0 + row;
-                if (vec_a && m < M && kk + 3 < K) {
-                    const float4 v = *(const float4*)(A + (size_t)m * K + kk);
-                    ra[h][0] = v.x; ra[h][1] = v.y; ra[h][2] = v.z; ra[h][3] = v.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        ra[h][e] = (m < M && kk + e < K) ? A[(size_t)m * K + kk + e] : 0.0f;
-                }
-            }
-            if (!TRANS) {   // W[n][k], k contiguous
-                const int row = (tid >> 3) + 32 * h, kk = kc + (tid & 7) * 4;
-                const int n = n0 + row;
-                if (vec_w && n < N && kk + 3 < K) {
-                    const float4 v = *(const float4*)(Wm + (size_t)n * ldw + kk);
-                    rb[h][0] = v.x; rb[h][1] = v.y; rb[h][2] = v.z; rb[h][3] = v.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        rb[h][e] = (n < N && kk + e < K) ? Wm[(size_t)n * ldw + kk + e] : 0.0f;
-                }
-            } else {        // W[k][n], n contiguous
-                const int krow = (tid >> 4) + 16 * h, nn = n0 + (tid & 15) * 4;
-                const int kk = kc + krow;
-                if (vec_w && kk < K && nn + 3 < N) {
-                    const float4 v = *(const float4*)(Wm + (size_t)kk * ldw + nn);
-                    rb[h][0] = v.x; rb[h][1] = v.y; rb[h][2] = v.z; rb[h][3] = v.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        rb[h][e] = (kk < K && nn + e < N) ? Wm[(size_t)kk * ldw + nn + e] : 0.0f;
-                }
-            }
+        const int kk = kc + (tid & 7) * 4, row = tid >> 3;
+        ra0 = load4(A, m0 + row, M, K, kk);
+        ra1 = load4(A, m0 + row + 32, M, K, kk);
+        if (AH == 4) {
+            ra2 = load4(A, m0 + row + 64, M, K, kk);
+            ra3 = load4(A, m0 + row + 96, M, K, kk);
+        }
+        if (!TRANS) {
+            rb0 = load4(Wm, n0 + row, N, ldw, kk);
+            rb1 = load4(Wm, n0 + row + 32, N, ldw, kk);
+        } else {
+            rb0 = load4_t(kc + (tid >> 4), n0 + (tid & 15) * 4);
+            rb1 = load4_t(kc + (tid >> 4) + 16, n0 + (tid & 15) * 4);
         }
     };
     auto stage = [&](int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int row = (tid >> 3) + 32 * h, kq = (tid & 7) * 4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) As[buf][kq + e][row] = ra[h][e];
-            if (!TRANS) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) Bs[buf][kq + e][row] = rb[h][e];
-            } else {
-                const int krow = (tid >> 4) + 16 * h, nq = (tid & 15) * 4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) Bs[buf][krow][nq + e] = rb[h][e];
-            }
+        float* ap = &As[buf][(tid >> 3) * LDK + (tid & 7) * 4];
+        *(float4*)ap = ra0;
+        *(float4*)(ap + 32 * LDK) = ra1;
+        if (AH == 4) {
+            *(float4*)(ap + 64 * LDK) = ra2;
+            *(float4*)(ap + 96 * LDK) = ra3;
+        }
+        if (!TRANS) {
+            float* bp = &Bs[buf][(tid >> 3) * LDK + (tid & 7) * 4];
+            *(float4*)bp = rb0;
+            *(float4*)(bp + 32 * LDK) = rb1;
+        } else {
+            float* bp = &Bs[buf][(tid >> 4) * LDN + (tid & 15) * 4];
+            *(float4*)bp = rb0;
+            *(float4*)(bp + 16 * LDN) = rb1;
         }
     };
 
-    floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    fetch(0);
-    stage(0);
-    __syncthreads();
-    const int nchunks = (K + BK - 1) / BK;
-    for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
-        if (c + 1 < nchunks) fetch((c + 1) * BK);           // global loads in flight during the MFMAs
-        const int arow = wm * 32 + (lane & 31), brow = wn * 32 + (lane & 31), kh = lane >> 5;
+    floatx16 acc[NACC];
 #pragma unroll
-        for (int s = 0; s < BK / 2; ++s) {
-            const float av = As[buf][2 * s + kh][arow];
-            const float bv = Bs[buf][2 * s + kh][brow];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
-        }
-        if (c + 1 < nchunks) stage(buf ^ 1);
+    for (int i = 0; i < NACC; ++i) acc[i] = floatx16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    if (c_begin < c_end) {                                  // block-uniform
+        fetch(c_begin * BK);
+        stage(0);
         __syncthreads();
+        const int kh = lane >> 5, l32 = lane & 31;
+        for (int c = c_begin; c < c_end; ++c) {
+            const int buf = (c - c_begin) & 1;
+            if (c + 1 < c_end) fetch((c + 1) * BK);         // global loads in flight during the MFMAs
+            float av[NACC][16], bv[16];
+#pragma unroll
+            for (int i = 0; i < NACC; ++i) {
+                const float* ap = &As[buf][(wm * (BM / 2) + 32 * i + l32) * LDK + 16 * kh];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = *(const float4*)(ap + 4 * q);
+                    av[i][4 * q] = v.x; av[i][4 * q + 1] = v.y; av[i][4 * q + 2] = v.z; av[i][4 * q + 3] = v.w;
+                }
+            }
+            if (!TRANS) {
+                const float* bp = &Bs[buf][(wn * 32 + l32) * LDK + 16 * kh];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = *(const float4*)(bp + 4 * q);
+                    bv[4 * q] = v.x; bv[4 * q + 1] = v.y; bv[4 * q + 2] = v.z; bv[4 * q + 3] = v.w;
+                }
+            } else {
+                const float* bp = &Bs[buf][(16 * kh) * LDN + wn * 32 + l32];
+#pragma unroll
+                for (int s = 0; s < 16; ++s) bv[s] = bp[s * LDN];
+            }
+            __builtin_amdgcn_sched_barrier(0);              // all LDS reads of the step are issued first
+#pragma unroll
+            for (int s = 0; s < 16; ++s)
+#pragma unroll
+                for (int i = 0; i < NACC; ++i)
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][s], bv[s], acc[i], 0, 0, 0);
+            if (c + 1 < c_end) stage(buf ^ 1);
+            __syncthreads();
+        }
     }
 
-    // epilogue: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of the wave's tile
+    // register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of a 32 x 32 tile
     const int n = n0 + wn * 32 + (lane & 31);
     const bool noisy = (io.w_noise > 0.0f) || (io.out_noise > 0.0f);
+    float* __restrict__ pz = (splits > 1) ? part + (size_t)z * (size_t)M * (size_t)N : nullptr;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m < M && n < N) {
-            float z = acc[r];
-            if (noisy) {
-                float g[4];
-                gauss4_fast(k0, k1, (uint32_t)n >> 1, (uint32_t)m, t, tag, g);
-                const float g_out = (n & 1) ? g[2] : g[0], g_w = (n & 1) ? g[3] : g[1];
-                float wn_ = io.w_noise * norm[m];
-                wn_ = wn_ * g_w;
-                z = z + wn_;
-                const float on = io.out_noise * g_out;
-                z = z + on;
+    for (int i = 0; i < NACC; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + wm * (BM / 2) + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (m < M && n < N) {
+                if (pz) {
+                    pz[(size_t)m * N + n] = acc[i][r];
+                } else {
+                    float g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (noisy) gauss4_fast(k0, k1, (uint32_t)n >> 1, (uint32_t)m, t, tag, g);
+                    mvm_finish(acc[i][r], (n & 1) ? g[2] : g[0], (n & 1) ? g[3] : g[1], noisy, io, norm[m], alpha[m],
+                               (size_t)m * N + n, y, pre);
+                }
             }
-            if (pre) pre[(size_t)m * N + n] = z;
-            float q = fminf(fmaxf(z, -io.out_bound), io.out_bound);
-            if (io.out_res > 0.0f) q = rintf(q / io.out_res) * io.out_res;
-            y[(size_t)m * N + n] = alpha[m] * q;
         }
     }
+}
+
+// Second pass of a K-split product: one thread per pair of neighbouring outputs (they share one
+// Philox block) adds the slices' partial sums in slice order and applies the analog epilogue.
+__global__ void __launch_bounds__(256)
+k_mvm_epilogue(const float* __restrict__ part, int splits, int M, int N, const float* __restrict__ alpha,
+               const float* __restrict__ norm, IoArgs io, uint32_t k0, uint32_t k1, uint32_t t, uint32_t tag,
+               float* __restrict__ y, float* __restrict__ pre)
+{
+    const int half = (N + 1) >> 1;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)M * half) return;
+    const int m = (int)(idx / half), n = 2 * (int)(idx % half);
+    const size_t at = (size_t)m * N + n, plane = (size_t)M * N;
+    const bool two = n + 1 < N;
+    float z0 = 0.0f, z1 = 0.0f;
+    for (int s = 0; s < splits; ++s) {
+        z0 += part[(size_t)s * plane + at];
+        if (two) z1 += part[(size_t)s * plane + at + 1];
+    }
+    const bool noisy = (io.w_noise > 0.0f) || (io.out_noise > 0.0f);
+    float g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (noisy) gauss4_fast(k0, k1, (uint32_t)n >> 1, (uint32_t)m, t, tag, g);
+    mvm_finish(z0, g[0], g[1], noisy, io, norm[m], alpha[m], at, y, pre);
+    if (two) mvm_finish(z1, g[2], g[3], noisy, io, norm[m], alpha[m], at + 1, y, pre);
 }
 
 }  // namespace aht

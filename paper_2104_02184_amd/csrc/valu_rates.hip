@@ -124,6 +124,39 @@ __global__ void __launch_bounds__(256) k_ldsw8(uint32_t* out, uint32_t seed) {
     if (buf[threadIdx.x*68] == 77 && seed == 99999) out[0] = 1;
 }
 
+// fp32 matrix-core rate: v_mfma_f32_32x32x2_f32 (4096 flops per wave instruction), NCHAIN
+// independent accumulators per wave.  Calibrates the roofline of the analog product.
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+template <int NCHAIN>
+__global__ void __launch_bounds__(256) k_mfma(uint32_t* out, uint32_t seed) {
+    floatx16 acc[NCHAIN];
+    for (int c = 0; c < NCHAIN; ++c)
+        for (int r = 0; r < 16; ++r) acc[c][r] = (float)(threadIdx.x + c + r);
+    const float a = (float)(seed | 1), b = 1.0f / (float)(seed | 3);
+    for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+        for (int c = 0; c < NCHAIN; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[c], 0, 0, 0);
+    }
+    float s = 0.0f;
+    for (int c = 0; c < NCHAIN; ++c)
+        for (int r = 0; r < 16; ++r) s += acc[c][r];
+    if (s == 12345.0f) out[0] = 1;
+}
+template <typename K> int run_mfma(const char* name, K kern, int nchain, int wg_per_cu, uint32_t* out) {
+    const int blocks = 256 * wg_per_cu, threads = 256;
+    hipEvent_t e0, e1; CHK(hipEventCreate(&e0)); CHK(hipEventCreate(&e1));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, out, 1u);
+    CHK(hipDeviceSynchronize());
+    CHK(hipEventRecord(e0));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, out, 1u);
+    CHK(hipEventRecord(e1)); CHK(hipEventSynchronize(e1));
+    float ms; CHK(hipEventElapsedTime(&ms, e0, e1));
+    const double flops = (double)blocks * (threads / 64) * ITERS * nchain * 4096.0;
+    printf("%-22s %8.3f ms  %8.2f TFLOP/s  (%.3f of 157.3)\n", name, ms, flops / ms / 1e9, flops / ms / 1e9 / 157.3);
+    fflush(stdout);
+    return 0;
+}
+
 template <typename K> int run(const char* name, K kern, double ops_per_thread_iter, uint32_t* out) {
     const int blocks = 256 * 8, threads = 256;  // 8 WG/CU -> 8 waves per SIMD
     hipEvent_t e0, e1; CHK(hipEventCreate(&e0)); CHK(hipEventCreate(&e1));
@@ -155,6 +188,10 @@ int main() {
     run("v_xor", k_xor, 8, out); run("v_or", k_or, 8, out); run("v_sub", k_sub, 8, out); run("v_max_f32", k_maxf, 8, out);
     run("v_cmp_gt", k_cmpgt, 8, out); run("v_cnd_e64", k_cnd64, 8, out); run("v_alignbit", k_alignbit, 8, out);
     run("v_lshl_b64", k_lshl64, 8, out);
+    run_mfma("mfma32x32x2 1ch 1wg/cu", k_mfma<1>, 1, 1, out);
+    run_mfma("mfma32x32x2 1ch 4wg/cu", k_mfma<1>, 1, 4, out);
+    run_mfma("mfma32x32x2 2ch 2wg/cu", k_mfma<2>, 2, 2, out);
+    run_mfma("mfma32x32x2 4ch 1wg/cu", k_mfma<4>, 4, 1, out);
     run("log+fma", k_logfma, 16, out); run("log+2fma", k_logfma2, 24, out); run("log+2and", k_logand2, 24, out);
     return 0;
 }

@@ -82,6 +82,21 @@ def test_noisy_quantised_product_matches(R, C, B, transposed):
     tile.close()
 
 
+@pytest.mark.parametrize("bm,splits", [(64, 1), (64, 3), (128, 1), (128, 2), (128, 16)])
+@pytest.mark.parametrize("R,C,B", [(130, 268, 70), (192, 256, 130)])
+@pytest.mark.parametrize("transposed", [False, True])
+def test_block_height_and_inner_split_do_not_change_the_result(R, C, B, transposed, bm, splits, monkeypatch):
+    """Every block height and every number of slices of the inner dimension (partial sums added
+    in a second pass) gives the oracle's product; ragged and whole tiles, both directions."""
+    monkeypatch.setenv("AHT_MVM_BM", str(bm))
+    monkeypatch.setenv("AHT_MVM_SPLITS", str(splits))
+    tile, W = _tile_with_weights(R, C)
+    g = np.random.default_rng(R + C + B + bm + splits)
+    x = g.normal(size=(B, R if transposed else C)).astype(np.float32)
+    _check(tile, W, x, NOISY, transposed, step=2)
+    tile.close()
+
+
 def test_bad_io_parameters_are_rejected():
     import torch
     tile, W = _tile_with_weights(8, 8)

@@ -403,8 +403,10 @@ __global__ void __launch_bounds__(256) k_debug_gauss(uint32_t k0, uint32_t k1, u
 // samples are not applied in lock-step.
 //   Phase A walks the samples at full lane occupancy: count = popcount(x word AND d word), and
 //   `count` copies of the direction bit (1 = up) are shifted into a per-cell bit stream, one bit
-//   per pulse, in sample order.  Full 32-bit words of the stream go to LDS (lane-interleaved,
-//   free of bank conflicts); a 64-bit register pair holds the unflushed tail.
+//   per pulse, in sample order.  The newest bits gather in a 32-bit pending word (two 32-bit
+//   operations per sample); only when a pending word of the wave would overflow are they moved
+//   to a 64-bit register tail, whose full 32-bit words go to LDS (lane-interleaved, free of
+//   bank conflicts).
 //   Phase B drains the streams: iteration i handles stream bits 4i..4i+3 of every cell with
 //   one Philox block = four Gaussians per cell; all cells of the wave run the same number of
 //   iterations (the wave's longest stream).
@@ -465,7 +467,7 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 // The pointers are separate restrict-qualified parameters so that the wave-uniform row words
 // are fetched with scalar loads.
 template <int KIND, typename WordT, bool NOISE, int RPL>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 3)     // at most 168 registers: three waves per SIMD, as many as the LDS streams allow
 k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
               const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
               const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
@@ -476,8 +478,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
     constexpr int kSign = WordTraits<WordT>::kSignBit;
     constexpr WordT kBits = (WordT)(~((WordT)1 << kSign));
-    // samples per group (one stream flush per group); sparse 32-bit words take longer groups
-    constexpr int G = (sizeof(WordT) == 4) ? 2 * AHT_GROUP : AHT_GROUP;
+    constexpr int G = AHT_GROUP;                  // samples per group: one load batch, one overflow check
     constexpr uint32_t kWordStride = 64 * 4;      // bytes between consecutive words of one stream
 
     // XCD-aware tile mapping.  Consecutive workgroup ids go round-robin to the 8 XCDs, so each
@@ -506,8 +507,13 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     const WordT* __restrict__ dp = dw + i0;
 
     float w[RPL], s_up[RPL], s_dn_neg[RPL], bmax[RPL], bmin[RPL], sl_up[RPL], sl_dn[RPL];
-    uint32_t q[RPL], cellid[RPL], qb[RPL];
+    uint32_t q[RPL], cellid[RPL];
+    // LDS address of the lane's first stream; stream c starts c * cell_stride bytes further (wave-uniform)
+    const uint32_t qb0 = lds0 + (uint32_t)((wave * RPL * a.qwords * 64 + lane) * 4);
+    const uint32_t cell_stride = (uint32_t)a.qwords * kWordStride;
+    auto qb = [&](int c) __attribute__((always_inline)) { return qb0 + (uint32_t)c * cell_stride; };
     uint32_t acc_lo[RPL], acc_hi[RPL], fill[RPL], wp[RPL];   // stream tail, its length, LDS write pointer
+    uint32_t pend[RPL], plen[RPL];                           // bits not yet in the tail (plen <= 31)
     bool cv[RPL];
 #pragma unroll
     for (int c = 0; c < RPL; ++c) {
@@ -531,11 +537,12 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             sl_dn[c] = (bmin[c] != 0.0f) ? 1.0f / bmin[c] : 0.0f;
         }
         q[c] = 0;
-        qb[c] = lds0 + (uint32_t)(((wave * RPL + c) * a.qwords * 64 + lane) * 4);
         acc_lo[c] = 0;
         acc_hi[c] = 0;
         fill[c] = 0;
-        wp[c] = qb[c];
+        wp[c] = qb(c);
+        pend[c] = 0;
+        plen[c] = 0;
     }
 
     // Append `n` (<= 31, and fill + n <= 64) copies of the direction bit to the stream tail.
@@ -551,8 +558,20 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     auto flush = [&](int c) __attribute__((always_inline)) {
         const uint64_t acc = ((uint64_t)acc_hi[c] << 32) | acc_lo[c];
         lds_store_u32(wp[c], (uint32_t)(acc >> ((fill[c] - 32u) & 63u)));
-        wp[c] += (fill[c] >> 5) * kWordStride;                       // fill < 64
+        wp[c] += (fill[c] & 32u) << 3;                               // one word = kWordStride bytes; fill < 64
         fill[c] &= 31u;
+    };
+    // The bits of several samples are first gathered in a 32-bit word with 32-bit operations
+    // (`pend`, newest bit lowest) and moved to the tail only when some cell of the wave would
+    // overflow it: one 64-bit shift and one flush per commit instead of per sample.
+    auto commit = [&](int c) __attribute__((always_inline)) {
+        const uint64_t acc = (((uint64_t)acc_hi[c] << 32) | acc_lo[c]) << plen[c];
+        acc_lo[c] = (uint32_t)acc | pend[c];
+        acc_hi[c] = (uint32_t)(acc >> 32);
+        fill[c] += plen[c];                                          // < 32 + 32
+        flush(c);
+        pend[c] = 0;
+        plen[c] = 0;
     };
 
     // ---- phase B: drain the streams ---------------------------------------------------
@@ -562,8 +581,9 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         int niter = 0;
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
+            commit(c);
             lds_store_u32(wp[c], acc_lo[c] << ((32u - fill[c]) & 31u));      // left-aligned partial word
-            endpos[c] = ((wp[c] - qb[c]) >> 3) + fill[c];                    // 32 bits per 256-byte step
+            endpos[c] = ((wp[c] - qb(c)) >> 3) + fill[c];                    // 32 bits per 256-byte step
             start[c] = q[c] & 31u;
             blk0[c] = (q[c] >> 5) << 3;
             D[c] = 0;
@@ -583,7 +603,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         auto iteration = [&](int i, auto masked) __attribute__((always_inline)) {
             if ((i & 7) == 0) {
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) D[c] = lds_load_u32(qb[c] + (uint32_t)(i >> 3) * kWordStride);
+                for (int c = 0; c < RPL; ++c) D[c] = lds_load_u32(qb0 + ((uint32_t)c * cell_stride + (uint32_t)(i >> 3) * kWordStride));
             }
 #pragma unroll
             for (int c = 0; c < RPL; ++c) {
@@ -617,7 +637,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             acc_lo[c] = 0;
             acc_hi[c] = 0;
             fill[c] = q[c] & 31u;
-            wp[c] = qb[c];
+            wp[c] = qb(c);
         }
     };
 
@@ -629,20 +649,27 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 #pragma unroll
         for (int u = 0; u < G; ++u) xg[u] = p0[(size_t)u * xstride];
     };
-    // counts and direction masks of one sample for the lane's cells
-    auto count = [&](WordT xv, const WordT (&dv)[RPL], uint32_t (&n)[RPL], uint32_t (&m)[RPL])
-                     __attribute__((always_inline)) {
-        uint32_t xm = (uint32_t)((int32_t)(uint32_t)(xv >> (kSign - 31)) >> 31);        // ~0 if x < 0
-        asm volatile("" : "+v"(xm));              // keep the row part of the direction on the scalar unit
+    // ~0 if the word's sign bit is set
+    auto sign_mask = [&](WordT v) __attribute__((always_inline)) {
+        return (uint32_t)((int32_t)(uint32_t)(v >> (kSign - 31)) >> 31);
+    };
+    // coincidence counts of one sample for the lane's cells
+    auto count = [&](WordT xv, const WordT (&dv)[RPL], uint32_t (&n)[RPL]) __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
-            const uint32_t dm = (uint32_t)((int32_t)(uint32_t)(dv[c] >> (kSign - 31)) >> 31);   // wave-uniform
             const WordT both = xv & (dv[c] & kBits);
             n[c] = (sizeof(WordT) == 8)
                        ? (uint32_t)__popc((uint32_t)((uint64_t)both >> 32)) + (uint32_t)__popc((uint32_t)both)
                        : (uint32_t)__popc((uint32_t)both);
-            m[c] = xm ^ dm;                                          // ~0: x_j d_i < 0, an UP pulse
         }
+    };
+    // direction masks of one sample: ~0 where x_j d_i < 0, an UP pulse.  The row part is
+    // wave-uniform and stays on the scalar unit.
+    auto direction = [&](WordT xv, const WordT (&dv)[RPL], uint32_t (&m)[RPL]) __attribute__((always_inline)) {
+        uint32_t xm = sign_mask(xv);
+        asm volatile("" : "+v"(xm));
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) m[c] = xm ^ sign_mask(dv[c]);
     };
     // a sample with any count: at most 16 bits at a time, flushing in between
     auto append_slow = [&](const uint32_t (&n)[RPL], const uint32_t (&m)[RPL]) __attribute__((always_inline)) {
@@ -659,44 +686,42 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         }
     };
 
-    // A stream may be extended while its word index is <= qwords - 3: one sample adds at most
-    // two words and the word under the write pointer must exist.
+    // A stream may be extended while the word under its write pointer has index <= qwords - 3:
+    // a commit adds at most one word, a sample on the slow path at most two, and the drain
+    // commits once more and stores the partial word under the pointer.
     const uint32_t last_ok = (uint32_t)(a.qwords - 3) * kWordStride;
-    WordT xg[G];
+    auto nearly_full = [&]() __attribute__((always_inline)) {
+        bool nf = false;
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) nf |= (wp[c] - qb(c)) > last_ok;
+        return __any(nf) != 0;
+    };
+    WordT xg[G], xn[G];                           // column words of the current and of the next group
     bool have_x = false;                          // xg holds the words of samples b .. b+G-1
+    bool more = false;                            // xn holds the words of samples b+G .. b+2G-1
     int b = 0;
     bool done = false;
     do {
         bool full = false;
         while (!full && b < B) {
             if (b + G <= B) {
-                if (!have_x) load_x(xcur, xg);
-                WordT dg[G][RPL];                 // row words of this group (scalar registers)
-#pragma unroll
-                for (int u = 0; u < G; ++u)
-#pragma unroll
-                    for (int c = 0; c < RPL; ++c) dg[u][c] = dw[doff + (size_t)u * dstride + c];
-                WordT xn[G];
-                const bool more = b + 2 * G <= B;
-                if (more) load_x(xcur + (size_t)G * xstride, xn);    // next group in flight meanwhile
-                uint32_t n[G][RPL], m[G][RPL];
-#pragma unroll
-                for (int u = 0; u < G; ++u) count(xg[u], dg[u], n[u], m[u]);
+                WordT dg[G][RPL];                 // row words of the group (scalar registers)
+                uint32_t n[G][RPL], sum[RPL];
                 bool big = false;
+                // the group's bits join the pending words; then on to the next group
+                auto take_group = [&]() __attribute__((always_inline)) {
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) {
-                    uint32_t sum = 0;
+                    for (int u = 0; u < G; ++u) {
+                        uint32_t m1[RPL];
+                        direction(xg[u], dg[u], m1);
 #pragma unroll
-                    for (int u = 0; u < G; ++u) sum += n[u][c];
-                    big |= sum > 31u;
-                }
-                if (!__any(big)) {                // usual case: the group adds < 32 bits per cell
-#pragma unroll
-                    for (int c = 0; c < RPL; ++c) {
-#pragma unroll
-                        for (int u = 0; u < G; ++u) append(c, n[u][c], m[u][c]);
-                        flush(c);
+                        for (int c = 0; c < RPL; ++c) {
+                            const uint32_t bits = __builtin_amdgcn_ubfe(m1[c], 0u, n[u][c]);   // n copies of the direction
+                            pend[c] = (pend[c] << n[u][c]) | bits;
+                        }
                     }
+#pragma unroll
+                    for (int c = 0; c < RPL; ++c) plen[c] += sum[c];
                     b += G;
                     xcur += (size_t)G * xstride;
                     doff += (size_t)G * dstride;
@@ -705,37 +730,81 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 #pragma unroll
                         for (int u = 0; u < G; ++u) xg[u] = xn[u];
                     }
-                } else {                          // a large count somewhere: sample by sample while room lasts
-                    have_x = false;
+                };
+                // Straight path: groups are taken until some pending word of the wave would overflow.
+                bool stopped = false;
+                for (;;) {
+                    if (!have_x) load_x(xcur, xg);
+                    have_x = true;
 #pragma unroll
-                    for (int u = 0; u < G; ++u) {
-                        append_slow(n[u], m[u]);
-                        b += 1;
-                        xcur += xstride;
-                        doff += dstride;
-                        if (u + 1 < G) {
-                            bool nf = false;
+                    for (int u = 0; u < G; ++u)
 #pragma unroll
-                            for (int c = 0; c < RPL; ++c) nf |= (wp[c] - qb[c]) > last_ok;
-                            if (__any(nf)) break;
+                        for (int c = 0; c < RPL; ++c) dg[u][c] = dw[doff + (size_t)u * dstride + c];
+                    more = b + 2 * G <= B;
+                    if (more) load_x(xcur + (size_t)G * xstride, xn);    // next group in flight meanwhile
+#pragma unroll
+                    for (int u = 0; u < G; ++u) count(xg[u], dg[u], n[u]);
+                    bool over = false;
+                    big = false;
+#pragma unroll
+                    for (int c = 0; c < RPL; ++c) {
+                        sum[c] = 0;
+#pragma unroll
+                        for (int u = 0; u < G; ++u) sum[c] += n[u][c];
+                        over |= plen[c] + sum[c] > 31u;
+                        big |= sum[c] > 31u;
+                    }
+                    if (__any(over)) {
+                        stopped = true;
+                        break;
+                    }
+                    take_group();
+                    if (!more) break;             // fewer than G samples left
+                }
+                if (stopped) {                    // empty the pending words, then deal with the group in hand
+#pragma unroll
+                    for (int c = 0; c < RPL; ++c) commit(c);
+                    if (nearly_full()) {          // drain first, then take this group again
+                        full = true;
+                    } else if (__any(big)) {      // a group with a large count: sample by sample while room lasts
+                        have_x = false;
+#pragma unroll
+                        for (int u = 0; u < G; ++u) {
+                            uint32_t m1[RPL];
+                            direction(xg[u], dg[u], m1);
+                            append_slow(n[u], m1);
+                            b += 1;
+                            xcur += xstride;
+                            doff += dstride;
+                            if (nearly_full()) {
+                                full = true;
+                                break;
+                            }
                         }
+                    } else {
+                        take_group();
                     }
                 }
             } else {                              // fewer than G samples left
+#pragma unroll
+                for (int c = 0; c < RPL; ++c) commit(c);
+                if (nearly_full()) {
+                    full = true;
+                    break;
+                }
                 WordT dv[RPL];
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) dv[c] = dw[doff + c];
                 uint32_t n1[RPL], m1[RPL];
-                count(*xcur, dv, n1, m1);
+                const WordT xv = *xcur;
+                count(xv, dv, n1);
+                direction(xv, dv, m1);
                 append_slow(n1, m1);
                 b += 1;
                 xcur += xstride;
                 doff += dstride;
+                full = nearly_full();
             }
-            bool nearly_full = false;
-#pragma unroll
-            for (int c = 0; c < RPL; ++c) nearly_full |= (wp[c] - qb[c]) > last_ok;
-            full = __any(nearly_full) != 0;
         }
         done = b >= B;
         drain();

@@ -575,10 +575,11 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     };
 
     // ---- phase B: drain the streams ---------------------------------------------------
-    auto drain = [&]() __attribute__((always_inline)) {
-        uint32_t endpos[RPL], start[RPL], blk0[RPL], D[RPL];
-        int row_iters[RPL];                       // wave-uniform: iterations the lanes' c-th cells need
-        int niter = 0;
+    // `last`: no more samples follow.  Then the lane's cells may change places: sorted by stream
+    // length, the c-th cells of the 64 lanes are more alike, the rows of the wave end closer to
+    // their longest stream and fewer of their iterations need masks.
+    auto drain = [&](bool last) __attribute__((always_inline)) {
+        uint32_t endpos[RPL], start[RPL], blk0[RPL], D[RPL], sb[RPL], home[RPL];
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
             commit(c);
@@ -587,53 +588,102 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             start[c] = q[c] & 31u;
             blk0[c] = (q[c] >> 5) << 3;
             D[c] = 0;
-            row_iters[c] = (int)((wave_max_u32(endpos[c]) + 3u) >> 2);
-            niter = niter > row_iters[c] ? niter : row_iters[c];
+            sb[c] = qb(c);                        // LDS address of the stream
+            home[c] = (uint32_t)c;                // the row this slot's cell belongs to
         }
-        // Iterations in which every cell of the wave has four valid pulses need no masks: from the
-        // last stream start (rounded up) to the first stream end (rounded down).
-        uint32_t first_end = 0xFFFFFFFFu, last_start = 0;
+        const bool sorted = (RPL == 4) && last;
+        if (sorted) {
+            auto cswap = [&](int x, int y) __attribute__((always_inline)) {
+                const bool sw = endpos[x] > endpos[y];
+                auto ex = [&](auto& p, auto& r) __attribute__((always_inline)) {
+                    const auto tp = sw ? r : p, tr = sw ? p : r;
+                    p = tp;
+                    r = tr;
+                };
+                ex(endpos[x], endpos[y]); ex(start[x], start[y]); ex(blk0[x], blk0[y]); ex(sb[x], sb[y]);
+                ex(home[x], home[y]); ex(cellid[x], cellid[y]); ex(w[x], w[y]); ex(s_up[x], s_up[y]);
+                ex(s_dn_neg[x], s_dn_neg[y]); ex(bmax[x], bmax[y]); ex(bmin[x], bmin[y]);
+                ex(sl_up[x], sl_up[y]); ex(sl_dn[x], sl_dn[y]);
+            };
+            if (RPL == 4) {                       // five-comparator network, ascending
+                cswap(0, 1); cswap(2 % RPL, 3 % RPL); cswap(0, 2 % RPL); cswap(1, 3 % RPL); cswap(1, 2 % RPL);
+            }
+        }
+        // Wave-uniform per row: iterations its longest stream needs, and the iteration from which
+        // some stream of the row has fewer than four pulses left.
+        int row_iters[RPL], row_plain_end[RPL];
+        int niter = 0, plain_end = 0x7FFFFFFF;
+        uint32_t last_start = 0;
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
-            first_end = first_end < endpos[c] ? first_end : endpos[c];
+            row_iters[c] = (int)((wave_max_u32(endpos[c]) + 3u) >> 2);
+            row_plain_end[c] = (int)(~wave_max_u32(~endpos[c]) >> 2);        // wave minimum, rounded down
+            niter = niter > row_iters[c] ? niter : row_iters[c];
+            plain_end = plain_end < row_plain_end[c] ? plain_end : row_plain_end[c];
             last_start = last_start > start[c] ? last_start : start[c];
         }
-        const int plain_begin = (int)((wave_max_u32(last_start) + 3u) >> 2);
-        const int plain_end = (int)(~wave_max_u32(~first_end) >> 2);          // wave minimum, rounded down
-        auto iteration = [&](int i, auto masked) __attribute__((always_inline)) {
+        const int plain_begin = (int)((wave_max_u32(last_start) + 3u) >> 2);  // every stream has started
+        const float c2c_unit = a.c2c * kGaussUnitScale;              // the Gaussians below come without this factor
+        auto load_words = [&](int i) __attribute__((always_inline)) {
             if ((i & 7) == 0) {
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) D[c] = lds_load_u32(qb0 + ((uint32_t)c * cell_stride + (uint32_t)(i >> 3) * kWordStride));
+                for (int c = 0; c < RPL; ++c) D[c] = lds_load_u32(sb[c] + (uint32_t)(i >> 3) * kWordStride);
             }
+        };
+        // Stream bits 4i .. 4i+3 of the lanes' c-th cells.  mode 0: all four pulses exist in every
+        // lane; 1: head (streams may start after bit 4i); 2: tail (streams may end before bit 4i + 4)
+        auto row_step = [&](int i, int c, auto mode_tag) __attribute__((always_inline)) {
+            constexpr int mode = decltype(mode_tag)::value;
+            float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (NOISE) gauss4_unit(a.k0, a.k1, cellid[c], blk0[c] + (uint32_t)i, a.t, kTagC2C, z);
+            const int lo = (int)start[c] - 4 * i, hi = (int)endpos[c] - 4 * i;
 #pragma unroll
-            for (int c = 0; c < RPL; ++c) {
-                if (decltype(masked)::value && i >= row_iters[c]) continue;   // all 64 cells of this row are done
-                float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (NOISE) gauss4_fast(a.k0, a.k1, cellid[c], blk0[c] + (uint32_t)i, a.t, kTagC2C, z);
-                const int lo = (int)start[c] - 4 * i, hi = (int)endpos[c] - 4 * i;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const uint32_t dmask = (uint32_t)__builtin_amdgcn_sbfe((int)D[c], 31 - k, 1);
-                    const float wn = device_step<KIND, NOISE>(w[c], dmask, z[k], a.c2c, s_up[c], s_dn_neg[c],
-                                                              bmax[c], bmin[c], sl_up[c], sl_dn[c]);
-                    if (decltype(masked)::value) {
-                        const bool act = (k >= lo) & (k < hi);
-                        w[c] = act ? wn : w[c];
-                    } else {
-                        w[c] = wn;
-                    }
-                }
-                D[c] <<= 4;
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t dmask = (uint32_t)__builtin_amdgcn_sbfe((int)D[c], 31 - k, 1);
+                const float wn = device_step<KIND, NOISE>(w[c], dmask, z[k], c2c_unit, s_up[c], s_dn_neg[c],
+                                                          bmax[c], bmin[c], sl_up[c], sl_dn[c]);
+                if (mode == 1) w[c] = ((k >= lo) & (k < hi)) ? wn : w[c];
+                else if (mode == 2) w[c] = (k < hi) ? wn : w[c];
+                else w[c] = wn;
             }
+            D[c] <<= 4;
         };
         int i = 0;
         const int head_end = plain_begin < niter ? plain_begin : niter;
-        for (; i < head_end; ++i) iteration(i, std::true_type{});
-        for (; i < plain_end; ++i) iteration(i, std::false_type{});
-        for (; i < niter; ++i) iteration(i, std::true_type{});
+        for (; i < head_end; ++i) {
+            load_words(i);
 #pragma unroll
-        for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31
-            q[c] += endpos[c] - start[c];
+            for (int c = 0; c < RPL; ++c)
+                if (i < row_iters[c]) row_step(i, c, std::integral_constant<int, 1>{});
+        }
+        for (; i < plain_end; ++i) {              // all rows in one block
+            load_words(i);
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) row_step(i, c, std::integral_constant<int, 0>{});
+        }
+        for (; i < niter; ++i) {                  // rows end one after the other
+            load_words(i);
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) {
+                if (i >= row_iters[c]) continue;  // all 64 cells of this row are done
+                if (i < row_plain_end[c]) row_step(i, c, std::integral_constant<int, 0>{});
+                else row_step(i, c, std::integral_constant<int, 2>{});
+            }
+        }
+        if (sorted) {                             // weights back to their rows (the stores stay coalesced)
+            float wo[RPL];
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) {
+                wo[c] = w[0];
+#pragma unroll
+                for (int sl = 1; sl < RPL; ++sl) wo[c] = (home[sl] == (uint32_t)c) ? w[sl] : wo[c];
+            }
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) w[c] = wo[c];
+        }
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31 (after a sorted
+            q[c] += endpos[c] - start[c];         // drain only the sum of q is still used)
             acc_lo[c] = 0;
             acc_hi[c] = 0;
             fill[c] = q[c] & 31u;
@@ -807,16 +857,14 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             }
         }
         done = b >= B;
-        drain();
+        drain(done);
     } while (!done);
 
     unsigned long long pulses = 0;
 #pragma unroll
     for (int c = 0; c < RPL; ++c) {
-        if (cv[c]) {
-            __builtin_nontemporal_store(w[c], W + (size_t)(i0 + c) * C + j);
-            pulses += q[c];
-        }
+        if (cv[c]) __builtin_nontemporal_store(w[c], W + (size_t)(i0 + c) * C + j);
+        pulses += q[c];                           // cells outside the matrix see zero words: no pulses
     }
     if (pulse_count) {
 #pragma unroll

@@ -67,6 +67,27 @@ __device__ __forceinline__ void gauss4_fast(uint32_t k0, uint32_t k1, uint32_t i
     box_muller_fast(r.z, r.w, z[2], z[3]);
 }
 
+// The same four Gaussians divided by sqrt(2 ln 2): the radius is sqrt(-log2 u1) as the
+// transcendental unit delivers it, and the caller folds the constant into its own scale factor
+// (one multiplication less per pair).
+constexpr float kGaussUnitScale = 1.1774100225154747f;               // sqrt(2 ln 2)
+__device__ __forceinline__ void box_muller_unit(uint32_t ra, uint32_t rb, float& z_even, float& z_odd)
+{
+    const float u1 = fmaf((float)(ra >> 8), 0x1p-24f, 0x1p-24f);
+    const float u2 = (float)(rb >> 8) * 0x1p-24f;
+    const float rad = __builtin_amdgcn_sqrtf(-__builtin_amdgcn_logf(u1));
+    z_even = rad * __builtin_amdgcn_cosf(u2);
+    z_odd = rad * __builtin_amdgcn_sinf(u2);
+}
+
+__device__ __forceinline__ void gauss4_unit(uint32_t k0, uint32_t k1, uint32_t index, uint32_t blk, uint32_t t,
+                                            uint32_t tag, float z[4])
+{
+    const U4 r = philox4x32_10(index, blk, t, tag << 24, k0, k1);
+    box_muller_unit(r.x, r.y, z[0], z[1]);
+    box_muller_unit(r.z, r.w, z[2], z[3]);
+}
+
 // Accurate variant (fp64 library functions, one rounding to fp32); used off the hot path,
 // at tile creation, so that the per-cell planes carry no approximation error.
 __device__ __forceinline__ void gauss4_accurate(uint32_t k0, uint32_t k1, uint32_t index, uint32_t blk,

@@ -506,7 +506,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     const WordT* __restrict__ xp = xw + j;
     const WordT* __restrict__ dp = dw + i0;
 
-    float w[RPL], s_up[RPL], s_dn_neg[RPL], bmax[RPL], bmin[RPL], sl_up[RPL], sl_dn[RPL];
+    float w[RPL];
     uint32_t q[RPL], cellid[RPL];
     // LDS address of the lane's first stream; stream c starts c * cell_stride bytes further (wave-uniform)
     const uint32_t qb0 = lds0 + (uint32_t)((wave * RPL * a.qwords * 64 + lane) * 4);
@@ -520,22 +520,9 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         cv[c] = ((i0 + c) < R) && (j < C);
         const size_t k = cv[c] ? ((size_t)(i0 + c) * C + j) : 0;
         cellid[c] = (uint32_t)k;
-        // weights and planes are touched once per call: stream them past the L2 so that the
-        // pulse words, which every tile of a super-tile re-reads, stay resident
+        // weights and device parameters are touched once per call: stream them past the L2 so that
+        // the pulse words, which every tile of a super-tile re-reads, stay resident
         w[c] = __builtin_nontemporal_load(W + k);
-        s_up[c] = __builtin_nontemporal_load(p_dw_up + k);
-        s_dn_neg[c] = -__builtin_nontemporal_load(p_dw_down + k);
-        bmax[c] = __builtin_nontemporal_load(p_b_max + k);
-        bmin[c] = __builtin_nontemporal_load(p_b_min + k);
-        sl_up[c] = 0.0f;
-        sl_dn[c] = 0.0f;
-        if (KIND == kLinearStep) {
-            sl_up[c] = __builtin_nontemporal_load(p_slope_up + k);
-            sl_dn[c] = __builtin_nontemporal_load(p_slope_down + k);
-        } else if (KIND == kSoftBounds) {
-            sl_up[c] = (bmax[c] != 0.0f) ? 1.0f / bmax[c] : 0.0f;
-            sl_dn[c] = (bmin[c] != 0.0f) ? 1.0f / bmin[c] : 0.0f;
-        }
         q[c] = 0;
         acc_lo[c] = 0;
         acc_hi[c] = 0;
@@ -579,6 +566,28 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     // length, the c-th cells of the 64 lanes are more alike, the rows of the wave end closer to
     // their longest stream and fewer of their iterations need masks.
     auto drain = [&](bool last) __attribute__((always_inline)) {
+        // The device parameters are needed only here.  Loading them now (normally once per call)
+        // keeps 6 registers per cell free during phase A; the cell index is made opaque so that
+        // the 24 addresses are formed here as well and not kept from the start of the kernel.
+        float s_up[RPL], s_dn_neg[RPL], bmax[RPL], bmin[RPL], sl_up[RPL], sl_dn[RPL];
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) {
+            uint32_t k = cellid[c];
+            asm volatile("" : "+v"(k));
+            s_up[c] = __builtin_nontemporal_load(p_dw_up + k);
+            s_dn_neg[c] = -__builtin_nontemporal_load(p_dw_down + k);
+            bmax[c] = __builtin_nontemporal_load(p_b_max + k);
+            bmin[c] = __builtin_nontemporal_load(p_b_min + k);
+            sl_up[c] = 0.0f;
+            sl_dn[c] = 0.0f;
+            if (KIND == kLinearStep) {
+                sl_up[c] = __builtin_nontemporal_load(p_slope_up + k);
+                sl_dn[c] = __builtin_nontemporal_load(p_slope_down + k);
+            } else if (KIND == kSoftBounds) {
+                sl_up[c] = (bmax[c] != 0.0f) ? 1.0f / bmax[c] : 0.0f;
+                sl_dn[c] = (bmin[c] != 0.0f) ? 1.0f / bmin[c] : 0.0f;
+            }
+        }
         uint32_t endpos[RPL], start[RPL], blk0[RPL], D[RPL], sb[RPL], home[RPL];
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {

@@ -512,15 +512,16 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     const int vec_in = (K % 4 == 0) && (((uintptr_t)x | (uintptr_t)t->mvm_xq) % 16 == 0);
     hipLaunchKernelGGL(k_mvm_prepare, dim3((unsigned)B), dim3(1024), 0, s, x, K, vec_in, a, k0, k1, step, tag_in,
                        t->mvm_xq, t->mvm_alpha, t->mvm_norm);
-    // Block height 128 when the batch fills it; K split aiming at two workgroups of 64 rows per
-    // compute unit or one of 128 rows (measured optimum: more slices only add partial-sum
-    // traffic), at least four K steps per slice.
-    int bm = (B > 64) ? 128 : 64;
+    // K split aiming at two workgroups per compute unit (measured optimum at 4096 x 4096, B = 256:
+    // more slices only add partial-sum traffic), at least four K steps per slice.
+    // Blocks of 64 vectors keep three workgroups resident per compute unit; when there are more
+    // tiles than that, blocks of 128 halve their number and read the weights half as often.
+    int bm = ((long)((B + 63) / 64) * ((N + 63) / 64) > 3L * 256) ? 128 : 64;
     if (const int e = env_int("AHT_MVM_BM", 0)) bm = (e == 128) ? 128 : 64;
     const int mb = (B + bm - 1) / bm, nb = (N + 63) / 64, nchunks = (K + 31) / 32;
     int splits = env_int("AHT_MVM_SPLITS", 0);
     if (splits <= 0) {
-        const long tiles = (long)mb * nb, want = (bm == 128) ? 256 : 512;
+        const long tiles = (long)mb * nb, want = (bm == 128) ? 256 : 512;     // 256 compute units
         splits = (int)((want + tiles - 1) / tiles);
         if (splits > nchunks / 4) splits = nchunks / 4;
     }

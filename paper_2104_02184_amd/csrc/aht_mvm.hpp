@@ -144,6 +144,8 @@ __device__ __forceinline__ void mvm_finish(float z, float g_out, float g_w, bool
 // per compute unit) still puts several workgroups on every compute unit, whose loads, barriers
 // and matrix instructions overlap.  splits == 1: the analog epilogue is fused.  splits > 1:
 // slice z writes its partial sums to part[z][M][N] and k_mvm_epilogue adds them in slice order.
+// (Letting the slice that finishes last do the epilogue saves the second launch but needs a
+// device-scope fence in every workgroup, which costs far more on this chip: 0.17 against 0.10 ms.)
 //
 // Workgroup ids go round-robin to the 8 XCDs; the id -> (tile, slice) map gives each XCD a
 // contiguous range with the row blocks of A fastest, so that the workgroups sharing a tile of
@@ -208,85 +210,158 @@ k_mvm_gemm(const float* __restrict__ A, const float* __restrict__ Wm, int M, int
         }
         return make_float4(v[0], v[1], v[2], v[3]);
     };
-    float4 ra0, ra1, ra2 = {}, ra3 = {}, rb0, rb1;
-    auto fetch = [&](int kc) __attribute__((always_inline)) {
-        const int kk = kc + (tid & 7) * 4, row = tid >> 3;
-        ra0 = load4(A, m0 + row, M, K, kk);
-        ra1 = load4(A, m0 + row + 32, M, K, kk);
-        if (AH == 4) {
-            ra2 = load4(A, m0 + row + 64, M, K, kk);
-            ra3 = load4(A, m0 + row + 96, M, K, kk);
-        }
-        if (!TRANS) {
-            rb0 = load4(Wm, n0 + row, N, ldw, kk);
-            rb1 = load4(Wm, n0 + row + 32, N, ldw, kk);
-        } else {
-            rb0 = load4_t(kc + (tid >> 4), n0 + (tid & 15) * 4);
-            rb1 = load4_t(kc + (tid >> 4) + 16, n0 + (tid & 15) * 4);
-        }
+    // Software pipeline over the K steps: while the matrix cores work on step c from registers,
+    // the operands of step c+1 are read from LDS into a second register set, step c+2 is moved
+    // from its staging registers to the LDS buffer step c has left, and the global loads of step
+    // c+3 are in flight.  The workgroup barrier only orders LDS (its fences name the local address
+    // space), so the global loads stay in flight across it.  (Register sets are plain variables
+    // and the steps macros: anything passed by reference here ended up in scratch memory.)
+    const int frow = tid >> 3, k_first = c_begin * BK + (tid & 7) * 4;
+    auto a_row = [&](int h) __attribute__((always_inline)) {
+        const int m = m0 + frow + 32 * h;
+        return A + (size_t)(m < M ? m : M - 1) * K + k_first;
     };
-    auto stage = [&](int buf) __attribute__((always_inline)) {
-        float* ap = &As[buf][(tid >> 3) * LDK + (tid & 7) * 4];
-        *(float4*)ap = ra0;
-        *(float4*)(ap + 32 * LDK) = ra1;
-        if (AH == 4) {
-            *(float4*)(ap + 64 * LDK) = ra2;
-            *(float4*)(ap + 96 * LDK) = ra3;
-        }
+    auto w_row = [&](int h) __attribute__((always_inline)) {
         if (!TRANS) {
-            float* bp = &Bs[buf][(tid >> 3) * LDK + (tid & 7) * 4];
-            *(float4*)bp = rb0;
-            *(float4*)(bp + 32 * LDK) = rb1;
-        } else {
-            float* bp = &Bs[buf][(tid >> 4) * LDN + (tid & 15) * 4];
-            *(float4*)bp = rb0;
-            *(float4*)(bp + 16 * LDN) = rb1;
+            const int n = n0 + frow + 32 * h;
+            return Wm + (size_t)(n < N ? n : N - 1) * ldw + k_first;
         }
+        const int nn = n0 + (tid & 15) * 4;
+        return Wm + (size_t)(c_begin * BK + (tid >> 4) + 16 * h) * ldw + (nn + 3 < N ? nn : N - 4);
     };
-
+    // ALIGNED: running pointers, advanced in place (no address temporaries next to the staging registers)
+    const float *pa0 = a_row(0), *pa1 = a_row(1), *pa2 = a_row(2), *pa3 = a_row(3);
+    const float *pw0 = w_row(0), *pw1 = w_row(1);
+    const size_t w_step = TRANS ? (size_t)BK * ldw : (size_t)BK;
+    int fetched = 0;                                        // K steps fetched so far
+#define AHT_FETCH(G)                                                                       \
+    do {                                                                                   \
+        if (ALIGNED) {                                                                     \
+            G##a0 = *(const float4*)pa0;                                                   \
+            G##a1 = *(const float4*)pa1;                                                   \
+            if (AH == 4) {                                                                 \
+                G##a2 = *(const float4*)pa2;                                               \
+                G##a3 = *(const float4*)pa3;                                               \
+            }                                                                              \
+            G##b0 = *(const float4*)pw0;                                                   \
+            G##b1 = *(const float4*)pw1;                                                   \
+            pa0 += BK;                                                                     \
+            pa1 += BK;                                                                     \
+            if (AH == 4) {                                                                 \
+                pa2 += BK;                                                                 \
+                pa3 += BK;                                                                 \
+            }                                                                              \
+            pw0 += w_step;                                                                 \
+            pw1 += w_step;                                                                 \
+        } else {                                                                           \
+            const int kc_ = (c_begin + fetched) * BK, kk_ = kc_ + (tid & 7) * 4;           \
+            G##a0 = load4(A, m0 + frow, M, K, kk_);                                        \
+            G##a1 = load4(A, m0 + frow + 32, M, K, kk_);                                   \
+            if (AH == 4) {                                                                 \
+                G##a2 = load4(A, m0 + frow + 64, M, K, kk_);                               \
+                G##a3 = load4(A, m0 + frow + 96, M, K, kk_);                               \
+            }                                                                              \
+            if (!TRANS) {                                                                  \
+                G##b0 = load4(Wm, n0 + frow, N, ldw, kk_);                                 \
+                G##b1 = load4(Wm, n0 + frow + 32, N, ldw, kk_);                            \
+            } else {                                                                       \
+                G##b0 = load4_t(kc_ + (tid >> 4), n0 + (tid & 15) * 4);                    \
+                G##b1 = load4_t(kc_ + (tid >> 4) + 16, n0 + (tid & 15) * 4);               \
+            }                                                                              \
+        }                                                                                  \
+        fetched += 1;                                                                      \
+    } while (0)
+#define AHT_STAGE(BUF, G)                                                                  \
+    do {                                                                                   \
+        float* ap_ = &As[BUF][(tid >> 3) * LDK + (tid & 7) * 4];                           \
+        *(float4*)ap_ = G##a0;                                                             \
+        *(float4*)(ap_ + 32 * LDK) = G##a1;                                                \
+        if (AH == 4) {                                                                     \
+            *(float4*)(ap_ + 64 * LDK) = G##a2;                                            \
+            *(float4*)(ap_ + 96 * LDK) = G##a3;                                            \
+        }                                                                                  \
+        if (!TRANS) {                                                                      \
+            float* bp_ = &Bs[BUF][(tid >> 3) * LDK + (tid & 7) * 4];                       \
+            *(float4*)bp_ = G##b0;                                                         \
+            *(float4*)(bp_ + 32 * LDK) = G##b1;                                            \
+        } else {                                                                           \
+            float* bp_ = &Bs[BUF][(tid >> 4) * LDN + (tid & 15) * 4];                      \
+            *(float4*)bp_ = G##b0;                                                         \
+            *(float4*)(bp_ + 16 * LDN) = G##b1;                                            \
+        }                                                                                  \
+    } while (0)
+    const int kh = lane >> 5, l32 = lane & 31;
+#define AHT_LDS_READ(BUF, OA, OB)                                                          \
+    do {                                                                                   \
+        _Pragma("unroll") for (int i_ = 0; i_ < NACC; ++i_) {                              \
+            const float* ap_ = &As[BUF][(wm * (BM / 2) + 32 * i_ + l32) * LDK + 16 * kh];  \
+            _Pragma("unroll") for (int q_ = 0; q_ < 4; ++q_) {                             \
+                const float4 v_ = *(const float4*)(ap_ + 4 * q_);                          \
+                OA[i_][4 * q_] = v_.x; OA[i_][4 * q_ + 1] = v_.y;                          \
+                OA[i_][4 * q_ + 2] = v_.z; OA[i_][4 * q_ + 3] = v_.w;                      \
+            }                                                                              \
+        }                                                                                  \
+        if (!TRANS) {                                                                      \
+            const float* bp_ = &Bs[BUF][(wn * 32 + l32) * LDK + 16 * kh];                  \
+            _Pragma("unroll") for (int q_ = 0; q_ < 4; ++q_) {                             \
+                const float4 v_ = *(const float4*)(bp_ + 4 * q_);                          \
+                OB[4 * q_] = v_.x; OB[4 * q_ + 1] = v_.y;                                  \
+                OB[4 * q_ + 2] = v_.z; OB[4 * q_ + 3] = v_.w;                              \
+            }                                                                              \
+        } else {                                                                           \
+            const float* bp_ = &Bs[BUF][(16 * kh) * LDN + wn * 32 + l32];                  \
+            _Pragma("unroll") for (int s_ = 0; s_ < 16; ++s_) OB[s_] = bp_[s_ * LDN];      \
+        }                                                                                  \
+    } while (0)
     floatx16 acc[NACC];
 #pragma unroll
     for (int i = 0; i < NACC; ++i) acc[i] = floatx16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    if (c_begin < c_end) {                                  // block-uniform
-        fetch(c_begin * BK);
-        stage(0);
-        __syncthreads();
-        const int kh = lane >> 5, l32 = lane & 31;
-        for (int c = c_begin; c < c_end; ++c) {
-            const int buf = (c - c_begin) & 1;
-            if (c + 1 < c_end) fetch((c + 1) * BK);         // global loads in flight during the MFMAs
-            float av[NACC][16], bv[16];
-#pragma unroll
-            for (int i = 0; i < NACC; ++i) {
-                const float* ap = &As[buf][(wm * (BM / 2) + 32 * i + l32) * LDK + 16 * kh];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 v = *(const float4*)(ap + 4 * q);
-                    av[i][4 * q] = v.x; av[i][4 * q + 1] = v.y; av[i][4 * q + 2] = v.z; av[i][4 * q + 3] = v.w;
-                }
-            }
-            if (!TRANS) {
-                const float* bp = &Bs[buf][(wn * 32 + l32) * LDK + 16 * kh];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 v = *(const float4*)(bp + 4 * q);
-                    bv[4 * q] = v.x; bv[4 * q + 1] = v.y; bv[4 * q + 2] = v.z; bv[4 * q + 3] = v.w;
-                }
-            } else {
-                const float* bp = &Bs[buf][(16 * kh) * LDN + wn * 32 + l32];
-#pragma unroll
-                for (int s = 0; s < 16; ++s) bv[s] = bp[s * LDN];
-            }
-            __builtin_amdgcn_sched_barrier(0);              // all LDS reads of the step are issued first
-#pragma unroll
-            for (int s = 0; s < 16; ++s)
-#pragma unroll
-                for (int i = 0; i < NACC; ++i)
-                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][s], bv[s], acc[i], 0, 0, 0);
-            if (c + 1 < c_end) stage(buf ^ 1);
-            __syncthreads();
+#define AHT_MMA(OA, OB)                                                                    \
+    do {                                                                                   \
+        _Pragma("unroll") for (int s_ = 0; s_ < 16; ++s_)                                  \
+            _Pragma("unroll") for (int i_ = 0; i_ < NACC; ++i_)                            \
+                acc[i_] = __builtin_amdgcn_mfma_f32_32x32x2f32(OA[i_][s_], OB[s_], acc[i_], 0, 0, 0); \
+    } while (0)
+    auto lds_sync = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    };
+
+    const int nsteps = c_end - c_begin;                     // block-uniform, as is every branch below
+    if (nsteps > 0) {
+        float4 g0a0, g0a1, g0a2 = {}, g0a3 = {}, g0b0, g0b1;     // staging registers, two sets
+        float4 g1a0 = {}, g1a1 = {}, g1a2 = {}, g1a3 = {}, g1b0 = {}, g1b1 = {};
+        float o0a[NACC][16], o0b[16], o1a[NACC][16], o1b[16];    // operands, two sets
+        AHT_FETCH(g0);
+        if (nsteps > 1) AHT_FETCH(g1);
+        AHT_STAGE(0, g0);
+        lds_sync();
+        AHT_LDS_READ(0, o0a, o0b);
+        if (nsteps > 2) AHT_FETCH(g0);
+        if (nsteps > 1) AHT_STAGE(1, g1);
+        lds_sync();
+        int c = 0;
+        for (; c + 1 < nsteps; c += 2) {
+            // step c: operands in set 0, its LDS buffer 0 is free for step c+2
+            if (c + 3 < nsteps) AHT_FETCH(g1);
+            AHT_LDS_READ(1, o1a, o1b);
+            AHT_MMA(o0a, o0b);
+            if (c + 2 < nsteps) AHT_STAGE(0, g0);
+            lds_sync();
+            // step c+1: operands in set 1, LDS buffer 1 is free for step c+3
+            if (c + 4 < nsteps) AHT_FETCH(g0);
+            if (c + 2 < nsteps) AHT_LDS_READ(0, o0a, o0b);
+            AHT_MMA(o1a, o1b);
+            if (c + 3 < nsteps) AHT_STAGE(1, g1);
+            lds_sync();
         }
+        if (c < nsteps) AHT_MMA(o0a, o0b);                  // odd number of steps: the last one
     }
+#undef AHT_FETCH
+#undef AHT_STAGE
+#undef AHT_LDS_READ
+#undef AHT_MMA
 
     // register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of a 32 x 32 tile
     const int n = n0 + wn * 32 + (lane & 31);

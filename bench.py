@@ -146,6 +146,40 @@ def bench_mvm(args, transposed):
     }), flush=True)
 
 
+def bench_transfer(args):
+    """Side benchmark: one transfer event between two coupled tiles of the headline shape (analog read
+    of one column of the fast tile, pulsed write onto the slow tile)."""
+    import torch
+
+    import paper_2104_02184_amd as aht
+    from paper_2104_02184_amd import workloads as wl
+
+    w = wl.WORKLOADS[args.workload or wl.HEADLINE]
+    fast = aht.Tile(w.rows, w.cols, aht.DeviceParams(**w.device), w.bl, w.update_management, w.seed)
+    slow = aht.Tile(w.rows, w.cols, aht.DeviceParams(**w.device), w.bl, w.update_management, w.seed + 1)
+    fast.set_weights(torch.from_numpy(wl.initial_weights(w)).cuda())
+    io = aht.IOParams(inp_noise=0.0, w_noise=0.0, out_noise=0.02)
+    cols = [(7919 * k) % w.cols for k in range(args.warmup + args.steps)]
+    for k in range(args.warmup):
+        fast.transfer_column_to(slow, cols[k], 0.1, io)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for k in range(args.steps):
+        fast.transfer_column_to(slow, cols[args.warmup + k], 0.1, io)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    pulses = slow.pulse_count()
+    fast.close()
+    slow.close()
+    print(json.dumps({
+        "metric": "transfer events/s", "value": 1e3 / ms, "unit": "events/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name} transfer of one column", "pulses_total": pulses},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,7 +188,7 @@ def main():
     ap.add_argument("--workload", default=None, help="workload name (default: the headline one)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-rows", type=int, default=512)
-    ap.add_argument("--op", default="pulsed_update", choices=["pulsed_update", "decay_diffuse", "forward", "backward"],
+    ap.add_argument("--op", default="pulsed_update", choices=["pulsed_update", "decay_diffuse", "forward", "backward", "transfer"],
                     help="side benchmarks of other operations; the default is the headline metric")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -173,6 +207,9 @@ def main():
     aht.load_library()
     if args.op == "decay_diffuse":
         bench_decay_diffuse(args)
+        return
+    if args.op == "transfer":
+        bench_transfer(args)
         return
     if args.op in ("forward", "backward"):
         bench_mvm(args, args.op == "backward")

@@ -236,7 +236,8 @@ int choose_rpl(const aht_tile* t)
 }
 
 // the cell update of step `step` from the words in the tile's scratch
-aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s)
+// `strip0`, `strips`: the range of 64-column strips to work on (the caller knows that x is zero elsewhere)
+aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strip0, uint32_t strips)
 {
     const int rpl = choose_rpl(t);
     // stream storage per cell: 12 words hold 320 pulses before an early drain is needed
@@ -260,7 +261,8 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s)
     a.B = B;
     a.Rpad = rpad(t);
     a.Cpad = cpad(t);
-    a.nbx = (uint32_t)((t->cols + 63) / 64);
+    a.nbx = strips;
+    a.bx0 = strip0;
     a.nby = (uint32_t)((t->rows + 4 * rpl - 1) / (4 * rpl));
     a.k0 = (uint32_t)t->seed;
     a.k1 = (uint32_t)(t->seed >> 32);
@@ -407,8 +409,9 @@ aht_status aht_get_weights(const aht_tile* t, float* w_dev_out, void* stream)
     return AHT_OK;
 }
 
+// `col_lo .. col_hi`: columns outside this range are known to be zero in every x (all columns if col_hi < 0)
 static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const float* d_dev, int64_t B64, float lr,
-                                     void* stream, const ConvView& conv)
+                                     void* stream, const ConvView& conv, int col_lo = 0, int col_hi = -1)
 {
     if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
     if (B64 < 0) return fail(AHT_ERR_INVALID_ARG, "B must be >= 0");
@@ -433,7 +436,9 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         if (ev) AHT_HIP(hipEventRecord(ev[0], s));
         if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
         if (ev) AHT_HIP(hipEventRecord(ev[1], s));
-        if ((st = launch_cells(t, B, t->step, s)) != AHT_OK) return st;
+        const uint32_t strip0 = col_hi < 0 ? 0u : (uint32_t)(col_lo / 64);
+        const uint32_t strips = (col_hi < 0 ? (uint32_t)((t->cols + 63) / 64) : (uint32_t)(col_hi / 64 + 1)) - strip0;
+        if ((st = launch_cells(t, B, t->step, s, strip0, strips)) != AHT_OK) return st;
         if (ev) {
             AHT_HIP(hipEventRecord(ev[2], s));
             t->events_used += 3;
@@ -591,12 +596,27 @@ aht_status aht_transfer_column(aht_tile* src, aht_tile* dst, int32_t col, float 
     float* read = dst->xfer + C;
     float* neg = read + R;
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(k_one_hot, dim3(blocks_for((size_t)C)), dim3(256), 0, s, onehot, C, col);
-    AHT_HIP(hipGetLastError());
-    if ((st = analog_mvm(src, io, onehot, read, nullptr, 1, false, s)) != AHT_OK) return st;
-    hipLaunchKernelGGL(k_negate, dim3(blocks_for((size_t)R)), dim3(256), 0, s, read, neg, R);
-    AHT_HIP(hipGetLastError());
-    return pulsed_update_impl(dst, onehot, neg, 1, lr, stream, ConvView{});   // dst -= lr * (-read) e_col^T
+    if (io->inp_noise == 0.0f) {
+        // without input noise only the column itself enters the product: read it directly
+        if (!finite_nonneg(io->inp_res) || !finite_nonneg(io->w_noise) || !finite_nonneg(io->out_noise) ||
+            !finite_nonneg(io->out_res) || !(io->inp_bound > 0.0f) || !(io->out_bound > 0.0f))
+            return fail(AHT_ERR_INVALID_ARG, "io parameters must be finite and >= 0, bounds > 0");
+        if ((st = check_device(src)) != AHT_OK) return st;
+        IoArgs a{io->inp_res, io->inp_bound, io->inp_noise, io->w_noise, io->out_noise, io->out_res, io->out_bound,
+                 io->noise_management ? 1 : 0};
+        hipLaunchKernelGGL(k_mvm_column_read, dim3(blocks_for((size_t)(R > C ? R : C))), dim3(256), 0, s, src->W, R, C,
+                           col, a, (uint32_t)src->seed, (uint32_t)(src->seed >> 32), src->fwd_step, 8u, read, neg, onehot);
+        AHT_HIP(hipGetLastError());
+        src->fwd_step += 1;
+    } else {
+        hipLaunchKernelGGL(k_one_hot, dim3(blocks_for((size_t)C)), dim3(256), 0, s, onehot, C, col);
+        AHT_HIP(hipGetLastError());
+        if ((st = analog_mvm(src, io, onehot, read, nullptr, 1, false, s)) != AHT_OK) return st;
+        hipLaunchKernelGGL(k_negate, dim3(blocks_for((size_t)R)), dim3(256), 0, s, read, neg, R);
+        AHT_HIP(hipGetLastError());
+    }
+    // dst -= lr * (-read) e_col^T; only the strip of 64 columns that holds `col` can receive pulses
+    return pulsed_update_impl(dst, onehot, neg, 1, lr, stream, ConvView{}, col, col);
 }
 
 aht_status aht_get_mvm_steps(const aht_tile* t, uint32_t* f, uint32_t* b)
@@ -867,7 +887,7 @@ aht_status aht_debug_apply_words(aht_tile* t, const uint64_t* xw_dev, const uint
         hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint64_t*)t->dw, B, t->rows, rpad(t), t->upd.bl);
     }
     AHT_HIP(hipGetLastError());
-    return launch_cells(t, B, step, s);
+    return launch_cells(t, B, step, s, 0u, (uint32_t)((t->cols + 63) / 64));
 }
 
 aht_status aht_debug_philox(const uint32_t* ctr_dev, const uint32_t* key_dev, int32_t n, uint32_t* out_dev, void* stream)

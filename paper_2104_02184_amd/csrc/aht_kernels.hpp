@@ -421,6 +421,8 @@ __global__ void __launch_bounds__(256) k_debug_gauss(uint32_t k0, uint32_t k1, u
 struct CellArgs {
     int R, C, B, Rpad, Cpad;
     uint32_t nbx, nby;            // tiles along columns / rows
+    uint32_t bx0;                 // first column strip of this launch (a caller that knows where x is
+                                  // non-zero leaves the other strips out: their cells get no pulses)
     uint32_t k0, k1, t;
     float c2c;
     int qwords;                   // 32-bit words of stream storage per cell (>= 5)
@@ -493,8 +495,9 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     if (seq >= total) return;
     const uint32_t st = seq / (kSuperY * kSuperX), in = seq - st * (kSuperY * kSuperX);
     const uint32_t sy = st % nsy, sx = st / nsy;
-    const uint32_t by = sy * kSuperY + (in % kSuperY), bx = sx * kSuperX + (in / kSuperY);
-    if (by >= a.nby || bx >= a.nbx) return;
+    const uint32_t by = sy * kSuperY + (in % kSuperY), bxr = sx * kSuperX + (in / kSuperY);
+    if (by >= a.nby || bxr >= a.nbx) return;
+    const uint32_t bx = a.bx0 + bxr;              // the launch covers strips bx0 .. bx0 + nbx - 1
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));

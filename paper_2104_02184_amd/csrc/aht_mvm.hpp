@@ -411,4 +411,26 @@ k_mvm_epilogue(const float* __restrict__ part, int splits, int M, int N, const f
     if (two) mvm_finish(z1, g[2], g[3], noisy, io, norm[m], alpha[m], at + 1, y, pre);
 }
 
+// Analog read of one column: the product of W with the one-hot vector e_col when the input
+// carries no noise.  Then x~ = xq e_col with xq = DAC(1) (alpha = 1), |x~| = |xq|, and the
+// pre-activation of row i is the single product w[i][col] * xq, which is also what the matrix
+// kernel's sum reduces to; the epilogue is the common one, so the two paths agree bit for bit.
+// Also writes the negated read and the one-hot vector itself (inputs of the pulsed write).
+__global__ void __launch_bounds__(256)
+k_mvm_column_read(const float* __restrict__ W, int R, int C, int col, IoArgs io, uint32_t k0, uint32_t k1, uint32_t t,
+                  uint32_t tag, float* __restrict__ read, float* __restrict__ neg, float* __restrict__ onehot)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < C) onehot[i] = (i == col) ? 1.0f : 0.0f;
+    if (i >= R) return;
+    float xq = fminf(fmaxf(1.0f, -io.inp_bound), io.inp_bound);
+    if (io.inp_res > 0.0f) xq = rintf(xq / io.inp_res) * io.inp_res;
+    const float z = W[(size_t)i * C + col] * xq;
+    const bool noisy = (io.w_noise > 0.0f) || (io.out_noise > 0.0f);
+    float g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (noisy) gauss4_fast(k0, k1, (uint32_t)i >> 1, 0u, t, tag, g);
+    mvm_finish(z, (i & 1) ? g[2] : g[0], (i & 1) ? g[3] : g[1], noisy, io, fabsf(xq), 1.0f, (size_t)i, read, nullptr);
+    neg[i] = -read[i];
+}
+
 }  // namespace aht

@@ -12,12 +12,14 @@ from common import gpu_params, oracle_params, to_dev
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("R,C", [(64, 64), (70, 131)])
-def test_transfer_events_match_the_oracle_composition(R, C):
+# without input noise the library reads the column directly, with it through the full analog product
+@pytest.mark.parametrize("inp_noise,w_noise", [(0.0, 0.0), (0.0, 0.03), (0.01, 0.03)])
+@pytest.mark.parametrize("R,C", [(64, 64), (70, 131), (300, 70)])
+def test_transfer_events_match_the_oracle_composition(R, C, inp_noise, w_noise):
     dev = dict(kind=aht.SOFT_BOUNDS, dw_min=0.002, dw_min_dtod=0.3, dw_min_std=0.3, w_max=0.6, w_max_dtod=0.2,
                w_min=-0.6, w_min_dtod=0.2)
-    io_kw = dict(inp_res=1.0 / 126.0, inp_bound=1.0, inp_noise=0.0, w_noise=0.0, out_noise=0.02, out_res=2.0 / 254.0,
-                 out_bound=2.0, noise_management=True)
+    io_kw = dict(inp_res=1.0 / 126.0, inp_bound=1.0, inp_noise=inp_noise, w_noise=w_noise, out_noise=0.02,
+                 out_res=2.0 / 254.0, out_bound=2.0, noise_management=True)
     g = np.random.default_rng(R)
     A0 = g.uniform(-0.3, 0.3, size=(R, C)).astype(np.float32)
     seed_a, seed_c, bl, lr = 5, 6, 31, 0.05

@@ -225,6 +225,30 @@ aht_status aht_set_mvm_steps(aht_tile* tile, uint32_t forward_calls, uint32_t ba
 aht_status aht_transfer_column(aht_tile* src, aht_tile* dst, int32_t col, float lr, const aht_io_params* io,
                                void* stream);
 
+/* Unit cells of several devices (Sec. 4: a cross-point may hold several conductive elements, each
+ * with its own material properties, updated one by one or all together).  A unit cell is given as
+ * an array of 1..8 distinct tiles of the same shape, GPU and train length; device k holds the
+ * conductances w^(k), and the cell's weight is sum_k gamma_k w^(k).  `gamma` is a HOST array.
+ *
+ * aht_unit_cell_update: the devices of a cell sit on the same row and column lines, so one set of
+ *   pulse trains is drawn -- with device 0's seed, update parameters and pulse mode at device 0's
+ *   step count -- and applied to every device (which = -1) or to device `which` only, each through
+ *   its own response model and pulse-to-pulse noise stream.  The step counters of all devices are
+ *   set to device 0's count + 1.  B = 0 and lr = 0 as for aht_pulsed_update.
+ * aht_unit_cell_weights: w_out[rows][cols] = sum_k gamma_k w^(k), added in device order in fp32.
+ * aht_unit_cell_forward / _backward: aht_forward / aht_backward on that effective weight (it is
+ *   formed in scratch owned by device 0, whose call counters and seed serve the product).
+ * Errors: INVALID_ARG (null, n out of range, a tile twice, mismatched devices, which out of range,
+ * non-finite gamma or lr), OOM, DEVICE. */
+aht_status aht_unit_cell_update(aht_tile* const* devices, int32_t n, int32_t which, const float* x_dev,
+                                const float* d_dev, int32_t B, float lr, void* stream);
+aht_status aht_unit_cell_weights(aht_tile* const* devices, const float* gamma, int32_t n, float* w_out_dev,
+                                 void* stream);
+aht_status aht_unit_cell_forward(aht_tile* const* devices, const float* gamma, int32_t n, const aht_io_params* io,
+                                 const float* x_dev, float* y_dev, float* pre_dev, int32_t B, void* stream);
+aht_status aht_unit_cell_backward(aht_tile* const* devices, const float* gamma, int32_t n, const aht_io_params* io,
+                                  const float* d_dev, float* g_dev, float* pre_dev, int32_t B, void* stream);
+
 /* Once-per-mini-batch temporal processes with device-to-device variability (Sec. 4, last
  * paragraph: conductance decay, reset and diffusion).  Per-cell planes are drawn at
  * aht_set_temporal from the tile's seed:

@@ -374,3 +374,30 @@ def num_threads():
 
 def set_num_threads(n):
     lib().orc_set_num_threads(int(n))
+
+
+# ---------------------------------------------------------------------------------------------
+# Unit cells of several devices (Sec. 4 of the paper: a cross-point may hold several conductive
+# elements with their own material properties, updated one by one or all together).  Reading:
+# the devices of a cell share the row and column lines, so one set of pulse trains (drawn with
+# device 0's seed at the cell's step) reaches every updated device, which steps through its own
+# response model and pulse-to-pulse noise stream; the cell's weight is sum_k gamma_k w^(k).
+# ---------------------------------------------------------------------------------------------
+def unit_cell_update(Ws, planes, params, seeds, BL, update_management, x, d, lr, t, which=-1):
+    """In place on the list of device weights ``Ws``; returns the pulses applied per device."""
+    xw, dw = pulse_words(x, d, lr, params[0].dw_min, BL, update_management, seeds[0], t)
+    counts = []
+    for k, W in enumerate(Ws):
+        if which >= 0 and k != which:
+            counts.append(0)
+            continue
+        counts.append(apply_words(W, planes[k], params[k].kind, params[k].dw_min_std, xw, dw, BL, seeds[k], t))
+    return counts
+
+
+def unit_cell_weights(Ws, gamma):
+    """float32 [R][C]: sum_k gamma_k W_k, added in device order, every operation rounded to fp32."""
+    acc = np.zeros_like(Ws[0], dtype=np.float32)
+    for g, W in zip(gamma, Ws):
+        acc = (acc + np.float32(g) * W.astype(np.float32)).astype(np.float32)
+    return acc

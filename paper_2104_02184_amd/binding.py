@@ -25,6 +25,7 @@ EXPORTS = (
     "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
     "aht_pulsed_update_conv2d", "aht_debug_pulse_words_conv2d", "aht_forward", "aht_backward",
     "aht_transfer_column", "aht_get_mvm_steps", "aht_set_mvm_steps",
+    "aht_unit_cell_update", "aht_unit_cell_weights", "aht_unit_cell_forward", "aht_unit_cell_backward",
     "aht_set_pulse_mode", "aht_set_temporal", "aht_decay_diffuse", "aht_reset_columns", "aht_get_temporal_plane",
     "aht_get_temporal_step", "aht_set_temporal_step",
     "aht_status_string", "aht_last_error", "aht_version",
@@ -140,6 +141,11 @@ def load_library() -> ctypes.CDLL:
     L.aht_forward.argtypes = [vp, ctypes.POINTER(aht_io_params), vp, vp, vp, i32, vp]
     L.aht_backward.argtypes = [vp, ctypes.POINTER(aht_io_params), vp, vp, vp, i32, vp]
     L.aht_transfer_column.argtypes = [vp, vp, i32, f32, ctypes.POINTER(aht_io_params), vp]
+    L.aht_unit_cell_update.argtypes = [ctypes.POINTER(vp), i32, i32, vp, vp, i32, f32, vp]
+    L.aht_unit_cell_weights.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(f32), i32, vp, vp]
+    L.aht_unit_cell_forward.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(f32), i32, ctypes.POINTER(aht_io_params),
+                                        vp, vp, vp, i32, vp]
+    L.aht_unit_cell_backward.argtypes = L.aht_unit_cell_forward.argtypes
     L.aht_get_mvm_steps.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(u32)]
     L.aht_set_mvm_steps.argtypes = [vp, u32, u32]
     L.aht_set_pulse_mode.argtypes = [vp, i32, i32]
@@ -394,6 +400,57 @@ class Tile:
         _check(self._lib.aht_debug_apply_words(self._h, _ptr(xw, torch.int64, (B, self.cols)),
                                                _ptr(dw, torch.int64, (B, self.rows)), B, ctypes.c_uint32(step),
                                                _stream()))
+
+
+class UnitCell:
+    """Several tiles used as the devices of one unit cell (wraps the ``aht_unit_cell_*`` calls);
+    ``gamma[k]`` weighs device k in the cell's effective weight."""
+
+    def __init__(self, devices, gamma=None):
+        self.devices = list(devices)
+        self.gamma = [1.0] * len(self.devices) if gamma is None else [float(g) for g in gamma]
+        assert len(self.gamma) == len(self.devices)
+        self._lib = load_library()
+
+    def _handles(self):
+        return (ctypes.c_void_p * len(self.devices))(*[t._h for t in self.devices])
+
+    def _gamma(self):
+        return (ctypes.c_float * len(self.gamma))(*self.gamma)
+
+    def pulsed_update(self, x, d, lr: float, which: int = -1):
+        """One set of pulse trains for the cell; applied to all devices (which = -1) or to one."""
+        import torch
+        lead = self.devices[0]
+        B = int(x.shape[0])
+        _check(self._lib.aht_unit_cell_update(self._handles(), len(self.devices), which,
+                                              _ptr(x, torch.float32, (B, lead.cols)),
+                                              _ptr(d, torch.float32, (B, lead.rows)), B, ctypes.c_float(lr), _stream()))
+
+    def weights(self):
+        import torch
+        lead = self.devices[0]
+        out = torch.empty((lead.rows, lead.cols), dtype=torch.float32, device="cuda")
+        _check(self._lib.aht_unit_cell_weights(self._handles(), self._gamma(), len(self.devices),
+                                               _ptr(out, torch.float32), _stream()))
+        return out
+
+    def _mvm(self, fn, io, x, n_in, n_out):
+        import torch
+        B = int(x.shape[0])
+        y = torch.empty((B, n_out), dtype=torch.float32, device="cuda")
+        c = io.to_c()
+        _check(fn(self._handles(), self._gamma(), len(self.devices), ctypes.byref(c), _ptr(x, torch.float32, (B, n_in)),
+                  _ptr(y, torch.float32), ctypes.c_void_p(), B, _stream()))
+        return y
+
+    def forward(self, x, io: "IOParams"):
+        lead = self.devices[0]
+        return self._mvm(self._lib.aht_unit_cell_forward, io, x, lead.cols, lead.rows)
+
+    def backward(self, d, io: "IOParams"):
+        lead = self.devices[0]
+        return self._mvm(self._lib.aht_unit_cell_backward, io, d, lead.rows, lead.cols)
 
 
 def debug_philox(ctr, key):

@@ -46,6 +46,7 @@ struct aht_tile {
     float* mvm_norm = nullptr;
     size_t mvm_xq_floats = 0;
     float* mvm_part = nullptr;    // partial sums of a K-split product [splits][B][N]
+    float* ucell_w = nullptr;     // effective weights of the unit cell this tile leads [rows][cols]
     size_t mvm_part_floats = 0;
     int mvm_b_cap = 0;
     uint32_t fwd_step = 0, bwd_step = 0;
@@ -237,7 +238,9 @@ int choose_rpl(const aht_tile* t)
 
 // the cell update of step `step` from the words in the tile's scratch
 // `strip0`, `strips`: the range of 64-column strips to work on (the caller knows that x is zero elsewhere)
-aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strip0, uint32_t strips)
+// `words`: the tile whose scratch holds the pulse words (the tile itself, or the first device of its unit cell)
+aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strip0, uint32_t strips,
+                        const aht_tile* words = nullptr)
 {
     const int rpl = choose_rpl(t);
     // stream storage per cell: 12 words hold 320 pulses before an early drain is needed
@@ -252,8 +255,8 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     p.b_min = t->planes[AHT_PLANE_B_MIN];
     p.slope_up = t->planes[AHT_PLANE_SLOPE_UP];
     p.slope_down = t->planes[AHT_PLANE_SLOPE_DOWN];
-    p.xw = t->xw;
-    p.dw = t->dw;
+    p.xw = words ? words->xw : t->xw;
+    p.dw = words ? words->dw : t->dw;
     p.pulse_count = t->pulse_count;
     CellArgs a{};
     a.R = t->rows;
@@ -382,7 +385,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     for (auto* p : t->planes) rel(p);
     rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->bl_b); rel(t->pulse_count);
     for (auto* p : t->tplanes) rel(p);
-    rel(t->mvm_xq); rel(t->mvm_part); rel(t->mvm_alpha); rel(t->mvm_norm); rel(t->xfer);
+    rel(t->mvm_xq); rel(t->mvm_part); rel(t->ucell_w); rel(t->mvm_alpha); rel(t->mvm_norm); rel(t->xfer);
     for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
     delete t;
     if (first != hipSuccess) return hip_fail(first, "aht_tile_destroy");
@@ -482,8 +485,9 @@ aht_status aht_pulsed_update_conv2d(aht_tile* t, const float* img_dev, const flo
     return pulsed_update_impl(t, img_dev, grad_dev, B, lr, stream, v);
 }
 
+// `w_eff`: weights to multiply with instead of the tile's own (the effective weights of a unit cell)
 static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* x, float* y, float* pre, int32_t B,
-                             bool transposed, hipStream_t s)
+                             bool transposed, hipStream_t s, const float* w_eff = nullptr)
 {
     if (!t || !io || !x || !y) return fail(AHT_ERR_INVALID_ARG, "null argument");
     if (B <= 0) return fail(AHT_ERR_INVALID_ARG, "B must be > 0");
@@ -544,10 +548,11 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     const unsigned total = (unsigned)mb * (unsigned)nb * (unsigned)splits;
     const dim3 grid(((total + 7u) / 8u) * 8u);
     // 16-byte accesses need aligned rows and whole groups; the tile's weights start 256-byte aligned
+    const float* wmat = w_eff ? w_eff : t->W;
     const bool aligned = (K % 32 == 0) && (t->cols % 4 == 0) && (N % 4 == 0) &&
-                         (((uintptr_t)t->mvm_xq | (uintptr_t)t->W) % 16 == 0);
+                         (((uintptr_t)t->mvm_xq | (uintptr_t)wmat) % 16 == 0);
 #define AHT_MVM_LAUNCH(TR, BMV, AL)                                                                              \
-    hipLaunchKernelGGL((k_mvm_gemm<TR, BMV, AL>), grid, dim3(256), 0, s, t->mvm_xq, t->W, B, N, K, t->cols,       \
+    hipLaunchKernelGGL((k_mvm_gemm<TR, BMV, AL>), grid, dim3(256), 0, s, t->mvm_xq, wmat, B, N, K, t->cols,       \
                        t->mvm_alpha, t->mvm_norm, a, k0, k1, step, tag_out, y, pre, t->mvm_part, splits, mb, nb)
 #define AHT_MVM_PICK(TR)                                                                                         \
     do {                                                                                                         \
@@ -617,6 +622,93 @@ aht_status aht_transfer_column(aht_tile* src, aht_tile* dst, int32_t col, float 
     }
     // dst -= lr * (-read) e_col^T; only the strip of 64 columns that holds `col` can receive pulses
     return pulsed_update_impl(dst, onehot, neg, 1, lr, stream, ConvView{}, col, col);
+}
+
+static aht_status check_unit_cell(aht_tile* const* dev, int32_t n)
+{
+    if (!dev || n < 1 || n > 8) return fail(AHT_ERR_INVALID_ARG, "a unit cell has 1..8 devices");
+    for (int k = 0; k < n; ++k) {
+        if (!dev[k]) return fail(AHT_ERR_INVALID_ARG, "null device");
+        for (int j = 0; j < k; ++j)
+            if (dev[j] == dev[k]) return fail(AHT_ERR_INVALID_ARG, "a tile appears twice in the unit cell");
+        if (dev[k]->rows != dev[0]->rows || dev[k]->cols != dev[0]->cols || dev[k]->device != dev[0]->device ||
+            dev[k]->upd.bl != dev[0]->upd.bl)
+            return fail(AHT_ERR_INVALID_ARG, "devices of a unit cell must agree in shape, device and train length");
+    }
+    return check_device(dev[0]);
+}
+
+aht_status aht_unit_cell_update(aht_tile* const* dev, int32_t n, int32_t which, const float* x_dev, const float* d_dev,
+                                int32_t B, float lr, void* stream)
+{
+    aht_status st = check_unit_cell(dev, n);
+    if (st != AHT_OK) return st;
+    if (which < -1 || which >= n) return fail(AHT_ERR_INVALID_ARG, "device index %d out of range", which);
+    if (B < 0) return fail(AHT_ERR_INVALID_ARG, "B must be >= 0");
+    if (!(lr >= 0.0f) || !std::isfinite(lr)) return fail(AHT_ERR_INVALID_ARG, "lr must be finite and >= 0");
+    if (B > 0 && (!x_dev || !d_dev)) return fail(AHT_ERR_INVALID_ARG, "null x or d");
+    aht_tile* lead = dev[0];
+    const uint32_t step = lead->step;
+    if (B > 0 && lr > 0.0f) {
+        if ((st = ensure_scratch(lead, B)) != AHT_OK) return st;
+        hipStream_t s = (hipStream_t)stream;
+        if ((st = launch_words(lead, x_dev, d_dev, B, lr, step, s, ConvView{})) != AHT_OK) return st;
+        const uint32_t strips = (uint32_t)((lead->cols + 63) / 64);
+        for (int k = 0; k < n; ++k) {
+            if (which >= 0 && k != which) continue;
+            if ((st = launch_cells(dev[k], B, step, s, 0u, strips, lead)) != AHT_OK) return st;
+        }
+    }
+    for (int k = 0; k < n; ++k) dev[k]->step = step + 1;     // the cell's devices count calls together
+    return AHT_OK;
+}
+
+static aht_status unit_cell_weights(aht_tile* const* dev, const float* gamma, int32_t n, float* w_out_dev, hipStream_t s)
+{
+    UnitCellArgs u{};
+    u.n = n;
+    for (int k = 0; k < n; ++k) {
+        if (!std::isfinite(gamma[k])) return fail(AHT_ERR_INVALID_ARG, "gamma must be finite");
+        u.w[k] = dev[k]->W;
+        u.gamma[k] = gamma[k];
+    }
+    const size_t cells = (size_t)dev[0]->rows * dev[0]->cols;
+    hipLaunchKernelGGL(k_unit_cell_weights, dim3(blocks_for((cells + 3) / 4)), dim3(256), 0, s, u, w_out_dev, cells);
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+aht_status aht_unit_cell_weights(aht_tile* const* dev, const float* gamma, int32_t n, float* w_out_dev, void* stream)
+{
+    aht_status st = check_unit_cell(dev, n);
+    if (st != AHT_OK) return st;
+    if (!gamma || !w_out_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    return unit_cell_weights(dev, gamma, n, w_out_dev, (hipStream_t)stream);
+}
+
+static aht_status unit_cell_mvm(aht_tile* const* dev, const float* gamma, int32_t n, const aht_io_params* io,
+                                const float* x_dev, float* y_dev, float* pre_dev, int32_t B, bool transposed, void* stream)
+{
+    aht_status st = check_unit_cell(dev, n);
+    if (st != AHT_OK) return st;
+    if (!gamma) return fail(AHT_ERR_INVALID_ARG, "null gamma");
+    aht_tile* lead = dev[0];
+    if (!lead->ucell_w)
+        AHT_HIP(hipMalloc((void**)&lead->ucell_w, sizeof(float) * (size_t)lead->rows * lead->cols));
+    if ((st = unit_cell_weights(dev, gamma, n, lead->ucell_w, (hipStream_t)stream)) != AHT_OK) return st;
+    return analog_mvm(lead, io, x_dev, y_dev, pre_dev, B, transposed, (hipStream_t)stream, lead->ucell_w);
+}
+
+aht_status aht_unit_cell_forward(aht_tile* const* dev, const float* gamma, int32_t n, const aht_io_params* io,
+                                 const float* x_dev, float* y_dev, float* pre_dev, int32_t B, void* stream)
+{
+    return unit_cell_mvm(dev, gamma, n, io, x_dev, y_dev, pre_dev, B, false, stream);
+}
+
+aht_status aht_unit_cell_backward(aht_tile* const* dev, const float* gamma, int32_t n, const aht_io_params* io,
+                                  const float* d_dev, float* g_dev, float* pre_dev, int32_t B, void* stream)
+{
+    return unit_cell_mvm(dev, gamma, n, io, d_dev, g_dev, pre_dev, B, true, stream);
 }
 
 aht_status aht_get_mvm_steps(const aht_tile* t, uint32_t* f, uint32_t* b)

@@ -92,6 +92,41 @@ __global__ void __launch_bounds__(256) k_one_hot(float* x, int n, int hot)
     if (k < n) x[k] = (k == hot) ? 1.0f : 0.0f;
 }
 
+// effective weight of a unit cell: out = sum_k gamma_k W_k, added in device order, four cells per thread
+struct UnitCellArgs {
+    const float* w[8];
+    float gamma[8];
+    int n;
+};
+__global__ void __launch_bounds__(256) k_unit_cell_weights(UnitCellArgs u, float* __restrict__ out, size_t cells)
+{
+    const size_t i4 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i4 >= cells) return;
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const bool whole = i4 + 3 < cells;
+    for (int k = 0; k < u.n; ++k) {
+        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (whole) {
+            const float4 q = *(const float4*)(u.w[k] + i4);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (i4 + e < cells) v[e] = u.w[k][i4 + e];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float term = u.gamma[k] * v[e];
+            acc[e] = acc[e] + term;
+        }
+    }
+    if (whole) {
+        *(float4*)(out + i4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    } else {
+        for (int e = 0; e < 4; ++e)
+            if (i4 + e < cells) out[i4 + e] = acc[e];
+    }
+}
+
 __global__ void __launch_bounds__(256) k_negate(const float* in, float* out, int n)
 {
     const int k = blockIdx.x * 256 + threadIdx.x;

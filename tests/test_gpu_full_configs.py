@@ -69,3 +69,29 @@ def test_full_size_workload_matches_oracle_on_sampled_cells(name):
     # properties that hold for every cell: inside the per-cell bounds, finite
     assert np.isfinite(Wg).all()
     assert (Wg <= oplanes["b_max"] * (1 + 1e-6) + 1e-12).all() and (Wg >= oplanes["b_min"] * (1 + 1e-6) - 1e-12).all()
+
+
+@pytest.mark.parametrize("transposed", [False, True])
+def test_full_size_analog_product_matches_oracle(transposed):
+    """The analog product of the side benchmark (headline tile, B = 256, the benchmark's noise
+    settings plus quantisation) against the oracle's full result."""
+    w = wl.WORKLOADS[wl.HEADLINE]
+    io_kw = dict(inp_res=1.0 / 126.0, inp_bound=1.0, inp_noise=0.01, w_noise=0.02, out_noise=0.06,
+                 out_res=12.0 / 254.0, out_bound=12.0, noise_management=True)
+    tile = make_tile(w)
+    W = wl.initial_weights(w)
+    tile.set_weights(to_dev(W))
+    g = wl.rng_for(w, 3)
+    n_in = w.rows if transposed else w.cols
+    x = g.standard_normal((w.batch, n_in), dtype="float32")
+    fn = tile.backward if transposed else tile.forward
+    y, pre = fn(to_dev(x), aht.IOParams(**io_kw), with_pre=True)
+    y, pre = y.cpu().numpy(), pre.cpu().numpy()
+    yo, po = oracle.analog_mvm(W, x, oracle.IOParams(**io_kw), w.seed, 0, transposed=transposed, return_pre=True)
+    tol = 2e-5 * max(1.0, float(np.abs(po).max())) * max(1.0, np.sqrt(n_in) / 16)
+    assert np.abs(pre.astype(np.float64) - po).max() <= tol
+    step_out = io_kw["out_res"] * np.abs(x).max(axis=1, keepdims=True)
+    diff = np.abs(y.astype(np.float64) - yo)
+    same = diff <= 1e-6 * np.maximum(1.0, np.abs(yo))
+    assert (diff <= step_out * (1 + 1e-5) + 1e-9).all() and same.mean() > 0.999
+    tile.close()

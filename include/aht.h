@@ -220,7 +220,9 @@ aht_status aht_set_mvm_steps(aht_tile* tile, uint32_t forward_calls, uint32_t ba
  * and writes it onto the slow tile `dst` with one pulsed update: dst[:, col] += lr * read, in
  * the mean, through dst's own device model.  Both tiles must have the same shape and live on
  * the same device.  Uses and advances src's forward counter and dst's step counter; asynchronous
- * on `stream`; scratch is owned by `dst`.  Errors: INVALID_ARG (null, shape mismatch, col out
+ * on `stream`; scratch is owned by `dst`.  Without input noise the product reduces to the column
+ * itself, which is then read directly (same values bit for bit); the pulsed write only visits the
+ * 64 columns around `col`.  Errors: INVALID_ARG (null, shape mismatch, col out
  * of range, lr < 0), OOM, DEVICE. */
 aht_status aht_transfer_column(aht_tile* src, aht_tile* dst, int32_t col, float lr, const aht_io_params* io,
                                void* stream);

@@ -629,17 +629,17 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                 sl_dn[c] = (bmin[c] != 0.0f) ? 1.0f / bmin[c] : 0.0f;
             }
         }
-        uint32_t endpos[RPL], start[RPL], blk0[RPL], D[RPL], sb[RPL], home[RPL];
+        // Per cell: stream end, Gaussian block of the next iteration, current stream word, and the
+        // row the cell belongs to (cells may change slots below).  A stream starts at bit q & 31.
+        uint32_t endpos[RPL], blk[RPL], D[RPL], home[RPL];
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
             commit(c);
             lds_store_u32(wp[c], acc_lo[c] << ((32u - fill[c]) & 31u));      // left-aligned partial word
             endpos[c] = ((wp[c] - qb(c)) >> 3) + fill[c];                    // 32 bits per 256-byte step
-            start[c] = q[c] & 31u;
-            blk0[c] = (q[c] >> 5) << 3;
+            blk[c] = (q[c] >> 5) << 3;
             D[c] = 0;
-            sb[c] = qb(c);                        // LDS address of the stream
-            home[c] = (uint32_t)c;                // the row this slot's cell belongs to
+            home[c] = (uint32_t)c;
         }
         const bool sorted = (RPL == 4) && last;
         if (sorted) {
@@ -650,7 +650,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                     p = tp;
                     r = tr;
                 };
-                ex(endpos[x], endpos[y]); ex(start[x], start[y]); ex(blk0[x], blk0[y]); ex(sb[x], sb[y]);
+                ex(endpos[x], endpos[y]); ex(q[x], q[y]); ex(blk[x], blk[y]);
                 ex(home[x], home[y]); ex(cellid[x], cellid[y]); ex(w[x], w[y]); ex(s_up[x], s_up[y]);
                 ex(s_dn_neg[x], s_dn_neg[y]); ex(bmax[x], bmax[y]); ex(bmin[x], bmin[y]);
                 ex(sl_up[x], sl_up[y]); ex(sl_dn[x], sl_dn[y]);
@@ -670,14 +670,15 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             row_plain_end[c] = (int)(~wave_max_u32(~endpos[c]) >> 2);        // wave minimum, rounded down
             niter = niter > row_iters[c] ? niter : row_iters[c];
             plain_end = plain_end < row_plain_end[c] ? plain_end : row_plain_end[c];
-            last_start = last_start > start[c] ? last_start : start[c];
+            last_start = last_start > (q[c] & 31u) ? last_start : (q[c] & 31u);
         }
         const int plain_begin = (int)((wave_max_u32(last_start) + 3u) >> 2);  // every stream has started
         const float c2c_unit = a.c2c * kGaussUnitScale;              // the Gaussians below come without this factor
         auto load_words = [&](int i) __attribute__((always_inline)) {
             if ((i & 7) == 0) {
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) D[c] = lds_load_u32(sb[c] + (uint32_t)(i >> 3) * kWordStride);
+                for (int c = 0; c < RPL; ++c)
+                    D[c] = lds_load_u32(qb0 + home[c] * cell_stride + (uint32_t)(i >> 3) * kWordStride);
             }
         };
         // Stream bits 4i .. 4i+3 of the lanes' c-th cells.  mode 0: all four pulses exist in every
@@ -685,8 +686,9 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         auto row_step = [&](int i, int c, auto mode_tag) __attribute__((always_inline)) {
             constexpr int mode = decltype(mode_tag)::value;
             float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (NOISE) gauss4_unit(a.k0, a.k1, cellid[c], blk0[c] + (uint32_t)i, a.t, kTagC2C, z);
-            const int lo = (int)start[c] - 4 * i, hi = (int)endpos[c] - 4 * i;
+            if (NOISE) gauss4_unit(a.k0, a.k1, cellid[c], blk[c], a.t, kTagC2C, z);
+            blk[c] += 1;
+            const int lo = (int)(q[c] & 31u) - 4 * i, hi = (int)endpos[c] - 4 * i;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint32_t dmask = (uint32_t)__builtin_amdgcn_sbfe((int)D[c], 31 - k, 1);
@@ -733,7 +735,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         }
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31 (after a sorted
-            q[c] += endpos[c] - start[c];         // drain only the sum of q is still used)
+            q[c] += endpos[c] - (q[c] & 31u);     // drain only the sum of q is still used)
             acc_lo[c] = 0;
             acc_hi[c] = 0;
             fill[c] = q[c] & 31u;

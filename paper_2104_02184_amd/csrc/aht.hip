@@ -246,7 +246,8 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     // stream storage per cell: 12 words hold 320 pulses before an early drain is needed
     int qwords = env_int("AHT_QWORDS", 0);
     if (qwords < 5 || qwords > 160) qwords = 12;
-    while (qwords > 5 && (size_t)4 * rpl * 64 * qwords * 4 > 160 * 1024) --qwords;   // LDS of one CU
+    const size_t lds_extra = (rpl > 1) ? 4 * 1024 : 0;       // exchange buffers of the last drain, 1 KB per wave
+    while (qwords > 5 && (size_t)4 * rpl * 64 * qwords * 4 + lds_extra > 160 * 1024) --qwords;   // LDS of one CU
     CellPtrs p{};
     p.W = t->W;
     p.dw_up = t->planes[AHT_PLANE_DW_UP];
@@ -277,7 +278,7 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     const uint64_t per = (total + 7) / 8;
     if (per * 8 > 0x7FFFFFFFull) return fail(AHT_ERR_UNSUPPORTED, "tile too large for one launch");
     const dim3 grid((unsigned)(per * 8));
-    const size_t lds = (size_t)4 * rpl * 64 * qwords * 4;
+    const size_t lds = (size_t)4 * rpl * 64 * qwords * 4 + lds_extra;
     const bool noise = t->dev.dw_min_std > 0.0f;
     if (use_u32(t)) launch_cells_kind<uint32_t>(t->dev.kind, noise, rpl, grid, lds, s, p, a);
     else launch_cells_kind<uint64_t>(t->dev.kind, noise, rpl, grid, lds, s, p, a);

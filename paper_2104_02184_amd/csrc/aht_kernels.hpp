@@ -489,6 +489,14 @@ __device__ __forceinline__ float device_step(float w, uint32_t dmask, float z, f
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
 __device__ __forceinline__ void lds_store_u32(uint32_t addr, uint32_t v) { *(lds_u32*)(size_t)addr = v; }
 __device__ __forceinline__ uint32_t lds_load_u32(uint32_t addr) { return *(const lds_u32*)(size_t)addr; }
+__device__ __forceinline__ void lds_atomic_add_u32(uint32_t addr, uint32_t v)
+{
+    (void)__hip_atomic_fetch_add((lds_u32*)(size_t)addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ uint32_t lds_atomic_add_rtn_u32(uint32_t addr, uint32_t v)
+{
+    return __hip_atomic_fetch_add((lds_u32*)(size_t)addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
@@ -629,36 +637,77 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                 sl_dn[c] = (bmin[c] != 0.0f) ? 1.0f / bmin[c] : 0.0f;
             }
         }
-        // Per cell: stream end, Gaussian block of the next iteration, current stream word, and the
-        // row the cell belongs to (cells may change slots below).  A stream starts at bit q & 31.
-        uint32_t endpos[RPL], blk[RPL], D[RPL], home[RPL];
+        // Per cell: stream end, Gaussian block of the next iteration, current stream word, the LDS
+        // address of its stream, and where it came from (cells may change lanes below).  A stream
+        // starts at bit q & 31.
+        uint32_t endpos[RPL], blk[RPL], D[RPL], sbase[RPL], origin[RPL];
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
             commit(c);
             lds_store_u32(wp[c], acc_lo[c] << ((32u - fill[c]) & 31u));      // left-aligned partial word
             endpos[c] = ((wp[c] - qb(c)) >> 3) + fill[c];                    // 32 bits per 256-byte step
-            blk[c] = (q[c] >> 5) << 3;
             D[c] = 0;
-            home[c] = (uint32_t)c;
+            sbase[c] = qb(c);
+            origin[c] = (uint32_t)(lane * RPL + c);
         }
-        const bool sorted = (RPL == 4) && last;
+        // Last drain of a call, several rows per lane: the wave's cells are dealt out again, the 64
+        // shortest streams to slot 0 of the 64 lanes, the next 64 to slot 1, and so on, so that the
+        // cells a drain iteration handles together are alike in length and few lanes idle while a
+        // row finishes.  A cell's whole state moves through a 1 KB exchange buffer behind the
+        // wave's streams.  Positions come from a counting sort on the stream length (buckets of two
+        // pulses): histogram, exclusive scan, one returning atomic per cell.  A wave's LDS
+        // operations take effect in program order, so the steps need no barrier.
+        const bool sorted = (RPL > 1) && last;
+        const uint32_t xbuf = lds0 + (uint32_t)(4 * RPL * 64 * a.qwords * 4) + (uint32_t)wave * 1024u;
         if (sorted) {
-            auto cswap = [&](int x, int y) __attribute__((always_inline)) {
-                const bool sw = endpos[x] > endpos[y];
-                auto ex = [&](auto& p, auto& r) __attribute__((always_inline)) {
-                    const auto tp = sw ? r : p, tr = sw ? p : r;
-                    p = tp;
-                    r = tr;
-                };
-                ex(endpos[x], endpos[y]); ex(q[x], q[y]); ex(blk[x], blk[y]);
-                ex(home[x], home[y]); ex(cellid[x], cellid[y]); ex(w[x], w[y]); ex(s_up[x], s_up[y]);
-                ex(s_dn_neg[x], s_dn_neg[y]); ex(bmax[x], bmax[y]); ex(bmin[x], bmin[y]);
-                ex(sl_up[x], sl_up[y]); ex(sl_dn[x], sl_dn[y]);
+            constexpr uint32_t kBuckets = 192;                       // 3 per lane
+            uint32_t bucket[RPL], pos[RPL];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) lds_store_u32(xbuf + (uint32_t)(3 * lane + k) * 4u, 0u);
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) {
+                const uint32_t bk = endpos[c] >> 1;
+                bucket[c] = bk < kBuckets - 1 ? bk : kBuckets - 1;
+                lds_atomic_add_u32(xbuf + bucket[c] * 4u, 1u);
+            }
+            uint32_t h[3];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) h[k] = lds_load_u32(xbuf + (uint32_t)(3 * lane + k) * 4u);
+            const uint32_t mine = h[0] + h[1] + h[2];
+            uint32_t incl = mine;                                    // inclusive scan over the lanes
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t up = (uint32_t)__shfl_up((int)incl, off, 64);
+                incl += (lane >= off) ? up : 0u;
+            }
+            const uint32_t excl = incl - mine;
+            lds_store_u32(xbuf + (uint32_t)(3 * lane) * 4u, excl);
+            lds_store_u32(xbuf + (uint32_t)(3 * lane + 1) * 4u, excl + h[0]);
+            lds_store_u32(xbuf + (uint32_t)(3 * lane + 2) * 4u, excl + h[0] + h[1]);
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) pos[c] = lds_atomic_add_rtn_u32(xbuf + bucket[c] * 4u, 1u);   // 0 .. 64 RPL - 1, each once
+            // every field: four stores to the cells' new places, four loads of the lane's new cells
+            auto move_u32 = [&](uint32_t (&v)[RPL]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + pos[c] * 4u, v[c]);
+#pragma unroll
+                for (int c = 0; c < RPL; ++c) v[c] = lds_load_u32(xbuf + (uint32_t)(c * 64 + lane) * 4u);
             };
-            if (RPL == 4) {                       // five-comparator network, ascending
-                cswap(0, 1); cswap(2 % RPL, 3 % RPL); cswap(0, 2 % RPL); cswap(1, 3 % RPL); cswap(1, 2 % RPL);
+            auto move_f32 = [&](float (&v)[RPL]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + pos[c] * 4u, __float_as_uint(v[c]));
+#pragma unroll
+                for (int c = 0; c < RPL; ++c) v[c] = __uint_as_float(lds_load_u32(xbuf + (uint32_t)(c * 64 + lane) * 4u));
+            };
+            move_u32(endpos); move_u32(q); move_u32(sbase); move_u32(origin); move_u32(cellid);
+            move_f32(w); move_f32(s_up); move_f32(s_dn_neg); move_f32(bmax); move_f32(bmin);
+            if (KIND != kConstantStep) {
+                move_f32(sl_up);
+                move_f32(sl_dn);
             }
         }
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) blk[c] = (q[c] >> 5) << 3;
         // Wave-uniform per row: iterations its longest stream needs, and the iteration from which
         // some stream of the row has fewer than four pulses left.
         int row_iters[RPL], row_plain_end[RPL];
@@ -678,7 +727,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             if ((i & 7) == 0) {
 #pragma unroll
                 for (int c = 0; c < RPL; ++c)
-                    D[c] = lds_load_u32(qb0 + home[c] * cell_stride + (uint32_t)(i >> 3) * kWordStride);
+                    D[c] = lds_load_u32(sbase[c] + (uint32_t)(i >> 3) * kWordStride);
             }
         };
         // Stream bits 4i .. 4i+3 of the lanes' c-th cells.  mode 0: all four pulses exist in every
@@ -722,16 +771,11 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                 else row_step(i, c, std::integral_constant<int, 2>{});
             }
         }
-        if (sorted) {                             // weights back to their rows (the stores stay coalesced)
-            float wo[RPL];
+        if (sorted) {                             // weights back to where their cells came from
 #pragma unroll
-            for (int c = 0; c < RPL; ++c) {
-                wo[c] = w[0];
+            for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + origin[c] * 4u, __float_as_uint(w[c]));
 #pragma unroll
-                for (int sl = 1; sl < RPL; ++sl) wo[c] = (home[sl] == (uint32_t)c) ? w[sl] : wo[c];
-            }
-#pragma unroll
-            for (int c = 0; c < RPL; ++c) w[c] = wo[c];
+            for (int c = 0; c < RPL; ++c) w[c] = __uint_as_float(lds_load_u32(xbuf + (uint32_t)(lane * RPL + c) * 4u));
         }
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31 (after a sorted

@@ -498,6 +498,14 @@ __device__ __forceinline__ uint32_t lds_atomic_add_rtn_u32(uint32_t addr, uint32
     return __hip_atomic_fetch_add((lds_u32*)(size_t)addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
+// lane index from the execution mask: valid where all lanes of the wave are active, which holds
+// everywhere in the cell kernel (its branches are wave-uniform); costs two instructions and no
+// long-lived register
+__device__ __forceinline__ uint32_t lane_by_count()
+{
+    return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
 #pragma unroll
@@ -661,15 +669,14 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         const uint32_t xbuf = lds0 + (uint32_t)(4 * RPL * 64 * a.qwords * 4) + (uint32_t)wave * 1024u;
         if (sorted) {
             constexpr uint32_t kBuckets = 192;                       // 3 per lane
-            uint32_t bucket[RPL], pos[RPL];
+            auto bucket_of = [&](int c) __attribute__((always_inline)) {
+                const uint32_t bk = endpos[c] >> 1;
+                return bk < kBuckets - 1 ? bk : kBuckets - 1;
+            };
 #pragma unroll
             for (int k = 0; k < 3; ++k) lds_store_u32(xbuf + (uint32_t)(3 * lane + k) * 4u, 0u);
 #pragma unroll
-            for (int c = 0; c < RPL; ++c) {
-                const uint32_t bk = endpos[c] >> 1;
-                bucket[c] = bk < kBuckets - 1 ? bk : kBuckets - 1;
-                lds_atomic_add_u32(xbuf + bucket[c] * 4u, 1u);
-            }
+            for (int c = 0; c < RPL; ++c) lds_atomic_add_u32(xbuf + bucket_of(c) * 4u, 1u);
             uint32_t h[3];
 #pragma unroll
             for (int k = 0; k < 3; ++k) h[k] = lds_load_u32(xbuf + (uint32_t)(3 * lane + k) * 4u);
@@ -684,18 +691,20 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             lds_store_u32(xbuf + (uint32_t)(3 * lane) * 4u, excl);
             lds_store_u32(xbuf + (uint32_t)(3 * lane + 1) * 4u, excl + h[0]);
             lds_store_u32(xbuf + (uint32_t)(3 * lane + 2) * 4u, excl + h[0] + h[1]);
+            uint32_t pos[RPL];                                       // LDS byte offset of the cell's new place
 #pragma unroll
-            for (int c = 0; c < RPL; ++c) pos[c] = lds_atomic_add_rtn_u32(xbuf + bucket[c] * 4u, 1u);   // 0 .. 64 RPL - 1, each once
+            for (int c = 0; c < RPL; ++c)
+                pos[c] = lds_atomic_add_rtn_u32(xbuf + bucket_of(c) * 4u, 1u) * 4u;   // places 0 .. 64 RPL - 1, each once
             // every field: four stores to the cells' new places, four loads of the lane's new cells
             auto move_u32 = [&](uint32_t (&v)[RPL]) __attribute__((always_inline)) {
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + pos[c] * 4u, v[c]);
+                for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + pos[c], v[c]);
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) v[c] = lds_load_u32(xbuf + (uint32_t)(c * 64 + lane) * 4u);
             };
             auto move_f32 = [&](float (&v)[RPL]) __attribute__((always_inline)) {
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + pos[c] * 4u, __float_as_uint(v[c]));
+                for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + pos[c], __float_as_uint(v[c]));
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) v[c] = __uint_as_float(lds_load_u32(xbuf + (uint32_t)(c * 64 + lane) * 4u));
             };
@@ -775,7 +784,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 #pragma unroll
             for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + origin[c] * 4u, __float_as_uint(w[c]));
 #pragma unroll
-            for (int c = 0; c < RPL; ++c) w[c] = __uint_as_float(lds_load_u32(xbuf + (uint32_t)(lane * RPL + c) * 4u));
+            for (int c = 0; c < RPL; ++c)
+                w[c] = __uint_as_float(lds_load_u32(xbuf + (lane_by_count() * RPL + (uint32_t)c) * 4u));
         }
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31 (after a sorted
@@ -957,9 +967,12 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     } while (!done);
 
     unsigned long long pulses = 0;
+    // the column is worked out again (lane index from the execution mask), so that neither the
+    // thread index nor a store address has to stay in registers from the start of the kernel to here
+    const int j_out = (int)bx * 64 + (int)lane_by_count();
 #pragma unroll
     for (int c = 0; c < RPL; ++c) {
-        if (cv[c]) __builtin_nontemporal_store(w[c], W + (size_t)(i0 + c) * C + j);
+        if ((i0 + c) < R && j_out < C) __builtin_nontemporal_store(w[c], W + (size_t)(i0 + c) * C + j_out);
         pulses += q[c];                           // cells outside the matrix see zero words: no pulses
     }
     if (pulse_count) {

@@ -658,14 +658,14 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             sbase[c] = qb(c);
             origin[c] = (uint32_t)(lane * RPL + c);
         }
-        // Last drain of a call, several rows per lane: the wave's cells are dealt out again, the 64
+        // Several rows per lane: before a drain the wave's cells are dealt out again, the 64
         // shortest streams to slot 0 of the 64 lanes, the next 64 to slot 1, and so on, so that the
         // cells a drain iteration handles together are alike in length and few lanes idle while a
         // row finishes.  A cell's whole state moves through a 1 KB exchange buffer behind the
         // wave's streams.  Positions come from a counting sort on the stream length (buckets of two
         // pulses): histogram, exclusive scan, one returning atomic per cell.  A wave's LDS
         // operations take effect in program order, so the steps need no barrier.
-        const bool sorted = (RPL > 1) && last;
+        const bool sorted = RPL > 1;
         const uint32_t xbuf = lds0 + (uint32_t)(4 * RPL * 64 * a.qwords * 4) + (uint32_t)wave * 1024u;
         if (sorted) {
             constexpr uint32_t kBuckets = 192;                       // 3 per lane
@@ -780,16 +780,30 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                 else row_step(i, c, std::integral_constant<int, 2>{});
             }
         }
-        if (sorted) {                             // weights back to where their cells came from
 #pragma unroll
-            for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + origin[c] * 4u, __float_as_uint(w[c]));
+        for (int c = 0; c < RPL; ++c) q[c] += endpos[c] - (q[c] & 31u);      // pulses applied so far
+        if (sorted) {
+            // The weights go back to where their cells came from; if more samples follow, so do the
+            // pulse counts and the cell indices (after the last drain only the sum of q is used).
+            auto send_home = [&](uint32_t (&v)[RPL]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int c = 0; c < RPL; ++c)
-                w[c] = __uint_as_float(lds_load_u32(xbuf + (lane_by_count() * RPL + (uint32_t)c) * 4u));
+                for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + origin[c] * 4u, v[c]);
+#pragma unroll
+                for (int c = 0; c < RPL; ++c) v[c] = lds_load_u32(xbuf + (lane_by_count() * RPL + (uint32_t)c) * 4u);
+            };
+            uint32_t wbits[RPL];
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) wbits[c] = __float_as_uint(w[c]);
+            send_home(wbits);
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) w[c] = __uint_as_float(wbits[c]);
+            if (!last) {
+                send_home(q);
+                send_home(cellid);
+            }
         }
 #pragma unroll
-        for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31 (after a sorted
-            q[c] += endpos[c] - (q[c] & 31u);     // drain only the sum of q is still used)
+        for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31
             acc_lo[c] = 0;
             acc_hi[c] = 0;
             fill[c] = q[c] & 31u;

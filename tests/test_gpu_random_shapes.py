@@ -1,0 +1,94 @@
+"""GPU parity on seeded random shapes and settings: small tiles of arbitrary size, every device
+kind, train length, rows-per-lane setting and stream capacity for the pulsed update (pulse counts
+exact, weights within 1e-5 w_max), and every block height and inner split for the analog product."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2104_02184_amd as aht
+
+from common import gpu_params, oracle_params, to_dev
+
+pytestmark = pytest.mark.gpu
+ENV_KEYS = ("AHT_RPL", "AHT_QWORDS", "AHT_MVM_BM", "AHT_MVM_SPLITS")
+
+
+@pytest.fixture
+def clean_env():
+    saved = {k: os.environ.get(k) for k in ENV_KEYS}
+    yield
+    for k, v in saved.items():
+        if v is None:
+            os.environ.pop(k, None)
+        else:
+            os.environ[k] = v
+
+
+def _setenv(**kw):
+    for k, v in kw.items():
+        if v:
+            os.environ[k] = str(v)
+        else:
+            os.environ.pop(k, None)
+
+
+@pytest.mark.parametrize("seed", [101, 202, 303])
+def test_pulsed_update_random_cases(seed, clean_env):
+    g = np.random.default_rng(seed)
+    for case in range(25):
+        R, C = int(g.integers(1, 200)), int(g.integers(1, 300))
+        B = int(g.integers(1, 70))
+        bl = int(g.choice([1, 7, 31, 32, 63]))
+        um = bool(g.integers(0, 2))
+        kind = int(g.integers(0, 3))
+        c2c, d2d = float(g.choice([0.0, 0.3])), float(g.choice([0.0, 0.3]))
+        lr, scale = float(g.choice([0.01, 0.1, 1.0, 5.0])), float(g.choice([0.1, 1.0, 30.0]))
+        _setenv(AHT_RPL=int(g.choice([0, 1, 2, 4])), AHT_QWORDS=int(g.choice([0, 5, 6, 12])))
+        dev = dict(kind=kind, dw_min=0.002, dw_min_dtod=d2d, dw_min_std=c2c, up_down=0.02,
+                   up_down_dtod=0.01 if d2d else 0.0, w_max=0.6, w_max_dtod=d2d, w_min=-0.6, w_min_dtod=d2d,
+                   gamma_up=0.7, gamma_down=0.5, gamma_dtod=d2d)
+        tseed = int(g.integers(1, 1 << 30))
+        tile = aht.Tile(R, C, gpu_params(dev), bl, um, tseed)
+        planes = oracle.device_planes(oracle_params(dev), tseed, R, C)
+        W0 = np.clip(g.uniform(-0.3, 0.3, size=(R, C)), planes["b_min"], planes["b_max"]).astype(np.float32)
+        tile.set_weights(to_dev(W0))
+        Wo, total = W0.copy(), 0
+        for t in range(3):
+            x = (g.normal(size=(B, C)) * scale).astype(np.float32)
+            d = (g.normal(size=(B, R)) * scale).astype(np.float32)
+            if g.integers(0, 4) == 0:
+                x[g.integers(0, B)] = 0
+            tile.pulsed_update(to_dev(x), to_dev(d), lr)
+            total += oracle.pulsed_update(Wo, planes, oracle_params(dev), bl, um, x, d, lr, tseed, t)
+        Wg = tile.get_weights().cpu().numpy()
+        what = dict(case=case, R=R, C=C, B=B, bl=bl, um=um, kind=kind, c2c=c2c, d2d=d2d, lr=lr, scale=scale)
+        assert tile.pulse_count() == total, what
+        assert np.abs(Wg.astype(np.float64) - Wo).max() / 0.6 <= 1e-5, what
+        tile.close()
+
+
+@pytest.mark.parametrize("seed", [11, 22])
+def test_analog_product_random_cases(seed, clean_env):
+    g = np.random.default_rng(seed)
+    for case in range(30):
+        R, C, B = int(g.integers(1, 260)), int(g.integers(1, 400)), int(g.integers(1, 200))
+        transposed = bool(g.integers(0, 2))
+        _setenv(AHT_MVM_BM=int(g.choice([0, 64, 128])), AHT_MVM_SPLITS=int(g.choice([0, 1, 2, 5])))
+        nm = bool(g.integers(0, 2))
+        io_kw = dict(inp_res=float(g.choice([0.0, 1 / 126])), inp_bound=1.0 if nm else 1e30,
+                     inp_noise=float(g.choice([0.0, 0.01])), w_noise=float(g.choice([0.0, 0.02])),
+                     out_noise=float(g.choice([0.0, 0.05])), out_res=0.0, out_bound=1e30, noise_management=nm)
+        tseed = int(g.integers(1, 1 << 30))
+        tile = aht.Tile(R, C, aht.DeviceParams(w_max=1.0, w_min=-1.0), 31, False, tseed)
+        W = g.uniform(-0.6, 0.6, size=(R, C)).astype(np.float32)
+        tile.set_weights(to_dev(W))
+        x = g.normal(size=(B, R if transposed else C)).astype(np.float32)
+        fn = tile.backward if transposed else tile.forward
+        y = fn(to_dev(x), aht.IOParams(**io_kw)).cpu().numpy()
+        yo = oracle.analog_mvm(W, x, oracle.IOParams(**io_kw), tseed, 0, transposed=transposed)
+        tol = (3e-5 * max(1.0, float(np.abs(yo).max())) * max(1.0, np.sqrt(x.shape[1]) / 16)
+               * max(1.0, float(np.abs(x).max())))
+        assert np.abs(y.astype(np.float64) - yo).max() <= tol, dict(case=case, R=R, C=C, B=B, transposed=transposed, **io_kw)
+        tile.close()

@@ -183,14 +183,10 @@ struct CellPtrs {
 template <int KIND, typename WordT, bool NOISE, int RPL>
 void launch_cells_one(dim3 grid, size_t lds, hipStream_t s, const CellPtrs& p, const CellArgs& a)
 {
-    if (lds > 64 * 1024) {   // more dynamic LDS than the default limit: opt in (gfx950 has 160 KB per CU)
-        static size_t allowed = 0;
-        if (lds > allowed) {
-            (void)hipFuncSetAttribute((const void*)k_cell_update<KIND, WordT, NOISE, RPL>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            allowed = lds;
-        }
-    }
+    if (lds > 64 * 1024)     // more dynamic LDS than the default limit: opt in (gfx950 has 160 KB per CU);
+                             // per call, because the attribute belongs to the current device's copy of the kernel
+        (void)hipFuncSetAttribute((const void*)k_cell_update<KIND, WordT, NOISE, RPL>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL((k_cell_update<KIND, WordT, NOISE, RPL>), grid, dim3(256), lds, s, p.W, p.dw_up, p.dw_down,
                        p.b_max, p.b_min, p.slope_up, p.slope_down, (const WordT*)p.xw, (const WordT*)p.dw,
                        p.pulse_count, a);

@@ -48,29 +48,56 @@ def algorithmic_lane_ops(w, pulses_per_call):
     return C_CS[word_bytes] * w.rows * w.cols * w.batch + c_p * pulses_per_call
 
 
-def cpu_baseline(w, target_rows):
-    """The oracle, as it stands, on a row slice of the same workload (same device law, same
-    input law, same B and BL); all host threads."""
+def host_cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def oracle_call(w, rows, threads):
+    """One oracle call on the first `rows` rows of workload `w`; returns (work, pulses, seconds)."""
     import numpy as np
 
     import oracle
     from paper_2104_02184_amd import workloads as wl
 
-    s = wl.scaled(w, rows=target_rows, steps=1, name=w.name + "_cpu_sample")
+    s = wl.scaled(w, rows=rows, steps=1, name=w.name + "_cpu_sample")
     p = oracle.DeviceParams(**s.device)
     planes = oracle.device_planes(p, s.seed, s.rows, s.cols)
     W = np.clip(wl.initial_weights(s), planes["b_min"], planes["b_max"]).astype(np.float32)
     _, x, d = next(iter(wl.input_stream(s)))
+    oracle.set_num_threads(threads)
     t0 = time.perf_counter()
     pulses = oracle.pulsed_update(W, planes, p, s.bl, s.update_management, x, d, s.lr, s.seed, 0)
     dt = time.perf_counter() - t0
+    return s, pulses, dt
+
+
+def cpu_baseline(w, target_rows):
+    """The oracle, as it stands, on a row slice of the same workload (same device law, same
+    input law, same B and BL): all host threads on `target_rows` rows, then one thread on an
+    quarter of them (the pulse words of all 4096 columns are part of both samples)."""
+    import oracle
+
+    all_threads = oracle.num_threads()
+    s, pulses, dt = oracle_call(w, target_rows, all_threads)
+    s1, pulses1, dt1 = oracle_call(w, max(1, target_rows // 4), 1)
+    oracle.set_num_threads(all_threads)
     return {
         "value": s.cell_pulse_updates_per_call / dt / 1e9,
         "unit": "Gcell-pulse-updates/s",
-        "cores": oracle.num_threads(),
+        "cores": all_threads,
         "kind": "oracle",
         "sample": f"{s.rows}x{s.cols} row slice of the headline tile, B={s.batch}, BL={s.bl}, 1 call "
                   f"({pulses} pulses, {dt:.2f} s wall)",
+        "single_thread_value": s1.cell_pulse_updates_per_call / dt1 / 1e9,
+        "single_thread_sample": f"{s1.rows}x{s1.cols} row slice, 1 call ({pulses1} pulses, {dt1:.2f} s wall)",
+        "host": f"{host_cpu_model()}, {os.cpu_count()} logical CPUs",
     }
 
 

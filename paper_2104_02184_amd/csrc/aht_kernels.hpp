@@ -560,7 +560,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     if (i0 >= a.R) return;                        // wave-uniform; the kernel has no barriers
     const int R = a.R, C = a.C, B = a.B;
     const size_t xstride = (size_t)a.Cpad, dstride = (size_t)a.Rpad;
-    const WordT* __restrict__ xp = xw + j;
+    const WordT* __restrict__ xp = xw + (size_t)bx * 64;   // wave-uniform: the strip's first column
     const WordT* __restrict__ dp = dw + i0;
 
     float w[RPL];
@@ -812,12 +812,21 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     };
 
     // ---- phase A ----------------------------------------------------------------------
-    const WordT* __restrict__ xcur = xp;          // column words of sample b
+    const WordT* __restrict__ xcur = xp;          // column words of sample b from the strip's first column on: a
+                                                  // scalar base, so that the loads take the lane as a 32-bit
+                                                  // offset and need no per-lane address arithmetic
+    const uint32_t xlane = (uint32_t)lane;
+    uint32_t xoff[G];                             // byte offsets of the lane's words of a group's G samples
+#pragma unroll
+    for (int u = 0; u < G; ++u) xoff[u] = (uint32_t)(((size_t)u * xstride + xlane) * sizeof(WordT));
     size_t doff = (size_t)i0;                     // dw[doff + c]: row words of sample b (wave-uniform,
                                                   // indexed off the kernel argument so that they stay scalar loads)
     auto load_x = [&](const WordT* __restrict__ p0, WordT (&xg)[G]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < G; ++u) xg[u] = p0[(size_t)u * xstride];
+        for (int u = 0; u < G; ++u) {
+            asm volatile("" : "+v"(xoff[u]));     // stays a 32-bit offset beside the scalar base
+            xg[u] = *(const WordT*)((const char*)p0 + xoff[u]);
+        }
     };
     // ~0 if the word's sign bit is set
     auto sign_mask = [&](WordT v) __attribute__((always_inline)) {
@@ -827,7 +836,9 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     auto count = [&](WordT xv, const WordT (&dv)[RPL], uint32_t (&n)[RPL]) __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
-            const WordT both = xv & (dv[c] & kBits);
+            WordT dm = dv[c] & kBits;             // the row word without its sign: on the scalar unit
+            if constexpr (sizeof(WordT) == 4) asm("" : "+s"(dm));            // (not folded into a three-input vector op)
+            const WordT both = xv & dm;
             n[c] = (sizeof(WordT) == 8)
                        ? (uint32_t)__popc((uint32_t)((uint64_t)both >> 32)) + (uint32_t)__popc((uint32_t)both)
                        : (uint32_t)__popc((uint32_t)both);
@@ -835,11 +846,14 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     };
     // direction masks of one sample: ~0 where x_j d_i < 0, an UP pulse.  The row part is
     // wave-uniform and stays on the scalar unit.
+    auto direction_of = [&](uint32_t xm, const WordT (&dv)[RPL], uint32_t (&m)[RPL]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) m[c] = xm ^ sign_mask(dv[c]);
+    };
     auto direction = [&](WordT xv, const WordT (&dv)[RPL], uint32_t (&m)[RPL]) __attribute__((always_inline)) {
         uint32_t xm = sign_mask(xv);
         asm volatile("" : "+v"(xm));
-#pragma unroll
-        for (int c = 0; c < RPL; ++c) m[c] = xm ^ sign_mask(dv[c]);
+        direction_of(xm, dv, m);
     };
     // a sample with any count: at most 16 bits at a time, flushing in between
     auto append_slow = [&](const uint32_t (&n)[RPL], const uint32_t (&m)[RPL]) __attribute__((always_inline)) {
@@ -866,9 +880,9 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         for (int c = 0; c < RPL; ++c) nf |= (wp[c] - qb(c)) > last_ok;
         return __any(nf) != 0;
     };
-    WordT xg[G], xn[G];                           // column words of the current and of the next group
-    bool have_x = false;                          // xg holds the words of samples b .. b+G-1
-    bool more = false;                            // xn holds the words of samples b+G .. b+2G-1
+    WordT xg[G];                                  // column words of the group in hand
+    bool have_x = false;                          // xg holds (or is about to receive) the words of samples b .. b+G-1
+    bool more = false;
     int b = 0;
     bool done = false;
     do {
@@ -876,44 +890,50 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         while (!full && b < B) {
             if (b + G <= B) {
                 WordT dg[G][RPL];                 // row words of the group (scalar registers)
-                uint32_t n[G][RPL], sum[RPL];
+                uint32_t n[G][RPL], xm[G], sum[RPL];
                 bool big = false;
-                // the group's bits join the pending words; then on to the next group
+                // the group's bits join the pending words (whose lengths the caller has advanced); then
+                // on to the next group, whose column words are already on their way into xg
                 auto take_group = [&]() __attribute__((always_inline)) {
 #pragma unroll
                     for (int u = 0; u < G; ++u) {
                         uint32_t m1[RPL];
-                        direction(xg[u], dg[u], m1);
+                        direction_of(xm[u], dg[u], m1);
 #pragma unroll
                         for (int c = 0; c < RPL; ++c) {
                             const uint32_t bits = __builtin_amdgcn_ubfe(m1[c], 0u, n[u][c]);   // n copies of the direction
                             pend[c] = (pend[c] << n[u][c]) | bits;
                         }
                     }
-#pragma unroll
-                    for (int c = 0; c < RPL; ++c) plen[c] += sum[c];
                     b += G;
                     xcur += (size_t)G * xstride;
                     doff += (size_t)G * dstride;
                     have_x = more;
-                    if (more) {
-#pragma unroll
-                        for (int u = 0; u < G; ++u) xg[u] = xn[u];
-                    }
                 };
                 // Straight path: groups are taken until some pending word of the wave would overflow.
+                // All that a group needs from its column words are the counts and the sign masks; once
+                // these are taken, the next group's words load into the same registers and arrive while
+                // the bits of this group are appended.
                 bool stopped = false;
+                if (!have_x) load_x(xcur, xg);
+                have_x = true;
                 for (;;) {
-                    if (!have_x) load_x(xcur, xg);
-                    have_x = true;
 #pragma unroll
                     for (int u = 0; u < G; ++u)
 #pragma unroll
                         for (int c = 0; c < RPL; ++c) dg[u][c] = dw[doff + (size_t)u * dstride + c];
-                    more = b + 2 * G <= B;
-                    if (more) load_x(xcur + (size_t)G * xstride, xn);    // next group in flight meanwhile
+                    __builtin_amdgcn_sched_barrier(0);        // all row words requested before the first is waited for
 #pragma unroll
-                    for (int u = 0; u < G; ++u) count(xg[u], dg[u], n[u]);
+                    for (int u = 0; u < G; ++u) {
+                        count(xg[u], dg[u], n[u]);
+                        xm[u] = sign_mask(xg[u]);
+                        asm volatile("" : "+v"(xm[u]));
+                    }
+                    more = b + 2 * G <= B;
+                    // the loads must not move above the last use of xg (they would need registers of
+                    // their own and copies); without a next group the same words are read again
+                    asm volatile("" ::: "memory");
+                    load_x(more ? xcur + (size_t)G * xstride : xcur, xg);
                     bool over = false;
                     big = false;
 #pragma unroll
@@ -921,7 +941,9 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                         sum[c] = 0;
 #pragma unroll
                         for (int u = 0; u < G; ++u) sum[c] += n[u][c];
-                        over |= plen[c] + sum[c] > 31u;
+                        // in place: the old length need not stay live (it is worked out again if needed)
+                        asm volatile("v_add_u32_e32 %0, %0, %1" : "+v"(plen[c]) : "v"(sum[c]));
+                        over |= plen[c] > 31u;
                         big |= sum[c] > 31u;
                     }
                     if (__any(over)) {
@@ -933,15 +955,19 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                 }
                 if (stopped) {                    // empty the pending words, then deal with the group in hand
 #pragma unroll
-                    for (int c = 0; c < RPL; ++c) commit(c);
-                    if (nearly_full()) {          // drain first, then take this group again
-                        full = true;
+                    for (int c = 0; c < RPL; ++c) {
+                        plen[c] -= sum[c];        // the group was not taken: the lengths before it
+                        commit(c);
+                    }
+                    if (nearly_full()) {          // drain first, then take this group again (its words have
+                        full = true;              // been overwritten: they are loaded once more)
+                        have_x = false;
                     } else if (__any(big)) {      // a group with a large count: sample by sample while room lasts
                         have_x = false;
 #pragma unroll
                         for (int u = 0; u < G; ++u) {
                             uint32_t m1[RPL];
-                            direction(xg[u], dg[u], m1);
+                            direction_of(xm[u], dg[u], m1);
                             append_slow(n[u], m1);
                             b += 1;
                             xcur += xstride;
@@ -952,6 +978,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                             }
                         }
                     } else {
+#pragma unroll
+                        for (int c = 0; c < RPL; ++c) plen[c] += sum[c];
                         take_group();
                     }
                 }
@@ -966,7 +994,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) dv[c] = dw[doff + c];
                 uint32_t n1[RPL], m1[RPL];
-                const WordT xv = *xcur;
+                const WordT xv = xcur[xlane];
                 count(xv, dv, n1);
                 direction(xv, dv, m1);
                 append_slow(n1, m1);

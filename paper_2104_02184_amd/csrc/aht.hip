@@ -95,6 +95,7 @@ inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 // internal word buffers are padded so that the cell kernel needs no edge masks
 inline int cpad(const aht_tile* t) { return (t->cols + 63) & ~63; }
 inline int rpad(const aht_tile* t) { return (t->rows + 15) & ~15; }
+inline int bpad(int B) { return (B + 15) & ~15; }       // samples per row of the row-word buffer
 
 int env_int(const char* name, int dflt)
 {
@@ -115,7 +116,7 @@ aht_status check_device(const aht_tile* t)
 aht_status ensure_scratch(aht_tile* t, int B)
 {
     const size_t need_x = (size_t)B * cpad(t) * word_bytes(t);
-    const size_t need_d = (size_t)B * rpad(t) * word_bytes(t);
+    const size_t need_d = (size_t)bpad(B) * rpad(t) * word_bytes(t);
     if (need_x > t->xw_bytes) {
         if (t->xw) AHT_HIP(hipFree(t->xw));
         t->xw = nullptr; t->xw_bytes = 0;
@@ -164,10 +165,10 @@ aht_status launch_words(aht_tile* t, const float* x, const float* d, int B, floa
     const int Cp = cpad(t), Rp = rpad(t);
     const dim3 grid(blocks_for((size_t)Cp + Rp), (unsigned)(B < 32768 ? B : 32768));
     if (use_u32(t))
-        hipLaunchKernelGGL(k_pulse_words<uint32_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp,
+        hipLaunchKernelGGL(k_pulse_words<uint32_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp, bpad(B),
                            t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint32_t*)t->xw, (uint32_t*)t->dw, conv);
     else
-        hipLaunchKernelGGL(k_pulse_words<uint64_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp,
+        hipLaunchKernelGGL(k_pulse_words<uint64_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp, bpad(B),
                            t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint64_t*)t->xw, (uint64_t*)t->dw, conv);
     AHT_HIP(hipGetLastError());
     return AHT_OK;
@@ -259,7 +260,7 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     a.R = t->rows;
     a.C = t->cols;
     a.B = B;
-    a.Rpad = rpad(t);
+    a.Bpad = bpad(B);
     a.Cpad = cpad(t);
     a.nbx = strips;
     a.bx0 = strip0;
@@ -415,7 +416,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
 {
     if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
     if (B64 < 0) return fail(AHT_ERR_INVALID_ARG, "B must be >= 0");
-    if (B64 > 0x7FFFFFFF) return fail(AHT_ERR_INVALID_ARG, "too many update vectors for one call");
+    if (B64 > 0x7FFFFFF0) return fail(AHT_ERR_INVALID_ARG, "too many update vectors for one call");
     const int B = (int)B64;
     if (!(lr >= 0.0f) || !std::isfinite(lr)) return fail(AHT_ERR_INVALID_ARG, "lr must be finite and >= 0");
     if (B > 0 && (!x_dev || !d_dev)) return fail(AHT_ERR_INVALID_ARG, "null x or d");
@@ -907,7 +908,7 @@ static aht_status debug_pulse_words_impl(aht_tile* t, const float* x_dev, const 
                                          uint64_t* xw_dev, uint64_t* dw_dev, void* stream, const ConvView& conv)
 {
     if (!t || !x_dev || !d_dev || !xw_dev || !dw_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
-    if (B64 <= 0 || B64 > 0x7FFFFFFF) return fail(AHT_ERR_INVALID_ARG, "B must be > 0");
+    if (B64 <= 0 || B64 > 0x7FFFFFF0) return fail(AHT_ERR_INVALID_ARG, "B must be > 0");
     const int B = (int)B64;
     if (!(lr >= 0.0f) || !std::isfinite(lr)) return fail(AHT_ERR_INVALID_ARG, "lr must be finite and >= 0");
     aht_status st = check_device(t);
@@ -917,11 +918,11 @@ static aht_status debug_pulse_words_impl(aht_tile* t, const float* x_dev, const 
     if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
     const size_t nx = (size_t)B * t->cols, nd = (size_t)B * t->rows;
     if (use_u32(t)) {
-        hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint32_t*)t->xw, xw_dev, B, t->cols, cpad(t));
-        hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nd)), dim3(256), 0, s, (const uint32_t*)t->dw, dw_dev, B, t->rows, rpad(t));
+        hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint32_t*)t->xw, xw_dev, B, t->cols, cpad(t), 0);
+        hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nd)), dim3(256), 0, s, (const uint32_t*)t->dw, dw_dev, B, t->rows, rpad(t), bpad(B));
     } else {
-        hipLaunchKernelGGL(k_words_to_public<uint64_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint64_t*)t->xw, xw_dev, B, t->cols, cpad(t));
-        hipLaunchKernelGGL(k_words_to_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, (const uint64_t*)t->dw, dw_dev, B, t->rows, rpad(t));
+        hipLaunchKernelGGL(k_words_to_public<uint64_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint64_t*)t->xw, xw_dev, B, t->cols, cpad(t), 0);
+        hipLaunchKernelGGL(k_words_to_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, (const uint64_t*)t->dw, dw_dev, B, t->rows, rpad(t), bpad(B));
     }
     AHT_HIP(hipGetLastError());
     return AHT_OK;
@@ -969,11 +970,11 @@ aht_status aht_debug_apply_words(aht_tile* t, const uint64_t* xw_dev, const uint
     hipStream_t s = (hipStream_t)stream;
     const size_t nx = (size_t)B * cpad(t), nd = (size_t)B * rpad(t);
     if (use_u32(t)) {
-        hipLaunchKernelGGL(k_words_from_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, xw_dev, (uint32_t*)t->xw, B, t->cols, cpad(t), t->upd.bl);
-        hipLaunchKernelGGL(k_words_from_public<uint32_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint32_t*)t->dw, B, t->rows, rpad(t), t->upd.bl);
+        hipLaunchKernelGGL(k_words_from_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, xw_dev, (uint32_t*)t->xw, B, t->cols, cpad(t), 0, t->upd.bl);
+        hipLaunchKernelGGL(k_words_from_public<uint32_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint32_t*)t->dw, B, t->rows, rpad(t), bpad(B), t->upd.bl);
     } else {
-        hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nx)), dim3(256), 0, s, xw_dev, (uint64_t*)t->xw, B, t->cols, cpad(t), t->upd.bl);
-        hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint64_t*)t->dw, B, t->rows, rpad(t), t->upd.bl);
+        hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nx)), dim3(256), 0, s, xw_dev, (uint64_t*)t->xw, B, t->cols, cpad(t), 0, t->upd.bl);
+        hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint64_t*)t->dw, B, t->rows, rpad(t), bpad(B), t->upd.bl);
     }
     AHT_HIP(hipGetLastError());
     return launch_cells(t, B, step, s, 0u, (uint32_t)((t->cols + 63) / 64));

@@ -305,8 +305,11 @@ __global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
 // ------------------------------------------------------------------------------------------
 // Pulse words.  One thread per line value: threshold T = floor(min(1, a|v|) 2^32) in fp64,
 // pulse n set iff Philox word n&3 of block n>>2 is below T; top bit = line value negative.
-// Internal layout: xw[B][Cpad], dw[B][Rpad] with Cpad = C rounded up to 64 and Rpad = R rounded
-// up to 16, the padding filled with zero words so that the cell kernel needs no edge masks.
+// Internal layout: xw[B][Cpad] and dw[Rpad][Bpad] (a row's words of consecutive samples lie side by
+// side: the cell kernel fetches them a group of samples at a time with one scalar load per row, and
+// consecutive groups share a cache line) with Cpad = C rounded up to 64, Rpad = R rounded up to 16
+// and Bpad = B rounded up to 16; the padding columns and rows are filled with zero words so that
+// the cell kernel needs no edge masks, the padding samples are never read.
 // grid.x covers the Cpad + Rpad lines of one sample, grid.y strides over the samples.
 // ------------------------------------------------------------------------------------------
 // Deterministic trains use no random numbers: pulse n is set iff u_n < T / 2^32 with
@@ -315,7 +318,7 @@ __global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
 template <typename WordT>
 __global__ void __launch_bounds__(256)
 k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int Rpad, int Cpad,
-              int BL, double A, const double* __restrict__ a_x, const double* __restrict__ a_d,
+              int Bpad, int BL, double A, const double* __restrict__ a_x, const double* __restrict__ a_d,
               const int32_t* __restrict__ bl_b, int deterministic,
               uint32_t k0, uint32_t k1, uint32_t t, WordT* __restrict__ xw, WordT* __restrict__ dw, ConvView conv)
 {
@@ -361,25 +364,27 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
             }
         }
         if (is_x) xw[(size_t)b * Cpad + idx] = word;
-        else dw[(size_t)b * Rpad + idx] = word;
+        else dw[(size_t)idx * Bpad + b] = word;
     }
 }
 
 // word format conversions for the debug entry points (public format: u64 [B][len], sign in bit 63;
 // internal format: WordT [B][lpad], sign in the top bit, zero padding)
+// `bpad` > 0: the internal buffer is sample-contiguous, in[idx][bpad] (row words); 0: in[b][lpad]
 template <typename WordT>
-__global__ void __launch_bounds__(256) k_words_to_public(const WordT* in, uint64_t* out, int B, int len, int lpad)
+__global__ void __launch_bounds__(256) k_words_to_public(const WordT* in, uint64_t* out, int B, int len, int lpad, int bpad)
 {
     const size_t k = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (k >= (size_t)B * len) return;
     const size_t b = k / (size_t)len, idx = k - b * (size_t)len;
-    const WordT w = in[b * (size_t)lpad + idx];
+    const WordT w = bpad ? in[idx * (size_t)bpad + b] : in[b * (size_t)lpad + idx];
     const WordT sign = (WordT)1 << WordTraits<WordT>::kSignBit;
     out[k] = (uint64_t)(w & ~sign) | ((w & sign) ? (1ull << 63) : 0ull);
 }
 
 template <typename WordT>
-__global__ void __launch_bounds__(256) k_words_from_public(const uint64_t* in, WordT* out, int B, int len, int lpad, int BL)
+__global__ void __launch_bounds__(256) k_words_from_public(const uint64_t* in, WordT* out, int B, int len, int lpad, int bpad,
+                                                           int BL)
 {
     const size_t k = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (k >= (size_t)B * lpad) return;
@@ -390,7 +395,8 @@ __global__ void __launch_bounds__(256) k_words_from_public(const uint64_t* in, W
         r = (WordT)(w & ((1ull << BL) - 1));
         if (w >> 63) r |= (WordT)1 << WordTraits<WordT>::kSignBit;
     }
-    out[k] = r;
+    if (bpad) out[idx * (size_t)bpad + b] = r;
+    else out[k] = r;
 }
 
 // signed coincidence counts of sample b (debug): +n UP (x_j d_i < 0), -n DOWN
@@ -454,7 +460,7 @@ __global__ void __launch_bounds__(256) k_debug_gauss(uint32_t k0, uint32_t k1, u
 // early and starts new streams.
 // ------------------------------------------------------------------------------------------
 struct CellArgs {
-    int R, C, B, Rpad, Cpad;
+    int R, C, B, Bpad, Cpad;
     uint32_t nbx, nby;            // tiles along columns / rows
     uint32_t bx0;                 // first column strip of this launch (a caller that knows where x is
                                   // non-zero leaves the other strips out: their cells get no pulses)
@@ -516,7 +522,7 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
 }
 
-// W [R][C] in/out; planes [R][C]; xw[B][Cpad], dw[B][Rpad]: internal zero-padded pulse words.
+// W [R][C] in/out; planes [R][C]; xw[B][Cpad], dw[Rpad][Bpad]: internal zero-padded pulse words.
 // The pointers are separate restrict-qualified parameters so that the wave-uniform row words
 // are fetched with scalar loads.
 template <int KIND, typename WordT, bool NOISE, int RPL>
@@ -559,9 +565,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     const int i0 = ((int)by * 4 + wave) * RPL;    // i0 + RPL <= Rpad
     if (i0 >= a.R) return;                        // wave-uniform; the kernel has no barriers
     const int R = a.R, C = a.C, B = a.B;
-    const size_t xstride = (size_t)a.Cpad, dstride = (size_t)a.Rpad;
+    const size_t xstride = (size_t)a.Cpad, drow = (size_t)a.Bpad;
     const WordT* __restrict__ xp = xw + (size_t)bx * 64;   // wave-uniform: the strip's first column
-    const WordT* __restrict__ dp = dw + i0;
 
     float w[RPL];
     uint32_t q[RPL], cellid[RPL];
@@ -819,7 +824,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     uint32_t xoff[G];                             // byte offsets of the lane's words of a group's G samples
 #pragma unroll
     for (int u = 0; u < G; ++u) xoff[u] = (uint32_t)(((size_t)u * xstride + xlane) * sizeof(WordT));
-    size_t doff = (size_t)i0;                     // dw[doff + c]: row words of sample b (wave-uniform,
+    size_t doff = (size_t)i0 * drow;              // dw[doff + c * drow]: row words of sample b (wave-uniform,
                                                   // indexed off the kernel argument so that they stay scalar loads)
     auto load_x = [&](const WordT* __restrict__ p0, WordT (&xg)[G]) __attribute__((always_inline)) {
 #pragma unroll
@@ -907,7 +912,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                     }
                     b += G;
                     xcur += (size_t)G * xstride;
-                    doff += (size_t)G * dstride;
+                    doff += (size_t)G;
                     have_x = more;
                 };
                 // Straight path: groups are taken until some pending word of the wave would overflow.
@@ -921,7 +926,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 #pragma unroll
                     for (int u = 0; u < G; ++u)
 #pragma unroll
-                        for (int c = 0; c < RPL; ++c) dg[u][c] = dw[doff + (size_t)u * dstride + c];
+                        for (int c = 0; c < RPL; ++c) dg[u][c] = dw[doff + (size_t)c * drow + u];
                     __builtin_amdgcn_sched_barrier(0);        // all row words requested before the first is waited for
 #pragma unroll
                     for (int u = 0; u < G; ++u) {
@@ -971,7 +976,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                             append_slow(n[u], m1);
                             b += 1;
                             xcur += xstride;
-                            doff += dstride;
+                            doff += 1;
                             if (nearly_full()) {
                                 full = true;
                                 break;
@@ -992,7 +997,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                 }
                 WordT dv[RPL];
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) dv[c] = dw[doff + c];
+                for (int c = 0; c < RPL; ++c) dv[c] = dw[doff + (size_t)c * drow];
                 uint32_t n1[RPL], m1[RPL];
                 const WordT xv = xcur[xlane];
                 count(xv, dv, n1);
@@ -1000,7 +1005,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                 append_slow(n1, m1);
                 b += 1;
                 xcur += xstride;
-                doff += dstride;
+                doff += 1;
                 full = nearly_full();
             }
         }

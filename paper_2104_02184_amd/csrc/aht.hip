@@ -240,9 +240,10 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
                         const aht_tile* words = nullptr)
 {
     const int rpl = choose_rpl(t);
-    // stream storage per cell: 12 words hold 320 pulses before an early drain is needed
+    // stream storage per cell: 12 words hold 320 pulses before an early drain is needed; at 4 rows
+    // per lane, 9 words (224 pulses) let four workgroups share a compute unit's LDS
     int qwords = env_int("AHT_QWORDS", 0);
-    if (qwords < 5 || qwords > 160) qwords = 12;
+    if (qwords < 5 || qwords > 160) qwords = (rpl == 4) ? 9 : 12;
     const size_t lds_extra = (rpl > 1) ? 4 * 1024 : 0;       // exchange buffers of the last drain, 1 KB per wave
     while (qwords > 5 && (size_t)4 * rpl * 64 * qwords * 4 + lds_extra > 160 * 1024) --qwords;   // LDS of one CU
     CellPtrs p{};

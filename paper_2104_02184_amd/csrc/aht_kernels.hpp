@@ -526,10 +526,12 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 // The pointers are separate restrict-qualified parameters so that the wave-uniform row words
 // are fetched with scalar loads.
 template <int KIND, typename WordT, bool NOISE, int RPL>
-// Register budget: three waves per SIMD (168 registers), as many as the LDS streams allow at four
-// rows per lane; five (96 registers) for 32-bit words at two rows per lane, the variant long
-// batches on small tiles run, which gains more from the fifth wave than it loses to a few spills.
-__global__ void __launch_bounds__(256, (sizeof(WordT) == 4 && RPL == 2) ? 5 : 3)
+// Register budget: four waves per SIMD (128 registers) at four rows per lane, the variant of large
+// tiles, where the host also keeps the LDS streams short enough for four workgroups per compute unit
+// (the fourth wave gains more than the dozen spills outside the inner loops cost); five (96
+// registers) for 32-bit words at two rows per lane, the variant long batches on small tiles run;
+// three otherwise.
+__global__ void __launch_bounds__(256, (sizeof(WordT) == 4 && RPL == 2) ? 5 : (RPL == 4) ? 4 : 3)
 k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
               const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
               const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,

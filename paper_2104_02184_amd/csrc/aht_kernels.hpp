@@ -571,7 +571,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     const WordT* __restrict__ xp = xw + (size_t)bx * 64;   // wave-uniform: the strip's first column
 
     float w[RPL];
-    uint32_t q[RPL], cellid[RPL];
+    uint32_t q[RPL];
     // LDS address of the lane's first stream; stream c starts c * cell_stride bytes further (wave-uniform)
     const uint32_t qb0 = lds0 + (uint32_t)((wave * RPL * a.qwords * 64 + lane) * 4);
     const uint32_t cell_stride = (uint32_t)a.qwords * kWordStride;
@@ -583,7 +583,6 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     for (int c = 0; c < RPL; ++c) {
         cv[c] = ((i0 + c) < R) && (j < C);
         const size_t k = cv[c] ? ((size_t)(i0 + c) * C + j) : 0;
-        cellid[c] = (uint32_t)k;
         // weights and device parameters are touched once per call: stream them past the L2 so that
         // the pulse words, which every tile of a super-tile re-reads, stay resident
         w[c] = __builtin_nontemporal_load(W + k);
@@ -630,14 +629,20 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     // length, the c-th cells of the 64 lanes are more alike, the rows of the wave end closer to
     // their longest stream and fewer of their iterations need masks.
     auto drain = [&](bool last) __attribute__((always_inline)) {
+        // The lane index is worked out again and made opaque: whatever the drain derives from it (the
+        // cells' indices, the LDS addresses of the dealing, origins) is then formed here and not kept
+        // in registers through phase A.
+        int dlane = (int)lane_by_count();
+        asm volatile("" : "+v"(dlane));
         // The device parameters are needed only here.  Loading them now (normally once per call)
-        // keeps 6 registers per cell free during phase A; the cell index is made opaque so that
-        // the 24 addresses are formed here as well and not kept from the start of the kernel.
+        // keeps 6 registers per cell free during phase A.
         float s_up[RPL], s_dn_neg[RPL], bmax[RPL], bmin[RPL], sl_up[RPL], sl_dn[RPL];
+        uint32_t cellid[RPL];                     // index of the cell in the matrix (0 for cells outside it)
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
-            uint32_t k = cellid[c];
-            asm volatile("" : "+v"(k));
+            const int jd = (int)bx * 64 + dlane;
+            const uint32_t k = ((i0 + c) < R && jd < C) ? (uint32_t)((size_t)(i0 + c) * C + jd) : 0u;
+            cellid[c] = k;
             s_up[c] = __builtin_nontemporal_load(p_dw_up + k);
             s_dn_neg[c] = -__builtin_nontemporal_load(p_dw_down + k);
             bmax[c] = __builtin_nontemporal_load(p_b_max + k);
@@ -663,7 +668,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             endpos[c] = ((wp[c] - qb(c)) >> 3) + fill[c];                    // 32 bits per 256-byte step
             D[c] = 0;
             sbase[c] = qb(c);
-            origin[c] = (uint32_t)(lane * RPL + c);
+            origin[c] = (uint32_t)(dlane * RPL + c);
         }
         // Several rows per lane: before a drain the wave's cells are dealt out again, the 64
         // shortest streams to slot 0 of the 64 lanes, the next 64 to slot 1, and so on, so that the
@@ -681,23 +686,23 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                 return bk < kBuckets - 1 ? bk : kBuckets - 1;
             };
 #pragma unroll
-            for (int k = 0; k < 3; ++k) lds_store_u32(xbuf + (uint32_t)(3 * lane + k) * 4u, 0u);
+            for (int k = 0; k < 3; ++k) lds_store_u32(xbuf + (uint32_t)(3 * dlane + k) * 4u, 0u);
 #pragma unroll
             for (int c = 0; c < RPL; ++c) lds_atomic_add_u32(xbuf + bucket_of(c) * 4u, 1u);
             uint32_t h[3];
 #pragma unroll
-            for (int k = 0; k < 3; ++k) h[k] = lds_load_u32(xbuf + (uint32_t)(3 * lane + k) * 4u);
+            for (int k = 0; k < 3; ++k) h[k] = lds_load_u32(xbuf + (uint32_t)(3 * dlane + k) * 4u);
             const uint32_t mine = h[0] + h[1] + h[2];
             uint32_t incl = mine;                                    // inclusive scan over the lanes
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 const uint32_t up = (uint32_t)__shfl_up((int)incl, off, 64);
-                incl += (lane >= off) ? up : 0u;
+                incl += (dlane >= off) ? up : 0u;
             }
             const uint32_t excl = incl - mine;
-            lds_store_u32(xbuf + (uint32_t)(3 * lane) * 4u, excl);
-            lds_store_u32(xbuf + (uint32_t)(3 * lane + 1) * 4u, excl + h[0]);
-            lds_store_u32(xbuf + (uint32_t)(3 * lane + 2) * 4u, excl + h[0] + h[1]);
+            lds_store_u32(xbuf + (uint32_t)(3 * dlane) * 4u, excl);
+            lds_store_u32(xbuf + (uint32_t)(3 * dlane + 1) * 4u, excl + h[0]);
+            lds_store_u32(xbuf + (uint32_t)(3 * dlane + 2) * 4u, excl + h[0] + h[1]);
             uint32_t pos[RPL];                                       // LDS byte offset of the cell's new place
 #pragma unroll
             for (int c = 0; c < RPL; ++c)
@@ -707,13 +712,13 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + pos[c], v[c]);
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) v[c] = lds_load_u32(xbuf + (uint32_t)(c * 64 + lane) * 4u);
+                for (int c = 0; c < RPL; ++c) v[c] = lds_load_u32(xbuf + (uint32_t)(c * 64 + dlane) * 4u);
             };
             auto move_f32 = [&](float (&v)[RPL]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + pos[c], __float_as_uint(v[c]));
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) v[c] = __uint_as_float(lds_load_u32(xbuf + (uint32_t)(c * 64 + lane) * 4u));
+                for (int c = 0; c < RPL; ++c) v[c] = __uint_as_float(lds_load_u32(xbuf + (uint32_t)(c * 64 + dlane) * 4u));
             };
             move_u32(endpos); move_u32(q); move_u32(sbase); move_u32(origin); move_u32(cellid);
             move_f32(w); move_f32(s_up); move_f32(s_dn_neg); move_f32(bmax); move_f32(bmin);
@@ -791,7 +796,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         for (int c = 0; c < RPL; ++c) q[c] += endpos[c] - (q[c] & 31u);      // pulses applied so far
         if (sorted) {
             // The weights go back to where their cells came from; if more samples follow, so do the
-            // pulse counts and the cell indices (after the last drain only the sum of q is used).
+            // pulse counts (after the last drain only the sum of q is used).
             auto send_home = [&](uint32_t (&v)[RPL]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + origin[c] * 4u, v[c]);
@@ -804,10 +809,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
             send_home(wbits);
 #pragma unroll
             for (int c = 0; c < RPL; ++c) w[c] = __uint_as_float(wbits[c]);
-            if (!last) {
-                send_home(q);
-                send_home(cellid);
-            }
+            if (!last) send_home(q);
         }
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {           // restart the streams at bit q & 31
@@ -1001,7 +1003,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) dv[c] = dw[doff + (size_t)c * drow];
                 uint32_t n1[RPL], m1[RPL];
-                const WordT xv = xcur[xlane];
+                const WordT xv = *(const WordT*)((const char*)xcur + xoff[0]);
                 count(xv, dv, n1);
                 direction(xv, dv, m1);
                 append_slow(n1, m1);

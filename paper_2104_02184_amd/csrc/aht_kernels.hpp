@@ -595,6 +595,17 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         plen[c] = 0;
     }
 
+    // At four rows per lane, where registers are short, the pulse counts of a wave's cells rest in its
+    // exchange buffer between drains (only the drain uses it), at the cells' home places, and not in
+    // registers.
+    constexpr bool kParkCounts = RPL == 4;
+    if (kParkCounts) {
+        const uint32_t xhome = lds0 + (uint32_t)(4 * RPL * 64 * a.qwords * 4) + (uint32_t)wave * 1024u +
+                               (uint32_t)(lane * RPL) * 4u;
+#pragma unroll
+        for (int c = 0; c < RPL; ++c) lds_store_u32(xhome + (uint32_t)c * 4u, 0u);
+    }
+
     // Append `n` (<= 31, and fill + n <= 64) copies of the direction bit to the stream tail.
     auto append = [&](int c, uint32_t n, uint32_t m) __attribute__((always_inline)) {
         const uint64_t acc = (((uint64_t)acc_hi[c] << 32) | acc_lo[c]) << n;
@@ -661,6 +672,12 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         // address of its stream, and where it came from (cells may change lanes below).  A stream
         // starts at bit q & 31.
         uint32_t endpos[RPL], blk[RPL], D[RPL], sbase[RPL], origin[RPL];
+        if (kParkCounts) {                        // the pulse counts, parked by the previous drain
+            const uint32_t xhome = lds0 + (uint32_t)(4 * RPL * 64 * a.qwords * 4) + (uint32_t)wave * 1024u +
+                                   (uint32_t)(dlane * RPL) * 4u;
+#pragma unroll
+            for (int c = 0; c < RPL; ++c) q[c] = lds_load_u32(xhome + (uint32_t)c * 4u);
+        }
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
             commit(c);
@@ -796,7 +813,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         for (int c = 0; c < RPL; ++c) q[c] += endpos[c] - (q[c] & 31u);      // pulses applied so far
         if (sorted) {
             // The weights go back to where their cells came from; if more samples follow, so do the
-            // pulse counts (after the last drain only the sum of q is used).
+            // pulse counts, last of all, so that they stay in the buffer for the next drain (after the
+            // last drain only the sum of q is used).
             auto send_home = [&](uint32_t (&v)[RPL]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int c = 0; c < RPL; ++c) lds_store_u32(xbuf + origin[c] * 4u, v[c]);

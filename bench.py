@@ -37,7 +37,7 @@ C_STEP = {0: 4.0, 1: 8.0, 2: 8.0}
 # HBM-side bytes of one headline call of the cell-update kernel, from rocprofv3 --pmc
 # FETCH_SIZE and WRITE_SIZE (profiles/cell_update_cfg5_counters.md; FETCH_SIZE scaled by the
 # factor a plain copy of known size gives).  None for other workloads.
-MEASURED_TRAFFIC_BYTES = {"cfg5_4096x4096_linearstep": 773.0e6}
+MEASURED_TRAFFIC_BYTES = {"cfg5_4096x4096_linearstep": 717.0e6}
 
 
 def algorithmic_lane_ops(w, pulses_per_call):

@@ -622,12 +622,14 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         wp[c] += (fill[c] & 32u) << 3;                               // one word = kWordStride bytes; fill < 64
         fill[c] &= 31u;
     };
-    // The bits of several samples are first gathered in a 32-bit word with 32-bit operations
-    // (`pend`, newest bit lowest) and moved to the tail only when some cell of the wave would
-    // overflow it: one 64-bit shift and one flush per commit instead of per sample.
+    // The bits of several samples are first gathered in a 32-bit word (`pend`: they enter at the top,
+    // one funnel shift per sample, so the newest bit is the highest and the bits below the `plen`
+    // valid ones are zero) and moved to the tail, newest bit lowest, only when some cell of the wave
+    // would overflow it: one bit reversal, one 64-bit shift and one flush per commit instead of per
+    // sample.
     auto commit = [&](int c) __attribute__((always_inline)) {
         const uint64_t acc = (((uint64_t)acc_hi[c] << 32) | acc_lo[c]) << plen[c];
-        acc_lo[c] = (uint32_t)acc | pend[c];
+        acc_lo[c] = (uint32_t)acc | __builtin_bitreverse32(pend[c]);
         acc_hi[c] = (uint32_t)(acc >> 32);
         fill[c] += plen[c];                                          // < 32 + 32
         flush(c);
@@ -927,10 +929,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
                         uint32_t m1[RPL];
                         direction_of(xm[u], dg[u], m1);
 #pragma unroll
-                        for (int c = 0; c < RPL; ++c) {
-                            const uint32_t bits = __builtin_amdgcn_ubfe(m1[c], 0u, n[u][c]);   // n copies of the direction
-                            pend[c] = (pend[c] << n[u][c]) | bits;
-                        }
+                        for (int c = 0; c < RPL; ++c)       // n (<= 31) copies of the direction enter at the top
+                            pend[c] = __builtin_amdgcn_alignbit(m1[c], pend[c], n[u][c]);
                     }
                     b += G;
                     xcur += (size_t)G * xstride;

@@ -127,6 +127,33 @@ __global__ void __launch_bounds__(256) k_ldsw8(uint32_t* out, uint32_t seed) {
 // fp32 matrix-core rate: v_mfma_f32_32x32x2_f32 (4096 flops per wave instruction), NCHAIN
 // independent accumulators per wave.  Calibrates the roofline of the analog product.
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+// Placement of 8-byte (VOP3) instructions: the same run of eight, once starting at an address that
+// is a multiple of 8 and once 4 bytes further (both variants execute two s_nop per iteration).
+#define KPLACE(NAME, PRE, POST, INSTR)                                                     \
+__global__ void __launch_bounds__(256) NAME(uint32_t* out, uint32_t seed) {                \
+    uint32_t a0 = threadIdx.x + seed, a1 = a0 + 1, a2 = a0 + 2, a3 = a0 + 3, a4 = a0 + 4, a5 = a0 + 5,      \
+             a6 = a0 + 6, a7 = a0 + 7;                                                     \
+    uint32_t b = seed | 3;                                                                 \
+    for (int i = 0; i < ITERS; ++i) {                                                      \
+        asm volatile(".p2align 3\n" PRE                                                    \
+                     INSTR(0) INSTR(1) INSTR(2) INSTR(3) INSTR(4) INSTR(5) INSTR(6) INSTR(7) POST           \
+                     : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7)      \
+                     : "v"(b));                                                            \
+    }                                                                                      \
+    uint32_t s = a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7;                                    \
+    if (s == 12345u) out[0] = 1;                                                           \
+}
+#define I_BITOP3(k) "v_bitop3_b32 %" #k ", %" #k ", %8, %8 bitop3:0x96\n"
+#define I_FMA64(k) "v_fma_f32 %" #k ", %" #k ", %8, %8\n"
+KPLACE(k_place_bitop3_2, "s_nop 0\ns_nop 0\n", "", I_BITOP3)
+KPLACE(k_place_bitop3_3, "s_nop 0\ns_nop 0\ns_nop 0\n", "", I_BITOP3)
+KPLACE(k_place_bitop3_4, "s_nop 0\ns_nop 0\ns_nop 0\ns_nop 0\n", "", I_BITOP3)
+KPLACE(k_place_bitop3_5, "s_nop 0\ns_nop 0\ns_nop 0\ns_nop 0\ns_nop 0\n", "", I_BITOP3)
+KPLACE(k_place_fma_2, "s_nop 0\ns_nop 0\n", "", I_FMA64)
+KPLACE(k_place_fma_3, "s_nop 0\ns_nop 0\ns_nop 0\n", "", I_FMA64)
+KPLACE(k_place_fma_4, "s_nop 0\ns_nop 0\ns_nop 0\ns_nop 0\n", "", I_FMA64)
+KPLACE(k_place_fma_5, "s_nop 0\ns_nop 0\ns_nop 0\ns_nop 0\ns_nop 0\n", "", I_FMA64)
+
 template <int NCHAIN>
 __global__ void __launch_bounds__(256) k_mfma(uint32_t* out, uint32_t seed) {
     floatx16 acc[NCHAIN];
@@ -192,6 +219,12 @@ int main() {
     run_mfma("mfma32x32x2 1ch 4wg/cu", k_mfma<1>, 1, 4, out);
     run_mfma("mfma32x32x2 2ch 2wg/cu", k_mfma<2>, 2, 2, out);
     run_mfma("mfma32x32x2 4ch 1wg/cu", k_mfma<4>, 4, 1, out);
+    // runs of eight 8-byte instructions after 2..5 s_nop from an 8-byte boundary: an even number
+    // puts every instruction of the run on a multiple of 8, an odd number 4 bytes past one
+    run("bitop3 +8", k_place_bitop3_2, 8, out); run("bitop3 +12", k_place_bitop3_3, 8, out);
+    run("bitop3 +16", k_place_bitop3_4, 8, out); run("bitop3 +20", k_place_bitop3_5, 8, out);
+    run("fma64 +8", k_place_fma_2, 8, out); run("fma64 +12", k_place_fma_3, 8, out);
+    run("fma64 +16", k_place_fma_4, 8, out); run("fma64 +20", k_place_fma_5, 8, out);
     run("log+fma", k_logfma, 16, out); run("log+2fma", k_logfma2, 24, out); run("log+2and", k_logand2, 24, out);
     return 0;
 }

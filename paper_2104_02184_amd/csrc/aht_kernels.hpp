@@ -302,6 +302,23 @@ __global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
     }
 }
 
+// OR of a value over aligned groups of 8 or 16 lanes, in every lane of the group: data-parallel
+// primitives of the vector ALU (quad permutes, then mirrors of the half row and of the row), no LDS.
+template <int GROUP>
+__device__ __forceinline__ uint32_t or_across_lines(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);      // quad_perm [1,0,3,2]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);      // quad_perm [2,3,0,1]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true);     // row_half_mirror
+    if (GROUP == 16) v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true);   // row_mirror
+    return v;
+}
+template <int GROUP>
+__device__ __forceinline__ uint64_t or_across_lines(uint64_t v)
+{
+    return ((uint64_t)or_across_lines<GROUP>((uint32_t)(v >> 32)) << 32) | or_across_lines<GROUP>((uint32_t)v);
+}
+
 // ------------------------------------------------------------------------------------------
 // Pulse words.  One thread per line value: threshold T = floor(min(1, a|v|) 2^32) in fp64,
 // pulse n set iff Philox word n&3 of block n>>2 is below T; top bit = line value negative.
@@ -315,6 +332,12 @@ __global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
 // Deterministic trains use no random numbers: pulse n is set iff u_n < T / 2^32 with
 // u_n = (n + 1/2) / BL for column lines and the bit-reversed, digitally shifted pulse number
 // (brev(n) xor 0xAAAAAAAA) / 2^32 for row lines (a shifted Hammersley point set).
+// Stochastic trains need random numbers only for line values with 0 < a|v| < 1: a zero value has
+// no pulses and a saturated one has them all.  Where many lanes of a wave need none (activations
+// after a rectifier: about half are zero), the lanes that do are listed in LDS and their Philox
+// blocks are dealt out over the whole wave, 64 / kBlocks lines at a time with one block per lane;
+// the four compare bits of each block are OR-ed together across the lanes of a line and the owner
+// of the line fetches the word.  The counters are those of the plain path: same words.
 template <typename WordT>
 __global__ void __launch_bounds__(256)
 k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int Rpad, int Cpad,
@@ -322,18 +345,26 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
               const int32_t* __restrict__ bl_b, int deterministic,
               uint32_t k0, uint32_t k1, uint32_t t, WordT* __restrict__ xw, WordT* __restrict__ dw, ConvView conv)
 {
+    constexpr int kBlocks = (sizeof(WordT) == 4) ? 8 : 16;       // Philox blocks per line value, at most
+    constexpr int kLines = 64 / kBlocks;                         // lines served at a time by the shared path
+    __shared__ uint32_t needy_list[4][64][2];                    // per wave: lane and threshold of the lines that need random numbers
     const int l = (int)(blockIdx.x * 256 + threadIdx.x);
-    if (l >= Cpad + Rpad) return;
-    const bool is_x = l < Cpad;                         // uniform per wave (Cpad % 64 == 0)
+    const bool live = l < Cpad + Rpad;                           // (no early exit: the shared path needs whole waves)
+    const bool is_x = l < Cpad;                                  // uniform per wave (Cpad % 64 == 0)
     const int idx = is_x ? l : l - Cpad;
     const int len = is_x ? C : R;
     const uint32_t tagw = (is_x ? kTagX : kTagD) << 24;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     for (uint32_t b = blockIdx.y; b < (uint32_t)B; b += gridDim.y) {
         WordT word = 0;
-        if (idx < len) {
+        const int bl = bl_b ? bl_b[b] : BL;
+        const int nblk = (bl + 3) >> 2;
+        bool random = false;                                     // this line needs random numbers
+        bool negative = false;
+        uint32_t Tlo = 0;
+        if (live && idx < len) {
             const float v = is_x ? view_x(x, conv, b, idx, C) : view_d(d, conv, b, idx, R);
             const double a = a_x ? (is_x ? a_x[b] : a_d[b]) : A;
-            const int bl = bl_b ? bl_b[b] : BL;
             const float av = fabsf(v);
             if (av > 0.0f && av < __builtin_inff() && a > 0.0) {
                 double p = a * (double)av;
@@ -347,24 +378,59 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
                                                   : (uint64_t)(__brev((uint32_t)n) ^ 0xAAAAAAAAu) < T;
                             word |= (WordT)(set ? 1u : 0u) << n;
                         }
+                    } else if ((T >> 32) != 0) {
+                        word = (((WordT)1 << bl) - 1);                // saturated: every pulse
                     } else {
-                        const bool sat = (T >> 32) != 0;
-                        const uint32_t Tlo = (uint32_t)T;
-                        const int nblk = (bl + 3) >> 2;
-                        for (int blk = 0; blk < nblk; ++blk) {
-                            const U4 r = philox4x32_10((uint32_t)idx, b, t, tagw | (uint32_t)blk, k0, k1);
-                            const uint32_t bits = (uint32_t)(sat | (r.x < Tlo)) | ((uint32_t)(sat | (r.y < Tlo)) << 1) |
-                                                  ((uint32_t)(sat | (r.z < Tlo)) << 2) | ((uint32_t)(sat | (r.w < Tlo)) << 3);
-                            word |= (WordT)bits << (4 * blk);
-                        }
-                        word &= (((WordT)1 << bl) - 1);
+                        random = true;
+                        Tlo = (uint32_t)T;
                     }
                 }
-                if (v < 0.0f) word |= (WordT)1 << WordTraits<WordT>::kSignBit;
+                negative = v < 0.0f;
             }
         }
-        if (is_x) xw[(size_t)b * Cpad + idx] = word;
-        else dw[(size_t)idx * Bpad + b] = word;
+        const unsigned long long need = __ballot(random);
+        const int count = __popcll(need);
+        // one block per lane and round for ceil(count / kLines) rounds, against nblk blocks per lane
+        if (count != 0 && (count + kLines - 1) / kLines * 3 < nblk * 2) {
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(need >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)need, 0u));
+            if (random) {
+                needy_list[wave][rank][0] = lane;
+                needy_list[wave][rank][1] = Tlo;
+            }
+            __builtin_amdgcn_wave_barrier();     // a wave's LDS operations take effect in program order
+            const uint32_t blk = lane % kBlocks, slot = lane / kBlocks;
+            for (int r0 = 0; r0 < count; r0 += kLines) {
+                const uint32_t r = (uint32_t)r0 + slot;              // the listed line this lane works for
+                uint32_t part = 0;
+                if (r < (uint32_t)count && blk < (uint32_t)nblk) {
+                    const uint32_t src = needy_list[wave][r][0], Ts = needy_list[wave][r][1];
+                    const uint32_t sidx = (uint32_t)idx - lane + src;
+                    const U4 q = philox4x32_10(sidx, b, t, tagw | blk, k0, k1);
+                    part = (uint32_t)(q.x < Ts) | ((uint32_t)(q.y < Ts) << 1) | ((uint32_t)(q.z < Ts) << 2) |
+                           ((uint32_t)(q.w < Ts) << 3);
+                }
+                WordT w = (WordT)part << (4 * blk);
+                w = or_across_lines<kBlocks>(w);
+                // the owner of listed line r0 + s finds its word in the lanes of slot s
+                const WordT got = (WordT)__shfl(w, (int)((rank % kLines) * kBlocks), 64);
+                if (random && rank >= (uint32_t)r0 && rank < (uint32_t)(r0 + kLines)) word = got;
+            }
+            __builtin_amdgcn_wave_barrier();     // the list is written again for the next sample
+            if (random) word &= (((WordT)1 << bl) - 1);
+        } else if (random) {
+            for (int blk = 0; blk < nblk; ++blk) {
+                const U4 r = philox4x32_10((uint32_t)idx, b, t, tagw | (uint32_t)blk, k0, k1);
+                const uint32_t bits = (uint32_t)(r.x < Tlo) | ((uint32_t)(r.y < Tlo) << 1) |
+                                      ((uint32_t)(r.z < Tlo) << 2) | ((uint32_t)(r.w < Tlo) << 3);
+                word |= (WordT)bits << (4 * blk);
+            }
+            word &= (((WordT)1 << bl) - 1);
+        }
+        if (negative) word |= (WordT)1 << WordTraits<WordT>::kSignBit;
+        if (live) {
+            if (is_x) xw[(size_t)b * Cpad + idx] = word;
+            else dw[(size_t)idx * Bpad + b] = word;
+        }
     }
 }
 

@@ -167,6 +167,40 @@ def test_pulse_words_every_length_and_saturation(bl):
                 assert (tile.debug_counts(xw, dw, 0).cpu().numpy() == bl).all()
 
 
+@pytest.mark.parametrize("bl", [1, 4, 13, 31, 32, 47, 63])
+@pytest.mark.parametrize("um", [False, True])
+def test_pulse_words_with_few_to_all_lines_needing_random_numbers(bl, um):
+    """Waves in which 0, 1, a few, most or all line values lie strictly between zero and
+    saturation (the library shares the random blocks of sparse waves among all lanes), ragged
+    tails in both directions, zeros after a rectifier, saturated and negative values."""
+    g = np.random.default_rng(100 + bl)
+    R, C, B = 150, 333, 12
+    dev = dict(kind=aht.CONSTANT_STEP, dw_min=0.001, w_max=1.0, w_min=-1.0)
+    lr = 0.02
+    x = np.zeros((B, C), dtype=np.float32)
+    d = np.zeros((B, R), dtype=np.float32)
+    fractions = [0.0, 0.01, 0.05, 0.2, 0.4, 0.6, 0.63, 0.7, 0.9, 1.0, 0.3, 0.5]
+    for b, f in enumerate(fractions):
+        for arr, n in ((x, C), (d, R)):
+            v = g.normal(size=n).astype(np.float32) * 0.05          # partial probabilities
+            kind = g.random(n)
+            v[kind > f] = 0.0                                        # zeros
+            sat = (kind > f) & (g.random(n) < 0.3)
+            v[sat] = np.where(g.random(sat.sum()) < 0.5, 50.0, -50.0)   # saturated, both signs
+            arr[b] = v
+    x[10, :64] = g.normal(size=64).astype(np.float32) * 0.05         # one full wave beside sparse ones
+    with aht.Tile(R, C, aht.DeviceParams(**dev), bl, um, seed=11) as tile:
+        for t in (0, 3):
+            tile.step = t
+            xw, dw = tile.debug_pulse_words(to_dev(x), to_dev(d), lr)
+            oxw, odw = oracle.pulse_words(x, d, lr, 0.001, bl, um, 11, t)
+            assert (words_to_np(xw) == oxw).all()
+            assert (words_to_np(dw) == odw).all()
+    # the inputs do span the cases: a sample without, with few and with only partial line values
+    partial = (np.abs(x) > 0) & (np.abs(x) < 1)
+    assert partial[0].sum() == 0 and 0 < partial[1].sum() < 10 and partial[9].sum() == C
+
+
 # ------------------------------------------------------------------ integer-exact weights
 @pytest.mark.parametrize("rpl", [1, 2, 4])
 @pytest.mark.parametrize("bl,R,C,B", [(31, 45, 77, 13), (63, 70, 130, 22), (63, 16, 64, 4)])

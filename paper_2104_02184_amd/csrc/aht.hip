@@ -271,8 +271,8 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     a.t = step;
     a.c2c = t->dev.dw_min_std;
     a.qwords = qwords;
-    // the kernel walks a tile sequence padded to whole super-tiles (64 row blocks x 8 strips)
-    const uint64_t total = (uint64_t)((a.nby + 63) / 64) * ((a.nbx + 7) / 8) * 512;
+    // one workgroup per tile of 4 * rpl rows x 64 columns, in equal shares for the 8 XCDs
+    const uint64_t total = (uint64_t)a.nby * a.nbx;
     const uint64_t per = (total + 7) / 8;
     if (per * 8 > 0x7FFFFFFFull) return fail(AHT_ERR_UNSUPPORTED, "tile too large for one launch");
     const dim3 grid((unsigned)(per * 8));

@@ -614,17 +614,27 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     // XCD-aware tile mapping.  Consecutive workgroup ids go round-robin to the 8 XCDs, so each
     // XCD gets one contiguous range of the tile sequence; the sequence walks super-tiles of
     // kSuperY row blocks x kSuperX column strips so that the x words (per strip) and d words
-    // (per row block) a range touches stay resident in that XCD's 4 MB L2.
+    // (per row block) a range touches stay resident in that XCD's 4 MB L2.  Super-tiles at the
+    // lower and right edges are clipped to the tiles that exist, so that the sequence has no holes
+    // and every XCD gets the same number of tiles whatever the shape.
     constexpr uint32_t kSuperY = 64, kSuperX = 8;
-    const uint32_t nsy = (a.nby + kSuperY - 1) / kSuperY, nsx = (a.nbx + kSuperX - 1) / kSuperX;
-    const uint32_t total = nsy * nsx * kSuperY * kSuperX;            // padded tile sequence
+    const uint32_t total = a.nby * a.nbx;
     const uint32_t per = (total + 7u) >> 3;
     const uint32_t seq = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
-    if (seq >= total) return;
-    const uint32_t st = seq / (kSuperY * kSuperX), in = seq - st * (kSuperY * kSuperX);
-    const uint32_t sy = st % nsy, sx = st / nsy;
-    const uint32_t by = sy * kSuperY + (in % kSuperY), bxr = sx * kSuperX + (in / kSuperY);
-    if (by >= a.nby || bxr >= a.nbx) return;
+    if ((blockIdx.x >> 3) >= per || seq >= total) return;
+    const uint32_t colsize = a.nby * kSuperX;                        // tiles of a full-width column of super-tiles
+    uint32_t sx = seq / colsize;
+    const uint32_t full_x = a.nbx / kSuperX;
+    if (sx > full_x) sx = full_x;                                    // (the clipped last column is narrower)
+    const uint32_t off = seq - sx * colsize;
+    const uint32_t wd = sx < full_x ? kSuperX : a.nbx - full_x * kSuperX;    // strips in this column
+    const uint32_t rowsize = kSuperY * wd;                           // tiles of a full-height super-tile here
+    uint32_t sy = off / rowsize;
+    const uint32_t full_y = a.nby / kSuperY;
+    if (sy > full_y) sy = full_y;
+    const uint32_t in = off - sy * rowsize;
+    const uint32_t ht = sy < full_y ? kSuperY : a.nby - full_y * kSuperY;    // row blocks in this super-tile
+    const uint32_t by = sy * kSuperY + (in % ht), bxr = sx * kSuperX + (in / ht);
     const uint32_t bx = a.bx0 + bxr;              // the launch covers strips bx0 .. bx0 + nbx - 1
 
     const int lane = threadIdx.x & 63;

@@ -229,7 +229,7 @@ int choose_rpl(const aht_tile* t)
     if (forced == 1 || forced == 2 || forced == 4) return forced;
     const size_t cells = (size_t)t->rows * t->cols;
     if (cells / (64 * 4) >= 16384) return 4;      // measured: 4 rows per lane pay from ~4 M cells on
-    if (cells / (64 * 2) >= 2048) return 2;
+    if (cells >= 180000) return 2;                // measured: crossover between 384 x 384 and 448 x 448
     return 1;
 }
 

@@ -290,7 +290,10 @@ aht_status aht_profile_read(aht_tile* tile, double* ms_words, double* ms_cells, 
 
 /* Tuning overrides, read from the environment at every call (measurement aids; results do not
  * depend on them beyond the summation order of the analog product):
- *   AHT_RPL         rows per lane of the cell-update kernel (1, 2 or 4)
+ *   AHT_RPL         rows per lane of the cell-update kernel (1, 2 or 4); without it the library
+ *                   chooses from the tile size and, from 400 000 cells on, from the tile's own
+ *                   pulse rate: some update calls are followed by an asynchronous 8-byte copy of
+ *                   the pulse counter to pinned host memory on the caller's stream
  *   AHT_QWORDS      32-bit words of pulse-stream storage per cell in LDS
  *   AHT_MVM_BM      block height of the analog product (64 or 128 input vectors)
  *   AHT_MVM_SPLITS  number of slices the product's inner dimension is cut into (1..16) */

@@ -40,6 +40,14 @@ struct aht_tile {
     int train_kind = AHT_TRAIN_STOCHASTIC;
     int dynamic_bl = 0;
     unsigned long long* pulse_count = nullptr;
+    // Feedback for the launch shape of the cell update: a pinned host copy of the pulse counter,
+    // refreshed by an asynchronous copy behind each full update of a tile large enough to have a
+    // choice, and the number of such updates.  The host reads whatever has arrived; it never waits.
+    unsigned long long* pulses_seen = nullptr;
+    uint64_t full_updates = 0;                    // full updates issued so far
+    uint64_t copy_issued_at = 0;                  // ... when the last copy was issued
+    unsigned long long seen_value = 0;            // last value read from the pinned word
+    double pulse_rate = -1.0;                     // pulses per cell and full update; < 0: not known yet
     // analog matrix-vector product: scratch and call counters
     float* mvm_xq = nullptr;
     float* mvm_alpha = nullptr;
@@ -96,6 +104,8 @@ inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 inline int cpad(const aht_tile* t) { return (t->cols + 63) & ~63; }
 inline int rpad(const aht_tile* t) { return (t->rows + 15) & ~15; }
 inline int bpad(int B) { return (B + 15) & ~15; }       // samples per row of the row-word buffer
+// tiles from this size on choose the launch shape of the cell update from their pulse rate
+constexpr size_t kAdaptMinCells = 400000;
 
 int env_int(const char* name, int dflt)
 {
@@ -228,9 +238,29 @@ int choose_rpl(const aht_tile* t)
     const int forced = env_int("AHT_RPL", 0);
     if (forced == 1 || forced == 2 || forced == 4) return forced;
     const size_t cells = (size_t)t->rows * t->cols;
-    if (cells / (64 * 4) >= 16384) return 4;      // measured: 4 rows per lane pay from ~4 M cells on
-    if (cells >= 180000) return 2;                // measured: crossover between 384 x 384 and 448 x 448
-    return 1;
+    if (cells < 180000) return 1;                 // measured: crossover between 384 x 384 and 448 x 448
+    if (cells < kAdaptMinCells) return 2;
+    // Four rows per lane (with 9-word streams) pay when streams stay short: from 0.4 M cells on at
+    // about 110 pulses per cell and call, from 2.3 M at about 160, never at 200 (measured on three
+    // input laws).  The rate is the tile's own, from the pulse counter as last seen on the host.
+    if (t->pulse_rate >= 0.0) {
+        if (t->pulse_rate < 130.0) return 4;
+        if (t->pulse_rate < 185.0) return cells >= 2300000 ? 4 : 2;
+        return 2;
+    }
+    return cells >= (size_t)4 * 1024 * 1024 ? 4 : 2;      // no feedback yet
+}
+
+// Called before a full update is launched: takes note of a counter value that has arrived since the
+// last look (it belongs to the copy issued last; early on, when every update issues one, to that
+// or the one before: the estimate is then a little low for a few calls).
+void refresh_pulse_rate(aht_tile* t)
+{
+    if (!t->pulses_seen || t->copy_issued_at < 2) return;
+    const unsigned long long v = *(volatile unsigned long long*)t->pulses_seen;
+    if (v == t->seen_value) return;
+    t->seen_value = v;
+    t->pulse_rate = (double)v / ((double)t->rows * (double)t->cols * (double)t->copy_issued_at);
 }
 
 // the cell update of step `step` from the words in the tile's scratch
@@ -349,6 +379,10 @@ aht_status aht_tile_create(aht_tile** out, int32_t rows, int32_t cols, const aht
     if ((e = hipMemset(t->W, 0, n * sizeof(float))) != hipSuccess) return cleanup(hip_fail(e, "hipMemset"));
     if ((e = hipMemset(t->pulse_count, 0, sizeof(unsigned long long))) != hipSuccess)
         return cleanup(hip_fail(e, "hipMemset"));
+    if (n >= kAdaptMinCells) {                    // without the pinned word the static choice stays
+        if (hipHostMalloc((void**)&t->pulses_seen, 64, hipHostMallocDefault) == hipSuccess) *t->pulses_seen = 0;
+        else { t->pulses_seen = nullptr; (void)hipGetLastError(); }
+    }
     PlaneArgs pa{};
     pa.kind = dev->kind;
     pa.dw_min = dev->dw_min; pa.dw_min_dtod = dev->dw_min_dtod;
@@ -386,6 +420,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     for (auto* p : t->tplanes) rel(p);
     rel(t->mvm_xq); rel(t->mvm_part); rel(t->ucell_w); rel(t->mvm_alpha); rel(t->mvm_norm); rel(t->xfer);
     for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
+    if (t->pulses_seen) (void)hipHostFree(t->pulses_seen);
     delete t;
     if (first != hipSuccess) return hip_fail(first, "aht_tile_destroy");
     return AHT_OK;
@@ -436,6 +471,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
             ev = &t->events[t->events_used];
         }
         if (ev) AHT_HIP(hipEventRecord(ev[0], s));
+        if (col_hi < 0) refresh_pulse_rate(t);
         if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
         if (ev) AHT_HIP(hipEventRecord(ev[1], s));
         const uint32_t strip0 = col_hi < 0 ? 0u : (uint32_t)(col_lo / 64);
@@ -444,6 +480,15 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         if (ev) {
             AHT_HIP(hipEventRecord(ev[2], s));
             t->events_used += 3;
+        }
+        if (col_hi < 0) {
+            t->full_updates += 1;
+            // the first eight updates and every sixteenth after them report the counter
+            if (t->pulses_seen && (t->full_updates <= 8 || t->full_updates % 16 == 0)) {
+                AHT_HIP(hipMemcpyAsync(t->pulses_seen, t->pulse_count, sizeof(unsigned long long),
+                                       hipMemcpyDeviceToHost, s));
+                t->copy_issued_at = t->full_updates;
+            }
         }
     }
     t->step += 1;

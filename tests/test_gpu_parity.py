@@ -301,6 +301,22 @@ def test_small_and_large_streams_give_identical_bits(env, qwords):
         assert pg == pr and (got == ref).all(), (rpl, qwords)
 
 
+def test_launch_shape_chosen_from_the_pulse_rate_changes_no_bit(env):
+    # from 400 k cells on the library picks rows per lane from the tile's own pulse rate, which
+    # it learns over the first calls: a sequence that starts with the static choice and changes
+    # it on the way gives the bits of a sequence run with a fixed shape
+    w = wl.scaled(wl.WORKLOADS["cfg3_1024x1024_softbounds"], rows=640, cols=704, batch=24, steps=7)
+    W0 = wl.initial_weights(w)
+    env(AHT_RPL=2, AHT_QWORDS=None)
+    ref, pr = run_gpu(w, W0)
+    env(AHT_RPL=None, AHT_QWORDS=None)
+    got, pg = run_gpu(w, W0)
+    assert pg == pr and (got == ref).all()
+    env(AHT_RPL=4, AHT_QWORDS=None)
+    got4, p4 = run_gpu(w, W0)
+    assert p4 == pr and (got4 == ref).all()
+
+
 def test_saturated_lines_fill_whole_trains(env):
     # every sample has 63 coincidences per cell: queues overflow often, counts are maximal
     R, C, B, bl = 33, 65, 40, 63

@@ -54,6 +54,8 @@ struct aht_tile {
     float* mvm_norm = nullptr;
     size_t mvm_xq_floats = 0;
     float* mvm_part = nullptr;    // partial sums of a K-split product [splits][B][N]
+    uint16_t* mvm_codes = nullptr;   // DAC integers of the quantised inputs as bf16 [B][K]
+    size_t mvm_codes_elems = 0;
     float* ucell_w = nullptr;     // effective weights of the unit cell this tile leads [rows][cols]
     size_t mvm_part_floats = 0;
     int mvm_b_cap = 0;
@@ -418,7 +420,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     for (auto* p : t->planes) rel(p);
     rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->bl_b); rel(t->pulse_count);
     for (auto* p : t->tplanes) rel(p);
-    rel(t->mvm_xq); rel(t->mvm_part); rel(t->ucell_w); rel(t->mvm_alpha); rel(t->mvm_norm); rel(t->xfer);
+    rel(t->mvm_xq); rel(t->mvm_part); rel(t->mvm_codes); rel(t->ucell_w); rel(t->mvm_alpha); rel(t->mvm_norm); rel(t->xfer);
     for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
     if (t->pulses_seen) (void)hipHostFree(t->pulses_seen);
     delete t;
@@ -563,8 +565,58 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     const uint32_t step = transposed ? t->bwd_step : t->fwd_step;
     const uint32_t tag_in = transposed ? 9u : 7u, tag_out = transposed ? 10u : 8u;
     const int vec_in = (K % 4 == 0) && (((uintptr_t)x | (uintptr_t)t->mvm_xq) % 16 == 0);
+    // Quantised inputs without input noise are integers times the input grid: the forward product then
+    // runs on the bf16 matrix cores (integer codes exact in bf16, weights cut into three bf16 terms).
+    const float* wmat = w_eff ? w_eff : t->W;
+    const bool codes_path = !transposed && env_int("AHT_MVM_CODES", 1) != 0 && io->inp_res > 0.0f &&
+                            io->inp_noise == 0.0f && io->inp_bound / io->inp_res <= 256.0f && K % 16 == 0 &&
+                            N % 32 == 0 && ((uintptr_t)wmat % 16 == 0);
+    // codes in blocks of 32 vectors; whole groups of 8 blocks (the most a wave takes), zero where no vector is
+    const size_t cneed = (size_t)((B + 255) / 256) * 256 * (size_t)K;
+    if (codes_path && cneed > t->mvm_codes_elems) {
+        if (t->mvm_codes) AHT_HIP(hipFree(t->mvm_codes));
+        t->mvm_codes = nullptr; t->mvm_codes_elems = 0;
+        AHT_HIP(hipMalloc((void**)&t->mvm_codes, cneed * sizeof(uint16_t)));
+        AHT_HIP(hipMemset(t->mvm_codes, 0, cneed * sizeof(uint16_t)));
+        t->mvm_codes_elems = cneed;
+    }
     hipLaunchKernelGGL(k_mvm_prepare, dim3((unsigned)B), dim3(1024), 0, s, x, K, vec_in, a, k0, k1, step, tag_in,
-                       t->mvm_xq, t->mvm_alpha, t->mvm_norm);
+                       t->mvm_xq, t->mvm_alpha, t->mvm_norm, codes_path ? t->mvm_codes : nullptr);
+    if (codes_path) {
+        int mt = B > 128 ? 8 : B > 64 ? 4 : B > 32 ? 2 : 1;     // 32-vector tiles per wave
+        if (const int e = env_int("AHT_MVM_MT", 0)) mt = (e == 8 || e == 4 || e == 2 || e == 1) ? e : mt;
+        const int mchunks = (B + 32 * mt - 1) / (32 * mt), nslab = N / 32, steps = K / 16;
+        int splits = env_int("AHT_MVM_SPLITS", 0);
+        if (splits <= 0) {
+            const long units = (long)mchunks * nslab;
+            splits = (int)((1024 + units - 1) / units);                 // one wave per SIMD (measured optimum)
+            if (splits > steps / 8) splits = steps / 8;
+        }
+        if (splits > 16) splits = 16;
+        if (splits < 1) splits = 1;
+        const size_t pneed = (size_t)splits * (size_t)B * (size_t)N;
+        if (pneed > t->mvm_part_floats) {
+            if (t->mvm_part) AHT_HIP(hipFree(t->mvm_part));
+            t->mvm_part = nullptr; t->mvm_part_floats = 0;
+            AHT_HIP(hipMalloc((void**)&t->mvm_part, pneed * sizeof(float)));
+            t->mvm_part_floats = pneed;
+        }
+        const unsigned waves = (unsigned)mchunks * (unsigned)nslab * (unsigned)splits;
+        const dim3 cgrid((waves + 3u) / 4u);
+        switch (mt) {
+            case 8: hipLaunchKernelGGL(k_mvm_gemm_codes<8>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
+            case 4: hipLaunchKernelGGL(k_mvm_gemm_codes<4>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
+            case 2: hipLaunchKernelGGL(k_mvm_gemm_codes<2>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
+            default: hipLaunchKernelGGL(k_mvm_gemm_codes<1>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
+        }
+        AHT_HIP(hipGetLastError());
+        const size_t pairs = (size_t)B * (size_t)((N + 1) / 2);
+        hipLaunchKernelGGL(k_mvm_epilogue, dim3(blocks_for(pairs)), dim3(256), 0, s, t->mvm_part, splits, B, N,
+                           t->mvm_alpha, t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
+        AHT_HIP(hipGetLastError());
+        t->fwd_step += 1;
+        return AHT_OK;
+    }
     // K split aiming at two workgroups per compute unit (measured optimum at 4096 x 4096, B = 256:
     // more slices only add partial-sum traffic), at least four K steps per slice.
     // Blocks of 64 vectors keep three workgroups resident per compute unit; when there are more
@@ -592,7 +644,6 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     const unsigned total = (unsigned)mb * (unsigned)nb * (unsigned)splits;
     const dim3 grid(((total + 7u) / 8u) * 8u);
     // 16-byte accesses need aligned rows and whole groups; the tile's weights start 256-byte aligned
-    const float* wmat = w_eff ? w_eff : t->W;
     const bool aligned = (K % 32 == 0) && (t->cols % 4 == 0) && (N % 4 == 0) &&
                          (((uintptr_t)t->mvm_xq | (uintptr_t)wmat) % 16 == 0);
 #define AHT_MVM_LAUNCH(TR, BMV, AL)                                                                              \

@@ -97,6 +97,48 @@ def test_block_height_and_inner_split_do_not_change_the_result(R, C, B, transpos
     tile.close()
 
 
+# quantised inputs without input noise: the forward product takes the integer DAC codes through the
+# bf16 matrix cores (weights cut into three bf16 terms) when the shape allows, else the fp32 path
+QUANT = dict(inp_res=1.0 / 126.0, inp_bound=1.0, inp_noise=0.0, w_noise=0.02, out_noise=0.06, out_res=12.0 / 254.0,
+             out_bound=12.0, noise_management=True)
+QUANT_EXACT = dict(inp_res=1.0 / 126.0, inp_bound=1.0, inp_noise=0.0, w_noise=0.0, out_noise=0.0, out_res=0.0,
+                   out_bound=1e30, noise_management=True)
+
+
+@pytest.mark.parametrize("R,C,B", [(32, 16, 1), (64, 64, 20), (96, 160, 33), (160, 272, 70), (128, 512, 130),
+                                   (512, 1024, 256), (64, 1024, 300), (37, 304, 5), (96, 300, 40)])
+@pytest.mark.parametrize("io_kw", [QUANT, QUANT_EXACT])
+def test_quantised_forward_product_matches(R, C, B, io_kw):
+    tile, W = _tile_with_weights(R, C)
+    g = np.random.default_rng(R + C + B + 7)
+    x = g.normal(size=(B, C)).astype(np.float32)
+    if B > 4:
+        x[1] = 0.0
+        x[2, 3] = np.nan
+        x[3] *= 1e-3
+    _check(tile, W, x, io_kw, False, step=4)
+    xt = g.normal(size=(B, R)).astype(np.float32)
+    _check(tile, W, xt, io_kw, True, step=4)      # the transposed product keeps the fp32 path
+    tile.close()
+
+
+@pytest.mark.parametrize("splits", [1, 2, 5, 16])
+@pytest.mark.parametrize("B", [7, 40, 100, 200])
+def test_quantised_forward_every_split_and_both_paths_agree(B, splits, monkeypatch):
+    R, C = 96, 512
+    tile, W = _tile_with_weights(R, C)
+    g = np.random.default_rng(B + splits)
+    x = g.normal(size=(B, C)).astype(np.float32)
+    monkeypatch.setenv("AHT_MVM_SPLITS", str(splits))
+    _check(tile, W, x, QUANT_EXACT, False, step=1)
+    y_codes = tile.forward(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
+    monkeypatch.setenv("AHT_MVM_CODES", "0")
+    y_fp32 = tile.forward(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
+    scale = max(1.0, float(np.abs(y_fp32).max()))
+    assert np.abs(y_codes.astype(np.float64) - y_fp32).max() <= 2e-5 * scale * max(1.0, np.sqrt(C) / 16)
+    tile.close()
+
+
 def test_bad_io_parameters_are_rejected():
     import torch
     tile, W = _tile_with_weights(8, 8)

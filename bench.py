@@ -166,7 +166,7 @@ def bench_mvm(args, transposed):
     # quantised inputs without input noise: the forward product runs as three passes of the bf16 matrix
     # cores (integer DAC codes, fp32 weights cut into three bf16 terms, fp32 sums); else one fp32 pass
     codes = (not transposed) and args.inp_noise == 0.0 and os.environ.get("AHT_MVM_CODES", "1") != "0" \
-        and w.cols % 16 == 0 and w.rows % 32 == 0
+        and w.cols % 32 == 0 and w.rows % 16 == 0
     executed = 3.0 * flops if codes else flops
     peak = 2500.0 if codes else 157.3
     print(json.dumps({

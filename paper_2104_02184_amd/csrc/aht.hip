@@ -569,8 +569,8 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     // runs on the bf16 matrix cores (integer codes exact in bf16, weights cut into three bf16 terms).
     const float* wmat = w_eff ? w_eff : t->W;
     const bool codes_path = !transposed && env_int("AHT_MVM_CODES", 1) != 0 && io->inp_res > 0.0f &&
-                            io->inp_noise == 0.0f && io->inp_bound / io->inp_res <= 256.0f && K % 16 == 0 &&
-                            N % 32 == 0 && ((uintptr_t)wmat % 16 == 0);
+                            io->inp_noise == 0.0f && io->inp_bound / io->inp_res <= 256.0f && K % 32 == 0 &&
+                            N % 16 == 0 && ((uintptr_t)wmat % 16 == 0);
     // codes in blocks of 32 vectors; whole groups of 8 blocks (the most a wave takes), zero where no vector is
     const size_t cneed = (size_t)((B + 255) / 256) * 256 * (size_t)K;
     if (codes_path && cneed > t->mvm_codes_elems) {
@@ -583,14 +583,14 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     hipLaunchKernelGGL(k_mvm_prepare, dim3((unsigned)B), dim3(1024), 0, s, x, K, vec_in, a, k0, k1, step, tag_in,
                        t->mvm_xq, t->mvm_alpha, t->mvm_norm, codes_path ? t->mvm_codes : nullptr);
     if (codes_path) {
-        int mt = B > 128 ? 8 : B > 64 ? 4 : B > 32 ? 2 : 1;     // 32-vector tiles per wave
-        if (const int e = env_int("AHT_MVM_MT", 0)) mt = (e == 8 || e == 4 || e == 2 || e == 1) ? e : mt;
-        const int mchunks = (B + 32 * mt - 1) / (32 * mt), nslab = N / 32, steps = K / 16;
+        int mt = B > 128 ? 16 : B > 64 ? 8 : B > 32 ? 4 : 2;    // 16-vector tiles per wave
+        if (const int e = env_int("AHT_MVM_MT", 0)) mt = (e == 16 || e == 8 || e == 4 || e == 2) ? e : mt;
+        const int mchunks = (B + 16 * mt - 1) / (16 * mt), nslab = N / 16, steps = K / 32;
         int splits = env_int("AHT_MVM_SPLITS", 0);
         if (splits <= 0) {
             const long units = (long)mchunks * nslab;
             splits = (int)((1024 + units - 1) / units);                 // one wave per SIMD (measured optimum)
-            if (splits > steps / 8) splits = steps / 8;
+            if (splits > steps / 4) splits = steps / 4;
         }
         if (splits > 16) splits = 16;
         if (splits < 1) splits = 1;
@@ -604,10 +604,10 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
         const unsigned waves = (unsigned)mchunks * (unsigned)nslab * (unsigned)splits;
         const dim3 cgrid((waves + 3u) / 4u);
         switch (mt) {
+            case 16: hipLaunchKernelGGL(k_mvm_gemm_codes<16>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
             case 8: hipLaunchKernelGGL(k_mvm_gemm_codes<8>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
             case 4: hipLaunchKernelGGL(k_mvm_gemm_codes<4>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
-            case 2: hipLaunchKernelGGL(k_mvm_gemm_codes<2>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
-            default: hipLaunchKernelGGL(k_mvm_gemm_codes<1>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
+            default: hipLaunchKernelGGL(k_mvm_gemm_codes<2>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
         }
         AHT_HIP(hipGetLastError());
         const size_t pairs = (size_t)B * (size_t)((N + 1) / 2);

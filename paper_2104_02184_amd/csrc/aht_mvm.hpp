@@ -81,11 +81,11 @@ k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k
             if (io.inp_res > 0.0f) {
                 const float code = rintf(xh / io.inp_res);     // the DAC's integer, |code| <= bound / res
                 // as bf16 (exact up to 256) for the product on the bf16 matrix cores
-                // (operand layout of the matrix instruction: blocks of 32 vectors x 16 inputs, 64 lanes x 8 codes)
+                // (operand layout of the matrix instruction: blocks of 16 vectors x 32 inputs, 64 lanes x 8 codes)
                 if (codes && 4 * g + e < K) {
                     const int kk = 4 * g + e;
-                    const size_t block = (size_t)(b >> 5) * (size_t)(K >> 4) + (size_t)(kk >> 4);
-                    codes[(block * 64 + (size_t)(((kk >> 3) & 1) * 32 + (b & 31))) * 8 + (size_t)(kk & 7)] =
+                    const size_t block = (size_t)(b >> 4) * (size_t)(K >> 5) + (size_t)(kk >> 5);
+                    codes[(block * 64 + (size_t)(((kk >> 3) & 3) * 16 + (b & 15))) * 8 + (size_t)(kk & 7)] =
                         (uint16_t)(__float_as_uint(code) >> 16);
                 }
                 xh = code * io.inp_res;
@@ -401,12 +401,14 @@ k_mvm_gemm(const float* __restrict__ A, const float* __restrict__ Wm, int M, int
 // Forward product for quantised inputs without input noise: X~ = res * C with integer codes C,
 // |c| <= 256, exact in bf16.  Each weight is cut into three bf16 terms (8 + 8 + 8 mantissa bits:
 // w = hi + mid + lo up to the last bit of its fp32 value), so that Z = res * (C hi^T + C mid^T +
-// C lo^T) takes three passes of the bf16 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 sums) in
-// place of one pass of the fp32 ones at an eighth of their rate.  A wave owns 32 outputs x MT * 32
+// C lo^T) takes three passes of the bf16 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 sums) in
+// place of one pass of the fp32 ones at an eighth of their rate.  A wave owns 16 outputs x MT * 16
 // input vectors x one slice of the inner dimension: it reads its weights once, straight into the
-// operand layout (lane = output, 8 consecutive inner indices), no LDS, no barrier, and writes its
-// partial sums for k_mvm_epilogue.  Needs K % 16 == 0, N % 32 == 0, 16-byte aligned rows.
+// operand layout (lane = output and one of four groups of 8 inner indices: the four lanes of an
+// output read one whole 128-byte line per step), no LDS, no barrier, and writes its partial sums
+// for k_mvm_epilogue.  Needs K % 32 == 0, N % 16 == 0, 16-byte aligned rows.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 template <int MT>
 __global__ void __launch_bounds__(256)
@@ -415,46 +417,47 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int nslab = N >> 5, mchunks = (B + 32 * MT - 1) / (32 * MT);
+    const int nslab = N >> 4, mchunks = (B + 16 * MT - 1) / (16 * MT);
     const int unit = (int)blockIdx.x * 4 + wave;
     if (unit >= nslab * mchunks * splits) return;                  // wave-uniform; the kernel has no barriers
     const int z = unit / (nslab * mchunks), rem = unit - z * (nslab * mchunks);
     const int mc = rem / nslab, slab = rem - mc * nslab;
-    const int steps = K >> 4, per = (steps + splits - 1) / splits;
+    const int steps = K >> 5, per = (steps + splits - 1) / splits;
     const int s0 = z * per, s1 = (s0 + per < steps) ? s0 + per : steps;
-    const int j = lane & 31, g = lane >> 5;
-    const float* wp = W + (size_t)(slab * 32 + j) * ldw + 8 * g;
-    // codes: one contiguous 1 KB block per (32 vectors, 16 inputs); blocks past the batch hold zeros
+    const int j = lane & 15, g = lane >> 4;
+    const float* wp = W + (size_t)(slab * 16 + j) * ldw + 8 * g;
+    // codes: one contiguous 1 KB block per (16 vectors, 32 inputs); blocks past the batch hold zeros
     const uint16_t* ap[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m) ap[m] = xc + ((size_t)(mc * MT + m) * (size_t)steps * 64 + (size_t)lane) * 8;
-    floatx16 acc[MT];
+    floatx4_t acc[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[m][r] = 0.0f;
+        for (int r = 0; r < 4; ++r) acc[m][r] = 0.0f;
 
     // The weights come from HBM once and nothing hides their latency but loads in flight: a ring of
     // DW steps of weights and codes per wave.  (The codes are L2 resident, but loads complete in
     // order: fetched any later than the weights of their step, they would make the wave wait for
     // younger weight loads too.)  Fetches past the slice read its last step again: no branch around
     // a load, so that the compiler can count the loads in flight and wait for the oldest only.
-    constexpr int DW = (MT >= 8) ? 6 : 4;
+    constexpr int DW = (MT >= 16) ? 3 : 4;
     float4 wq[DW][2];
     uint4 av[DW][MT];
     auto fetch = [&](int s, float4 (&q)[2], uint4 (&v)[MT]) __attribute__((always_inline)) {
         typedef float f4_t __attribute__((ext_vector_type(4)));
-        const float* wr = wp + 16 * (size_t)s;
+        const float* wr = wp + 32 * (size_t)s;
         const f4_t u0 = __builtin_nontemporal_load((const f4_t*)wr), u1 = __builtin_nontemporal_load((const f4_t*)(wr + 4));
         q[0] = make_float4(u0.x, u0.y, u0.z, u0.w);
         q[1] = make_float4(u1.x, u1.y, u1.z, u1.w);
 #pragma unroll
         for (int m = 0; m < MT; ++m) v[m] = *(const uint4*)(ap[m] + 512 * (size_t)s);
     };
-    if (s0 >= s1) return;
     const int last = s1 - 1;
+    if (s0 < s1) {                                // (an empty slice still writes its zeros)
 #pragma unroll
-    for (int d = 0; d < DW; ++d) fetch(s0 + d < last ? s0 + d : last, wq[d], av[d]);
+        for (int d = 0; d < DW; ++d) fetch(s0 + d < last ? s0 + d : last, wq[d], av[d]);
+    }
     for (int s = s0; s < s1; s += DW) {
 #pragma unroll
         for (int d = 0; d < DW; ++d) {
@@ -485,20 +488,20 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
             for (int m = 0; m < MT; ++m) a[m] = __builtin_bit_cast(bf16x8_t, av[d][m]);
             fetch(sd + DW < last ? sd + DW : last, wq[d], av[d]);
 #pragma unroll
-            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], bl, acc[m], 0, 0, 0);
+            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bl, acc[m], 0, 0, 0);
 #pragma unroll
-            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], bm, acc[m], 0, 0, 0);
+            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bm, acc[m], 0, 0, 0);
 #pragma unroll
-            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], bh, acc[m], 0, 0, 0);
+            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bh, acc[m], 0, 0, 0);
         }
     }
-    // partial sums, in units of the input grid; lane = output, register r = row 8 (r / 4) + 4 g + r % 4
-    float* pz = part + (size_t)z * B * N + (size_t)(slab * 32 + j);
+    // partial sums, in units of the input grid; lane = output, register r = row 4 g + r of the tile
+    float* pz = part + (size_t)z * B * N + (size_t)(slab * 16 + j);
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = (mc * MT + m) * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        for (int r = 0; r < 4; ++r) {
+            const int row = (mc * MT + m) * 16 + 4 * g + r;
             if (row < B) pz[(size_t)row * N] = acc[m][r] * inp_res;
         }
 }

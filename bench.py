@@ -163,10 +163,10 @@ def bench_mvm(args, transposed):
     ms = e0.elapsed_time(e1) / args.steps
     tile.close()
     flops = 2.0 * w.batch * w.rows * w.cols
-    # quantised inputs without input noise: the forward product runs as three passes of the bf16 matrix
+    # quantised inputs without input noise: the product runs as three passes of the bf16 matrix
     # cores (integer DAC codes, fp32 weights cut into three bf16 terms, fp32 sums); else one fp32 pass
-    codes = (not transposed) and args.inp_noise == 0.0 and os.environ.get("AHT_MVM_CODES", "1") != "0" \
-        and w.cols % 32 == 0 and w.rows % 16 == 0
+    n_out = w.cols if transposed else w.rows
+    codes = args.inp_noise == 0.0 and os.environ.get("AHT_MVM_CODES", "1") != "0" and n_in % 32 == 0 and n_out % 16 == 0
     executed = 3.0 * flops if codes else flops
     peak = 2500.0 if codes else 157.3
     print(json.dumps({

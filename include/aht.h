@@ -297,7 +297,7 @@ aht_status aht_profile_read(aht_tile* tile, double* ms_words, double* ms_cells, 
  *   AHT_QWORDS      32-bit words of pulse-stream storage per cell in LDS
  *   AHT_MVM_BM      block height of the analog product (64 or 128 input vectors)
  *   AHT_MVM_SPLITS  number of slices the product's inner dimension is cut into (1..16)
- *   AHT_MVM_CODES   0: keep quantised forward products off the bf16 matrix cores
+ *   AHT_MVM_CODES   0: keep products of quantised inputs off the bf16 matrix cores
  *   AHT_MVM_MT      16-vector tiles per wave on that path (2, 4, 8 or 16) */
 
 const char* aht_status_string(aht_status s);

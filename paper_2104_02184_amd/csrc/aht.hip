@@ -565,10 +565,10 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     const uint32_t step = transposed ? t->bwd_step : t->fwd_step;
     const uint32_t tag_in = transposed ? 9u : 7u, tag_out = transposed ? 10u : 8u;
     const int vec_in = (K % 4 == 0) && (((uintptr_t)x | (uintptr_t)t->mvm_xq) % 16 == 0);
-    // Quantised inputs without input noise are integers times the input grid: the forward product then
+    // Quantised inputs without input noise are integers times the input grid: the product then
     // runs on the bf16 matrix cores (integer codes exact in bf16, weights cut into three bf16 terms).
     const float* wmat = w_eff ? w_eff : t->W;
-    const bool codes_path = !transposed && env_int("AHT_MVM_CODES", 1) != 0 && io->inp_res > 0.0f &&
+    const bool codes_path = env_int("AHT_MVM_CODES", 1) != 0 && io->inp_res > 0.0f &&
                             io->inp_noise == 0.0f && io->inp_bound / io->inp_res <= 256.0f && K % 32 == 0 &&
                             N % 16 == 0 && ((uintptr_t)wmat % 16 == 0);
     // codes in blocks of 32 vectors; whole groups of 8 blocks (the most a wave takes), zero where no vector is
@@ -603,18 +603,25 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
         }
         const unsigned waves = (unsigned)mchunks * (unsigned)nslab * (unsigned)splits;
         const dim3 cgrid((waves + 3u) / 4u);
-        switch (mt) {
-            case 16: hipLaunchKernelGGL(k_mvm_gemm_codes<16>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
-            case 8: hipLaunchKernelGGL(k_mvm_gemm_codes<8>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
-            case 4: hipLaunchKernelGGL(k_mvm_gemm_codes<4>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
-            default: hipLaunchKernelGGL(k_mvm_gemm_codes<2>, cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, splits, io->inp_res, t->mvm_part); break;
-        }
+#define AHT_CODES_LAUNCH(MTV, TR)                                                                               \
+    hipLaunchKernelGGL((k_mvm_gemm_codes<MTV, TR>), cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, \
+                       splits, io->inp_res, t->mvm_part)
+#define AHT_CODES_PICK(TR)                                                                                       \
+    switch (mt) {                                                                                                \
+        case 16: AHT_CODES_LAUNCH(16, TR); break;                                                                \
+        case 8: AHT_CODES_LAUNCH(8, TR); break;                                                                  \
+        case 4: AHT_CODES_LAUNCH(4, TR); break;                                                                  \
+        default: AHT_CODES_LAUNCH(2, TR); break;                                                                 \
+    }
+        if (transposed) { AHT_CODES_PICK(true) } else { AHT_CODES_PICK(false) }
+#undef AHT_CODES_PICK
+#undef AHT_CODES_LAUNCH
         AHT_HIP(hipGetLastError());
         const size_t pairs = (size_t)B * (size_t)((N + 1) / 2);
         hipLaunchKernelGGL(k_mvm_epilogue, dim3(blocks_for(pairs)), dim3(256), 0, s, t->mvm_part, splits, B, N,
                            t->mvm_alpha, t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
         AHT_HIP(hipGetLastError());
-        t->fwd_step += 1;
+        if (transposed) t->bwd_step += 1; else t->fwd_step += 1;
         return AHT_OK;
     }
     // K split aiming at two workgroups per compute unit (measured optimum at 4096 x 4096, B = 256:

@@ -398,7 +398,7 @@ k_mvm_gemm(const float* __restrict__ A, const float* __restrict__ Wm, int M, int
     }
 }
 
-// Forward product for quantised inputs without input noise: X~ = res * C with integer codes C,
+// Product for quantised inputs without input noise: X~ = res * C with integer codes C,
 // |c| <= 256, exact in bf16.  Each weight is cut into three bf16 terms (8 + 8 + 8 mantissa bits:
 // w = hi + mid + lo up to the last bit of its fp32 value), so that Z = res * (C hi^T + C mid^T +
 // C lo^T) takes three passes of the bf16 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 sums) in
@@ -406,11 +406,12 @@ k_mvm_gemm(const float* __restrict__ A, const float* __restrict__ Wm, int M, int
 // input vectors x one slice of the inner dimension: it reads its weights once, straight into the
 // operand layout (lane = output and one of four groups of 8 inner indices: the four lanes of an
 // output read one whole 128-byte line per step), no LDS, no barrier, and writes its partial sums
-// for k_mvm_epilogue.  Needs K % 32 == 0, N % 16 == 0, 16-byte aligned rows.
+// for k_mvm_epilogue.  Needs K % 32 == 0, N % 16 == 0, 16-byte aligned rows.  TRANS: the transposed
+// product (the weights of an output are a column: eight 4-byte loads per lane and step).
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
-template <int MT>
+template <int MT, bool TRANS>
 __global__ void __launch_bounds__(256)
 k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, int B, int N, int K, int ldw,
                  int splits, float inp_res, float* __restrict__ part)
@@ -425,7 +426,10 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
     const int steps = K >> 5, per = (steps + splits - 1) / splits;
     const int s0 = z * per, s1 = (s0 + per < steps) ? s0 + per : steps;
     const int j = lane & 15, g = lane >> 4;
-    const float* wp = W + (size_t)(slab * 16 + j) * ldw + 8 * g;
+    // forward: output n is row n of W, its inner indices lie side by side; transposed: output n is
+    // column n, inner index k is row k (the lanes of 16 neighbouring outputs read 64 bytes of a row)
+    const float* wp = TRANS ? W + (size_t)(8 * g) * ldw + (size_t)(slab * 16 + j)
+                            : W + (size_t)(slab * 16 + j) * ldw + 8 * g;
     // codes: one contiguous 1 KB block per (16 vectors, 32 inputs); blocks past the batch hold zeros
     const uint16_t* ap[MT];
 #pragma unroll
@@ -445,11 +449,20 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
     float4 wq[DW][2];
     uint4 av[DW][MT];
     auto fetch = [&](int s, float4 (&q)[2], uint4 (&v)[MT]) __attribute__((always_inline)) {
-        typedef float f4_t __attribute__((ext_vector_type(4)));
-        const float* wr = wp + 32 * (size_t)s;
-        const f4_t u0 = __builtin_nontemporal_load((const f4_t*)wr), u1 = __builtin_nontemporal_load((const f4_t*)(wr + 4));
-        q[0] = make_float4(u0.x, u0.y, u0.z, u0.w);
-        q[1] = make_float4(u1.x, u1.y, u1.z, u1.w);
+        if (TRANS) {
+            const float* wr = wp + (size_t)(32 * s) * ldw;
+            float e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) e[i] = __builtin_nontemporal_load(wr + (size_t)i * ldw);
+            q[0] = make_float4(e[0], e[1], e[2], e[3]);
+            q[1] = make_float4(e[4], e[5], e[6], e[7]);
+        } else {
+            typedef float f4_t __attribute__((ext_vector_type(4)));
+            const float* wr = wp + 32 * (size_t)s;
+            const f4_t u0 = __builtin_nontemporal_load((const f4_t*)wr), u1 = __builtin_nontemporal_load((const f4_t*)(wr + 4));
+            q[0] = make_float4(u0.x, u0.y, u0.z, u0.w);
+            q[1] = make_float4(u1.x, u1.y, u1.z, u1.w);
+        }
 #pragma unroll
         for (int m = 0; m < MT; ++m) v[m] = *(const uint4*)(ap[m] + 512 * (size_t)s);
     };

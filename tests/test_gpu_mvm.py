@@ -106,7 +106,7 @@ QUANT_EXACT = dict(inp_res=1.0 / 126.0, inp_bound=1.0, inp_noise=0.0, w_noise=0.
 
 
 @pytest.mark.parametrize("R,C,B", [(32, 16, 1), (64, 64, 20), (96, 160, 33), (160, 272, 70), (128, 512, 130),
-                                   (512, 1024, 256), (64, 1024, 300), (37, 304, 5), (96, 300, 40)])
+                                   (512, 1024, 256), (64, 1024, 300), (37, 304, 5), (96, 300, 40), (1024, 48, 17)])
 @pytest.mark.parametrize("io_kw", [QUANT, QUANT_EXACT])
 def test_quantised_forward_product_matches(R, C, B, io_kw):
     tile, W = _tile_with_weights(R, C)
@@ -118,24 +118,27 @@ def test_quantised_forward_product_matches(R, C, B, io_kw):
         x[3] *= 1e-3
     _check(tile, W, x, io_kw, False, step=4)
     xt = g.normal(size=(B, R)).astype(np.float32)
-    _check(tile, W, xt, io_kw, True, step=4)      # the transposed product keeps the fp32 path
+    _check(tile, W, xt, io_kw, True, step=4)      # the transposed product: same path when R % 32 == 0 and C % 16 == 0
     tile.close()
 
 
 @pytest.mark.parametrize("splits", [1, 2, 5, 16])
 @pytest.mark.parametrize("B", [7, 40, 100, 200])
-def test_quantised_forward_every_split_and_both_paths_agree(B, splits, monkeypatch):
-    R, C = 96, 512
+@pytest.mark.parametrize("transposed", [False, True])
+def test_quantised_product_every_split_and_both_paths_agree(B, splits, transposed, monkeypatch):
+    R, C = (512, 96) if transposed else (96, 512)
+    K = R if transposed else C
     tile, W = _tile_with_weights(R, C)
     g = np.random.default_rng(B + splits)
-    x = g.normal(size=(B, C)).astype(np.float32)
+    x = g.normal(size=(B, K)).astype(np.float32)
+    fn = tile.backward if transposed else tile.forward
     monkeypatch.setenv("AHT_MVM_SPLITS", str(splits))
-    _check(tile, W, x, QUANT_EXACT, False, step=1)
-    y_codes = tile.forward(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
+    _check(tile, W, x, QUANT_EXACT, transposed, step=1)
+    y_codes = fn(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
     monkeypatch.setenv("AHT_MVM_CODES", "0")
-    y_fp32 = tile.forward(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
+    y_fp32 = fn(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
     scale = max(1.0, float(np.abs(y_fp32).max()))
-    assert np.abs(y_codes.astype(np.float64) - y_fp32).max() <= 2e-5 * scale * max(1.0, np.sqrt(C) / 16)
+    assert np.abs(y_codes.astype(np.float64) - y_fp32).max() <= 2e-5 * scale * max(1.0, np.sqrt(K) / 16)
     tile.close()
 
 

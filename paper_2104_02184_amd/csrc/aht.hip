@@ -591,36 +591,57 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
             const long units = (long)mchunks * nslab;
             splits = (int)((1024 + units - 1) / units);                 // one wave per SIMD (measured optimum)
             if (splits > steps / 4) splits = steps / 4;
+            if (splits >= 3 && splits <= 6) splits = 4;                 // four slices can be finished in the kernel
         }
         if (splits > 16) splits = 16;
         if (splits < 1) splits = 1;
-        const size_t pneed = (size_t)splits * (size_t)B * (size_t)N;
-        if (pneed > t->mvm_part_floats) {
-            if (t->mvm_part) AHT_HIP(hipFree(t->mvm_part));
-            t->mvm_part = nullptr; t->mvm_part_floats = 0;
-            AHT_HIP(hipMalloc((void**)&t->mvm_part, pneed * sizeof(float)));
-            t->mvm_part_floats = pneed;
+        // Four slices: the four waves of a workgroup take one each and finish the product themselves.
+        // Not for the transposed product: there two neighbouring groups of 16 outputs share every
+        // 128-byte line of the weights, and they share it best as waves of one workgroup (measured:
+        // 64 us per call with partial sums, 68 us fused).
+        const bool fused = splits == 4 && !transposed && env_int("AHT_MVM_FUSED", 1) != 0;
+        if (!fused) {
+            const size_t pneed = (size_t)splits * (size_t)B * (size_t)N;
+            if (pneed > t->mvm_part_floats) {
+                if (t->mvm_part) AHT_HIP(hipFree(t->mvm_part));
+                t->mvm_part = nullptr; t->mvm_part_floats = 0;
+                AHT_HIP(hipMalloc((void**)&t->mvm_part, pneed * sizeof(float)));
+                t->mvm_part_floats = pneed;
+            }
         }
         const unsigned waves = (unsigned)mchunks * (unsigned)nslab * (unsigned)splits;
-        const dim3 cgrid((waves + 3u) / 4u);
-#define AHT_CODES_LAUNCH(MTV, TR)                                                                               \
-    hipLaunchKernelGGL((k_mvm_gemm_codes<MTV, TR>), cgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K, t->cols, \
-                       splits, io->inp_res, t->mvm_part)
-#define AHT_CODES_PICK(TR)                                                                                       \
+        const dim3 cgrid(fused ? (unsigned)mchunks * (unsigned)nslab : (waves + 3u) / 4u);
+        const MvmTail tail{t->mvm_alpha, t->mvm_norm, a, k0, k1, step, tag_out, y, pre};
+        const size_t xlds = fused ? (size_t)4 * mt * 256 * sizeof(float) : 0;
+#define AHT_CODES_LAUNCH(MTV, TR, FU)                                                                            \
+    do {                                                                                                         \
+        if (xlds > 48 * 1024)                                                                                    \
+            (void)hipFuncSetAttribute((const void*)k_mvm_gemm_codes<MTV, TR, FU>,                                \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)xlds);                    \
+        hipLaunchKernelGGL((k_mvm_gemm_codes<MTV, TR, FU>), cgrid, dim3(256), xlds, s, t->mvm_codes, wmat, B, N,  \
+                           K, t->cols, splits, io->inp_res, t->mvm_part, tail);                                  \
+    } while (0)
+#define AHT_CODES_PICK(TR, FU)                                                                                   \
     switch (mt) {                                                                                                \
-        case 16: AHT_CODES_LAUNCH(16, TR); break;                                                                \
-        case 8: AHT_CODES_LAUNCH(8, TR); break;                                                                  \
-        case 4: AHT_CODES_LAUNCH(4, TR); break;                                                                  \
-        default: AHT_CODES_LAUNCH(2, TR); break;                                                                 \
+        case 16: AHT_CODES_LAUNCH(16, TR, FU); break;                                                            \
+        case 8: AHT_CODES_LAUNCH(8, TR, FU); break;                                                              \
+        case 4: AHT_CODES_LAUNCH(4, TR, FU); break;                                                              \
+        default: AHT_CODES_LAUNCH(2, TR, FU); break;                                                             \
     }
-        if (transposed) { AHT_CODES_PICK(true) } else { AHT_CODES_PICK(false) }
+        if (fused) {
+            if (transposed) { AHT_CODES_PICK(true, true) } else { AHT_CODES_PICK(false, true) }
+        } else {
+            if (transposed) { AHT_CODES_PICK(true, false) } else { AHT_CODES_PICK(false, false) }
+        }
 #undef AHT_CODES_PICK
 #undef AHT_CODES_LAUNCH
         AHT_HIP(hipGetLastError());
-        const size_t pairs = (size_t)B * (size_t)((N + 1) / 2);
-        hipLaunchKernelGGL(k_mvm_epilogue, dim3(blocks_for(pairs)), dim3(256), 0, s, t->mvm_part, splits, B, N,
-                           t->mvm_alpha, t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
-        AHT_HIP(hipGetLastError());
+        if (!fused) {
+            const size_t pairs = (size_t)B * (size_t)((N + 1) / 2);
+            hipLaunchKernelGGL(k_mvm_epilogue, dim3(blocks_for(pairs)), dim3(256), 0, s, t->mvm_part, splits, B, N,
+                               t->mvm_alpha, t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
+            AHT_HIP(hipGetLastError());
+        }
         if (transposed) t->bwd_step += 1; else t->fwd_step += 1;
         return AHT_OK;
     }

@@ -411,16 +411,35 @@ k_mvm_gemm(const float* __restrict__ A, const float* __restrict__ Wm, int M, int
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
-template <int MT, bool TRANS>
+// FUSED: the four waves of a workgroup take four slices of the inner dimension of the same outputs
+// (splits == 4), exchange their partial sums through LDS, add them in slice order (the order of
+// k_mvm_epilogue: same bits) and apply the analog epilogue themselves, a quarter of the tile rows
+// each: no partial sums in memory, no second launch.
+struct MvmTail {
+    const float* alpha;
+    const float* norm;
+    IoArgs io;
+    uint32_t k0, k1, t, tag;
+    float* y;
+    float* pre;
+};
+
+template <int MT, bool TRANS, bool FUSED>
 __global__ void __launch_bounds__(256)
 k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, int B, int N, int K, int ldw,
-                 int splits, float inp_res, float* __restrict__ part)
+                 int splits, float inp_res, float* __restrict__ part, MvmTail tail)
 {
+    extern __shared__ float mvm_exchange[];                        // FUSED: [4 slices][MT tiles][4 registers][64 lanes]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int nslab = N >> 4, mchunks = (B + 16 * MT - 1) / (16 * MT);
-    const int unit = (int)blockIdx.x * 4 + wave;
-    if (unit >= nslab * mchunks * splits) return;                  // wave-uniform; the kernel has no barriers
+    // FUSED: one workgroup per (outputs, vectors), wave = slice; else one wave per (outputs, vectors, slice)
+    const int unit = FUSED ? wave * (nslab * mchunks) + (int)blockIdx.x : (int)blockIdx.x * 4 + wave;
+    if (FUSED) {
+        if ((int)blockIdx.x >= nslab * mchunks) return;            // uniform over the workgroup: its barrier stays safe
+    } else {
+        if (unit >= nslab * mchunks * splits) return;              // wave-uniform; no barriers on this path
+    }
     const int z = unit / (nslab * mchunks), rem = unit - z * (nslab * mchunks);
     const int mc = rem / nslab, slab = rem - mc * nslab;
     const int steps = K >> 5, per = (steps + splits - 1) / splits;
@@ -509,14 +528,43 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
         }
     }
     // partial sums, in units of the input grid; lane = output, register r = row 4 g + r of the tile
-    float* pz = part + (size_t)z * B * N + (size_t)(slab * 16 + j);
+    if (FUSED) {
+        float* mine = mvm_exchange + (size_t)wave * (MT * 256) + lane;
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
+        for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = (mc * MT + m) * 16 + 4 * g + r;
-            if (row < B) pz[(size_t)row * N] = acc[m][r] * inp_res;
+            for (int r = 0; r < 4; ++r) mine[(m * 4 + r) * 64] = acc[m][r] * inp_res;
+        __syncthreads();
+        const int n = slab * 16 + j;
+        const bool noisy = (tail.io.w_noise > 0.0f) || (tail.io.out_noise > 0.0f);
+        constexpr int kPerWave = (MT + 3) / 4;                     // tile rows this wave finishes
+#pragma unroll
+        for (int i = 0; i < kPerWave; ++i) {
+            const int m = wave * kPerWave + i;
+            if (m >= MT) break;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = (mc * MT + m) * 16 + 4 * g + r;
+                if (row >= B) continue;
+                float zsum = 0.0f;
+#pragma unroll
+                for (int sl = 0; sl < 4; ++sl) zsum += mvm_exchange[(size_t)sl * (MT * 256) + (m * 4 + r) * 64 + lane];
+                float gq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (noisy) gauss4_fast(tail.k0, tail.k1, (uint32_t)n >> 1, (uint32_t)row, tail.t, tail.tag, gq);
+                mvm_finish(zsum, (n & 1) ? gq[2] : gq[0], (n & 1) ? gq[3] : gq[1], noisy, tail.io, tail.norm[row],
+                           tail.alpha[row], (size_t)row * N + n, tail.y, tail.pre);
+            }
         }
+    } else {
+        float* pz = part + (size_t)z * B * N + (size_t)(slab * 16 + j);
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = (mc * MT + m) * 16 + 4 * g + r;
+                if (row < B) pz[(size_t)row * N] = acc[m][r] * inp_res;
+            }
+    }
 }
 
 // Second pass of a K-split product: one thread per pair of neighbouring outputs (they share one

@@ -135,6 +135,16 @@ def test_quantised_product_every_split_and_both_paths_agree(B, splits, transpose
     monkeypatch.setenv("AHT_MVM_SPLITS", str(splits))
     _check(tile, W, x, QUANT_EXACT, transposed, step=1)
     y_codes = fn(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
+    if splits == 4 and not transposed:            # four slices are added up and finished inside the kernel:
+        monkeypatch.setenv("AHT_MVM_FUSED", "0")  # the same bits as partial sums and a second kernel
+        y_two = fn(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
+        assert (y_two == y_codes).all()
+        tile.mvm_steps = (3, 3)
+        y_two = fn(to_dev(x), aht.IOParams(**QUANT)).cpu().numpy()
+        monkeypatch.setenv("AHT_MVM_FUSED", "1")
+        tile.mvm_steps = (3, 3)
+        y_one = fn(to_dev(x), aht.IOParams(**QUANT)).cpu().numpy()
+        assert (y_two == y_one).all()
     monkeypatch.setenv("AHT_MVM_CODES", "0")
     y_fp32 = fn(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
     scale = max(1.0, float(np.abs(y_fp32).max()))

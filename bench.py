@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# ---- roofline model of the cell-update kernel (derivation in DESIGN.md, "Roofline") ---------
+# ---- roofline model of the cell-update kernel ------------------------------------------------
 # The kernel is bound by plain vector-ALU issue.  Peak = one lane-op per lane and clock:
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz (the rate of v_fma_f32, i.e. half the 157.3 TFLOP/s
 # packed-fp32 figure).  Algorithmic work = the minimal ISA instruction stream of the method,
@@ -228,7 +228,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the pulsed update of one tile runs on a single MI355X "
-              "(see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+              "(it would shard by blocks of rows of the tile, not by batch); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -97,7 +97,9 @@ k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k
             o[e] = xh;
             if (4 * g + e < K) part += (double)xh * (double)xh;
         }
-        if (vec) {
+        if (codes) {
+            // the product reads the codes: the fp32 values are not stored
+        } else if (vec) {
             *(float4*)(qr + 4 * (size_t)g) = make_float4(o[0], o[1], o[2], o[3]);
         } else {
 #pragma unroll

@@ -405,9 +405,9 @@ k_mvm_gemm(const float* __restrict__ A, const float* __restrict__ Wm, int M, int
 // w = hi + mid + lo up to the last bit of its fp32 value), so that Z = res * (C hi^T + C mid^T +
 // C lo^T) takes three passes of the bf16 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 sums) in
 // place of one pass of the fp32 ones at an eighth of their rate.  A wave owns 16 outputs x MT * 16
-// input vectors x one slice of the inner dimension: it reads its weights once, straight into the
-// operand layout (lane = output and one of four groups of 8 inner indices: the four lanes of an
-// output read one whole 128-byte line per step), no LDS, no barrier, and writes its partial sums
+// input vectors x one slice of the inner dimension: it reads its weights once, row-contiguous (eight
+// lanes per 128-byte line), turns them into the operand layout (lane = output and one of four groups
+// of 8 inner indices) through a little LDS of its own, needs no barrier, and writes its partial sums
 // for k_mvm_epilogue.  Needs K % 32 == 0, N % 16 == 0, 16-byte aligned rows.  TRANS: the transposed
 // product (the weights of an output are a column: eight 4-byte loads per lane and step).
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -451,6 +451,12 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
     // column n, inner index k is row k (the lanes of 16 neighbouring outputs read 64 bytes of a row)
     const float* wp = TRANS ? W + (size_t)(8 * g) * ldw + (size_t)(slab * 16 + j)
                             : W + (size_t)(slab * 16 + j) * ldw + 8 * g;
+    // forward: the weights are loaded row-contiguous (lane = row lane / 8 (+ 8), 16-byte piece lane % 8)
+    // and turned into the operand layout through 2.25 KB of LDS of the wave's own (rows 144 bytes apart)
+    const float* wco = W + (size_t)(slab * 16 + (lane >> 3)) * ldw + 4 * (lane & 7);
+    __shared__ float wturn[4][16 * 36];
+    float* wt_st = &wturn[wave][(lane >> 3) * 36 + 4 * (lane & 7)];
+    const float* wt_ld = &wturn[wave][j * 36 + 8 * g];
     // codes: one contiguous 1 KB block per (16 vectors, 32 inputs); blocks past the batch hold zeros
     const uint16_t* ap[MT];
 #pragma unroll
@@ -478,9 +484,11 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
             q[0] = make_float4(e[0], e[1], e[2], e[3]);
             q[1] = make_float4(e[4], e[5], e[6], e[7]);
         } else {
+            // row-contiguous: eight lanes read the 128 bytes of one row and step, two loads cover the 16 rows
             typedef float f4_t __attribute__((ext_vector_type(4)));
-            const float* wr = wp + 32 * (size_t)s;
-            const f4_t u0 = __builtin_nontemporal_load((const f4_t*)wr), u1 = __builtin_nontemporal_load((const f4_t*)(wr + 4));
+            const float* wr = wco + 32 * (size_t)s;
+            const f4_t u0 = __builtin_nontemporal_load((const f4_t*)wr),
+                       u1 = __builtin_nontemporal_load((const f4_t*)(wr + 8 * (size_t)ldw));
             q[0] = make_float4(u0.x, u0.y, u0.z, u0.w);
             q[1] = make_float4(u1.x, u1.y, u1.z, u1.w);
         }
@@ -498,8 +506,16 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
             const int sd = s + d;
             if (sd >= s1) break;
             // three bf16 terms of the eight weights, packed two to a register
-            const float wv[8] = {wq[d][0].x, wq[d][0].y, wq[d][0].z, wq[d][0].w,
-                                 wq[d][1].x, wq[d][1].y, wq[d][1].z, wq[d][1].w};
+            float4 o0 = wq[d][0], o1 = wq[d][1];
+            if (!TRANS) {
+                *(float4*)wt_st = wq[d][0];
+                *(float4*)(wt_st + 8 * 36) = wq[d][1];
+                __builtin_amdgcn_wave_barrier();
+                o0 = *(const float4*)wt_ld;
+                o1 = *(const float4*)(wt_ld + 4);
+                __builtin_amdgcn_wave_barrier();
+            }
+            const float wv[8] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w};
             uint32_t hb[8], mb[8], lb[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {

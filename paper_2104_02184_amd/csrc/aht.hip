@@ -578,6 +578,7 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
         t->mvm_codes = nullptr; t->mvm_codes_elems = 0;
         AHT_HIP(hipMalloc((void**)&t->mvm_codes, cneed * sizeof(uint16_t)));
         AHT_HIP(hipMemset(t->mvm_codes, 0, cneed * sizeof(uint16_t)));
+        AHT_HIP(hipDeviceSynchronize());          // (the caller's stream may not wait for the null stream)
         t->mvm_codes_elems = cneed;
     }
     hipLaunchKernelGGL(k_mvm_prepare, dim3((unsigned)B), dim3(1024), 0, s, x, K, vec_in, a, k0, k1, step, tag_in,

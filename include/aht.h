@@ -239,7 +239,9 @@ aht_status aht_transfer_column(aht_tile* src, aht_tile* dst, int32_t col, float 
  *   set to device 0's count + 1.  B = 0 and lr = 0 as for aht_pulsed_update.
  * aht_unit_cell_weights: w_out[rows][cols] = sum_k gamma_k w^(k), added in device order in fp32.
  * aht_unit_cell_forward / _backward: aht_forward / aht_backward on that effective weight (it is
- *   formed in scratch owned by device 0, whose call counters and seed serve the product).
+ *   formed in scratch owned by device 0, whose call counters and seed serve the product; a call on
+ *   the same stream with the same devices and factors, none of them written since the last product,
+ *   multiplies the matrix formed then instead of forming it again).
  * Errors: INVALID_ARG (null, n out of range, a tile twice, mismatched devices, which out of range,
  * non-finite gamma or lr), OOM, DEVICE. */
 aht_status aht_unit_cell_update(aht_tile* const* devices, int32_t n, int32_t which, const float* x_dev,

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -56,7 +57,17 @@ struct aht_tile {
     float* mvm_part = nullptr;    // partial sums of a K-split product [splits][B][N]
     uint16_t* mvm_codes = nullptr;   // DAC integers of the quantised inputs as bf16 [B][K]
     size_t mvm_codes_elems = 0;
-    float* ucell_w = nullptr;     // effective weights of the unit cell this tile leads [rows][cols]
+    // Effective weights of the unit cell this tile leads [rows][cols], and what they were formed from:
+    // the devices, their weight versions, the factors and the stream.  A product on the same stream with
+    // all of these unchanged multiplies the stored matrix again instead of re-forming it.
+    float* ucell_w = nullptr;
+    int ucell_n = 0;
+    const aht_tile* ucell_dev[8] = {};
+    uint64_t ucell_ver[8] = {};
+    float ucell_gamma[8] = {};
+    hipStream_t ucell_stream = nullptr;
+    // Changes with every write to W (any tile's new value is one no tile has had before).
+    uint64_t w_version = 0;
     size_t mvm_part_floats = 0;
     int mvm_b_cap = 0;
     uint32_t fwd_step = 0, bwd_step = 0;
@@ -76,6 +87,9 @@ struct aht_tile {
 namespace {
 
 thread_local std::string g_last_error;
+
+std::atomic<uint64_t> g_w_versions{0};
+inline void weights_written(aht_tile* t) { t->w_version = ++g_w_versions; }
 
 aht_status fail(aht_status s, const char* fmt, ...)
 {
@@ -280,6 +294,7 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     while (qwords > 5 && (size_t)4 * rpl * 64 * qwords * 4 + lds_extra > 160 * 1024) --qwords;   // LDS of one CU
     CellPtrs p{};
     p.W = t->W;
+    weights_written(t);
     p.dw_up = t->planes[AHT_PLANE_DW_UP];
     p.dw_down = t->planes[AHT_PLANE_DW_DOWN];
     p.b_max = t->planes[AHT_PLANE_B_MAX];
@@ -379,6 +394,7 @@ aht_status aht_tile_create(aht_tile** out, int32_t rows, int32_t cols, const aht
     if ((e = hipMalloc((void**)&t->pulse_count, sizeof(unsigned long long))) != hipSuccess)
         return cleanup(hip_fail(e, "hipMalloc(counter)"));
     if ((e = hipMemset(t->W, 0, n * sizeof(float))) != hipSuccess) return cleanup(hip_fail(e, "hipMemset"));
+    weights_written(t);
     if ((e = hipMemset(t->pulse_count, 0, sizeof(unsigned long long))) != hipSuccess)
         return cleanup(hip_fail(e, "hipMemset"));
     if (n >= kAdaptMinCells) {                    // without the pinned word the static choice stays
@@ -433,6 +449,7 @@ aht_status aht_set_weights(aht_tile* t, const float* w_dev, void* stream)
     if (!t || !w_dev) return fail(AHT_ERR_INVALID_ARG, "null argument");
     aht_status st = check_device(t);
     if (st != AHT_OK) return st;
+    weights_written(t);
     AHT_HIP(hipMemcpyAsync(t->W, w_dev, (size_t)t->rows * t->cols * sizeof(float), hipMemcpyDeviceToDevice,
                            (hipStream_t)stream));
     return AHT_OK;
@@ -819,7 +836,21 @@ static aht_status unit_cell_mvm(aht_tile* const* dev, const float* gamma, int32_
     aht_tile* lead = dev[0];
     if (!lead->ucell_w)
         AHT_HIP(hipMalloc((void**)&lead->ucell_w, sizeof(float) * (size_t)lead->rows * lead->cols));
-    if ((st = unit_cell_weights(dev, gamma, n, lead->ucell_w, (hipStream_t)stream)) != AHT_OK) return st;
+    bool same = lead->ucell_n == n && lead->ucell_stream == (hipStream_t)stream;
+    for (int k = 0; same && k < n; ++k)
+        same = lead->ucell_dev[k] == dev[k] && lead->ucell_ver[k] == dev[k]->w_version &&
+               std::memcmp(&lead->ucell_gamma[k], &gamma[k], sizeof(float)) == 0;
+    if (!same) {
+        lead->ucell_n = 0;
+        if ((st = unit_cell_weights(dev, gamma, n, lead->ucell_w, (hipStream_t)stream)) != AHT_OK) return st;
+        for (int k = 0; k < n; ++k) {
+            lead->ucell_dev[k] = dev[k];
+            lead->ucell_ver[k] = dev[k]->w_version;
+            lead->ucell_gamma[k] = gamma[k];
+        }
+        lead->ucell_stream = (hipStream_t)stream;
+        lead->ucell_n = n;
+    }
     return analog_mvm(lead, io, x_dev, y_dev, pre_dev, B, transposed, (hipStream_t)stream, lead->ucell_w);
 }
 
@@ -882,6 +913,7 @@ aht_status aht_decay_diffuse(aht_tile* t, void* stream)
     aht_status st = check_device(t);
     if (st != AHT_OK) return st;
     const size_t n = (size_t)t->rows * t->cols;
+    weights_written(t);
     hipLaunchKernelGGL(k_decay_diffuse, dim3(blocks_for((n + 3) / 4)), dim3(256), 0, (hipStream_t)stream, t->W,
                        t->tplanes[0], t->tplanes[1], t->planes[AHT_PLANE_B_MAX], t->planes[AHT_PLANE_B_MIN], n,
                        (uint32_t)t->seed, (uint32_t)(t->seed >> 32), t->tstep, t->temporal.diffusion > 0.0f ? 1 : 0);
@@ -899,6 +931,7 @@ aht_status aht_reset_columns(aht_tile* t, int32_t c0, int32_t ncols, void* strea
     if (st != AHT_OK) return st;
     if (c0 >= t->cols || ncols == 0) return AHT_OK;
     if (ncols > t->cols - c0) ncols = t->cols - c0;
+    weights_written(t);
     hipLaunchKernelGGL(k_reset_columns, dim3(blocks_for((size_t)t->rows * ncols)), dim3(256), 0, (hipStream_t)stream, t->W,
                        t->tplanes[2], t->temporal.reset_std, t->planes[AHT_PLANE_B_MAX], t->planes[AHT_PLANE_B_MIN],
                        t->rows, t->cols, c0, ncols, (uint32_t)t->seed, (uint32_t)(t->seed >> 32), t->tstep);

@@ -7,7 +7,7 @@ import oracle
 import paper_2104_02184_amd as aht
 
 from common import gpu_params, oracle_params, to_dev
-from test_gpu_mvm import NOISY
+from test_gpu_mvm import IDEAL, NOISY
 
 pytestmark = pytest.mark.gpu
 
@@ -65,6 +65,68 @@ def test_unit_cell_updates_weights_and_products_match_the_oracle(R, C, B, bl, um
     assert (diff <= step_out * (1 + 1e-5) + 1e-9).all() and (diff <= 1e-6 * np.maximum(1, np.abs(ybo))).mean() > 0.99
     assert tiles[0].mvm_steps == (1, 1)
     for t_ in tiles:
+        t_.close()
+
+
+def test_unit_cell_product_follows_every_change_of_its_devices():
+    """The product of a unit cell uses the devices' weights as they are at the call: between two
+    products a device is updated, overwritten, decayed, reset, the factors change, another tile takes
+    a device's place; a product with nothing changed in between gives the same result again."""
+    R, C, bl = 48, 128, 31
+    g = np.random.default_rng(5)
+    seeds = [31, 32, 33]
+    tiles = [aht.Tile(R, C, gpu_params(dv), bl, True, s) for dv, s in zip(DEVS, seeds)]
+    spare = aht.Tile(R, C, gpu_params(DEVS[2]), bl, True, 34)
+    for t_ in tiles + [spare]:
+        t_.set_weights(to_dev(g.uniform(-0.3, 0.3, size=(R, C)).astype(np.float32)))
+    tiles[1].set_temporal(decay_rate=0.1, reset=0.05, reset_std=0.02)
+    cell = aht.UnitCell(tiles, [1.0, 0.5, -0.25])
+    io_g, io_o = aht.IOParams(**IDEAL), oracle.IOParams(**IDEAL)
+    xin = g.normal(size=(8, C)).astype(np.float32)
+    din = g.normal(size=(8, R)).astype(np.float32)
+    calls = [0, 0]
+
+    def check(what):
+        eff = oracle.unit_cell_weights([t_.get_weights().cpu().numpy() for t_ in cell.devices], cell.gamma)
+        for transposed, inp in ((False, xin), (True, din)):
+            y = (cell.backward if transposed else cell.forward)(to_dev(inp), io_g).cpu().numpy()
+            yo = oracle.analog_mvm(eff, inp, io_o, seeds[0], calls[transposed], transposed=transposed)
+            calls[transposed] += 1
+            assert np.abs(y - yo).max() <= 1e-5 * np.abs(yo).max(), (what, transposed)
+        return eff
+
+    e0 = check("first")
+    assert (check("nothing changed") == e0).all()
+    x = g.normal(size=(16, C)).astype(np.float32)
+    d = g.normal(size=(16, R)).astype(np.float32)
+    cell.pulsed_update(to_dev(x), to_dev(d), 0.1, 1)
+    e1 = check("one device updated through the cell")
+    assert (e1 != e0).any()
+    tiles[2].pulsed_update(to_dev(x), to_dev(d), 0.1)
+    e2 = check("a device updated on its own")
+    assert (e2 != e1).any()
+    tiles[0].set_weights(to_dev(g.uniform(-0.3, 0.3, size=(R, C)).astype(np.float32)))
+    e3 = check("weights of the leading device overwritten")
+    assert (e3 != e2).any()
+    tiles[1].decay_diffuse()
+    e4 = check("a device decayed")
+    assert (e4 != e3).any()
+    tiles[1].reset_columns(3, 2)
+    e5 = check("columns of a device reset")
+    assert (e5 != e4).any()
+    cell.gamma = [1.0, 0.5, 0.75]
+    e6 = check("factors changed")
+    assert (e6 != e5).any()
+    src = aht.Tile(R, C, gpu_params(DEVS[0]), bl, True, 35)
+    src.set_weights(to_dev(g.uniform(-0.3, 0.3, size=(R, C)).astype(np.float32)))
+    src.transfer_column_to(tiles[2], 7, 0.5, io_g)
+    e7 = check("a device received a transferred column")
+    assert (e7 != e6).any()
+    cell.devices[2] = spare
+    e8 = check("another tile in a device's place")
+    assert (e8 != e7).any()
+    assert (check("nothing changed again") == e8).all()
+    for t_ in tiles + [spare, src]:
         t_.close()
 
 

@@ -604,20 +604,25 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
         int mt = B > 128 ? 16 : B > 64 ? 8 : B > 32 ? 4 : 2;    // 16-vector tiles per wave
         if (const int e = env_int("AHT_MVM_MT", 0)) mt = (e == 16 || e == 8 || e == 4 || e == 2) ? e : mt;
         const int mchunks = (B + 16 * mt - 1) / (16 * mt), nslab = N / 16, steps = K / 32;
+        // From 65 vectors on (and whole groups of 64 outputs) the four waves of a workgroup share the
+        // codes of their vectors through LDS and write partial sums (measured at 4096 x 4096: 47 against
+        // 54 us per call at 256 vectors, 72 against 92 at 512; no gain below).
+        const bool shared = mt >= 8 && N % 64 == 0 && env_int("AHT_MVM_SHARED", 1) != 0;
         int splits = env_int("AHT_MVM_SPLITS", 0);
         if (splits <= 0) {
             const long units = (long)mchunks * nslab;
             splits = (int)((1024 + units - 1) / units);                 // one wave per SIMD (measured optimum)
+            if (shared && units >= 1024 && units < 2048) splits = 2;    // ... two, where the sharing kernel has room for them
             if (splits > steps / 4) splits = steps / 4;
-            if (splits >= 3 && splits <= 6) splits = 4;                 // four slices can be finished in the kernel
+            if (!shared && splits >= 3 && splits <= 6) splits = 4;      // four slices can be finished in the kernel
         }
         if (splits > 16) splits = 16;
         if (splits < 1) splits = 1;
-        // Four slices: the four waves of a workgroup take one each and finish the product themselves.
-        // Not for the transposed product: there two neighbouring groups of 16 outputs share every
-        // 128-byte line of the weights, and they share it best as waves of one workgroup (measured:
-        // 64 us per call with partial sums, 68 us fused).
-        const bool fused = splits == 4 && !transposed && env_int("AHT_MVM_FUSED", 1) != 0;
+        // Otherwise, with four slices, the four waves of a workgroup take one each and finish the
+        // product themselves.  Not for the transposed product: there two neighbouring groups of 16
+        // outputs share every 128-byte line of the weights, and they share it best as waves of one
+        // workgroup (measured: 64 us per call with partial sums, 68 us fused).
+        const bool fused = !shared && splits == 4 && !transposed && env_int("AHT_MVM_FUSED", 1) != 0;
         if (!fused) {
             const size_t pneed = (size_t)splits * (size_t)B * (size_t)N;
             if (pneed > t->mvm_part_floats) {
@@ -626,6 +631,28 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
                 AHT_HIP(hipMalloc((void**)&t->mvm_part, pneed * sizeof(float)));
                 t->mvm_part_floats = pneed;
             }
+        }
+        if (shared) {
+            const dim3 sgrid((unsigned)mchunks * (unsigned)(N / 64) * (unsigned)splits);
+#define AHT_SHARED_LAUNCH(MTV, TR)                                                                                \
+    hipLaunchKernelGGL((k_mvm_gemm_codes_shared<MTV, TR>), sgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K,   \
+                       t->cols, splits, io->inp_res, t->mvm_part)
+#define AHT_SHARED_PICK(TR)                                                                                       \
+    switch (mt) {                                                                                                \
+        case 16: AHT_SHARED_LAUNCH(16, TR); break;                                                               \
+        case 8: AHT_SHARED_LAUNCH(8, TR); break;                                                                 \
+        default: AHT_SHARED_LAUNCH(4, TR); break;                                                                \
+    }
+            if (transposed) { AHT_SHARED_PICK(true) } else { AHT_SHARED_PICK(false) }
+#undef AHT_SHARED_PICK
+#undef AHT_SHARED_LAUNCH
+            AHT_HIP(hipGetLastError());
+            const size_t pairs = (size_t)B * (size_t)((N + 1) / 2);
+            hipLaunchKernelGGL(k_mvm_epilogue, dim3(blocks_for(pairs)), dim3(256), 0, s, t->mvm_part, splits, B, N,
+                               t->mvm_alpha, t->mvm_norm, a, k0, k1, step, tag_out, y, pre);
+            AHT_HIP(hipGetLastError());
+            if (transposed) t->bwd_step += 1; else t->fwd_step += 1;
+            return AHT_OK;
         }
         const unsigned waves = (unsigned)mchunks * (unsigned)nslab * (unsigned)splits;
         const dim3 cgrid(fused ? (unsigned)mchunks * (unsigned)nslab : (waves + 3u) / 4u);

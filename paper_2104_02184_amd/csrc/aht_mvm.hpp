@@ -413,6 +413,31 @@ k_mvm_gemm(const float* __restrict__ A, const float* __restrict__ Wm, int M, int
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
+// Eight fp32 weights (o0, o1) as three bf16 terms each, packed two to a register in the order of
+// the matrix instruction's B operand: w = hi + mid + lo to the last bit (both subtractions are exact).
+__device__ __forceinline__ void split_bf16x3(const float4& o0, const float4& o1, bf16x8_t& bh, bf16x8_t& bm, bf16x8_t& bl)
+{
+    const float wv[8] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w};
+    uint32_t hb[8], mb[8], lb[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        hb[e] = __float_as_uint(wv[e]) & 0xFFFF0000u;
+        const float r1 = wv[e] - __uint_as_float(hb[e]);        // exact
+        mb[e] = __float_as_uint(r1) & 0xFFFF0000u;
+        const float r2 = r1 - __uint_as_float(mb[e]);           // exact
+        lb[e] = __float_as_uint(r2);
+    }
+    auto pack = [](uint32_t even, uint32_t odd) __attribute__((always_inline)) {
+        return __builtin_amdgcn_perm(odd, even, 0x07060302u);   // high halves: even element low, odd element high
+    };
+    const uint4 ph = make_uint4(pack(hb[0], hb[1]), pack(hb[2], hb[3]), pack(hb[4], hb[5]), pack(hb[6], hb[7]));
+    const uint4 pm = make_uint4(pack(mb[0], mb[1]), pack(mb[2], mb[3]), pack(mb[4], mb[5]), pack(mb[6], mb[7]));
+    const uint4 pl = make_uint4(pack(lb[0], lb[1]), pack(lb[2], lb[3]), pack(lb[4], lb[5]), pack(lb[6], lb[7]));
+    bh = __builtin_bit_cast(bf16x8_t, ph);
+    bm = __builtin_bit_cast(bf16x8_t, pm);
+    bl = __builtin_bit_cast(bf16x8_t, pl);
+}
+
 // FUSED: the four waves of a workgroup take four slices of the inner dimension of the same outputs
 // (splits == 4), exchange their partial sums through LDS, add them in slice order (the order of
 // k_mvm_epilogue: same bits) and apply the analog epilogue themselves, a quarter of the tile rows
@@ -500,51 +525,42 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
 #pragma unroll
         for (int d = 0; d < DW; ++d) fetch(s0 + d < last ? s0 + d : last, wq[d], av[d]);
     }
-    for (int s = s0; s < s1; s += DW) {
-#pragma unroll
-        for (int d = 0; d < DW; ++d) {
-            const int sd = s + d;
-            if (sd >= s1) break;
-            // three bf16 terms of the eight weights, packed two to a register
-            float4 o0 = wq[d][0], o1 = wq[d][1];
-            if (!TRANS) {
-                *(float4*)wt_st = wq[d][0];
-                *(float4*)(wt_st + 8 * 36) = wq[d][1];
-                __builtin_amdgcn_wave_barrier();
-                o0 = *(const float4*)wt_ld;
-                o1 = *(const float4*)(wt_ld + 4);
-                __builtin_amdgcn_wave_barrier();
-            }
-            const float wv[8] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w};
-            uint32_t hb[8], mb[8], lb[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                hb[e] = __float_as_uint(wv[e]) & 0xFFFF0000u;
-                const float r1 = wv[e] - __uint_as_float(hb[e]);        // exact
-                mb[e] = __float_as_uint(r1) & 0xFFFF0000u;
-                const float r2 = r1 - __uint_as_float(mb[e]);           // exact
-                lb[e] = __float_as_uint(r2);
-            }
-            auto pack = [](uint32_t even, uint32_t odd) __attribute__((always_inline)) {
-                return __builtin_amdgcn_perm(odd, even, 0x07060302u);   // high halves: even element low, odd element high
-            };
-            const uint4 ph = make_uint4(pack(hb[0], hb[1]), pack(hb[2], hb[3]), pack(hb[4], hb[5]), pack(hb[6], hb[7]));
-            const uint4 pm = make_uint4(pack(mb[0], mb[1]), pack(mb[2], mb[3]), pack(mb[4], mb[5]), pack(mb[6], mb[7]));
-            const uint4 pl = make_uint4(pack(lb[0], lb[1]), pack(lb[2], lb[3]), pack(lb[4], lb[5]), pack(lb[6], lb[7]));
-            const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, ph), bm = __builtin_bit_cast(bf16x8_t, pm),
-                           bl = __builtin_bit_cast(bf16x8_t, pl);
-            bf16x8_t a[MT];
-#pragma unroll
-            for (int m = 0; m < MT; ++m) a[m] = __builtin_bit_cast(bf16x8_t, av[d][m]);
-            fetch(sd + DW < last ? sd + DW : last, wq[d], av[d]);
-#pragma unroll
-            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bl, acc[m], 0, 0, 0);
-#pragma unroll
-            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bm, acc[m], 0, 0, 0);
-#pragma unroll
-            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bh, acc[m], 0, 0, 0);
+    // one step of the inner dimension from ring slot (q, v); then the slot is filled again for step `next`
+    auto step = [&](float4 (&q)[2], uint4 (&v)[MT], int next) __attribute__((always_inline)) {
+        // three bf16 terms of the eight weights, packed two to a register
+        float4 o0 = q[0], o1 = q[1];
+        if (!TRANS) {
+            *(float4*)wt_st = q[0];
+            *(float4*)(wt_st + 8 * 36) = q[1];
+            __builtin_amdgcn_wave_barrier();
+            o0 = *(const float4*)wt_ld;
+            o1 = *(const float4*)(wt_ld + 4);
+            __builtin_amdgcn_wave_barrier();
         }
+        bf16x8_t bh, bm, bl;
+        split_bf16x3(o0, o1, bh, bm, bl);
+        bf16x8_t a[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) a[m] = __builtin_bit_cast(bf16x8_t, v[m]);
+        fetch(next < last ? next : last, q, v);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bl, acc[m], 0, 0, 0);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bm, acc[m], 0, 0, 0);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bh, acc[m], 0, 0, 0);
+    };
+    // Whole turns of the ring in a loop with one way in and one way out (an exit from the middle of a
+    // turn would, for the compiler, lead back to the head of the loop, and the head would then wait for
+    // every load in flight); what is left of the slice, fewer than DW steps, after it.
+    int s = s0;
+    for (; s + DW <= s1; s += DW) {
+#pragma unroll
+        for (int d = 0; d < DW; ++d) step(wq[d], av[d], s + d + DW);
     }
+#pragma unroll
+    for (int d = 0; d < DW - 1; ++d)
+        if (s + d < s1) step(wq[d], av[d], last);                  // wave-uniform
     // partial sums, in units of the input grid; lane = output, register r = row 4 g + r of the tile
     if (FUSED) {
         float* mine = mvm_exchange + (size_t)wave * (MT * 256) + lane;
@@ -583,6 +599,126 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
                 if (row < B) pz[(size_t)row * N] = acc[m][r] * inp_res;
             }
     }
+}
+
+// The same product with the codes shared inside a workgroup: its four waves take four neighbouring
+// groups of 16 outputs of the SAME vectors and slice of the inner dimension, so that each 1 KB block of
+// codes is fetched once per workgroup (a quarter by each wave), passed through LDS (two stages, one
+// barrier per step) and read from there by all four.  Without this every wave fetches all the codes of
+// its slice itself: at 256 vectors eight times the bytes of its weights.  Needs N % 64 == 0 and
+// MT % 4 == 0; always writes partial sums for k_mvm_epilogue.
+template <int MT, bool TRANS>
+__global__ void __launch_bounds__(256, 2)
+k_mvm_gemm_codes_shared(const uint16_t* __restrict__ xc, const float* __restrict__ W, int B, int N, int K, int ldw,
+                        int splits, float inp_res, float* __restrict__ part)
+{
+    static_assert(MT % 4 == 0, "each wave fetches a quarter of the code blocks of a step");
+    constexpr int QT = MT / 4;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int ngroup = N >> 6, mchunks = (B + 16 * MT - 1) / (16 * MT);
+    const int unit = (int)blockIdx.x;
+    if (unit >= ngroup * mchunks * splits) return;                 // uniform over the workgroup
+    const int z = unit / (ngroup * mchunks), rem = unit - z * (ngroup * mchunks);
+    const int mc = rem / ngroup, slab = (rem - mc * ngroup) * 4 + wave;
+    const int steps = K >> 5, per = (steps + splits - 1) / splits;
+    const int s0 = z * per, s1 = (s0 + per < steps) ? s0 + per : steps;    // the same for the four waves
+    const int j = lane & 15, g = lane >> 4;
+    const float* wp = TRANS ? W + (size_t)(8 * g) * ldw + (size_t)(slab * 16 + j)
+                            : W + (size_t)(slab * 16 + j) * ldw + 8 * g;
+    const float* wco = W + (size_t)(slab * 16 + (lane >> 3)) * ldw + 4 * (lane & 7);
+    __shared__ float wturn[4][16 * 36];
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    __shared__ u32x4_t cstage[2][MT][64];
+    float* wt_st = &wturn[wave][(lane >> 3) * 36 + 4 * (lane & 7)];
+    const float* wt_ld = &wturn[wave][j * 36 + 8 * g];
+    const uint16_t* ap[QT];                                        // this wave's blocks: tiles wave, wave + 4, ...
+#pragma unroll
+    for (int i = 0; i < QT; ++i)
+        ap[i] = xc + ((size_t)(mc * MT + 4 * i + wave) * (size_t)steps * 64 + (size_t)lane) * 8;
+    floatx4_t acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[m][r] = 0.0f;
+
+    constexpr int DW = 4;
+    float4 wq[DW][2];
+    uint4 av[DW][QT];
+    auto fetch = [&](int s, float4 (&q)[2], uint4 (&v)[QT]) __attribute__((always_inline)) {
+        if (TRANS) {
+            const float* wr = wp + (size_t)(32 * s) * ldw;
+            float e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) e[i] = __builtin_nontemporal_load(wr + (size_t)i * ldw);
+            q[0] = make_float4(e[0], e[1], e[2], e[3]);
+            q[1] = make_float4(e[4], e[5], e[6], e[7]);
+        } else {
+            typedef float f4_t __attribute__((ext_vector_type(4)));
+            const float* wr = wco + 32 * (size_t)s;
+            const f4_t u0 = __builtin_nontemporal_load((const f4_t*)wr),
+                       u1 = __builtin_nontemporal_load((const f4_t*)(wr + 8 * (size_t)ldw));
+            q[0] = make_float4(u0.x, u0.y, u0.z, u0.w);
+            q[1] = make_float4(u1.x, u1.y, u1.z, u1.w);
+        }
+#pragma unroll
+        for (int i = 0; i < QT; ++i) v[i] = *(const uint4*)(ap[i] + 512 * (size_t)s);
+    };
+    const int last = s1 - 1;
+    if (s0 < s1) {
+#pragma unroll
+        for (int d = 0; d < DW; ++d) fetch(s0 + d < last ? s0 + d : last, wq[d], av[d]);
+    }
+    int buf = 0;
+    // one step of the inner dimension from ring slot (q, v); then the slot is filled again for step `next`
+    auto step = [&](float4 (&q)[2], uint4 (&v)[QT], int next) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < QT; ++i) cstage[buf][4 * i + wave][lane] = u32x4_t{v[i].x, v[i].y, v[i].z, v[i].w};
+        float4 o0 = q[0], o1 = q[1];
+        if (!TRANS) {
+            *(float4*)wt_st = q[0];
+            *(float4*)(wt_st + 8 * 36) = q[1];
+        }
+        // One barrier per step: a stage is written again two steps later, and by then every wave
+        // has passed the barrier of the step between, which it reaches after its reads of this one.
+        __syncthreads();
+        if (!TRANS) {
+            o0 = *(const float4*)wt_ld;
+            o1 = *(const float4*)(wt_ld + 4);
+        }
+        bf16x8_t a[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) a[m] = __builtin_bit_cast(bf16x8_t, cstage[buf][m][lane]);
+        buf ^= 1;
+        fetch(next < last ? next : last, q, v);
+        bf16x8_t bh, bm, bl;
+        split_bf16x3(o0, o1, bh, bm, bl);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bl, acc[m], 0, 0, 0);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bm, acc[m], 0, 0, 0);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bh, acc[m], 0, 0, 0);
+    };
+    // Whole turns of the ring in a loop with one way in and one way out (an exit from the middle of a
+    // turn would, for the compiler, lead back to the head of the loop, and the head would then wait for
+    // every load in flight); what is left of the slice, fewer than DW steps, after it.
+    int s = s0;
+    for (; s + DW <= s1; s += DW) {
+#pragma unroll
+        for (int d = 0; d < DW; ++d) step(wq[d], av[d], s + d + DW);
+    }
+#pragma unroll
+    for (int d = 0; d < DW - 1; ++d)
+        if (s + d < s1) step(wq[d], av[d], last);                  // uniform over the workgroup
+    float* pz = part + (size_t)z * B * N + (size_t)(slab * 16 + j);
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = (mc * MT + m) * 16 + 4 * g + r;
+            if (row < B) pz[(size_t)row * N] = acc[m][r] * inp_res;
+        }
 }
 
 // Second pass of a K-split product: one thread per pair of neighbouring outputs (they share one

@@ -169,6 +169,119 @@ __global__ void __launch_bounds__(256) k_mfma(uint32_t* out, uint32_t seed) {
         for (int r = 0; r < 16; ++r) s += acc[c][r];
     if (s == 12345.0f) out[0] = 1;
 }
+// bf16 matrix-core rate: v_mfma_f32_16x16x32_bf16 (16 384 flops per wave instruction) and
+// v_mfma_f32_32x32x16_bf16 (32 768), NCHAIN independent accumulators per wave.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+template <int NCHAIN>
+__global__ void __launch_bounds__(256) k_mfma_bf16_16(uint32_t* out, uint32_t seed) {
+    floatx4 acc[NCHAIN];
+    for (int c = 0; c < NCHAIN; ++c)
+        for (int r = 0; r < 4; ++r) acc[c][r] = (float)(threadIdx.x + c + r);
+    bf16x8 a, b;
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)((seed | 1) + e); b[e] = (__bf16)(1.0f / (float)((seed | 3) + e)); }
+    for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+        for (int c = 0; c < NCHAIN; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[c], 0, 0, 0);
+    }
+    float s = 0.0f;
+    for (int c = 0; c < NCHAIN; ++c)
+        for (int r = 0; r < 4; ++r) s += acc[c][r];
+    if (s == 12345.0f) out[0] = 1;
+}
+template <int NCHAIN>
+__global__ void __launch_bounds__(256) k_mfma_bf16_32(uint32_t* out, uint32_t seed) {
+    floatx16 acc[NCHAIN];
+    for (int c = 0; c < NCHAIN; ++c)
+        for (int r = 0; r < 16; ++r) acc[c][r] = (float)(threadIdx.x + c + r);
+    bf16x8 a, b;
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)((seed | 1) + e); b[e] = (__bf16)(1.0f / (float)((seed | 3) + e)); }
+    for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+        for (int c = 0; c < NCHAIN; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+    }
+    float s = 0.0f;
+    for (int c = 0; c < NCHAIN; ++c)
+        for (int r = 0; r < 16; ++r) s += acc[c][r];
+    if (s == 12345.0f) out[0] = 1;
+}
+// What a single wave overlaps with its matrix instructions: per iteration 16 independent
+// v_mfma_f32_16x16x32_bf16 (256 cycles of the matrix pipeline) and, interleaved with them,
+// MODE 1: 32 independent vector-ALU instructions; 2: 8 LDS reads of 16 bytes per lane;
+// 3: 4 global loads of 16 bytes per lane from a 64 KB buffer (cache resident); 0: nothing.
+template <int MODE>
+__global__ void __launch_bounds__(256) k_mfma_mix(uint32_t* out, uint32_t seed, const uint4* gbuf) {
+    __shared__ uint4 lbuf[1024];
+    for (int i = threadIdx.x; i < 1024; i += 256) lbuf[i] = make_uint4(i, seed, i, seed);
+    __syncthreads();
+    floatx4 acc[16];
+    for (int c = 0; c < 16; ++c)
+        for (int r = 0; r < 4; ++r) acc[c][r] = (float)(threadIdx.x + c + r);
+    bf16x8 a, b;
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)((seed | 1) + e); b[e] = (__bf16)(1.0f / (float)((seed | 3) + e)); }
+    uint32_t v[32];
+    for (int k = 0; k < 32; ++k) v[k] = threadIdx.x * 7 + k + seed;
+    uint4 ld[8];
+    for (int k = 0; k < 8; ++k) ld[k] = make_uint4(k, k, k, k);
+    const uint32_t lane = threadIdx.x;
+    for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[c], 0, 0, 0);
+            if (MODE == 1) {
+                asm volatile("v_and_b32 %0, %0, %2\nv_and_b32 %1, %1, %2" : "+v"(v[2 * c]), "+v"(v[2 * c + 1]) : "v"(seed | 0xFFFFFFF0u));
+            } else if (MODE == 2) {
+                if (c % 2 == 0) {
+                    const uint4 t = lbuf[(lane + 64 * (c / 2) + (uint32_t)i) & 1023];
+                    ld[c / 2].x ^= t.x; ld[c / 2].y ^= t.y; ld[c / 2].z ^= t.z; ld[c / 2].w ^= t.w;
+                }
+            } else if (MODE == 3) {
+                if (c % 4 == 0) {
+                    const uint4 t = gbuf[(lane + 256 * (c / 4) + 1024u * (blockIdx.x & 3u) + (uint32_t)i * 64u) & 4095u];
+                    ld[c / 4].x ^= t.x; ld[c / 4].y ^= t.y; ld[c / 4].z ^= t.z; ld[c / 4].w ^= t.w;
+                }
+            }
+        }
+    }
+    float s = 0.0f;
+    for (int c = 0; c < 16; ++c)
+        for (int r = 0; r < 4; ++r) s += acc[c][r];
+    uint32_t u = 0;
+    for (int k = 0; k < 32; ++k) u += v[k];
+    for (int k = 0; k < 8; ++k) u += ld[k].x + ld[k].y + ld[k].z + ld[k].w;
+    if (s == 12345.0f && u == 77u) out[0] = 1;
+}
+template <typename K> int run_mix(const char* name, K kern, int wg_per_cu, uint32_t* out, const uint4* gbuf) {
+    const int blocks = 256 * wg_per_cu, threads = 256;
+    hipEvent_t e0, e1; CHK(hipEventCreate(&e0)); CHK(hipEventCreate(&e1));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, out, 1u, gbuf);
+    CHK(hipDeviceSynchronize());
+    CHK(hipEventRecord(e0));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, out, 1u, gbuf);
+    CHK(hipEventRecord(e1)); CHK(hipEventSynchronize(e1));
+    float ms; CHK(hipEventElapsedTime(&ms, e0, e1));
+    // cycles of one SIMD per iteration of one wave, at 2.4 GHz, had the waves of a SIMD run one after the other
+    printf("%-34s %8.3f ms  %7.1f cycles per iteration and wave (matrix pipeline alone: 256)\n", name, ms,
+           ms * 1e-3 * 2.4e9 / ITERS / wg_per_cu);
+    fflush(stdout);
+    return 0;
+}
+
+template <typename K> int run_mfma_bf16(const char* name, K kern, int nchain, int wg_per_cu, double flops_per_instr, uint32_t* out) {
+    const int blocks = 256 * wg_per_cu, threads = 256;
+    hipEvent_t e0, e1; CHK(hipEventCreate(&e0)); CHK(hipEventCreate(&e1));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, out, 1u);
+    CHK(hipDeviceSynchronize());
+    CHK(hipEventRecord(e0));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, out, 1u);
+    CHK(hipEventRecord(e1)); CHK(hipEventSynchronize(e1));
+    float ms; CHK(hipEventElapsedTime(&ms, e0, e1));
+    const double flops = (double)blocks * (threads / 64) * ITERS * nchain * flops_per_instr;
+    printf("%-26s %8.3f ms  %8.2f TFLOP/s  (%.3f of 2500)\n", name, ms, flops / ms / 1e9, flops / ms / 1e9 / 2500.0);
+    fflush(stdout);
+    return 0;
+}
+
 template <typename K> int run_mfma(const char* name, K kern, int nchain, int wg_per_cu, uint32_t* out) {
     const int blocks = 256 * wg_per_cu, threads = 256;
     hipEvent_t e0, e1; CHK(hipEventCreate(&e0)); CHK(hipEventCreate(&e1));
@@ -219,6 +332,23 @@ int main() {
     run_mfma("mfma32x32x2 1ch 4wg/cu", k_mfma<1>, 1, 4, out);
     run_mfma("mfma32x32x2 2ch 2wg/cu", k_mfma<2>, 2, 2, out);
     run_mfma("mfma32x32x2 4ch 1wg/cu", k_mfma<4>, 4, 1, out);
+    run_mfma_bf16("mfma16x16x32bf16 1ch 1wg", k_mfma_bf16_16<1>, 1, 1, 16384.0, out);
+    run_mfma_bf16("mfma16x16x32bf16 4ch 1wg", k_mfma_bf16_16<4>, 4, 1, 16384.0, out);
+    run_mfma_bf16("mfma16x16x32bf16 16ch 1wg", k_mfma_bf16_16<16>, 16, 1, 16384.0, out);
+    run_mfma_bf16("mfma16x16x32bf16 4ch 2wg", k_mfma_bf16_16<4>, 4, 2, 16384.0, out);
+    run_mfma_bf16("mfma32x32x16bf16 1ch 1wg", k_mfma_bf16_32<1>, 1, 1, 32768.0, out);
+    run_mfma_bf16("mfma32x32x16bf16 4ch 1wg", k_mfma_bf16_32<4>, 4, 1, 32768.0, out);
+    run_mfma_bf16("mfma32x32x16bf16 4ch 2wg", k_mfma_bf16_32<4>, 4, 2, 32768.0, out);
+    {
+        uint4* gbuf; CHK(hipMalloc(&gbuf, 4096 * sizeof(uint4))); CHK(hipMemset(gbuf, 1, 4096 * sizeof(uint4)));
+        for (int wg = 1; wg <= 2; ++wg) {
+            run_mix(wg == 1 ? "16 mfma alone, 1 wave/SIMD" : "16 mfma alone, 2 waves/SIMD", k_mfma_mix<0>, wg, out, gbuf);
+            run_mix(wg == 1 ? "16 mfma + 32 valu, 1 wave/SIMD" : "16 mfma + 32 valu, 2 waves/SIMD", k_mfma_mix<1>, wg, out, gbuf);
+            run_mix(wg == 1 ? "16 mfma + 8 ds_read_b128, 1 wave" : "16 mfma + 8 ds_read_b128, 2 waves", k_mfma_mix<2>, wg, out, gbuf);
+            run_mix(wg == 1 ? "16 mfma + 4 global x4, 1 wave" : "16 mfma + 4 global x4, 2 waves", k_mfma_mix<3>, wg, out, gbuf);
+        }
+        CHK(hipFree(gbuf));
+    }
     // runs of eight 8-byte instructions after 2..5 s_nop from an 8-byte boundary: an even number
     // puts every instruction of the run on a multiple of 8, an odd number 4 bytes past one
     run("bitop3 +8", k_place_bitop3_2, 8, out); run("bitop3 +12", k_place_bitop3_3, 8, out);

@@ -122,11 +122,15 @@ def test_quantised_forward_product_matches(R, C, B, io_kw):
     tile.close()
 
 
-@pytest.mark.parametrize("splits", [1, 2, 5, 16])
+@pytest.mark.parametrize("splits", [1, 2, 4, 5, 16])
 @pytest.mark.parametrize("B", [7, 40, 100, 200])
 @pytest.mark.parametrize("transposed", [False, True])
-def test_quantised_product_every_split_and_both_paths_agree(B, splits, transposed, monkeypatch):
-    R, C = (512, 96) if transposed else (96, 512)
+@pytest.mark.parametrize("shape", [(96, 512), (128, 608)])
+def test_quantised_product_every_split_and_both_paths_agree(B, splits, transposed, shape, monkeypatch):
+    """(96, 512): 16 steps of the inner dimension, outputs not in whole groups of 64; (128, 608): 19
+    steps (slices that end inside a turn of the load ring, and empty ones), whole groups of 64
+    outputs, so that from 65 vectors on the kernel that shares the codes in LDS runs."""
+    R, C = shape[::-1] if transposed else shape
     K = R if transposed else C
     tile, W = _tile_with_weights(R, C)
     g = np.random.default_rng(B + splits)
@@ -145,6 +149,16 @@ def test_quantised_product_every_split_and_both_paths_agree(B, splits, transpose
         tile.mvm_steps = (3, 3)
         y_one = fn(to_dev(x), aht.IOParams(**QUANT)).cpu().numpy()
         assert (y_two == y_one).all()
+    # sharing the codes inside a workgroup changes no bit either
+    monkeypatch.setenv("AHT_MVM_SHARED", "0")
+    monkeypatch.setenv("AHT_MVM_FUSED", "0")
+    tile.mvm_steps = (5, 5)
+    y_plain = fn(to_dev(x), aht.IOParams(**QUANT)).cpu().numpy()
+    monkeypatch.setenv("AHT_MVM_SHARED", "1")
+    monkeypatch.setenv("AHT_MVM_FUSED", "1")
+    tile.mvm_steps = (5, 5)
+    y_shared = fn(to_dev(x), aht.IOParams(**QUANT)).cpu().numpy()
+    assert (y_plain == y_shared).all()
     monkeypatch.setenv("AHT_MVM_CODES", "0")
     y_fp32 = fn(to_dev(x), aht.IOParams(**QUANT_EXACT)).cpu().numpy()
     scale = max(1.0, float(np.abs(y_fp32).max()))

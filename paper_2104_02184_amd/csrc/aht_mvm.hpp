@@ -46,12 +46,17 @@ k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k
             for (int e = 0; e < 4; ++e) v[e] = (4 * g + e < K) ? xr[4 * (size_t)g + e] : 0.0f;
         }
     };
+    // up to 4096 inputs every thread has one group of four: read once, kept for both passes
+    const bool single = groups <= 1024;
+    float kept[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (single && tid < groups) load_group(tid, kept);
     float alpha = 1.0f;
     if (io.noise_management) {
         float m = 0.0f;
         for (int g = tid; g < groups; g += 1024) {
             float v[4];
-            load_group(g, v);
+            if (single) { v[0] = kept[0]; v[1] = kept[1]; v[2] = kept[2]; v[3] = kept[3]; }
+            else load_group(g, v);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float a = fabsf(v[e]);
@@ -71,7 +76,9 @@ k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k
         float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         if (io.inp_noise > 0.0f) gauss4_fast(k0, k1, (uint32_t)g, (uint32_t)b, t, tag, z);
         float v[4], o[4];
-        load_group(g, v);
+        uint32_t cbits[4] = {0u, 0u, 0u, 0u};
+        if (single) { v[0] = kept[0]; v[1] = kept[1]; v[2] = kept[2]; v[3] = kept[3]; }
+        else load_group(g, v);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             float u = v[e];
@@ -82,12 +89,9 @@ k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k
                 const float code = rintf(xh / io.inp_res);     // the DAC's integer, |code| <= bound / res
                 // as bf16 (exact up to 256) for the product on the bf16 matrix cores
                 // (operand layout of the matrix instruction: blocks of 16 vectors x 32 inputs, 64 lanes x 8 codes)
-                if (codes && 4 * g + e < K) {
-                    const int kk = 4 * g + e;
-                    const size_t block = (size_t)(b >> 4) * (size_t)(K >> 5) + (size_t)(kk >> 5);
-                    codes[(block * 64 + (size_t)(((kk >> 3) & 3) * 16 + (b & 15))) * 8 + (size_t)(kk & 7)] =
-                        (uint16_t)(__float_as_uint(code) >> 16);
-                }
+                // (the four codes of a group lie side by side there: one 8-byte store after the loop; the
+                // path needs K % 32 == 0, so a group is never ragged)
+                cbits[e] = __float_as_uint(code) >> 16;
                 xh = code * io.inp_res;
             }
             if (io.inp_noise > 0.0f) {
@@ -99,6 +103,10 @@ k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k
         }
         if (codes) {
             // the product reads the codes: the fp32 values are not stored
+            const int kk = 4 * g;
+            const size_t block = (size_t)(b >> 4) * (size_t)(K >> 5) + (size_t)(kk >> 5);
+            uint16_t* at = codes + (block * 64 + (size_t)(((kk >> 3) & 3) * 16 + (b & 15))) * 8 + (size_t)(kk & 7);
+            *(uint2*)at = make_uint2(cbits[0] | (cbits[1] << 16), cbits[2] | (cbits[3] << 16));
         } else if (vec) {
             *(float4*)(qr + 4 * (size_t)g) = make_float4(o[0], o[1], o[2], o[3]);
         } else {

@@ -604,25 +604,32 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
         int mt = B > 128 ? 16 : B > 64 ? 8 : B > 32 ? 4 : 2;    // 16-vector tiles per wave
         if (const int e = env_int("AHT_MVM_MT", 0)) mt = (e == 16 || e == 8 || e == 4 || e == 2) ? e : mt;
         const int mchunks = (B + 16 * mt - 1) / (16 * mt), nslab = N / 16, steps = K / 32;
-        // From 65 vectors on (and whole groups of 64 outputs) the four waves of a workgroup share the
-        // codes of their vectors through LDS and write partial sums (measured at 4096 x 4096: 47 against
-        // 54 us per call at 256 vectors, 72 against 92 at 512; no gain below).
-        const bool shared = mt >= 8 && N % 64 == 0 && env_int("AHT_MVM_SHARED", 1) != 0;
+        // Small products (up to 0.6 GFLOP: a 1024 x 1024 tile with 256 vectors) are bound by the chain of
+        // launches: a launch saved is 2.5 us of about 15, so they finish in the product kernel wherever
+        // they can.  Larger ones, from 65 vectors on (and whole groups of 64 outputs): the four waves of a
+        // workgroup share the codes of their vectors through LDS and write partial sums (measured at
+        // 4096 x 4096: 47 against 54 us per call at 256 vectors, 72 against 92 at 512; no gain below).
+        const bool small = 2.0 * (double)B * (double)N * (double)K <= 6e8;
+        const bool fuse_ok = env_int("AHT_MVM_FUSED", 1) != 0;
+        bool shared = mt >= 8 && N % 64 == 0 && env_int("AHT_MVM_SHARED", 1) != 0;
         int splits = env_int("AHT_MVM_SPLITS", 0);
         if (splits <= 0) {
             const long units = (long)mchunks * nslab;
             splits = (int)((1024 + units - 1) / units);                 // one wave per SIMD (measured optimum)
-            if (shared && units >= 1024 && units < 2048) splits = 2;    // ... two, where the sharing kernel has room for them
             if (splits > steps / 4) splits = steps / 4;
-            if (!shared && splits >= 3 && splits <= 6) splits = 4;      // four slices can be finished in the kernel
+            if (small && fuse_ok && splits >= 3 && splits <= 8) shared = false;     // four slices, finished in the kernel
+            if (shared && units >= 1024 && units < 2048 && steps >= 8) splits = 2;  // two waves per SIMD, where the sharing kernel has room
+            if (!shared && splits >= 3 && splits <= (small ? 8 : 6)) splits = 4;
+        } else if (small && fuse_ok && splits == 4) {
+            shared = false;
         }
         if (splits > 16) splits = 16;
         if (splits < 1) splits = 1;
-        // Otherwise, with four slices, the four waves of a workgroup take one each and finish the
-        // product themselves.  Not for the transposed product: there two neighbouring groups of 16
+        // With four slices the four waves of a workgroup take one each and finish the product
+        // themselves.  For large transposed products this loses: there two neighbouring groups of 16
         // outputs share every 128-byte line of the weights, and they share it best as waves of one
-        // workgroup (measured: 64 us per call with partial sums, 68 us fused).
-        const bool fused = !shared && splits == 4 && !transposed && env_int("AHT_MVM_FUSED", 1) != 0;
+        // workgroup (measured at 4096 x 4096: 64 us per call with partial sums, 68 us fused).
+        const bool fused = !shared && splits == 4 && (!transposed || small) && fuse_ok;
         if (!fused) {
             const size_t pneed = (size_t)splits * (size_t)B * (size_t)N;
             if (pneed > t->mvm_part_floats) {

@@ -13,10 +13,13 @@
  *   - every pointer named *_dev is a DEVICE pointer on the current HIP device; the caller
  *     owns x, d and every output buffer; the tile owns W, the device planes and scratch;
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); calls are
- *     asynchronous on it and never synchronise the host, except create/destroy;
+ *     asynchronous on it and do not synchronise the host, except create/destroy and a call
+ *     that has to grow the tile's scratch memory (the first call, or the first with a larger
+ *     batch: hipFree / hipMalloc, which wait for the device);
  *   - every function returns aht_status and never throws or aborts; on an error the tile
  *     is unchanged; aht_last_error() gives a thread-local message;
- *   - one tile must not be used from two streams at the same time;
+ *   - one tile must not be used from two streams or two host threads at the same time
+ *     (different tiles may be);
  *   - all quantities are in the paper's normalised units (Sec. 3, after Eq. (1)).
  */
 #ifndef AHT_H

@@ -305,7 +305,8 @@ aht_status aht_profile_read(aht_tile* tile, double* ms_words, double* ms_cells, 
  *   AHT_MVM_CODES   0: keep products of quantised inputs off the bf16 matrix cores
  *   AHT_MVM_MT      16-vector tiles per wave on that path (2, 4, 8 or 16)
  *   AHT_MVM_FUSED   0: always add the slices' partial sums in a second kernel
- *   AHT_MVM_SHARED  0: never share the input codes among the waves of a workgroup through LDS */
+ *   AHT_MVM_SHARED  0: never share the input codes among the waves of a workgroup through LDS
+ *   AHT_MVM_PLANES  0: products of other inputs (input noise, no or a finer DAC) on the fp32 matrix cores */
 
 const char* aht_status_string(aht_status s);
 const char* aht_last_error(void);

@@ -588,9 +588,14 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     const bool codes_path = env_int("AHT_MVM_CODES", 1) != 0 && io->inp_res > 0.0f &&
                             io->inp_noise == 0.0f && io->inp_bound / io->inp_res <= 256.0f && K % 32 == 0 &&
                             N % 16 == 0 && ((uintptr_t)wmat % 16 == 0);
+    // Any other input (input noise, no or a finer DAC) as three bf16 planes of its fp32 value: the same
+    // matrix cores, six passes instead of three.
+    const bool planes_path = !codes_path && env_int("AHT_MVM_PLANES", 1) != 0 && K % 32 == 0 && N % 64 == 0 &&
+                             ((uintptr_t)wmat % 16 == 0);
     // codes in blocks of 32 vectors; whole groups of 8 blocks (the most a wave takes), zero where no vector is
-    const size_t cneed = (size_t)((B + 255) / 256) * 256 * (size_t)K;
-    if (codes_path && cneed > t->mvm_codes_elems) {
+    const size_t plane_elems = (size_t)((B + 255) / 256) * 256 * (size_t)K;
+    const size_t cneed = plane_elems * (planes_path ? 3 : 1);
+    if ((codes_path || planes_path) && cneed > t->mvm_codes_elems) {
         if (t->mvm_codes) AHT_HIP(hipFree(t->mvm_codes));
         t->mvm_codes = nullptr; t->mvm_codes_elems = 0;
         AHT_HIP(hipMalloc((void**)&t->mvm_codes, cneed * sizeof(uint16_t)));
@@ -599,10 +604,14 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
         t->mvm_codes_elems = cneed;
     }
     hipLaunchKernelGGL(k_mvm_prepare, dim3((unsigned)B), dim3(1024), 0, s, x, K, vec_in, a, k0, k1, step, tag_in,
-                       t->mvm_xq, t->mvm_alpha, t->mvm_norm, codes_path ? t->mvm_codes : nullptr);
-    if (codes_path) {
+                       t->mvm_xq, t->mvm_alpha, t->mvm_norm, (codes_path || planes_path) ? t->mvm_codes : nullptr,
+                       planes_path ? 3 : 1, plane_elems);
+    if (codes_path || planes_path) {
         int mt = B > 128 ? 16 : B > 64 ? 8 : B > 32 ? 4 : 2;    // 16-vector tiles per wave
+        // (three planes: 8 at most, so that two workgroups fit a compute unit's LDS; 247 against 280 us at 1024 vectors)
+        if (planes_path) mt = B > 64 ? 8 : 4;
         if (const int e = env_int("AHT_MVM_MT", 0)) mt = (e == 16 || e == 8 || e == 4 || e == 2) ? e : mt;
+        if (planes_path && mt < 4) mt = 4;
         const int mchunks = (B + 16 * mt - 1) / (16 * mt), nslab = N / 16, steps = K / 32;
         // Small products (up to 0.6 GFLOP: a 1024 x 1024 tile with 256 vectors) are bound by the chain of
         // launches: a launch saved is 2.5 us of about 15, so they finish in the product kernel wherever
@@ -611,16 +620,16 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
         // 4096 x 4096: 47 against 54 us per call at 256 vectors, 72 against 92 at 512; no gain below).
         const bool small = 2.0 * (double)B * (double)N * (double)K <= 6e8;
         const bool fuse_ok = env_int("AHT_MVM_FUSED", 1) != 0;
-        bool shared = mt >= 8 && N % 64 == 0 && env_int("AHT_MVM_SHARED", 1) != 0;
+        bool shared = planes_path || (mt >= 8 && N % 64 == 0 && env_int("AHT_MVM_SHARED", 1) != 0);
         int splits = env_int("AHT_MVM_SPLITS", 0);
         if (splits <= 0) {
             const long units = (long)mchunks * nslab;
             splits = (int)((1024 + units - 1) / units);                 // one wave per SIMD (measured optimum)
             if (splits > steps / 4) splits = steps / 4;
-            if (small && fuse_ok && splits >= 3 && splits <= 8) shared = false;     // four slices, finished in the kernel
+            if (!planes_path && small && fuse_ok && splits >= 3 && splits <= 8) shared = false;   // four slices, finished in the kernel
             if (shared && units >= 1024 && units < 2048 && steps >= 8) splits = 2;  // two waves per SIMD, where the sharing kernel has room
             if (!shared && splits >= 3 && splits <= (small ? 8 : 6)) splits = 4;
-        } else if (small && fuse_ok && splits == 4) {
+        } else if (!planes_path && small && fuse_ok && splits == 4) {
             shared = false;
         }
         if (splits > 16) splits = 16;
@@ -640,17 +649,29 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
             }
         }
         if (shared) {
-            const dim3 sgrid((unsigned)mchunks * (unsigned)(N / 64) * (unsigned)splits);
-#define AHT_SHARED_LAUNCH(MTV, TR)                                                                                \
-    hipLaunchKernelGGL((k_mvm_gemm_codes_shared<MTV, TR>), sgrid, dim3(256), 0, s, t->mvm_codes, wmat, B, N, K,   \
-                       t->cols, splits, io->inp_res, t->mvm_part)
-#define AHT_SHARED_PICK(TR)                                                                                       \
+            if (mt < 4) mt = 4;
+            const dim3 sgrid((unsigned)((B + 16 * mt - 1) / (16 * mt)) * (unsigned)(N / 64) * (unsigned)splits);
+            const size_t slds = (size_t)2 * (planes_path ? 3 : 1) * mt * 64 * 16;      // two stages of the planes of a step
+#define AHT_SHARED_LAUNCH(MTV, TR, NPV)                                                                           \
+    do {                                                                                                         \
+        if (slds > 48 * 1024)                                                                                    \
+            (void)hipFuncSetAttribute((const void*)k_mvm_gemm_codes_shared<MTV, TR, NPV>,                        \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)slds);                    \
+        hipLaunchKernelGGL((k_mvm_gemm_codes_shared<MTV, TR, NPV>), sgrid, dim3(256), slds, s, t->mvm_codes,      \
+                           plane_elems, wmat, B, N, K, t->cols, splits, planes_path ? 1.0f : io->inp_res,        \
+                           t->mvm_part);                                                                         \
+    } while (0)
+#define AHT_SHARED_PICK(TR, NPV)                                                                                  \
     switch (mt) {                                                                                                \
-        case 16: AHT_SHARED_LAUNCH(16, TR); break;                                                               \
-        case 8: AHT_SHARED_LAUNCH(8, TR); break;                                                                 \
-        default: AHT_SHARED_LAUNCH(4, TR); break;                                                                \
+        case 16: AHT_SHARED_LAUNCH(16, TR, NPV); break;                                                          \
+        case 8: AHT_SHARED_LAUNCH(8, TR, NPV); break;                                                            \
+        default: AHT_SHARED_LAUNCH(4, TR, NPV); break;                                                           \
     }
-            if (transposed) { AHT_SHARED_PICK(true) } else { AHT_SHARED_PICK(false) }
+            if (planes_path) {
+                if (transposed) { AHT_SHARED_PICK(true, 3) } else { AHT_SHARED_PICK(false, 3) }
+            } else {
+                if (transposed) { AHT_SHARED_PICK(true, 1) } else { AHT_SHARED_PICK(false, 1) }
+            }
 #undef AHT_SHARED_PICK
 #undef AHT_SHARED_LAUNCH
             AHT_HIP(hipGetLastError());

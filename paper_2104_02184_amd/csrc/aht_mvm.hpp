@@ -29,7 +29,7 @@ struct IoArgs {
 __global__ void __launch_bounds__(1024)
 k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k0, uint32_t k1, uint32_t t,
               uint32_t tag, float* __restrict__ xq, float* __restrict__ alpha_out, float* __restrict__ norm_out,
-              uint16_t* __restrict__ codes)
+              uint16_t* __restrict__ codes, int nplanes, size_t plane_elems)
 {
     __shared__ float red[16];
     __shared__ double redd[16];
@@ -76,7 +76,7 @@ k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k
         float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         if (io.inp_noise > 0.0f) gauss4_fast(k0, k1, (uint32_t)g, (uint32_t)b, t, tag, z);
         float v[4], o[4];
-        uint32_t cbits[4] = {0u, 0u, 0u, 0u};
+        uint32_t cbits[4] = {0u, 0u, 0u, 0u}, mbits[4] = {0u, 0u, 0u, 0u}, lbits[4] = {0u, 0u, 0u, 0u};
         if (single) { v[0] = kept[0]; v[1] = kept[1]; v[2] = kept[2]; v[3] = kept[3]; }
         else load_group(g, v);
 #pragma unroll
@@ -99,6 +99,16 @@ k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k
                 xh = xh + nz;
             }
             o[e] = xh;
+            if (nplanes == 3) {
+                // the value itself as three bf16 terms, xh = h + m + l to the last bit (both subtractions exact)
+                const uint32_t hb = __float_as_uint(xh) & 0xFFFF0000u;
+                const float r1 = xh - __uint_as_float(hb);
+                const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
+                const float r2 = r1 - __uint_as_float(mb);
+                cbits[e] = hb >> 16;
+                mbits[e] = mb >> 16;
+                lbits[e] = __float_as_uint(r2) >> 16;
+            }
             if (4 * g + e < K) part += (double)xh * (double)xh;
         }
         if (codes) {
@@ -107,6 +117,10 @@ k_mvm_prepare(const float* __restrict__ x, int K, int vec, IoArgs io, uint32_t k
             const size_t block = (size_t)(b >> 4) * (size_t)(K >> 5) + (size_t)(kk >> 5);
             uint16_t* at = codes + (block * 64 + (size_t)(((kk >> 3) & 3) * 16 + (b & 15))) * 8 + (size_t)(kk & 7);
             *(uint2*)at = make_uint2(cbits[0] | (cbits[1] << 16), cbits[2] | (cbits[3] << 16));
+            if (nplanes == 3) {
+                *(uint2*)(at + plane_elems) = make_uint2(mbits[0] | (mbits[1] << 16), mbits[2] | (mbits[3] << 16));
+                *(uint2*)(at + 2 * plane_elems) = make_uint2(lbits[0] | (lbits[1] << 16), lbits[2] | (lbits[3] << 16));
+            }
         } else if (vec) {
             *(float4*)(qr + 4 * (size_t)g) = make_float4(o[0], o[1], o[2], o[3]);
         } else {
@@ -615,11 +629,16 @@ k_mvm_gemm_codes(const uint16_t* __restrict__ xc, const float* __restrict__ W, i
 // barrier per step) and read from there by all four.  Without this every wave fetches all the codes of
 // its slice itself: at 256 vectors eight times the bytes of its weights.  Needs N % 64 == 0 and
 // MT % 4 == 0; always writes partial sums for k_mvm_epilogue.
-template <int MT, bool TRANS>
-__global__ void __launch_bounds__(256, 2)
-k_mvm_gemm_codes_shared(const uint16_t* __restrict__ xc, const float* __restrict__ W, int B, int N, int K, int ldw,
-                        int splits, float inp_res, float* __restrict__ part)
+// NP = 3: inputs of any value, given as three bf16 planes (x~ = h + m + l to the last bit, as the weights
+// are cut; planes `plane_elems` apart).  Of the nine products of a term of x~ and a term of w the six
+// down to 2^-16 of the largest are formed (l H, m M, h L, m H, h M, h H, small ones first), the three
+// left out are each 2^-24 of it: an fp32 product at six sixteenths of the time of the fp32 matrix cores.
+template <int MT, bool TRANS, int NP>
+__global__ void __launch_bounds__(256, NP == 1 ? 2 : 1)
+k_mvm_gemm_codes_shared(const uint16_t* __restrict__ xc, size_t plane_elems, const float* __restrict__ W, int B, int N,
+                        int K, int ldw, int splits, float inp_res, float* __restrict__ part)
 {
+    static_assert(NP == 1 || NP == 3, "one plane of integer codes or three planes of an fp32 value");
     static_assert(MT % 4 == 0, "each wave fetches a quarter of the code blocks of a step");
     constexpr int QT = MT / 4;
     const int lane = threadIdx.x & 63;
@@ -637,23 +656,29 @@ k_mvm_gemm_codes_shared(const uint16_t* __restrict__ xc, const float* __restrict
     const float* wco = W + (size_t)(slab * 16 + (lane >> 3)) * ldw + 4 * (lane & 7);
     __shared__ float wturn[4][16 * 36];
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-    __shared__ u32x4_t cstage[2][MT][64];
+    extern __shared__ u32x4_t cstage[];                            // [2 stages][NP][MT][64 lanes]
+    auto staged = [&](int buf, int p, int m) __attribute__((always_inline)) -> u32x4_t& {
+        return cstage[((buf * NP + p) * MT + m) * 64 + lane];
+    };
     float* wt_st = &wturn[wave][(lane >> 3) * 36 + 4 * (lane & 7)];
     const float* wt_ld = &wturn[wave][j * 36 + 8 * g];
-    const uint16_t* ap[QT];                                        // this wave's blocks: tiles wave, wave + 4, ...
+    const uint16_t* ap[NP * QT];                                   // this wave's blocks: tiles wave, wave + 4, ... of every plane
 #pragma unroll
-    for (int i = 0; i < QT; ++i)
-        ap[i] = xc + ((size_t)(mc * MT + 4 * i + wave) * (size_t)steps * 64 + (size_t)lane) * 8;
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int i = 0; i < QT; ++i)
+            ap[p * QT + i] = xc + (size_t)p * plane_elems +
+                             ((size_t)(mc * MT + 4 * i + wave) * (size_t)steps * 64 + (size_t)lane) * 8;
     floatx4_t acc[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[m][r] = 0.0f;
 
-    constexpr int DW = 4;
+    constexpr int DW = (NP == 1) ? 4 : 3;
     float4 wq[DW][2];
-    uint4 av[DW][QT];
-    auto fetch = [&](int s, float4 (&q)[2], uint4 (&v)[QT]) __attribute__((always_inline)) {
+    uint4 av[DW][NP * QT];
+    auto fetch = [&](int s, float4 (&q)[2], uint4 (&v)[NP * QT]) __attribute__((always_inline)) {
         if (TRANS) {
             const float* wr = wp + (size_t)(32 * s) * ldw;
             float e[8];
@@ -670,7 +695,7 @@ k_mvm_gemm_codes_shared(const uint16_t* __restrict__ xc, const float* __restrict
             q[1] = make_float4(u1.x, u1.y, u1.z, u1.w);
         }
 #pragma unroll
-        for (int i = 0; i < QT; ++i) v[i] = *(const uint4*)(ap[i] + 512 * (size_t)s);
+        for (int i = 0; i < NP * QT; ++i) v[i] = *(const uint4*)(ap[i] + 512 * (size_t)s);
     };
     const int last = s1 - 1;
     if (s0 < s1) {
@@ -679,9 +704,12 @@ k_mvm_gemm_codes_shared(const uint16_t* __restrict__ xc, const float* __restrict
     }
     int buf = 0;
     // one step of the inner dimension from ring slot (q, v); then the slot is filled again for step `next`
-    auto step = [&](float4 (&q)[2], uint4 (&v)[QT], int next) __attribute__((always_inline)) {
+    auto step = [&](float4 (&q)[2], uint4 (&v)[NP * QT], int next) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < QT; ++i) cstage[buf][4 * i + wave][lane] = u32x4_t{v[i].x, v[i].y, v[i].z, v[i].w};
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int i = 0; i < QT; ++i)
+                staged(buf, p, 4 * i + wave) = u32x4_t{v[p * QT + i].x, v[p * QT + i].y, v[p * QT + i].z, v[p * QT + i].w};
         float4 o0 = q[0], o1 = q[1];
         if (!TRANS) {
             *(float4*)wt_st = q[0];
@@ -694,19 +722,31 @@ k_mvm_gemm_codes_shared(const uint16_t* __restrict__ xc, const float* __restrict
             o0 = *(const float4*)wt_ld;
             o1 = *(const float4*)(wt_ld + 4);
         }
-        bf16x8_t a[MT];
-#pragma unroll
-        for (int m = 0; m < MT; ++m) a[m] = __builtin_bit_cast(bf16x8_t, cstage[buf][m][lane]);
-        buf ^= 1;
-        fetch(next < last ? next : last, q, v);
         bf16x8_t bh, bm, bl;
         split_bf16x3(o0, o1, bh, bm, bl);
+        bf16x8_t a[MT];
+        if (NP == 3) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m) a[m] = __builtin_bit_cast(bf16x8_t, staged(buf, 2, m));
+#pragma unroll
+            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bh, acc[m], 0, 0, 0);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) a[m] = __builtin_bit_cast(bf16x8_t, staged(buf, 1, m));
+#pragma unroll
+            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bm, acc[m], 0, 0, 0);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bh, acc[m], 0, 0, 0);
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m) a[m] = __builtin_bit_cast(bf16x8_t, staged(buf, 0, m));
+        fetch(next < last ? next : last, q, v);
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bl, acc[m], 0, 0, 0);
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bm, acc[m], 0, 0, 0);
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], bh, acc[m], 0, 0, 0);
+        buf ^= 1;
     };
     // Whole turns of the ring in a loop with one way in and one way out (an exit from the middle of a
     // turn would, for the compiler, lead back to the head of the loop, and the head would then wait for

@@ -166,6 +166,36 @@ def test_quantised_product_every_split_and_both_paths_agree(B, splits, transpose
     tile.close()
 
 
+@pytest.mark.parametrize("B", [3, 64, 130, 300])
+@pytest.mark.parametrize("transposed", [False, True])
+@pytest.mark.parametrize("io_kw", [IDEAL, NOISY], ids=["ideal", "noisy"])
+def test_three_plane_product_matches_oracle_and_the_fp32_cores(B, transposed, io_kw, monkeypatch):
+    """Inputs that are no 8-bit DAC codes (no DAC at all, or input noise) go to the bf16 matrix cores
+    as three bf16 planes when the shape allows (inner dimension in steps of 32, outputs in groups of
+    64): same tolerance against the oracle as the fp32 cores, and the two agree with each other."""
+    R, C = (608, 128) if transposed else (128, 608)
+    K = R if transposed else C
+    tile, W = _tile_with_weights(R, C)
+    g = np.random.default_rng(B)
+    x = g.normal(size=(B, K)).astype(np.float32)
+    x[0, :5] = [0.0, -0.0, 1e-30, -3.5, 7.25]
+    for splits in (0, 1, 3, 16):
+        monkeypatch.setenv("AHT_MVM_SPLITS", str(splits))
+        _check(tile, W, x, io_kw, transposed, step=2)
+    monkeypatch.setenv("AHT_MVM_SPLITS", "0")
+    fn = tile.backward if transposed else tile.forward
+    tile.mvm_steps = (4, 4)
+    _, pre_planes = fn(to_dev(x), aht.IOParams(**io_kw), with_pre=True)
+    monkeypatch.setenv("AHT_MVM_PLANES", "0")
+    tile.mvm_steps = (4, 4)
+    _, pre_fp32 = fn(to_dev(x), aht.IOParams(**io_kw), with_pre=True)
+    pre_planes, pre_fp32 = pre_planes.cpu().numpy().astype(np.float64), pre_fp32.cpu().numpy().astype(np.float64)
+    scale = max(1.0, float(np.abs(pre_fp32).max()))
+    assert np.abs(pre_planes - pre_fp32).max() <= 5e-6 * scale * max(1.0, np.sqrt(K) / 16)
+    assert (pre_planes != pre_fp32).any()          # (two different kernels did run)
+    tile.close()
+
+
 def test_bad_io_parameters_are_rejected():
     import torch
     tile, W = _tile_with_weights(8, 8)

@@ -317,6 +317,35 @@ def test_launch_shape_chosen_from_the_pulse_rate_changes_no_bit(env):
     assert p4 == pr and (got4 == ref).all()
 
 
+@pytest.mark.parametrize("kind,bl", [(aht.CONSTANT_STEP, 31), (aht.SOFT_BOUNDS, 63)])
+def test_two_launches_side_by_side_change_no_bit(kind, bl, monkeypatch):
+    """256 x 2304 at two rows per lane makes 4.5 waves per SIMD; long calls then run 32 column strips at
+    two rows per lane and 4 at one, as two launches on two streams.  Same weights and pulse counts,
+    bit for bit, as the single launch, call after call, and the caller's stream sees the result."""
+    R, C, B = 256, 2304, 48
+    dev = dict(kind=kind, dw_min=0.002, dw_min_dtod=0.3, dw_min_std=0.3, w_max=0.6, w_max_dtod=0.2, w_min=-0.6,
+               w_min_dtod=0.2)
+    g = np.random.default_rng(bl)
+    W0 = g.uniform(-0.3, 0.3, size=(R, C)).astype(np.float32)
+    xs = [g.normal(size=(B, C)).astype(np.float32) for _ in range(3)]
+    ds = [g.normal(size=(B, R)).astype(np.float32) for _ in range(3)]
+    out = {}
+    for mode in ("0", "2"):
+        monkeypatch.setenv("AHT_EVEN_ROUND", mode)
+        tile = aht.Tile(R, C, gpu_params(dev), bl, True, 77)
+        tile.set_weights(to_dev(W0))
+        steps = []
+        for x, d in zip(xs, ds):
+            tile.pulsed_update(to_dev(x), to_dev(d), 0.1)
+            steps.append(tile.get_weights().cpu().numpy())
+        out[mode] = (steps, tile.pulse_count())
+        tile.close()
+    assert out["0"][1] == out["2"][1] > 0
+    for a, b in zip(out["0"][0], out["2"][0]):
+        assert (a.view(np.uint32) == b.view(np.uint32)).all()
+    assert (out["0"][0][0] != W0).any()
+
+
 def test_saturated_lines_fill_whole_trains(env):
     # every sample has 63 coincidences per cell: queues overflow often, counts are maximal
     R, C, B, bl = 33, 65, 40, 63

@@ -352,11 +352,12 @@ void even_round(const aht_tile* t, int B, uint32_t strips, uint32_t* strips_main
     if (r < 2 || t->rows % (4 * r) != 0) return;
     // lane operations of the call at a quarter of the chip's rate, which is what tiles of this size reach
     const double cells = (double)t->rows * (double)t->cols;
-    const double est_s = cells * (4.0 * B + 21.0 * (t->pulse_rate > 0.0 ? t->pulse_rate : 0.0)) / (39.3e12 * 0.25);
+    // (one pulse per cell and sample where the tile's own rate is not known: small tiles never report it)
+    const double est_s = cells * (4.0 * B + 21.0 * (t->pulse_rate >= 0.0 ? t->pulse_rate : (double)B)) / (39.3e12 * 0.25);
     if (est_s < 0.4e-3 && env_int("AHT_EVEN_ROUND", 1) != 2) return;          // (2: whatever the length, for tests)
     const uint64_t simds = 1024, R = (uint64_t)t->rows;
     const uint64_t waves = R / r * strips;                        // all strips at r rows per lane
-    if (waves % simds == 0 || waves >= 8 * simds || waves < 2 * simds) return;
+    if (waves % simds == 0 || waves >= 8 * simds || waves <= simds) return;
     // strips in groups that give every SIMD one more wave: ga strips at r rows per lane, gb at r / 2
     if ((simds * r) % R != 0 || (simds * r / 2) % R != 0) return;
     const uint64_t ga = simds * r / R, gb = simds * r / 2 / R;

@@ -239,7 +239,8 @@ aht_status aht_transfer_column(aht_tile* src, aht_tile* dst, int32_t col, float 
  *   pulse trains is drawn -- with device 0's seed, update parameters and pulse mode at device 0's
  *   step count -- and applied to every device (which = -1) or to device `which` only, each through
  *   its own response model and pulse-to-pulse noise stream.  The step counters of all devices are
- *   set to device 0's count + 1.  B = 0 and lr = 0 as for aht_pulsed_update.
+ *   set to device 0's count + 1.  B = 0 and lr = 0 as for aht_pulsed_update.  With which = -1 the
+ *   devices after the first are updated on streams of their own tiles, which `stream` waits for.
  * aht_unit_cell_weights: w_out[rows][cols] = sum_k gamma_k w^(k), added in device order in fp32.
  * aht_unit_cell_forward / _backward: aht_forward / aht_backward on that effective weight (it is
  *   formed in scratch owned by device 0, whose call counters and seed serve the product; a call on
@@ -301,8 +302,9 @@ aht_status aht_profile_read(aht_tile* tile, double* ms_words, double* ms_cells, 
  *                   the pulse counter to pinned host memory on the caller's stream
  *   AHT_QWORDS      32-bit words of pulse-stream storage per cell in LDS
  *   AHT_EVEN_ROUND  0: never run the cell update as two launches side by side (on a stream of the
- *                   tile's own, between two events) to fill the chip's last round of waves evenly;
- *                   2: whenever the shape allows, however short the call
+ *                   tile's own, between two events) to fill the chip's last round of waves evenly,
+ *                   nor the devices of a unit cell beside each other; 2: the former whenever the
+ *                   shape allows, however short the call
  *   AHT_MVM_BM      block height of the analog product (64 or 128 input vectors)
  *   AHT_MVM_SPLITS  number of slices the product's inner dimension is cut into (1..16)
  *   AHT_MVM_CODES   0: keep products of quantised inputs off the bf16 matrix cores

@@ -343,10 +343,10 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
 // for 256 x 2304 with 12 544 vectors, 0.47 -> 0.42 ms with 256 dense ones, but 0.07 -> 0.09 ms for
 // 512 x 640 with 128 sparse ones), so the call's length is estimated first, from the batch and the
 // tile's pulse rate as far as the host has seen it.
-void even_round(const aht_tile* t, int B, uint32_t strips, uint32_t* strips_main, int* rpl_main)
+void even_round(const aht_tile* t, int B, uint32_t strips, uint32_t* strips_main, int* rpl_main, int* rpl_side)
 {
     *strips_main = strips;
-    *rpl_main = 0;
+    *rpl_main = *rpl_side = 0;
     if (env_int("AHT_EVEN_ROUND", 1) == 0 || env_int("AHT_RPL", 0) != 0) return;
     const int r = choose_rpl(t);
     if (r < 2 || t->rows % (4 * r) != 0) return;
@@ -359,13 +359,17 @@ void even_round(const aht_tile* t, int B, uint32_t strips, uint32_t* strips_main
     const uint64_t waves = R / r * strips;                        // all strips at r rows per lane
     if (waves % simds == 0 || waves >= 8 * simds || waves <= simds) return;
     // strips in groups that give every SIMD one more wave: ga strips at r rows per lane, gb at r / 2
-    if ((simds * r) % R != 0 || (simds * r / 2) % R != 0) return;
-    const uint64_t ga = simds * r / R, gb = simds * r / 2 / R;
-    for (uint64_t kb = 1; kb <= 2; ++kb) {
-        if (kb * gb >= strips || (strips - kb * gb) % ga != 0) continue;
-        *strips_main = (uint32_t)(strips - kb * gb);
-        *rpl_main = r;
-        return;
+    // (or, from four rows per lane, at r / 4)
+    for (int side = r / 2; side >= 1; side /= 2) {
+        if ((simds * r) % R != 0 || (simds * side) % R != 0) continue;
+        const uint64_t ga = simds * r / R, gb = simds * side / R;
+        for (uint64_t kb = 1; kb <= 3; ++kb) {
+            if (kb * gb >= strips || (strips - kb * gb) % ga != 0) continue;
+            *strips_main = (uint32_t)(strips - kb * gb);
+            *rpl_main = r;
+            *rpl_side = side;
+            return;
+        }
     }
 }
 
@@ -537,10 +541,10 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         const uint32_t strip0 = col_hi < 0 ? 0u : (uint32_t)(col_lo / 64);
         const uint32_t strips = (col_hi < 0 ? (uint32_t)((t->cols + 63) / 64) : (uint32_t)(col_hi / 64 + 1)) - strip0;
         uint32_t strips_main = strips;
-        int rpl_main = 0;
-        if (col_hi < 0) even_round(t, B, strips, &strips_main, &rpl_main);
+        int rpl_main = 0, rpl_side = 0;
+        if (col_hi < 0) even_round(t, B, strips, &strips_main, &rpl_main, &rpl_side);
         if (strips_main < strips) {
-            // the last strips with half as many rows per lane, beside the others, on a stream of the tile's own
+            // the last strips with fewer rows per lane, beside the others, on a stream of the tile's own
             if (!t->side_stream) AHT_HIP(hipStreamCreateWithFlags(&t->side_stream, hipStreamNonBlocking));
             if (!t->side_fork) AHT_HIP(hipEventCreateWithFlags(&t->side_fork, hipEventDisableTiming));
             if (!t->side_join) AHT_HIP(hipEventCreateWithFlags(&t->side_join, hipEventDisableTiming));
@@ -548,7 +552,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
             AHT_HIP(hipStreamWaitEvent(t->side_stream, t->side_fork, 0));
             if ((st = launch_cells(t, B, t->step, s, 0u, strips_main, nullptr, rpl_main)) != AHT_OK) return st;
             if ((st = launch_cells(t, B, t->step, t->side_stream, strips_main, strips - strips_main, nullptr,
-                                   rpl_main / 2)) != AHT_OK) return st;
+                                   rpl_side)) != AHT_OK) return st;
             AHT_HIP(hipEventRecord(t->side_join, t->side_stream));
             AHT_HIP(hipStreamWaitEvent(s, t->side_join, 0));
         } else if ((st = launch_cells(t, B, t->step, s, strip0, strips)) != AHT_OK) return st;

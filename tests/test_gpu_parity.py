@@ -317,18 +317,22 @@ def test_launch_shape_chosen_from_the_pulse_rate_changes_no_bit(env):
     assert p4 == pr and (got4 == ref).all()
 
 
-@pytest.mark.parametrize("kind,bl", [(aht.CONSTANT_STEP, 31), (aht.SOFT_BOUNDS, 63)])
-def test_two_launches_side_by_side_change_no_bit(kind, bl, monkeypatch):
-    """256 x 2304 at two rows per lane makes 4.5 waves per SIMD; long calls then run 32 column strips at
-    two rows per lane and 4 at one, as two launches on two streams.  Same weights and pulse counts,
-    bit for bit, as the single launch, call after call, and the caller's stream sees the result."""
-    R, C, B = 256, 2304, 48
+@pytest.mark.parametrize("R,C,B,lr,calls,kind,bl", [
+    (256, 2304, 48, 0.1, 3, aht.CONSTANT_STEP, 31),      # two rows per lane on 32 strips, one on 4
+    (256, 2304, 48, 0.1, 3, aht.SOFT_BOUNDS, 63),
+    (1024, 576, 16, 0.02, 6, aht.LINEAR_STEP, 31),       # few pulses: four rows per lane on 8 strips once the
+])                                                       # tile has seen its pulse rate, one row on the ninth
+def test_two_launches_side_by_side_change_no_bit(R, C, B, lr, calls, kind, bl, monkeypatch):
+    """A tile whose waves do not fill the SIMDs a whole number of times (256 x 2304 at two rows per lane:
+    4.5 waves per SIMD) runs most column strips at the chosen rows per lane and a few at fewer, as two
+    launches on two streams.  Same weights and pulse counts, bit for bit, as the single launch, call
+    after call, and the caller's stream sees the result."""
     dev = dict(kind=kind, dw_min=0.002, dw_min_dtod=0.3, dw_min_std=0.3, w_max=0.6, w_max_dtod=0.2, w_min=-0.6,
-               w_min_dtod=0.2)
-    g = np.random.default_rng(bl)
+               w_min_dtod=0.2, gamma_up=0.4, gamma_down=0.6, gamma_dtod=0.1)
+    g = np.random.default_rng(bl + R)
     W0 = g.uniform(-0.3, 0.3, size=(R, C)).astype(np.float32)
-    xs = [g.normal(size=(B, C)).astype(np.float32) for _ in range(3)]
-    ds = [g.normal(size=(B, R)).astype(np.float32) for _ in range(3)]
+    xs = [g.normal(size=(B, C)).astype(np.float32) for _ in range(calls)]
+    ds = [g.normal(size=(B, R)).astype(np.float32) for _ in range(calls)]
     out = {}
     for mode in ("0", "2"):
         monkeypatch.setenv("AHT_EVEN_ROUND", mode)
@@ -336,7 +340,7 @@ def test_two_launches_side_by_side_change_no_bit(kind, bl, monkeypatch):
         tile.set_weights(to_dev(W0))
         steps = []
         for x, d in zip(xs, ds):
-            tile.pulsed_update(to_dev(x), to_dev(d), 0.1)
+            tile.pulsed_update(to_dev(x), to_dev(d), lr)
             steps.append(tile.get_weights().cpu().numpy())
         out[mode] = (steps, tile.pulse_count())
         tile.close()

@@ -336,40 +336,48 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
 
 // A tile whose waves fill the chip's 1024 SIMDs a few times only, and not a whole number of times,
 // ends with part of the chip idle (256 x 2304 at two rows per lane: 4 608 waves, five on half of the
-// SIMDs and four on the others).  If the column strips can be divided so that `*strips_main` of them at
-// `*rpl_main` rows per lane and the rest at half as many give every SIMD whole numbers of both kinds of
-// waves, says so; else leaves *strips_main = strips.  The second launch runs on a stream of the tile's
-// own, between two events: about 20 us, worth it for calls of some length only (measured: 2.77 -> 2.40 ms
-// for 256 x 2304 with 12 544 vectors, 0.47 -> 0.42 ms with 256 dense ones, but 0.07 -> 0.09 ms for
-// 512 x 640 with 128 sparse ones), so the call's length is estimated first, from the batch and the
-// tile's pulse rate as far as the host has seen it.
+// SIMDs and four on the others).  Looks for a division of the column strips, `*strips_main` of them at
+// `*rpl_main` rows per lane and the rest at `*rpl_side` (half or a quarter as many), under which the
+// busiest compute unit has at least 7 % fewer rows to work through; else leaves *strips_main = strips.
+// The second launch runs on a stream of the tile's own, between two events: about 20 us, worth it for
+// calls of some length only (measured: 2.77 -> 2.40 ms for 256 x 2304 with 12 544 vectors, 3.02 -> 2.50 ms
+// for 500 x 784 with 2 048 dense ones, but 0.07 -> 0.09 ms for 512 x 640 with 128 sparse ones), so the
+// call's length is estimated first, from the batch and the tile's pulse rate as far as the host has seen it.
 void even_round(const aht_tile* t, int B, uint32_t strips, uint32_t* strips_main, int* rpl_main, int* rpl_side)
 {
     *strips_main = strips;
     *rpl_main = *rpl_side = 0;
     if (env_int("AHT_EVEN_ROUND", 1) == 0 || env_int("AHT_RPL", 0) != 0) return;
     const int r = choose_rpl(t);
-    if (r < 2 || t->rows % (4 * r) != 0) return;
+    if (r < 2) return;
     // lane operations of the call at a quarter of the chip's rate, which is what tiles of this size reach
-    const double cells = (double)t->rows * (double)t->cols;
     // (one pulse per cell and sample where the tile's own rate is not known: small tiles never report it)
+    const double cells = (double)t->rows * (double)t->cols;
     const double est_s = cells * (4.0 * B + 21.0 * (t->pulse_rate >= 0.0 ? t->pulse_rate : (double)B)) / (39.3e12 * 0.25);
     if (est_s < 0.4e-3 && env_int("AHT_EVEN_ROUND", 1) != 2) return;          // (2: whatever the length, for tests)
-    const uint64_t simds = 1024, R = (uint64_t)t->rows;
-    const uint64_t waves = R / r * strips;                        // all strips at r rows per lane
-    if (waves % simds == 0 || waves >= 8 * simds || waves <= simds) return;
-    // strips in groups that give every SIMD one more wave: ga strips at r rows per lane, gb at r / 2
-    // (or, from four rows per lane, at r / 4)
-    for (int side = r / 2; side >= 1; side /= 2) {
-        if ((simds * r) % R != 0 || (simds * side) % R != 0) continue;
-        const uint64_t ga = simds * r / R, gb = simds * side / R;
-        for (uint64_t kb = 1; kb <= 3; ++kb) {
-            if (kb * gb >= strips || (strips - kb * gb) % ga != 0) continue;
-            *strips_main = (uint32_t)(strips - kb * gb);
-            *rpl_main = r;
-            *rpl_side = side;
-            return;
+    // Workgroups (four waves, 4 * rows-per-lane rows of a strip) spread evenly over the 256 compute
+    // units; the call lasts as long as the unit with the most rows.  A row on the side launch is counted
+    // as 1.15 rows: fewer rows per lane reuse the column words less.
+    const uint64_t cus = 256, R = (uint64_t)t->rows;
+    auto groups = [&](int rows_per_lane, uint64_t nstrips) { return (R + 4 * rows_per_lane - 1) / (4 * rows_per_lane) * nstrips; };
+    const uint64_t all = groups(r, strips);
+    if (all <= cus || all >= 8 * cus) return;                     // less than a wave per SIMD, or several rounds anyway
+    const double single = (double)((all + cus - 1) / cus) * (4.0 * r);
+    double best = single;
+    for (int side = r / 2; side >= 1; side /= 2)
+        for (uint32_t sb = 1; sb < strips; ++sb) {
+            const uint64_t ga = groups(r, strips - sb), gb = groups(side, sb);
+            const double m = (double)((ga + cus - 1) / cus) * (4.0 * r) + (double)((gb + cus - 1) / cus) * (4.0 * side) * 1.15;
+            if (m < best - 1e-9) {
+                best = m;
+                *strips_main = strips - sb;
+                *rpl_main = r;
+                *rpl_side = side;
+            }
         }
+    if (best > 0.93 * single) {                                  // not worth two events
+        *strips_main = strips;
+        *rpl_main = *rpl_side = 0;
     }
 }
 

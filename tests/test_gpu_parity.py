@@ -320,6 +320,7 @@ def test_launch_shape_chosen_from_the_pulse_rate_changes_no_bit(env):
 @pytest.mark.parametrize("R,C,B,lr,calls,kind,bl", [
     (256, 2304, 48, 0.1, 3, aht.CONSTANT_STEP, 31),      # two rows per lane on 32 strips, one on 4
     (256, 2304, 48, 0.1, 3, aht.SOFT_BOUNDS, 63),
+    (500, 784, 24, 0.1, 3, aht.SOFT_BOUNDS, 31),         # ragged in both directions
     (1024, 576, 16, 0.02, 6, aht.LINEAR_STEP, 31),       # few pulses: four rows per lane on 8 strips once the
 ])                                                       # tile has seen its pulse rate, one row on the ninth
 def test_two_launches_side_by_side_change_no_bit(R, C, B, lr, calls, kind, bl, monkeypatch):

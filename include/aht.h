@@ -301,10 +301,10 @@ aht_status aht_profile_read(aht_tile* tile, double* ms_words, double* ms_cells, 
  *                   pulse rate: some update calls are followed by an asynchronous 8-byte copy of
  *                   the pulse counter to pinned host memory on the caller's stream
  *   AHT_QWORDS      32-bit words of pulse-stream storage per cell in LDS
- *   AHT_EVEN_ROUND  0: never run the cell update as two launches side by side (on a stream of the
- *                   tile's own, between two events) to fill the chip's last round of waves evenly,
- *                   nor the devices of a unit cell beside each other; 2: the former whenever the
- *                   shape allows, however short the call
+ *   AHT_EVEN_ROUND  0: never give some column strips fewer rows per lane than the others to fill
+ *                   the chip's last round of waves evenly, nor update the devices of a unit cell
+ *                   beside each other (on streams of their own tiles, between events); 2: the
+ *                   former whenever the shape allows, however short the call
  *   AHT_MVM_BM      block height of the analog product (64 or 128 input vectors)
  *   AHT_MVM_SPLITS  number of slices the product's inner dimension is cut into (1..16)
  *   AHT_MVM_CODES   0: keep products of quantised inputs off the bf16 matrix cores

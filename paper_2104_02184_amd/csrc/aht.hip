@@ -49,7 +49,7 @@ struct aht_tile {
     uint64_t copy_issued_at = 0;                  // ... when the last copy was issued
     unsigned long long seen_value = 0;            // last value read from the pinned word
     double pulse_rate = -1.0;                     // pulses per cell and full update; < 0: not known yet
-    // second stream and events for an update whose cells run as two launches side by side
+    // stream and events for the update of a unit cell, whose devices run beside each other
     hipStream_t side_stream = nullptr;
     hipEvent_t side_fork = nullptr, side_join = nullptr;
     // analog matrix-vector product: scratch and call counters
@@ -339,10 +339,11 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
 // SIMDs and four on the others).  Looks for a division of the column strips, `*strips_main` of them at
 // `*rpl_main` rows per lane and the rest at `*rpl_side` (half or a quarter as many), under which the
 // busiest compute unit has at least 7 % fewer rows to work through; else leaves *strips_main = strips.
-// The second launch runs on a stream of the tile's own, between two events: about 20 us, worth it for
-// calls of some length only (measured: 2.77 -> 2.40 ms for 256 x 2304 with 12 544 vectors, 3.02 -> 2.50 ms
-// for 500 x 784 with 2 048 dense ones, but 0.07 -> 0.09 ms for 512 x 640 with 128 sparse ones), so the
-// call's length is estimated first, from the batch and the tile's pulse rate as far as the host has seen it.
+// Both shapes then run in one launch (k_cell_update_pair).  Measured: 2.77 -> 2.40 ms for 256 x 2304 with
+// 12 544 vectors, 2.98 -> 2.49 ms for 500 x 784 with 2 048 dense ones, 0.095 -> 0.076 ms with 128 sparse
+// ones; very short calls lose (0.053 -> 0.059 ms for 256 x 768 with 128 sparse vectors: the waves with
+// fewer rows per lane then take longer than the others), so the call's length is estimated first, from
+// the batch and the tile's pulse rate as far as the host has seen it.
 void even_round(const aht_tile* t, int B, uint32_t strips, uint32_t* strips_main, int* rpl_main, int* rpl_side)
 {
     *strips_main = strips;
@@ -354,7 +355,7 @@ void even_round(const aht_tile* t, int B, uint32_t strips, uint32_t* strips_main
     // (one pulse per cell and sample where the tile's own rate is not known: small tiles never report it)
     const double cells = (double)t->rows * (double)t->cols;
     const double est_s = cells * (4.0 * B + 21.0 * (t->pulse_rate >= 0.0 ? t->pulse_rate : (double)B)) / (39.3e12 * 0.25);
-    if (est_s < 0.4e-3 && env_int("AHT_EVEN_ROUND", 1) != 2) return;          // (2: whatever the length, for tests)
+    if (est_s < 0.12e-3 && env_int("AHT_EVEN_ROUND", 1) != 2) return;         // (2: whatever the length, for tests)
     // Workgroups (four waves, 4 * rows-per-lane rows of a strip) spread evenly over the 256 compute
     // units; the call lasts as long as the unit with the most rows.  A row on the side launch is counted
     // as 1.15 rows: fewer rows per lane reuse the column words less.
@@ -375,10 +376,98 @@ void even_round(const aht_tile* t, int B, uint32_t strips, uint32_t* strips_main
                 *rpl_side = side;
             }
         }
-    if (best > 0.93 * single) {                                  // not worth two events
+    if (best > 0.93 * single) {                                  // too little to gain
         *strips_main = strips;
         *rpl_main = *rpl_side = 0;
     }
+}
+
+// The cell update of step `step` as ONE launch of two shapes: strips 0 .. strips_main - 1 at rpl_main
+// rows per lane, the others at rpl_side (see even_round and k_cell_update_pair).
+template <int KIND, typename WordT, bool NOISE>
+void launch_pair_shape(int rpl_main, int rpl_side, dim3 grid, size_t lds, hipStream_t s, const CellPtrs& p,
+                       const CellArgs& a, const CellArgs& b, uint32_t main_blocks)
+{
+#define AHT_PAIR(RM, RS)                                                                                          \
+    do {                                                                                                         \
+        if (lds > 64 * 1024)                                                                                     \
+            (void)hipFuncSetAttribute((const void*)k_cell_update_pair<KIND, WordT, NOISE, RM, RS>,               \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                     \
+        hipLaunchKernelGGL((k_cell_update_pair<KIND, WordT, NOISE, RM, RS>), grid, dim3(256), lds, s, p.W, p.dw_up, \
+                           p.dw_down, p.b_max, p.b_min, p.slope_up, p.slope_down, (const WordT*)p.xw,            \
+                           (const WordT*)p.dw, p.pulse_count, a, b, main_blocks);                                \
+    } while (0)
+    if (rpl_main == 2) AHT_PAIR(2, 1);
+    else if (rpl_side == 2) AHT_PAIR(4, 2);
+    else AHT_PAIR(4, 1);
+#undef AHT_PAIR
+}
+
+template <typename WordT>
+void launch_pair_kind(int kind, bool noise, int rpl_main, int rpl_side, dim3 grid, size_t lds, hipStream_t s,
+                      const CellPtrs& p, const CellArgs& a, const CellArgs& b, uint32_t main_blocks)
+{
+#define AHT_PAIR_KIND(K)                                                                                          \
+    do {                                                                                                         \
+        if (noise) launch_pair_shape<K, WordT, true>(rpl_main, rpl_side, grid, lds, s, p, a, b, main_blocks);    \
+        else launch_pair_shape<K, WordT, false>(rpl_main, rpl_side, grid, lds, s, p, a, b, main_blocks);         \
+    } while (0)
+    switch (kind) {
+        case AHT_CONSTANT_STEP: AHT_PAIR_KIND(kConstantStep); break;
+        case AHT_LINEAR_STEP: AHT_PAIR_KIND(kLinearStep); break;
+        default: AHT_PAIR_KIND(kSoftBounds); break;
+    }
+#undef AHT_PAIR_KIND
+}
+
+aht_status launch_cells_pair(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strips, uint32_t strips_main,
+                             int rpl_main, int rpl_side)
+{
+    CellPtrs p{};
+    p.W = t->W;
+    weights_written(t);
+    p.dw_up = t->planes[AHT_PLANE_DW_UP];
+    p.dw_down = t->planes[AHT_PLANE_DW_DOWN];
+    p.b_max = t->planes[AHT_PLANE_B_MAX];
+    p.b_min = t->planes[AHT_PLANE_B_MIN];
+    p.slope_up = t->planes[AHT_PLANE_SLOPE_UP];
+    p.slope_down = t->planes[AHT_PLANE_SLOPE_DOWN];
+    p.xw = t->xw;
+    p.dw = t->dw;
+    p.pulse_count = t->pulse_count;
+    size_t lds = 0;
+    auto shape = [&](int rpl, uint32_t strip0, uint32_t nstrips) {
+        int qwords = env_int("AHT_QWORDS", 0);
+        if (qwords < 5 || qwords > 160) qwords = (rpl == 4) ? 9 : 12;
+        const size_t lds_extra = (rpl > 1) ? 4 * 1024 : 0;
+        while (qwords > 5 && (size_t)4 * rpl * 64 * qwords * 4 + lds_extra > 160 * 1024) --qwords;
+        const size_t need = (size_t)4 * rpl * 64 * qwords * 4 + lds_extra;
+        lds = need > lds ? need : lds;
+        CellArgs a{};
+        a.R = t->rows;
+        a.C = t->cols;
+        a.B = B;
+        a.Bpad = bpad(B);
+        a.Cpad = cpad(t);
+        a.nbx = nstrips;
+        a.bx0 = strip0;
+        a.nby = (uint32_t)((t->rows + 4 * rpl - 1) / (4 * rpl));
+        a.k0 = (uint32_t)t->seed;
+        a.k1 = (uint32_t)(t->seed >> 32);
+        a.t = step;
+        a.c2c = t->dev.dw_min_std;
+        a.qwords = qwords;
+        return a;
+    };
+    const CellArgs a = shape(rpl_main, 0u, strips_main), b = shape(rpl_side, strips_main, strips - strips_main);
+    const uint64_t main_blocks = ((uint64_t)a.nby * a.nbx + 7) / 8 * 8, side_blocks = ((uint64_t)b.nby * b.nbx + 7) / 8 * 8;
+    if (main_blocks + side_blocks > 0x7FFFFFFFull) return fail(AHT_ERR_UNSUPPORTED, "tile too large for one launch");
+    const dim3 grid((unsigned)(main_blocks + side_blocks));
+    const bool noise = t->dev.dw_min_std > 0.0f;
+    if (use_u32(t)) launch_pair_kind<uint32_t>(t->dev.kind, noise, rpl_main, rpl_side, grid, lds, s, p, a, b, (uint32_t)main_blocks);
+    else launch_pair_kind<uint64_t>(t->dev.kind, noise, rpl_main, rpl_side, grid, lds, s, p, a, b, (uint32_t)main_blocks);
+    AHT_HIP(hipGetLastError());
+    return AHT_OK;
 }
 
 bool finite_nonneg(float v) { return std::isfinite(v) && v >= 0.0f; }
@@ -552,17 +641,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         int rpl_main = 0, rpl_side = 0;
         if (col_hi < 0) even_round(t, B, strips, &strips_main, &rpl_main, &rpl_side);
         if (strips_main < strips) {
-            // the last strips with fewer rows per lane, beside the others, on a stream of the tile's own
-            if (!t->side_stream) AHT_HIP(hipStreamCreateWithFlags(&t->side_stream, hipStreamNonBlocking));
-            if (!t->side_fork) AHT_HIP(hipEventCreateWithFlags(&t->side_fork, hipEventDisableTiming));
-            if (!t->side_join) AHT_HIP(hipEventCreateWithFlags(&t->side_join, hipEventDisableTiming));
-            AHT_HIP(hipEventRecord(t->side_fork, s));
-            AHT_HIP(hipStreamWaitEvent(t->side_stream, t->side_fork, 0));
-            if ((st = launch_cells(t, B, t->step, s, 0u, strips_main, nullptr, rpl_main)) != AHT_OK) return st;
-            if ((st = launch_cells(t, B, t->step, t->side_stream, strips_main, strips - strips_main, nullptr,
-                                   rpl_side)) != AHT_OK) return st;
-            AHT_HIP(hipEventRecord(t->side_join, t->side_stream));
-            AHT_HIP(hipStreamWaitEvent(s, t->side_join, 0));
+            if ((st = launch_cells_pair(t, B, t->step, s, strips, strips_main, rpl_main, rpl_side)) != AHT_OK) return st;
         } else if ((st = launch_cells(t, B, t->step, s, strip0, strips)) != AHT_OK) return st;
         if (ev) {
             AHT_HIP(hipEventRecord(ev[2], s));

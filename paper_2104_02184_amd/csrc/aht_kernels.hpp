@@ -591,18 +591,15 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 // W [R][C] in/out; planes [R][C]; xw[B][Cpad], dw[Rpad][Bpad]: internal zero-padded pulse words.
 // The pointers are separate restrict-qualified parameters so that the wave-uniform row words
 // are fetched with scalar loads.
+// (The body is a device function of its own so that one launch can run it with two different
+// numbers of rows per lane, see k_cell_update_pair; `block` is the workgroup's index in its part.)
 template <int KIND, typename WordT, bool NOISE, int RPL>
-// Register budget: four waves per SIMD (128 registers) at four rows per lane, the variant of large
-// tiles, where the host also keeps the LDS streams short enough for four workgroups per compute unit
-// (the fourth wave gains more than the dozen spills outside the inner loops cost); five (96
-// registers) for 32-bit words at two rows per lane, the variant long batches on small tiles run;
-// three otherwise.
-__global__ void __launch_bounds__(256, (sizeof(WordT) == 4 && RPL == 2) ? 5 : (RPL == 4) ? 4 : 3)
-k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
-              const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
-              const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
-              const WordT* __restrict__ xw, const WordT* __restrict__ dw,
-              unsigned long long* __restrict__ pulse_count, CellArgs a)
+__device__ __forceinline__ void
+cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
+                 const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
+                 const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
+                 const WordT* __restrict__ xw, const WordT* __restrict__ dw,
+                 unsigned long long* __restrict__ pulse_count, const CellArgs& a, const uint32_t block)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
@@ -620,8 +617,8 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
     constexpr uint32_t kSuperY = 64, kSuperX = 8;
     const uint32_t total = a.nby * a.nbx;
     const uint32_t per = (total + 7u) >> 3;
-    const uint32_t seq = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
-    if ((blockIdx.x >> 3) >= per || seq >= total) return;
+    const uint32_t seq = (block & 7u) * per + (block >> 3);
+    if ((block >> 3) >= per || seq >= total) return;
     const uint32_t colsize = a.nby * kSuperX;                        // tiles of a full-width column of super-tiles
     uint32_t sx = seq / colsize;
     const uint32_t full_x = a.nbx / kSuperX;
@@ -1125,6 +1122,48 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
         for (int off = 32; off > 0; off >>= 1) pulses += __shfl_xor(pulses, off, 64);
         if (lane == 0 && pulses) atomicAdd(pulse_count, pulses);
     }
+}
+
+// Register budget: four waves per SIMD (128 registers) at four rows per lane, the variant of large
+// tiles, where the host also keeps the LDS streams short enough for four workgroups per compute unit
+// (the fourth wave gains more than the dozen spills outside the inner loops cost); five (96
+// registers) for 32-bit words at two rows per lane, the variant long batches on small tiles run;
+// three otherwise.
+template <typename WordT, int RPL>
+struct CellOccupancy {
+    static constexpr int kWorkgroups = (sizeof(WordT) == 4 && RPL == 2) ? 5 : (RPL == 4) ? 4 : 3;
+};
+
+template <int KIND, typename WordT, bool NOISE, int RPL>
+__global__ void __launch_bounds__(256, (CellOccupancy<WordT, RPL>::kWorkgroups))
+k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
+              const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
+              const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
+              const WordT* __restrict__ xw, const WordT* __restrict__ dw,
+              unsigned long long* __restrict__ pulse_count, CellArgs a)
+{
+    cell_update_body<KIND, WordT, NOISE, RPL>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down, xw, dw,
+                                              pulse_count, a, blockIdx.x);
+}
+
+// One launch, two shapes: the first `main_blocks` workgroups work on their range of column strips at RPL
+// rows per lane (arguments `a`), the others on theirs at SIDE rows per lane (arguments `b`), so that a
+// tile whose waves would not fill the SIMDs a whole number of times ends evenly without a second
+// launch.  Registers and LDS are those of the larger shape.
+template <int KIND, typename WordT, bool NOISE, int RPL, int SIDE>
+__global__ void __launch_bounds__(256, (CellOccupancy<WordT, RPL>::kWorkgroups))
+k_cell_update_pair(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
+                   const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
+                   const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
+                   const WordT* __restrict__ xw, const WordT* __restrict__ dw,
+                   unsigned long long* __restrict__ pulse_count, CellArgs a, CellArgs b, uint32_t main_blocks)
+{
+    if (blockIdx.x < main_blocks)
+        cell_update_body<KIND, WordT, NOISE, RPL>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down, xw,
+                                                  dw, pulse_count, a, blockIdx.x);
+    else
+        cell_update_body<KIND, WordT, NOISE, SIDE>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down, xw,
+                                                   dw, pulse_count, b, blockIdx.x - main_blocks);
 }
 
 }  // namespace aht

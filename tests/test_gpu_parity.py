@@ -323,11 +323,11 @@ def test_launch_shape_chosen_from_the_pulse_rate_changes_no_bit(env):
     (500, 784, 24, 0.1, 3, aht.SOFT_BOUNDS, 31),         # ragged in both directions
     (1024, 576, 16, 0.02, 6, aht.LINEAR_STEP, 31),       # few pulses: four rows per lane on 8 strips once the
 ])                                                       # tile has seen its pulse rate, one row on the ninth
-def test_two_launches_side_by_side_change_no_bit(R, C, B, lr, calls, kind, bl, monkeypatch):
+def test_two_shapes_in_one_launch_change_no_bit(R, C, B, lr, calls, kind, bl, monkeypatch):
     """A tile whose waves do not fill the SIMDs a whole number of times (256 x 2304 at two rows per lane:
-    4.5 waves per SIMD) runs most column strips at the chosen rows per lane and a few at fewer, as two
-    launches on two streams.  Same weights and pulse counts, bit for bit, as the single launch, call
-    after call, and the caller's stream sees the result."""
+    4.5 waves per SIMD) runs most column strips at the chosen rows per lane and a few at fewer, in one
+    launch of two shapes.  Same weights and pulse counts, bit for bit, as the single shape, call after
+    call."""
     dev = dict(kind=kind, dw_min=0.002, dw_min_dtod=0.3, dw_min_std=0.3, w_max=0.6, w_max_dtod=0.2, w_min=-0.6,
                w_min_dtod=0.2, gamma_up=0.4, gamma_down=0.6, gamma_dtod=0.1)
     g = np.random.default_rng(bl + R)

@@ -421,7 +421,7 @@ void launch_pair_kind(int kind, bool noise, int rpl_main, int rpl_side, dim3 gri
 }
 
 aht_status launch_cells_pair(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strips, uint32_t strips_main,
-                             int rpl_main, int rpl_side)
+                             int rpl_main, int rpl_side, const aht_tile* words = nullptr)
 {
     CellPtrs p{};
     p.W = t->W;
@@ -432,8 +432,8 @@ aht_status launch_cells_pair(aht_tile* t, int B, uint32_t step, hipStream_t s, u
     p.b_min = t->planes[AHT_PLANE_B_MIN];
     p.slope_up = t->planes[AHT_PLANE_SLOPE_UP];
     p.slope_down = t->planes[AHT_PLANE_SLOPE_DOWN];
-    p.xw = t->xw;
-    p.dw = t->dw;
+    p.xw = words ? words->xw : t->xw;
+    p.dw = words ? words->dw : t->dw;
     p.pulse_count = t->pulse_count;
     size_t lds = 0;
     auto shape = [&](int rpl, uint32_t strip0, uint32_t nstrips) {
@@ -1015,7 +1015,13 @@ aht_status aht_unit_cell_update(aht_tile* const* dev, int32_t n, int32_t which, 
                 sk = dev[k]->side_stream;
                 AHT_HIP(hipStreamWaitEvent(sk, lead->side_fork, 0));
             }
-            if ((st = launch_cells(dev[k], B, step, sk, 0u, strips, lead)) != AHT_OK) return st;
+            uint32_t strips_main = strips;
+            int rpl_main = 0, rpl_side = 0;
+            even_round(dev[k], B, strips, &strips_main, &rpl_main, &rpl_side);
+            if (strips_main < strips) {
+                if ((st = launch_cells_pair(dev[k], B, step, sk, strips, strips_main, rpl_main, rpl_side, lead)) != AHT_OK)
+                    return st;
+            } else if ((st = launch_cells(dev[k], B, step, sk, 0u, strips, lead)) != AHT_OK) return st;
             if (sk != s) {
                 AHT_HIP(hipEventRecord(dev[k]->side_join, sk));
                 AHT_HIP(hipStreamWaitEvent(s, dev[k]->side_join, 0));

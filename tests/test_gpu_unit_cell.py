@@ -130,6 +130,32 @@ def test_unit_cell_product_follows_every_change_of_its_devices():
         t_.close()
 
 
+def test_unit_cell_devices_beside_each_other_and_in_two_shapes_change_no_bit(monkeypatch):
+    """All devices updated: those after the first run on streams of their own tiles, and a 256 x 768 tile
+    (1.5 waves per SIMD at two rows per lane) takes some strips at one row per lane.  Same bits as one
+    device after the other in a single shape."""
+    R, C, B, bl = 256, 768, 20, 31
+    g = np.random.default_rng(8)
+    W0 = [g.uniform(-0.2, 0.2, size=(R, C)).astype(np.float32) for _ in DEVS]
+    xs = [g.normal(size=(B, C)).astype(np.float32) for _ in range(3)]
+    ds = [g.normal(size=(B, R)).astype(np.float32) for _ in range(3)]
+    out = {}
+    for mode in ("0", "2"):
+        monkeypatch.setenv("AHT_EVEN_ROUND", mode)
+        tiles = [aht.Tile(R, C, gpu_params(dv), bl, True, 40 + k) for k, dv in enumerate(DEVS)]
+        for t_, W in zip(tiles, W0):
+            t_.set_weights(to_dev(W))
+        cell = aht.UnitCell(tiles, [1.0, 0.5, -0.25])
+        for x, d, which in zip(xs, ds, (-1, 2, -1)):
+            cell.pulsed_update(to_dev(x), to_dev(d), 0.1, which)
+        out[mode] = ([t_.get_weights().cpu().numpy() for t_ in tiles], [t_.pulse_count() for t_ in tiles])
+        for t_ in tiles:
+            t_.close()
+    assert out["0"][1] == out["2"][1] and all(p > 0 for p in out["0"][1])
+    for a, b in zip(out["0"][0], out["2"][0]):
+        assert (a.view(np.uint32) == b.view(np.uint32)).all()
+
+
 def test_unit_cell_rejects_mismatched_devices():
     a = aht.Tile(64, 64, aht.DeviceParams(), 31, False, 1)
     b = aht.Tile(64, 128, aht.DeviceParams(), 31, False, 2)

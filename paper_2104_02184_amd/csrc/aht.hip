@@ -286,9 +286,9 @@ void refresh_pulse_rate(aht_tile* t)
 // `strip0`, `strips`: the range of 64-column strips to work on (the caller knows that x is zero elsewhere)
 // `words`: the tile whose scratch holds the pulse words (the tile itself, or the first device of its unit cell)
 aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strip0, uint32_t strips,
-                        const aht_tile* words = nullptr, int rpl_forced = 0)
+                        const aht_tile* words = nullptr)
 {
-    const int rpl = rpl_forced ? rpl_forced : choose_rpl(t);
+    const int rpl = choose_rpl(t);
     // stream storage per cell: 12 words hold 320 pulses before an early drain is needed; at 4 rows
     // per lane, 9 words (224 pulses) let four workgroups share a compute unit's LDS
     int qwords = env_int("AHT_QWORDS", 0);

@@ -19,7 +19,9 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "pulsed_update_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# AHT_ORACLE_LIB names an already built oracle library to load instead (the sanitizer and
+# mutation checks of the test-suite build their own copies elsewhere and point here).
+_LIB = os.environ.get("AHT_ORACLE_LIB") or os.path.join(_HERE, "liboracle.so")
 
 CONSTANT_STEP, LINEAR_STEP, SOFT_BOUNDS = 0, 1, 2
 TAG_X, TAG_D, TAG_C2C, TAG_D2D = 1, 2, 3, 4
@@ -27,6 +29,8 @@ TAG_X, TAG_D, TAG_C2C, TAG_D2D = 1, 2, 3, 4
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no FMA contraction, no fast-math)."""
+    if os.environ.get("AHT_ORACLE_LIB"):
+        return _LIB                    # a library built by the caller: never overwritten
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
                "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
@@ -95,6 +99,8 @@ def _declare(L):
     L.orc_pulsed_update_ex.restype = ctypes.c_int64
     L.orc_analog_mvm.argtypes = [_f32p, _i, _i, _i, _f32p, _i] + [_f] * 7 + [_i, _u64, _u32, _f32p, _f32p]
     L.orc_analog_mvm.restype = None
+    L.orc_analog_mvm_cellwise.argtypes = L.orc_analog_mvm.argtypes
+    L.orc_analog_mvm_cellwise.restype = None
     L.orc_conv_patches.argtypes = [_f32p] + [_i] * 8 + [_f32p]
     L.orc_conv_patches.restype = None
     L.orc_conv_rows.argtypes = [_f32p, _i, _i, _i, _i, _f32p]
@@ -299,8 +305,10 @@ class IOParams:
     noise_management: bool = True
 
 
-def analog_mvm(W, x, io: IOParams, seed, t, transposed=False, return_pre=False):
-    """y[B][R] = analog product of x[B][C] with W[R][C] (transposed: x[B][R] -> y[B][C])."""
+def analog_mvm(W, x, io: IOParams, seed, t, transposed=False, return_pre=False, cellwise_weight_noise=False):
+    """y[B][R] = analog product of x[B][C] with W[R][C] (transposed: x[B][R] -> y[B][C]).
+    ``cellwise_weight_noise``: a fresh Gaussian for every cell and vector, Eq. (1) as printed,
+    instead of the output-referred draw (same law)."""
     W = _f32(W)
     x = _f32(x)
     R, C = W.shape
@@ -309,7 +317,8 @@ def analog_mvm(W, x, io: IOParams, seed, t, transposed=False, return_pre=False):
     assert x.shape[1] == (R if transposed else C)
     y = np.zeros((B, N), dtype=np.float32)
     pre = np.zeros((B, N), dtype=np.float32)
-    lib().orc_analog_mvm(_p(W, _f32p), R, C, int(transposed), _p(x, _f32p), B, io.inp_res, io.inp_bound,
+    fn = lib().orc_analog_mvm_cellwise if cellwise_weight_noise else lib().orc_analog_mvm
+    fn(_p(W, _f32p), R, C, int(transposed), _p(x, _f32p), B, io.inp_res, io.inp_bound,
                          io.inp_noise, io.w_noise, io.out_noise, io.out_res, io.out_bound,
                          int(io.noise_management), seed, t, _p(y, _f32p), _p(pre, _f32p))
     return (y, pre) if return_pre else y

@@ -258,8 +258,8 @@ uint64_t orc_pulse_word(uint64_t seed, uint32_t t, uint32_t tag, uint32_t index,
     return word;
 }
 
-/* Deterministic train (reading R15 of the paper's "stochastic (or deterministic) pulse
- * trains"): no random numbers; pulse n of a line is set iff u_n < T/2^32 with
+/* Deterministic train (reading R15; Sec. 3 names trains without randomness beside the
+ * stochastic ones, and gives no rule): no random numbers; pulse n of a line is set iff u_n < T/2^32 with
  *   column lines:  u_n = (n + 1/2) / BL        (evenly spaced pulses)
  *   row lines:     u_n = (bit-reversal of n  XOR  0xAAAAAAAA) / 2^32
  *                  (van der Corput sequence with an alternating digital shift)
@@ -483,11 +483,11 @@ void orc_gauss_fill(uint64_t seed, uint32_t index0, int n_index, uint32_t t, int
  *     reset_ij  = reset + reset_dtod*g9
  *   once per mini-batch (temporal step tau):
  *     w <- w * (1 - lambda_ij)                      (decay toward 0)
- *     w <- w + sdiff_ij * xi,  xi = Gaussian (cell & 3) of block
- *          (index = cell >> 2, blk = 0, t = tau, tag 5)   (four neighbours share a block)
+ *     w <- w + sdiff_ij * xi,  xi = Gaussian number `cell` of the step's one stream
+ *          (index 0, t = tau, tag 5): the cells of the tile number the stream's Gaussians
  *     w <- clamp(w, b_min, b_max)
  *   reset of columns [c0, c0+n): w <- clamp(reset_ij + reset_std * xi', ...),
- *     xi' from the same keying with tag 6.
+ *     xi' = Gaussian number `cell` of stream (index 0, t = tau, tag 6).
  * fp32 arithmetic, every operation rounded separately.
  * ---------------------------------------------------------------------- */
 enum { ORC_TAG_DIFFUSION = 5, ORC_TAG_RESET = 6 };
@@ -514,9 +514,7 @@ void orc_temporal_planes(float decay_rate, float decay_rate_dtod, float diffusio
 
 static float temporal_gauss(uint64_t seed, uint32_t cell, uint32_t tau, uint32_t tag)
 {
-    double z[4];
-    orc_gauss_block_f64(seed, cell >> 2, tau, 0u, tag, z);
-    return (float)z[cell & 3];
+    return orc_gauss(seed, 0u, tau, cell, tag);
 }
 
 void orc_decay_diffuse(float *W, const float *lambda, const float *sdiff, const float *b_max,
@@ -566,7 +564,10 @@ void orc_reset_columns(float *W, const float *reset_plane, float reset_std, cons
  *      t = call counter, tag 7 forward / 9 backward).
  *   F4 weight noise, output referred: the sum over j of s_w xi_ij xq_j of fresh
  *      independent xi_ij is N(0, s_w^2 |xq|^2) and independent across i, so it is
- *      drawn as s_w * |xq|_2 * one Gaussian per output.
+ *      drawn as s_w * |xq|_2 * one Gaussian per output.  orc_analog_mvm_cellwise is
+ *      Eq. (1) as printed, with a fresh xi_ij for every cell and vector (Gaussian 0 of
+ *      block (index = cell i*C+j, word b, t, tag 11 forward / 12 backward)); the tests
+ *      hold the output-referred form against it in law.
  *   F5 output noise: s_out * one Gaussian per output.  Output i takes Gaussians
  *      2(i&1) (output noise) and 2(i&1)+1 (weight noise) of block (index i>>1,
  *      word b, t, tag 8 forward / 10 backward).
@@ -577,9 +578,10 @@ void orc_reset_columns(float *W, const float *reset_plane, float reset_std, cons
  * transposed == 0: x[B][C] -> y[B][R] with W[R][C];  != 0: x[B][R] -> y[B][C].
  * pre (optional) receives the value entering f_adc.
  * ---------------------------------------------------------------------- */
-void orc_analog_mvm(const float *W, int R, int C, int transposed, const float *x, int B, float inp_res,
-                    float inp_bound, float inp_noise, float w_noise, float out_noise, float out_res,
-                    float out_bound, int noise_management, uint64_t seed, uint32_t t, float *y, float *pre)
+static void analog_mvm(const float *W, int R, int C, int transposed, const float *x, int B, float inp_res,
+                       float inp_bound, float inp_noise, float w_noise, float out_noise, float out_res,
+                       float out_bound, int noise_management, uint64_t seed, uint32_t t, float *y, float *pre,
+                       int cellwise)
 {
     const int K = transposed ? R : C;      /* input length */
     const int N = transposed ? C : R;      /* output length */
@@ -618,17 +620,25 @@ void orc_analog_mvm(const float *W, int R, int C, int transposed, const float *x
         for (int i = 0; i < N; ++i) {
             double acc = 0.0;
             for (int j = 0; j < K; ++j) {
-                float w = transposed ? W[(size_t)j * C + i] : W[(size_t)i * C + j];
-                acc += (double)w * (double)xq[j];
+                size_t cell = transposed ? (size_t)j * C + i : (size_t)i * C + j;
+                double w = (double)W[cell];
+                if (cellwise && w_noise > 0.0f) {  /* Eq. (1) as printed: w_ij + s_w xi_ij */
+                    double zc[4];
+                    orc_gauss_block_f64(seed, (uint32_t)cell, t, (uint32_t)b, transposed ? 12u : 11u, zc);
+                    w += (double)w_noise * zc[0];
+                }
+                acc += w * (double)xq[j];
             }
             float z = (float)acc;
             if (w_noise > 0.0f || out_noise > 0.0f) {
                 double zb[4];                     /* counter (i>>1, b, t, tag) */
                 orc_gauss_block_f64(seed, (uint32_t)i >> 1, t, (uint32_t)b, tag_out, zb);
                 float g_out = (float)zb[2 * (i & 1)], g_w = (float)zb[2 * (i & 1) + 1];
-                float wn = w_noise * norm;
-                wn = wn * g_w;
-                z = z + wn;
+                if (!cellwise) {                  /* F4: the same law, one Gaussian per output */
+                    float wn = w_noise * norm;
+                    wn = wn * g_w;
+                    z = z + wn;
+                }
                 float on = out_noise * g_out;
                 z = z + on;
             }
@@ -641,9 +651,27 @@ void orc_analog_mvm(const float *W, int R, int C, int transposed, const float *x
     }
 }
 
+void orc_analog_mvm(const float *W, int R, int C, int transposed, const float *x, int B, float inp_res,
+                    float inp_bound, float inp_noise, float w_noise, float out_noise, float out_res,
+                    float out_bound, int noise_management, uint64_t seed, uint32_t t, float *y, float *pre)
+{
+    analog_mvm(W, R, C, transposed, x, B, inp_res, inp_bound, inp_noise, w_noise, out_noise, out_res, out_bound,
+               noise_management, seed, t, y, pre, 0);
+}
+
+/* Eq. (1) with the weight noise drawn per cell and vector, as printed (R*C Gaussians per vector). */
+void orc_analog_mvm_cellwise(const float *W, int R, int C, int transposed, const float *x, int B, float inp_res,
+                             float inp_bound, float inp_noise, float w_noise, float out_noise, float out_res,
+                             float out_bound, int noise_management, uint64_t seed, uint32_t t, float *y,
+                             float *pre)
+{
+    analog_mvm(W, R, C, transposed, x, B, inp_res, inp_bound, inp_noise, w_noise, out_noise, out_res, out_bound,
+               noise_management, seed, t, y, pre, 1);
+}
+
 /* ------------------------------------------------------------------------
- * Convolution layers (Sec. 3: "gradient accumulation happens using parallel update in
- * analog memory even for batch sizes larger than 1 or in case of convolutions").  A
+ * Convolution layers (Sec. 3, paragraph on batch sizes larger than one and convolutions: their
+ * rank-1 updates, too, are summed up by the analog weights themselves, one after the other).  A
  * convolution maps on a tile with one row per output channel and one column per
  * (input channel, kernel row, kernel column); every output position of every image is one
  * update vector.  These two functions write the update vectors out explicitly:

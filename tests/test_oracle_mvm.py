@@ -109,3 +109,55 @@ def test_noise_is_keyed_by_output_sample_and_call():
         for i in range(8):
             z = oracle.gauss_block_f64(9, i >> 1, 4, b, 8)[2 * (i & 1)]
             assert pre[b, i] - clean[b, i] == pytest.approx(0.5 * z, abs=2e-6)
+
+
+def test_output_referred_weight_noise_has_the_law_of_a_fresh_gaussian_per_cell():
+    """Eq. (1) puts a Gaussian on every weight of every product.  The oracle's (and the kernels')
+    product draws the sum of those terms directly, one Gaussian per output (reading F4); here it is
+    held against the equation as printed, orc_analog_mvm_cellwise, in law: mean, variance per vector
+    and output, independence across outputs and vectors, and the whole distribution (two-sample KS)."""
+    from scipy import stats
+    W, x, d = data(R=10, C=24, B=3, seed=4)
+    x[1] *= f32(3.0)                                   # vectors of different norm
+    base = IOParams(inp_res=0.0, inp_bound=1e30, out_res=0.0, out_bound=1e30, out_noise=0.0, noise_management=False)
+    io = IOParams(**{**base.__dict__, "w_noise": 0.05})
+    for transposed, inp in ((False, x), (True, d)):
+        clean = oracle.analog_mvm(W, inp, base, 7, 0, transposed=transposed, return_pre=True)[1]
+        # without weight noise the two forms are the same function
+        assert (oracle.analog_mvm(W, inp, base, 7, 0, transposed=transposed, cellwise_weight_noise=True) ==
+                oracle.analog_mvm(W, inp, base, 7, 0, transposed=transposed)).all()
+        N = 1500
+        ref = np.stack([oracle.analog_mvm(W, inp, io, 7, t, transposed=transposed, return_pre=True)[1]
+                        for t in range(N)]) - clean
+        cel = np.stack([oracle.analog_mvm(W, inp, io, 7, t, transposed=transposed, return_pre=True,
+                                          cellwise_weight_noise=True)[1] for t in range(N)]) - clean
+        want = 0.05 * np.linalg.norm(inp.astype(np.float64), axis=1)          # std per vector
+        for r in (ref, cel):
+            assert np.abs(r.mean(axis=0)).max() < 5 * want.max() / math.sqrt(N)
+            assert np.allclose(r.std(axis=0), want[:, None], rtol=0.12)       # every (vector, output)
+            assert np.allclose(r.std(axis=(0, 2)), want, rtol=0.03)
+            assert abs(np.corrcoef(r[:, 0, 0], r[:, 0, 1])[0, 1]) < 4.5 / math.sqrt(N)     # across outputs
+            assert abs(np.corrcoef(r[:, 0, 2], r[:, 1, 2])[0, 1]) < 4.5 / math.sqrt(N)     # across vectors
+        for b in range(inp.shape[0]):
+            assert stats.ks_2samp(ref[:, b, :].ravel(), cel[:, b, :].ravel()).pvalue > 1e-3
+            assert stats.kstest(cel[:, b, :].ravel() / want[b], "norm").pvalue > 1e-3
+        # the two forms use different random numbers (the cellwise one its own streams)
+        assert abs(np.corrcoef(ref.ravel(), cel.ravel())[0, 1]) < 0.02
+
+
+def test_cellwise_weight_noise_is_keyed_by_cell_vector_and_call():
+    W, x, d = data(R=3, C=5, B=2, seed=6)
+    base = IOParams(inp_res=0.0, inp_bound=1e30, out_res=0.0, out_bound=1e30, out_noise=0.0, noise_management=False)
+    io = IOParams(**{**base.__dict__, "w_noise": 0.25})
+    pre = oracle.analog_mvm(W, x, io, 3, 9, return_pre=True, cellwise_weight_noise=True)[1]
+    for b in range(2):
+        for i in range(3):
+            acc = sum((float(W[i, j]) + float(f32(0.25)) * oracle.gauss_block_f64(3, i * 5 + j, 9, b, 11)[0]) * float(x[b, j])
+                      for j in range(5))
+            assert pre[b, i] == pytest.approx(acc, rel=1e-6, abs=1e-6)
+    pre = oracle.analog_mvm(W, d, io, 3, 9, transposed=True, return_pre=True, cellwise_weight_noise=True)[1]
+    for b in range(2):
+        for j in range(5):
+            acc = sum((float(W[i, j]) + float(f32(0.25)) * oracle.gauss_block_f64(3, i * 5 + j, 9, b, 12)[0]) * float(d[b, i])
+                      for i in range(3))
+            assert pre[b, j] == pytest.approx(acc, rel=1e-6, abs=1e-6)

@@ -52,15 +52,16 @@ def test_diffusion_is_a_gaussian_random_walk():
     n = R * C
     assert abs(W.mean()) < 4 * sd * math.sqrt(K / n)
     assert abs(W.var() / (K * sd * sd) - 1) < 4 * math.sqrt(2.0 / n)
-    # increments of different steps and of neighbouring cells (same Philox block) are uncorrelated
+    # increments of different steps and of neighbouring cells (numbers of one block) are uncorrelated
     a, b = incs[0].ravel(), incs[1].ravel()
     assert abs(np.corrcoef(a, b)[0, 1]) < 4 / math.sqrt(n)
     assert abs(np.corrcoef(a[0::4], a[1::4])[0, 1]) < 4 / math.sqrt(n / 4)
     assert abs(np.corrcoef(a[0::4], a[3::4])[0, 1]) < 4 / math.sqrt(n / 4)
-    # and each increment is the stream's Gaussian (cell & 3) of block (cell >> 2, t = tau, tag 5)
+    # and each increment is Gaussian number `cell` of the step's stream (index 0, t = tau, tag 5)
     for cell in (0, 1, 2, 3, 4, 77, n - 1):
-        z = oracle.gauss_block_f64(5, cell >> 2, 3, 0, 5)[cell & 3]
+        z = oracle.gauss(5, 0, 3, cell, 5)
         assert incs[3].ravel()[cell] == pytest.approx(float(f32(z)), abs=1e-5)
+        assert z == float(f32(oracle.gauss_block_f64(5, 0, 3, cell >> 2, 5)[cell & 3]))
 
 
 def test_clipping_after_diffusion_and_bounds_hold():
@@ -107,6 +108,10 @@ def test_reset_touches_only_the_selected_columns():
     assert (W[:, :5] == W0[:, :5]).all() and (W[:, 15:] == W0[:, 15:]).all()
     dev = (W[:, 5:15].astype(np.float64) - tpl["reset"][:, 5:15]) / 0.002
     assert abs(dev.mean()) < 4 / math.sqrt(dev.size) and abs(dev.std() - 1) < 0.2
+    # every reset value is the plane plus Gaussian number `cell` of stream (index 0, t = tau, tag 6)
+    for i, j in ((0, 5), (3, 9), (R - 1, 14)):
+        want = float(tpl["reset"][i, j]) + float(f32(0.002)) * oracle.gauss(4, 0, 7, i * C + j, 6)
+        assert W[i, j] == pytest.approx(want, abs=1e-7)
     # without noise the reset value is the plane itself
     W2 = W0.copy()
     oracle.reset_columns(W2, tpl, 0.0, wide_planes(R, C), 4, 7, 0, C)

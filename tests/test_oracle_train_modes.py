@@ -1,6 +1,6 @@
-"""Pins for the oracle's alternative pulse-train generators: per-sample train length
-("variable or fixed length") and deterministic trains ("stochastic (or deterministic) pulse
-trains"), arXiv 2104.02184 Sec. 3.  Expected values: exact integer/rational closed forms, the
+"""Pins for the oracle's alternative pulse-train generators: a train length chosen per update
+vector and trains without randomness, both of which arXiv 2104.02184 Sec. 3 names beside the
+stochastic fixed-length trains without giving their rules.  Expected values: exact integer/rational closed forms, the
 Hammersley discrepancy bound, and the unchanged mean update."""
 import math
 from fractions import Fraction

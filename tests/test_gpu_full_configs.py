@@ -1,8 +1,14 @@
 """GPU parity at the full sizes of the five workloads, in the launch configuration the
-benchmark uses.  The GPU runs the whole tile for the full number of update calls; the oracle
-draws all pulse words of every call but applies them to a sample of cells only (cells are
-independent given the words): 4096 random cells, the first and last row, the first and last
-column.  Pulse words of the first call are compared bit for bit on the whole tile."""
+benchmark uses, on EVERY cell of the tile and for EVERY update call of the workload.
+
+Per workload the GPU runs the whole sequence of calls once (weights and the device's pulse
+counter are read back after every call, the pulse words of every call are compared bit for
+bit with the oracle's).  The oracle then repeats the sequence on all cells; since cells are
+independent given the pulse words, the large tiles are cut into slabs of rows, one test per
+slab, so that no single test is silent for long.  Compared: weights after every call within
+1e-5 w_max on every cell, and the number of coincidence pulses applied by every call, which
+must be equal (a dropped or doubled tile of cells changes it).
+"""
 import time
 
 import numpy as np
@@ -17,58 +23,109 @@ from common import gpu_planes, make_tile, oracle_params, to_dev, words_to_np
 pytestmark = pytest.mark.gpu
 WEIGHT_TOL = 1e-5
 
+# slabs of rows per workload: the oracle needs about 35 s per slab on 16 host threads
+SLABS = {"cfg1_64x64_constant": 1, "cfg2_512x512_constant_d2d": 1, "cfg3_1024x1024_softbounds": 1,
+         "cfg4_conv_256x2304": 2, "cfg5_4096x4096_linearstep": 4}
+_CASES = [(name, k) for name in wl.WORKLOADS for k in range(SLABS[name])]
 
-def _sample_cells(w, n_random=4096):
-    g = np.random.default_rng(12345)
-    R, C = w.rows, w.cols
-    cells = set(int(v) for v in g.integers(0, R * C, size=n_random))
-    cells.update(range(0, C))                              # first row
-    cells.update(range((R - 1) * C, R * C))                # last row
-    cells.update(range(0, R * C, C))                       # first column
-    cells.update(range(C - 1, R * C, C))                   # last column
-    return np.array(sorted(cells), dtype=np.int64)
+_runs = {}            # workload name -> what the GPU produced (freed when the module is done)
+_oracle_pulses = {}   # (workload name, slab) -> applied pulses per call on that slab
 
 
-@pytest.mark.parametrize("name", list(wl.WORKLOADS))
-def test_full_size_workload_matches_oracle_on_sampled_cells(name):
+@pytest.fixture(scope="module", autouse=True)
+def _free_runs():
+    yield
+    _runs.clear()
+    _oracle_pulses.clear()
+
+
+def _say(capsys, msg):
+    with capsys.disabled():
+        print(msg, flush=True)
+
+
+def _gpu_run(name, capsys):
+    """All update calls of the workload on the GPU; weights and pulse counter after every call."""
+    if name in _runs:
+        return _runs[name]
     import torch
     w = wl.WORKLOADS[name]
     t0 = time.time()
     tile = make_tile(w)
-    cells = _sample_cells(w)
-    # planes: oracle's own, compared with the library's on the sampled cells
     oplanes = oracle.device_planes(oracle_params(w.device), w.seed, w.rows, w.cols)
     gplanes = gpu_planes(tile)
-    for n in aht.PLANE_NAMES:
-        a, b = gplanes[n].ravel()[cells].astype(np.float64), oplanes[n].ravel()[cells].astype(np.float64)
+    for n in aht.PLANE_NAMES:                              # every cell of every plane
+        a, b = gplanes[n].astype(np.float64), oplanes[n].astype(np.float64)
         assert np.all(np.abs(a - b) <= 1e-6 * np.abs(b)), n
     del gplanes
     W0 = np.clip(wl.initial_weights(w), oplanes["b_min"], oplanes["b_max"]).astype(np.float32)
     tile.set_weights(to_dev(W0))
-    Wo = W0.copy()
-    p = oracle_params(w.device)
+    after, pulses, seen = [], [], 0
     for t, x, d in wl.input_stream(w):
         xd, dd = to_dev(x), to_dev(d)
-        if t == 0:                                         # whole-tile pulse words of the first call
-            xw, dw = tile.debug_pulse_words(xd, dd, w.lr)
-            oxw, odw = oracle.pulse_words(x, d, w.lr, w.device["dw_min"], w.bl, w.update_management, w.seed, 0)
-            assert (words_to_np(xw) == oxw).all() and (words_to_np(dw) == odw).all()
-            del xw, dw, oxw, odw
+        xw, dw = tile.debug_pulse_words(xd, dd, w.lr)      # whole-tile pulse words of this call
+        oxw, odw = oracle.pulse_words(x, d, w.lr, w.device["dw_min"], w.bl, w.update_management, w.seed, t)
+        assert (words_to_np(xw) == oxw).all() and (words_to_np(dw) == odw).all(), f"pulse words of call {t}"
+        del xw, dw, oxw, odw
         tile.pulsed_update(xd, dd, w.lr)
-        oracle.pulsed_update(Wo, oplanes, p, w.bl, w.update_management, x, d, w.lr, w.seed, t, cells=cells)
-        print(f"{name}: step {t + 1}/{w.steps} ({time.time() - t0:.0f} s)", flush=True)
+        after.append(tile.get_weights().cpu().numpy())
+        torch.cuda.synchronize()
+        total = tile.pulse_count()
+        pulses.append(total - seen)
+        seen = total
+        if (t + 1) % 10 == 0 or w.steps <= 20:
+            _say(capsys, f"  {name}: GPU call {t + 1}/{w.steps} ({time.time() - t0:.0f} s)")
     assert tile.step == w.steps
-    Wg = tile.get_weights().cpu().numpy()
-    torch.cuda.synchronize()
     tile.close()
-    err = np.abs(Wg.ravel()[cells].astype(np.float64) - Wo.ravel()[cells].astype(np.float64)) / w.device["w_max"]
-    moved = np.abs(Wo.ravel()[cells] - W0.ravel()[cells]).mean()
-    print(f"{name}: {cells.size} sampled cells, max |dw|/w_max = {err.max():.3e}, mean |w - w0| = {moved:.3e}")
-    assert err.max() <= WEIGHT_TOL
+    _runs[name] = dict(W0=W0, planes=oplanes, after=after, pulses=pulses)
+    return _runs[name]
+
+
+@pytest.mark.parametrize("name,slab", _CASES, ids=[f"{n}-slab{k}" for n, k in _CASES])
+def test_full_size_workload_matches_oracle_on_every_cell(name, slab, capsys):
+    w = wl.WORKLOADS[name]
+    run = _gpu_run(name, capsys)
+    nslabs = SLABS[name]
+    r0, r1 = w.rows * slab // nslabs, w.rows * (slab + 1) // nslabs
+    cells = np.arange(r0 * w.cols, r1 * w.cols, dtype=np.int64)
+    p = oracle_params(w.device)
+    Wo = run["W0"].copy()
+    t0 = time.time()
+    worst, counts = 0.0, []
+    for t, x, d in wl.input_stream(w):
+        counts.append(oracle.pulsed_update(Wo, run["planes"], p, w.bl, w.update_management, x, d, w.lr,
+                                           w.seed, t, cells=cells))
+        err = np.abs(run["after"][t][r0:r1].astype(np.float64) - Wo[r0:r1].astype(np.float64)).max() / w.device["w_max"]
+        worst = max(worst, float(err))
+        assert err <= WEIGHT_TOL, f"{name} rows {r0}..{r1 - 1} after call {t}: {err:.3e}"
+        if (t + 1) % 10 == 0 or w.steps <= 20:
+            _say(capsys, f"  {name} rows {r0}..{r1 - 1}: oracle call {t + 1}/{w.steps} ({time.time() - t0:.0f} s)")
+    _oracle_pulses[(name, slab)] = counts
+    Wg = run["after"][-1][r0:r1]
+    moved = np.abs(Wo[r0:r1] - run["W0"][r0:r1]).mean()
+    _say(capsys, f"  {name} rows {r0}..{r1 - 1}: every cell, {w.steps} calls, max |dw|/w_max = {worst:.3e}, "
+                 f"mean |w - w0| = {moved:.3e}")
     assert moved > 0                                       # the update did something
-    # properties that hold for every cell: inside the per-cell bounds, finite
+    bmax, bmin = run["planes"]["b_max"][r0:r1], run["planes"]["b_min"][r0:r1]
     assert np.isfinite(Wg).all()
-    assert (Wg <= oplanes["b_max"] * (1 + 1e-6) + 1e-12).all() and (Wg >= oplanes["b_min"] * (1 + 1e-6) - 1e-12).all()
+    assert (Wg <= bmax * (1 + 1e-6) + 1e-12).all() and (Wg >= bmin * (1 + 1e-6) - 1e-12).all()
+    if nslabs == 1:
+        assert run["pulses"] == counts
+
+
+@pytest.mark.parametrize("name", [n for n in wl.WORKLOADS if SLABS[n] > 1])
+def test_full_size_pulse_totals_equal_oracle(name, capsys):
+    """Applied pulses of every call: the device's counter against the oracle's count summed over
+    the slabs (which the slab tests above have left behind; a slab not yet run is run here)."""
+    w = wl.WORKLOADS[name]
+    run = _gpu_run(name, capsys)
+    for k in range(SLABS[name]):
+        if (name, k) not in _oracle_pulses:
+            test_full_size_workload_matches_oracle_on_every_cell(name, k, capsys)
+    per_call = [sum(_oracle_pulses[(name, k)][t] for k in range(SLABS[name])) for t in range(w.steps)]
+    _say(capsys, f"  {name}: pulses per call, first and last: GPU {run['pulses'][0]}, {run['pulses'][-1]}; "
+                 f"oracle {per_call[0]}, {per_call[-1]}")
+    assert run["pulses"] == per_call
 
 
 @pytest.mark.parametrize("transposed", [False, True])

@@ -136,8 +136,9 @@ __global__ void __launch_bounds__(256) k_negate(const float* in, float* out, int
 // ------------------------------------------------------------------------------------------
 // Temporal processes, once per mini-batch (Sec. 4, last paragraph of the paper): decay,
 // diffusion and reset with per-cell parameters.  The planes use Gaussians 6, 7, 8 of the
-// device-to-device stream; the per-step Gaussians of four neighbouring cells share one Philox
-// block (index = cell >> 2, t = temporal step, tag 5 for diffusion, 6 for reset).
+// device-to-device stream; the noise of a cell in one temporal step is Gaussian number `cell` of
+// that step's stream (index 0, t = temporal step, tag 5 for diffusion, 6 for reset), so that four
+// neighbouring cells use the four numbers of one block.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kTagDiffusion = 5u, kTagReset = 6u;
 
@@ -167,7 +168,7 @@ k_decay_diffuse(float* __restrict__ W, const float* __restrict__ decay, const fl
     const size_t k = g * 4;
     if (k >= n) return;
     float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (with_diffusion) gauss4_fast(k0, k1, (uint32_t)g, 0u, tau, kTagDiffusion, z);
+    if (with_diffusion) gauss4_fast(k0, k1, 0u, (uint32_t)g, tau, kTagDiffusion, z);
     if (k + 4 <= n) {
         float4 w = *(const float4*)(W + k);
         const float4 la = *(const float4*)(decay + k), sd = *(const float4*)(sdiff + k);
@@ -193,7 +194,7 @@ k_reset_columns(float* __restrict__ W, const float* __restrict__ rplane, float r
     const int i = (int)(t / (size_t)ncols), j = c0 + (int)(t % (size_t)ncols);
     const size_t k = (size_t)i * C + j;
     float z[4];
-    gauss4_fast(k0, k1, (uint32_t)(k >> 2), 0u, tau, kTagReset, z);
+    gauss4_fast(k0, k1, 0u, (uint32_t)(k >> 2), tau, kTagReset, z);
     const uint32_t e = (uint32_t)k & 3u;
     const float xi = e == 0 ? z[0] : e == 1 ? z[1] : e == 2 ? z[2] : z[3];
     W[k] = fminf(fmaxf(rplane[k] + reset_std * xi, b_min[k]), b_max[k]);

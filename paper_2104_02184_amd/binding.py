@@ -11,7 +11,8 @@ import os
 from dataclasses import dataclass, fields
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(HERE, "libaht.so")
+# AHT_LIB names a library built elsewhere to load instead (the host-sanitizer check of the test-suite)
+_LIB_PATH = os.environ.get("AHT_LIB") or os.path.join(HERE, "libaht.so")
 
 CONSTANT_STEP, LINEAR_STEP, SOFT_BOUNDS = 0, 1, 2
 PLANE_NAMES = ("dw_up", "dw_down", "b_max", "b_min", "slope_up", "slope_down")

@@ -161,3 +161,24 @@ def test_cellwise_weight_noise_is_keyed_by_cell_vector_and_call():
             acc = sum((float(W[i, j]) + float(f32(0.25)) * oracle.gauss_block_f64(3, i * 5 + j, 9, b, 12)[0]) * float(d[b, i])
                       for i in range(3))
             assert pre[b, j] == pytest.approx(acc, rel=1e-6, abs=1e-6)
+
+
+def test_input_noise_enters_after_the_dac_and_is_keyed_by_input_vector_and_call():
+    """F2/F3: the DAC rounds first, the input noise rides on the rounded value (it is not rounded
+    away), one Gaussian per input line, vector and call."""
+    W = np.eye(8, dtype=f32)
+    io = IOParams(inp_res=0.25, inp_bound=1.0, inp_noise=0.01, out_noise=0.0, out_res=0.0, out_bound=1e30,
+                  noise_management=False)
+    x = np.array([[0.0, 0.1, 0.13, 0.374, 0.376, -0.62, 0.9, 7.0],
+                  [0.5, -0.3, 0.2, 0.8, -0.9, 0.01, 0.49, -0.26]], dtype=f32)
+    grid = np.clip(np.round(np.clip(x.astype(np.float64), -1, 1) / 0.25) * 0.25, -1, 1)
+    pre = oracle.analog_mvm(W, x, io, 21, 6, return_pre=True)[1]
+    for b in range(2):
+        for j in range(8):
+            z = oracle.gauss_block_f64(21, j >> 2, 6, b, 7)[j & 3]
+            assert pre[b, j] == pytest.approx(grid[b, j] + float(f32(0.01)) * z, abs=1e-6)
+    assert (np.abs(pre - grid) > 1e-5).mean() > 0.9      # off the grid: the noise was not rounded away
+    # backward: its own tag
+    pre = oracle.analog_mvm(W, x, io, 21, 6, transposed=True, return_pre=True)[1]
+    z = oracle.gauss_block_f64(21, 1, 6, 1, 9)[2]
+    assert pre[1, 6] == pytest.approx(grid[1, 6] + float(f32(0.01)) * z, abs=1e-6)

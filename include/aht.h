@@ -121,6 +121,25 @@ aht_status aht_get_weights(const aht_tile* tile, float* w_dev_out, void* stream)
 aht_status aht_pulsed_update(aht_tile* tile, const float* x_dev, const float* d_dev, int32_t B,
                              float lr, void* stream);
 
+/* aht_pulsed_update for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, semantics, kernels and
+ * results (bit for bit) as aht_pulsed_update, but the pulse words and per-vector factors of the
+ * call live in a static device array of AHT_NOALLOC_SCRATCH_BYTES that the library holds on every
+ * GPU it runs on until the process ends; the call itself never calls hipMalloc, hipFree or any
+ * other allocating routine, records no events and issues no copy to the host.  (Its address on a
+ * device is looked up when the first tile is created there.)
+ *   Needs 3 * align256(8 B) + B * cols64 * w + B16 * rows16 * w bytes, cols64 / rows16 / B16 = cols /
+ *   rows / B rounded up to 64 / 16 / 16, w = 4 for bl <= 31 else 8: a 4096 x 4096 tile with bl = 63
+ *   takes up to 511 update vectors, a 1024 x 1024 tile with bl = 31 up to 4095.
+ * Errors: those of aht_pulsed_update, and UNSUPPORTED if the call needs more scratch than that
+ * (then nothing has been launched and the step counter has not advanced).
+ * Every call on one GPU uses the same array: calls that overlap in time on one GPU -- two streams,
+ * two tiles, two threads -- race; order them on one stream or with events.  Nothing in the array
+ * has to start at zero (each call writes every word it reads, padding included). */
+#define AHT_NOALLOC_SCRATCH_BYTES (32u << 20)
+aht_status aht_pulsed_update_noalloc(aht_tile* tile, const float* x_dev, const float* d_dev, int32_t B,
+                                     float lr, void* stream);
+
 /* The pulsed update of a convolution layer mapped on the tile (Sec. 3: convolutions accumulate
  * their rank-1 updates in analog memory): rows = output channels, cols = Cin * kh * kw, and
  * every output position of every image is one update vector, applied in the order

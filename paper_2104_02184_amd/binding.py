@@ -21,6 +21,7 @@ TEMPORAL_PLANE_NAMES = ("decay", "diffusion", "reset")
 # every symbol include/aht.h declares
 EXPORTS = (
     "aht_tile_create", "aht_tile_destroy", "aht_set_weights", "aht_get_weights", "aht_pulsed_update",
+    "aht_pulsed_update_noalloc",
     "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
     "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
     "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
@@ -127,6 +128,7 @@ def load_library() -> ctypes.CDLL:
     L.aht_set_weights.argtypes = [vp, vp, vp]
     L.aht_get_weights.argtypes = [vp, vp, vp]
     L.aht_pulsed_update.argtypes = [vp, vp, vp, i32, f32, vp]
+    L.aht_pulsed_update_noalloc.argtypes = [vp, vp, vp, i32, f32, vp]
     L.aht_get_step.argtypes = [vp, ctypes.POINTER(u32)]
     L.aht_set_step.argtypes = [vp, u32]
     L.aht_get_pulse_count.argtypes = [vp, ctypes.POINTER(u64), vp]
@@ -245,6 +247,16 @@ class Tile:
         else:
             xp = dp = ctypes.c_void_p()
         _check(self._lib.aht_pulsed_update(self._h, xp, dp, B, ctypes.c_float(lr), _stream()))
+
+    def pulsed_update_noalloc(self, x, d, lr: float):
+        """aht_pulsed_update_noalloc: the same update out of the library's static device scratch."""
+        import torch
+        B = int(x.shape[0]) if x.dim() == 2 else -1
+        if B > 0:
+            xp, dp = _ptr(x, torch.float32, (B, self.cols)), _ptr(d, torch.float32, (B, self.rows))
+        else:
+            xp = dp = ctypes.c_void_p()
+        _check(self._lib.aht_pulsed_update_noalloc(self._h, xp, dp, B, ctypes.c_float(lr), _stream()))
 
     # -- analog matrix-vector product ------------------------------------------------------
     def _mvm(self, fn, io, x, n_in, n_out, with_pre):

@@ -11,6 +11,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -175,8 +176,63 @@ aht_status ensure_scratch(aht_tile* t, int B)
     return AHT_OK;
 }
 
-// pulse trains of the call at step `step` into the tile's scratch
-aht_status launch_words(aht_tile* t, const float* x, const float* d, int B, float lr, uint32_t step,
+// Device memory between the pulse-train kernels and the cell update: the pulse words of the call,
+// the per-sample probability factors and train lengths.  Normally the tile's own (grown on demand);
+// the allocation-free entry point carves it out of a static device array instead.
+struct WordBufs {
+    void* xw = nullptr;
+    void* dw = nullptr;
+    double* a_x = nullptr;
+    double* a_d = nullptr;
+    int32_t* bl_b = nullptr;
+};
+
+inline WordBufs tile_bufs(const aht_tile* t) { return WordBufs{t->xw, t->dw, t->a_x, t->a_d, t->bl_b}; }
+
+// Scratch of aht_pulsed_update_noalloc: one array per GPU (every device that loads the library
+// holds its own copy at its own address until the process ends).  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels and copies take the address that call returns.
+constexpr size_t kStaticScratchBytes = AHT_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (asked for once per device, with that device
+// current: the caller has checked that `device` is the current one).
+aht_status static_scratch(int device, unsigned char** out)
+{
+    if (device < 0 || device >= kMaxDevices) return fail(AHT_ERR_UNSUPPORTED, "device index %d out of range", device);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        AHT_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(AHT_ERR_DEVICE, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[device] = (unsigned char*)p;
+    }
+    *out = g_scratch_ptr[device];
+    return AHT_OK;
+}
+
+inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// Bytes of static scratch a call with B update vectors needs, and where its parts lie.
+size_t static_scratch_layout(const aht_tile* t, int B, unsigned char* base, WordBufs* bufs)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return base ? base + at : nullptr; };
+    unsigned char* ax = take(sizeof(double) * (size_t)B);
+    unsigned char* ad = take(sizeof(double) * (size_t)B);
+    unsigned char* bl = take(sizeof(int32_t) * (size_t)B);
+    unsigned char* xw = take((size_t)B * cpad(t) * word_bytes(t));
+    unsigned char* dw = take((size_t)bpad(B) * rpad(t) * word_bytes(t));
+    if (bufs) *bufs = WordBufs{xw, dw, (double*)ax, (double*)ad, (int32_t*)bl};
+    return off;
+}
+
+// pulse trains of the call at step `step` into `w`
+aht_status launch_words(aht_tile* t, const WordBufs& w, const float* x, const float* d, int B, float lr, uint32_t step,
                         hipStream_t s, const ConvView& conv = ConvView{})
 {
     const double A = std::sqrt((double)lr / ((double)t->dev.dw_min * (double)t->upd.bl));
@@ -184,21 +240,21 @@ aht_status launch_words(aht_tile* t, const float* x, const float* d, int B, floa
     const int32_t* blb = nullptr;
     if (t->upd.update_management || t->dynamic_bl) {
         hipLaunchKernelGGL(k_line_scale, dim3((unsigned)B), dim3(256), 0, s, x, d, t->rows, t->cols, (double)lr,
-                           (double)t->dev.dw_min, t->upd.bl, t->upd.update_management, t->dynamic_bl, t->a_x, t->a_d,
-                           t->dynamic_bl ? t->bl_b : nullptr, conv);
-        ax = t->a_x;
-        ad = t->a_d;
-        blb = t->dynamic_bl ? t->bl_b : nullptr;
+                           (double)t->dev.dw_min, t->upd.bl, t->upd.update_management, t->dynamic_bl, w.a_x, w.a_d,
+                           t->dynamic_bl ? w.bl_b : nullptr, conv);
+        ax = w.a_x;
+        ad = w.a_d;
+        blb = t->dynamic_bl ? w.bl_b : nullptr;
     }
     const uint32_t k0 = (uint32_t)t->seed, k1 = (uint32_t)(t->seed >> 32);
     const int Cp = cpad(t), Rp = rpad(t);
     const dim3 grid(blocks_for((size_t)Cp + Rp), (unsigned)(B < 32768 ? B : 32768));
     if (use_u32(t))
         hipLaunchKernelGGL(k_pulse_words<uint32_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp, bpad(B),
-                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint32_t*)t->xw, (uint32_t*)t->dw, conv);
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint32_t*)w.xw, (uint32_t*)w.dw, conv);
     else
         hipLaunchKernelGGL(k_pulse_words<uint64_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp, bpad(B),
-                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint64_t*)t->xw, (uint64_t*)t->dw, conv);
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint64_t*)w.xw, (uint64_t*)w.dw, conv);
     AHT_HIP(hipGetLastError());
     return AHT_OK;
 }
@@ -284,9 +340,10 @@ void refresh_pulse_rate(aht_tile* t)
 
 // the cell update of step `step` from the words in the tile's scratch
 // `strip0`, `strips`: the range of 64-column strips to work on (the caller knows that x is zero elsewhere)
-// `words`: the tile whose scratch holds the pulse words (the tile itself, or the first device of its unit cell)
+// `words`: where the pulse words are (the tile's own scratch, that of the first device of its unit cell, or
+// the static scratch)
 aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strip0, uint32_t strips,
-                        const aht_tile* words = nullptr)
+                        const WordBufs& words)
 {
     const int rpl = choose_rpl(t);
     // stream storage per cell: 12 words hold 320 pulses before an early drain is needed; at 4 rows
@@ -304,8 +361,8 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     p.b_min = t->planes[AHT_PLANE_B_MIN];
     p.slope_up = t->planes[AHT_PLANE_SLOPE_UP];
     p.slope_down = t->planes[AHT_PLANE_SLOPE_DOWN];
-    p.xw = words ? words->xw : t->xw;
-    p.dw = words ? words->dw : t->dw;
+    p.xw = words.xw;
+    p.dw = words.dw;
     p.pulse_count = t->pulse_count;
     CellArgs a{};
     a.R = t->rows;
@@ -421,7 +478,7 @@ void launch_pair_kind(int kind, bool noise, int rpl_main, int rpl_side, dim3 gri
 }
 
 aht_status launch_cells_pair(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strips, uint32_t strips_main,
-                             int rpl_main, int rpl_side, const aht_tile* words = nullptr)
+                             int rpl_main, int rpl_side, const WordBufs& words)
 {
     CellPtrs p{};
     p.W = t->W;
@@ -432,8 +489,8 @@ aht_status launch_cells_pair(aht_tile* t, int B, uint32_t step, hipStream_t s, u
     p.b_min = t->planes[AHT_PLANE_B_MIN];
     p.slope_up = t->planes[AHT_PLANE_SLOPE_UP];
     p.slope_down = t->planes[AHT_PLANE_SLOPE_DOWN];
-    p.xw = words ? words->xw : t->xw;
-    p.dw = words ? words->dw : t->dw;
+    p.xw = words.xw;
+    p.dw = words.dw;
     p.pulse_count = t->pulse_count;
     size_t lds = 0;
     auto shape = [&](int rpl, uint32_t strip0, uint32_t nstrips) {
@@ -556,7 +613,8 @@ aht_status aht_tile_create(aht_tile** out, int32_t rows, int32_t cols, const aht
     hipLaunchKernelGGL(k_gen_planes, dim3(nb), dim3(256), 0, 0, pa);
     if ((e = hipGetLastError()) != hipSuccess) return cleanup(hip_fail(e, "k_gen_planes launch"));
     if ((e = hipDeviceSynchronize()) != hipSuccess) return cleanup(hip_fail(e, "k_gen_planes"));
-    (void)st;
+    unsigned char* primed = nullptr;              // the device's static scratch, looked up once per device here
+    if ((st = static_scratch(t->device, &primed)) != AHT_OK) return cleanup(st);
     *out = t;
     return AHT_OK;
 }
@@ -608,8 +666,10 @@ aht_status aht_get_weights(const aht_tile* t, float* w_dev_out, void* stream)
 }
 
 // `col_lo .. col_hi`: columns outside this range are known to be zero in every x (all columns if col_hi < 0)
+// `static_scratch_only`: the allocation-free variant (see aht_pulsed_update_noalloc)
 static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const float* d_dev, int64_t B64, float lr,
-                                     void* stream, const ConvView& conv, int col_lo = 0, int col_hi = -1)
+                                     void* stream, const ConvView& conv, int col_lo = 0, int col_hi = -1,
+                                     bool static_scratch_only = false)
 {
     if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
     if (B64 < 0) return fail(AHT_ERR_INVALID_ARG, "B must be >= 0");
@@ -620,10 +680,23 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
     aht_status st = check_device(t);
     if (st != AHT_OK) return st;
     if (B > 0 && lr > 0.0f) {
-        if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
+        WordBufs bufs;
+        if (static_scratch_only) {
+            const size_t need = static_scratch_layout(t, B, nullptr, nullptr);
+            if (need > kStaticScratchBytes)
+                return fail(AHT_ERR_UNSUPPORTED, "%d update vectors on a %d x %d tile need %zu bytes of scratch; the static "
+                            "scratch of aht_pulsed_update_noalloc holds %zu (use aht_pulsed_update)", B, t->rows, t->cols,
+                            need, kStaticScratchBytes);
+            unsigned char* base = nullptr;
+            if ((st = static_scratch(t->device, &base)) != AHT_OK) return st;
+            (void)static_scratch_layout(t, B, base, &bufs);
+        } else {
+            if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
+            bufs = tile_bufs(t);
+        }
         hipStream_t s = (hipStream_t)stream;
         hipEvent_t* ev = nullptr;
-        if (t->profiling && t->events_used + 3 <= 3 * 4096) {
+        if (!static_scratch_only && t->profiling && t->events_used + 3 <= 3 * 4096) {
             while (t->events.size() < t->events_used + 3) {
                 hipEvent_t e;
                 AHT_HIP(hipEventCreate(&e));
@@ -633,7 +706,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         }
         if (ev) AHT_HIP(hipEventRecord(ev[0], s));
         if (col_hi < 0) refresh_pulse_rate(t);
-        if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
+        if ((st = launch_words(t, bufs, x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
         if (ev) AHT_HIP(hipEventRecord(ev[1], s));
         const uint32_t strip0 = col_hi < 0 ? 0u : (uint32_t)(col_lo / 64);
         const uint32_t strips = (col_hi < 0 ? (uint32_t)((t->cols + 63) / 64) : (uint32_t)(col_hi / 64 + 1)) - strip0;
@@ -641,8 +714,8 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         int rpl_main = 0, rpl_side = 0;
         if (col_hi < 0) even_round(t, B, strips, &strips_main, &rpl_main, &rpl_side);
         if (strips_main < strips) {
-            if ((st = launch_cells_pair(t, B, t->step, s, strips, strips_main, rpl_main, rpl_side)) != AHT_OK) return st;
-        } else if ((st = launch_cells(t, B, t->step, s, strip0, strips)) != AHT_OK) return st;
+            if ((st = launch_cells_pair(t, B, t->step, s, strips, strips_main, rpl_main, rpl_side, bufs)) != AHT_OK) return st;
+        } else if ((st = launch_cells(t, B, t->step, s, strip0, strips, bufs)) != AHT_OK) return st;
         if (ev) {
             AHT_HIP(hipEventRecord(ev[2], s));
             t->events_used += 3;
@@ -650,7 +723,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         if (col_hi < 0) {
             t->full_updates += 1;
             // the first eight updates and every sixteenth after them report the counter
-            if (t->pulses_seen && (t->full_updates <= 8 || t->full_updates % 16 == 0)) {
+            if (!static_scratch_only && t->pulses_seen && (t->full_updates <= 8 || t->full_updates % 16 == 0)) {
                 AHT_HIP(hipMemcpyAsync(t->pulses_seen, t->pulse_count, sizeof(unsigned long long),
                                        hipMemcpyDeviceToHost, s));
                 t->copy_issued_at = t->full_updates;
@@ -664,6 +737,12 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
 aht_status aht_pulsed_update(aht_tile* t, const float* x_dev, const float* d_dev, int32_t B, float lr, void* stream)
 {
     return pulsed_update_impl(t, x_dev, d_dev, B, lr, stream, ConvView{});
+}
+
+aht_status aht_pulsed_update_noalloc(aht_tile* t, const float* x_dev, const float* d_dev, int32_t B, float lr,
+                                     void* stream)
+{
+    return pulsed_update_impl(t, x_dev, d_dev, B, lr, stream, ConvView{}, 0, -1, true);
 }
 
 // checks the convolution geometry against the tile and fills the view; B = number of update vectors
@@ -995,7 +1074,8 @@ aht_status aht_unit_cell_update(aht_tile* const* dev, int32_t n, int32_t which, 
     if (B > 0 && lr > 0.0f) {
         if ((st = ensure_scratch(lead, B)) != AHT_OK) return st;
         hipStream_t s = (hipStream_t)stream;
-        if ((st = launch_words(lead, x_dev, d_dev, B, lr, step, s, ConvView{})) != AHT_OK) return st;
+        const WordBufs bufs = tile_bufs(lead);
+        if ((st = launch_words(lead, bufs, x_dev, d_dev, B, lr, step, s, ConvView{})) != AHT_OK) return st;
         const uint32_t strips = (uint32_t)((lead->cols + 63) / 64);
         // The devices are tiles of their own, fed from the same words: those after the first run beside
         // it, each on its own tile's side stream (measured, all devices updated: two devices of 512 x 512
@@ -1019,9 +1099,9 @@ aht_status aht_unit_cell_update(aht_tile* const* dev, int32_t n, int32_t which, 
             int rpl_main = 0, rpl_side = 0;
             even_round(dev[k], B, strips, &strips_main, &rpl_main, &rpl_side);
             if (strips_main < strips) {
-                if ((st = launch_cells_pair(dev[k], B, step, sk, strips, strips_main, rpl_main, rpl_side, lead)) != AHT_OK)
+                if ((st = launch_cells_pair(dev[k], B, step, sk, strips, strips_main, rpl_main, rpl_side, bufs)) != AHT_OK)
                     return st;
-            } else if ((st = launch_cells(dev[k], B, step, sk, 0u, strips, lead)) != AHT_OK) return st;
+            } else if ((st = launch_cells(dev[k], B, step, sk, 0u, strips, bufs)) != AHT_OK) return st;
             if (sk != s) {
                 AHT_HIP(hipEventRecord(dev[k]->side_join, sk));
                 AHT_HIP(hipStreamWaitEvent(s, dev[k]->side_join, 0));
@@ -1302,7 +1382,7 @@ static aht_status debug_pulse_words_impl(aht_tile* t, const float* x_dev, const 
     if (st != AHT_OK) return st;
     if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
     hipStream_t s = (hipStream_t)stream;
-    if ((st = launch_words(t, x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
+    if ((st = launch_words(t, tile_bufs(t), x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
     const size_t nx = (size_t)B * t->cols, nd = (size_t)B * t->rows;
     if (use_u32(t)) {
         hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint32_t*)t->xw, xw_dev, B, t->cols, cpad(t), 0);
@@ -1364,7 +1444,7 @@ aht_status aht_debug_apply_words(aht_tile* t, const uint64_t* xw_dev, const uint
         hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint64_t*)t->dw, B, t->rows, rpad(t), bpad(B), t->upd.bl);
     }
     AHT_HIP(hipGetLastError());
-    return launch_cells(t, B, step, s, 0u, (uint32_t)((t->cols + 63) / 64));
+    return launch_cells(t, B, step, s, 0u, (uint32_t)((t->cols + 63) / 64), tile_bufs(t));
 }
 
 aht_status aht_debug_philox(const uint32_t* ctr_dev, const uint32_t* key_dev, int32_t n, uint32_t* out_dev, void* stream)

@@ -31,21 +31,163 @@ if ROOT not in sys.path:
 #       device step: ConstantStep 4 (select, noise fma, w fma, clamp); LinearStep/SoftBounds 8
 #       (two selects, slope fma, max, mul, noise fma, w fma, clamp)
 PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
-C_CS = {8: 6.0, 4: 4.0}
-C_PULSE_NOISE = 10.0 + 7.0
-C_STEP = {0: 4.0, 1: 8.0, 2: 8.0}
-# HBM-side bytes of one headline call of the cell-update kernel, from rocprofv3 --pmc
-# FETCH_SIZE and WRITE_SIZE (profiles/cell_update_cfg5_counters.md; FETCH_SIZE scaled by the
-# factor a plain copy of known size gives).  None for other workloads.
-MEASURED_TRAFFIC_BYTES = {"cfg5_4096x4096_linearstep": 717.0e6}
+# Measured issue rate of every instruction of that minimal stream, as a multiple of the nominal one
+# lane-op per lane and clock (profiles/valu_issue_rates_gfx950.md).  The plain count above treats them
+# all as 1.0; weighting the same stream by these gives the time the vector ALU needs at least for it
+# (`rate_weighted_bound_ms`): simple two-operand operations issue faster than nominal, the 64-bit
+# multiply-add and the population count a little slower, transcendentals at half rate.
+RATE = {"and": 1.58, "xor": 1.69, "bcnt": 0.895, "alignbit": 0.95, "mad_u64_u32": 0.823, "bitop3": 1.027,
+        "shift": 1.73, "add": 1.54, "cvt": 0.949, "mul": 1.58, "trans": 0.49, "bfi": 0.91, "fma": 0.99,
+        "max": 0.97, "med3": 0.93}
+# minimal stream: (instruction, how many) per unit
+STREAM_CELL_SAMPLE = {8: [("and", 2), ("bcnt", 2), ("xor", 1), ("alignbit", 1)],
+                      4: [("and", 1), ("bcnt", 1), ("xor", 1), ("alignbit", 1)]}
+STREAM_PHILOX_QUARTER = [("mad_u64_u32", 5), ("bitop3", 5)]                       # 20 + 20 per block of four
+STREAM_BOX_MULLER_HALF = [("shift", 1), ("add", 0.5), ("cvt", 1), ("mul", 2.5), ("trans", 2)]
+STREAM_STEP = {0: [("bfi", 1), ("fma", 2), ("med3", 1)],                          # ConstantStep: select, noise, w, clamp
+               1: [("bfi", 2), ("fma", 3), ("max", 1), ("mul", 1), ("med3", 1)],  # LinearStep / SoftBounds: + slope select,
+               2: [("bfi", 2), ("fma", 3), ("max", 1), ("mul", 1), ("med3", 1)]}  #   slope fma, max, mul
+COUNTERS_JSON = os.path.join(ROOT, "profiles", "cell_update_counters.json")
+
+
+def _count(stream):
+    return sum(n for _, n in stream)
+
+
+def _weighted(stream):
+    return sum(n / RATE[i] for i, n in stream)
+
+
+def lane_ops_model(w, pulses_per_call, cell_samples=None):
+    """(plain count, rate-weighted count) of the minimal instruction stream of one call; `cell_samples`
+    overrides the number of (cell, sample) pairs counted (row lists visit only part of them)."""
+    word_bytes = 4 if w.bl <= 31 else 8
+    noise = w.device["dw_min_std"] > 0
+    per_pulse = list(STREAM_STEP[w.device["kind"]])
+    if noise:
+        per_pulse += STREAM_PHILOX_QUARTER + STREAM_BOX_MULLER_HALF
+    else:
+        per_pulse = [(i, n - 1 if i == "fma" else n) for i, n in per_pulse]      # no noise fma
+    cs = w.rows * w.cols * w.batch if cell_samples is None else cell_samples
+    a = STREAM_CELL_SAMPLE[word_bytes]
+    return (_count(a) * cs + _count(per_pulse) * pulses_per_call,
+            _weighted(a) * cs + _weighted(per_pulse) * pulses_per_call)
 
 
 def algorithmic_lane_ops(w, pulses_per_call):
-    word_bytes = 4 if w.bl <= 31 else 8
-    c_p = C_STEP[w.device["kind"]] + (C_PULSE_NOISE if w.device["dw_min_std"] > 0 else 0.0)
-    if not w.device["dw_min_std"] > 0:
-        c_p -= 1.0                                   # no noise fma
-    return C_CS[word_bytes] * w.rows * w.cols * w.batch + c_p * pulses_per_call
+    return lane_ops_model(w, pulses_per_call)[0]
+
+
+def stored_counters(name):
+    """hardware counters of the cell-update kernel on workload `name`, per dispatch, from the last
+    rocprofv3 --pmc runs that `bench.py --pmc-summary` turned into profiles/cell_update_counters.json"""
+    try:
+        with open(COUNTERS_JSON) as f:
+            return json.load(f).get(name)
+    except (OSError, ValueError):
+        return None
+
+
+def pmc_summary(root_dir):
+    """Turns rocprofv3 counter runs of this program into profiles/cell_update_counters.json (+ .md).
+
+    Expected layout, one run per counter group and workload (rocprofv3 does not split counters over passes):
+        <root_dir>/<workload>/fetch/*_counter_collection.csv   rocprofv3 --pmc FETCH_SIZE  -- python3 bench.py --workload <workload> --steps 3 --warmup 2 --no-cpu
+        <root_dir>/<workload>/write/*_counter_collection.csv   rocprofv3 --pmc WRITE_SIZE  -- (same program)
+        <root_dir>/<workload>/valu/*_counter_collection.csv    rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_VALU_TRANS_F32 SQ_INSTS_SALU SQ_WAVES SQ_BUSY_CYCLES -- (same program)
+    Per workload: the mean per dispatch of the cell-update kernel of the timed calls (the most frequent
+    instantiation), and the byte counters' scale factors from the plain device-to-device copies of the
+    weight matrix that the same run makes (rows x cols x 4 bytes read and written each)."""
+    import csv
+    import datetime
+    import glob
+    from collections import Counter, defaultdict
+
+    from paper_2104_02184_amd import workloads as wl
+
+    def rows_of(d):
+        files = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
+        out = []
+        for f in files:
+            with open(f, newline="") as fh:
+                out += list(csv.DictReader(fh))
+        return out
+
+    def per_kernel(rows, want):
+        """kernel name -> counter -> list of per-dispatch values, for kernels whose name contains `want`"""
+        acc = defaultdict(lambda: defaultdict(list))
+        for r in rows:
+            if want in r["Kernel_Name"]:
+                acc[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        return acc
+
+    result, lines = {}, []
+    for name, w in wl.WORKLOADS.items():
+        base = os.path.join(root_dir, name)
+        if not os.path.isdir(base):
+            continue
+        entry = {"date": datetime.date.today().isoformat(),
+                 "command": f"rocprofv3 --pmc <counters> -- python3 bench.py --workload {name} --steps 3 --warmup 2 --no-cpu"}
+        copy_bytes = w.rows * w.cols * 4.0
+        for leg, counter, factor_key, kib_key in (("fetch", "FETCH_SIZE", "fetch_factor", "fetch_kib"),
+                                                  ("write", "WRITE_SIZE", "write_factor", "write_kib")):
+            rows = rows_of(os.path.join(base, leg))
+            cells = per_kernel(rows, "k_cell_update")
+            if not cells:
+                continue
+            kname = Counter({k: len(v[counter]) for k, v in cells.items()}).most_common(1)[0][0]
+            vals = cells[kname][counter]
+            entry[kib_key] = sum(vals) / len(vals)
+            entry["kernel"] = kname.split("(")[0]
+            entry["dispatches"] = len(vals)
+            copies = [v for k, c in per_kernel(rows, "copyBuffer").items() for v in c[counter]]
+            entry[factor_key] = (copy_bytes / 1024.0) / max(copies) if copies and max(copies) > 0 else None
+        rows = rows_of(os.path.join(base, "valu"))
+        cells = per_kernel(rows, "k_cell_update")
+        if cells:
+            kname = Counter({k: len(v["SQ_INSTS_VALU"]) for k, v in cells.items()}).most_common(1)[0][0]
+            for counter, key in (("SQ_INSTS_VALU", "insts_valu"), ("SQ_INSTS_VALU_TRANS_F32", "insts_trans"),
+                                 ("SQ_INSTS_SALU", "insts_salu"), ("SQ_WAVES", "waves"), ("SQ_BUSY_CYCLES", "busy_cycles")):
+                v = cells[kname].get(counter)
+                if v:
+                    entry[key] = sum(v) / len(v)
+        if "fetch_kib" in entry and "write_kib" in entry:
+            result[name] = entry
+    # scale factors of the byte counters: small tiles' copies are too short to calibrate on; they take the
+    # factors of the largest tile measured (the counters' units do not depend on the kernel)
+    ref = max(result, key=lambda n: wl.WORKLOADS[n].rows * wl.WORKLOADS[n].cols, default=None)
+    for name, e in result.items():
+        for k in ("fetch_factor", "write_factor"):
+            small = wl.WORKLOADS[name].rows * wl.WORKLOADS[name].cols < (1 << 20)
+            if e.get(k) is None or small:
+                e[k] = result[ref][k]
+            e[k] = round(e[k], 3)
+    with open(COUNTERS_JSON, "w") as f:
+        json.dump(result, f, indent=1, sort_keys=True)
+        f.write("\n")
+    lines.append("# Cell-update kernel: HBM-side bytes and executed vector instructions per dispatch, all workloads\n")
+    lines.append("Written by `python bench.py --pmc-summary <dir>` from these runs (on the MI355X box, from /tmp with TMPDIR=/tmp,")
+    lines.append("one counter group per run; W = a workload name, P = `python3 bench.py --workload W --steps 3 --warmup 2 --no-cpu`):\n")
+    lines.append("    rocprofv3 --pmc FETCH_SIZE -d <dir>/W/fetch -o fetch --output-format csv -- P")
+    lines.append("    rocprofv3 --pmc WRITE_SIZE -d <dir>/W/write -o write --output-format csv -- P")
+    lines.append("    rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_VALU_TRANS_F32 SQ_INSTS_SALU SQ_WAVES SQ_BUSY_CYCLES -d <dir>/W/valu -o valu --output-format csv -- P\n")
+    lines.append("The byte counters are scaled by what the same counters read for the run's plain copies of the weight matrix")
+    lines.append("(rows x cols x 4 bytes read and written).  `bench.py` reads the JSON beside this file for `roofline.traffic` and")
+    lines.append("`roofline.executed_over_minimal`; algorithmic bytes = cells x (8 + 4 planes) + one read of the pulse words.\n")
+    lines.append("| workload | kernel | FETCH_SIZE KiB x factor | WRITE_SIZE KiB x factor | HBM bytes | algorithmic bytes | vector instructions | x64 / minimal stream |")
+    lines.append("|---|---|---|---|---|---|---|---|")
+    for name, e in result.items():
+        w = wl.WORKLOADS[name]
+        traffic = e["fetch_kib"] * 1024 * e["fetch_factor"] + e["write_kib"] * 1024 * e["write_factor"]
+        planes = 6 if w.device["kind"] == 1 else 4
+        wb = 4 if w.bl <= 31 else 8
+        alg = w.rows * w.cols * (8 + 4 * planes) + wb * w.batch * (w.rows + w.cols)
+        lines.append(f"| {name} | `{e['kernel'].replace('aht::', '')}` | {e['fetch_kib']:.0f} x {e['fetch_factor']} | "
+                     f"{e['write_kib']:.0f} x {e['write_factor']} | {traffic / 1e6:.1f} MB | {alg / 1e6:.1f} MB | "
+                     f"{e.get('insts_valu', float('nan')):.4g} | see the bench line (needs the pulses of the timed calls) |")
+    with open(os.path.join(ROOT, "profiles", "cell_update_counters.md"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print(json.dumps(result, indent=1, sort_keys=True))
 
 
 def host_cpu_model():
@@ -161,24 +303,31 @@ def bench_mvm(args, transposed):
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / args.steps
+    info = tile.launch_info()
     tile.close()
-    flops = 2.0 * w.batch * w.rows * w.cols
-    # quantised inputs without input noise: the product runs as three passes of the bf16 matrix
-    # cores (integer DAC codes, fp32 weights cut into three bf16 terms, fp32 sums); other inputs as
-    # three bf16 terms too, six passes; where the shape rules both out, one pass of the fp32 cores
-    n_out = w.cols if transposed else w.rows
-    codes = args.inp_noise == 0.0 and os.environ.get("AHT_MVM_CODES", "1") != "0" and n_in % 32 == 0 and n_out % 16 == 0
-    planes = (not codes and os.environ.get("AHT_MVM_PLANES", "1") != "0" and n_in % 32 == 0 and n_out % 64 == 0)
-    executed = 3.0 * flops if codes else 6.0 * flops if planes else flops
-    peak = 2500.0 if (codes or planes) else 157.3
-    dtype = "bf16 x 3 terms, f32 sums" if codes else "bf16 x 3 x 3 terms (6 products), f32 sums" if planes else "f32"
+    flops = 2.0 * w.batch * w.rows * w.cols             # the method's work: one multiply-add per weight and vector
+    # Which path the library took is asked of the library.  Quantised inputs without input noise: three
+    # passes of the bf16 matrix cores (integer DAC codes, fp32 weights cut into three bf16 terms, fp32
+    # sums); other inputs as three bf16 terms too, six passes; where the shape rules both out, one pass of
+    # the fp32 cores.  `frac` prices the method's flops against the peak of the cores used; the passes the
+    # path executes for them are reported beside it, not in it.
+    path, passes = info["mvm_path"], {1: 1, 2: 3, 3: 6}[info["mvm_path"]]
+    peak = 157.3 if path == 1 else 2500.0
+    dtype = {1: "f32", 2: "bf16 x 3 terms, f32 sums", 3: "bf16 x 3 x 3 terms (6 products), f32 sums"}[path]
+    hbm_bytes = 4.0 * (w.rows * w.cols + w.batch * (w.rows + w.cols))
     print(json.dumps({
         "metric": "TFLOP/s of analog " + ("backward" if transposed else "forward"), "value": flops / (ms * 1e-3) / 1e12,
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name} analog MVM, B={w.batch}, inp_noise={args.inp_noise}"},
-        "roofline": {"bound": "mfma", "achieved": executed / (ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
-                     "frac": executed / (ms * 1e-3) / (peak * 1e12), "traffic": None},
+        "config": {"workload": f"{w.name} analog MVM, B={w.batch}, inp_noise={args.inp_noise}",
+                   "path": {1: "fp32 matrix cores", 2: "bf16 matrix cores, DAC codes", 3: "bf16 matrix cores, input planes"}[path],
+                   "slices": info["mvm_splits"]},
+        "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
+                     "frac": flops / (ms * 1e-3) / (peak * 1e12), "traffic": None,
+                     "matrix_passes_executed": passes,
+                     "executed_matrix_flops_frac": passes * flops / (ms * 1e-3) / (peak * 1e12),
+                     "bound_ms": {"matrix_cores_at_executed_passes": passes * flops / (peak * 1e12) * 1e3,
+                                  "hbm_weights_and_vectors_once": hbm_bytes / 8e12 * 1e3}},
     }), flush=True)
 
 
@@ -228,7 +377,12 @@ def main():
                     help="input noise of the forward/backward side benchmarks (0: quantised inputs only)")
     ap.add_argument("--op", default="pulsed_update", choices=["pulsed_update", "decay_diffuse", "forward", "backward", "transfer"],
                     help="side benchmarks of other operations; the default is the headline metric")
+    ap.add_argument("--pmc-summary", default=None, metavar="DIR",
+                    help="no benchmark: turn rocprofv3 --pmc runs of this program under DIR into profiles/cell_update_counters.json")
     args = ap.parse_args()
+    if args.pmc_summary:
+        pmc_summary(args.pmc_summary)
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: the pulsed update of one tile runs on a single MI355X "
               "(it would shard by blocks of rows of the tile, not by batch); run with --gpus 1", file=sys.stderr)
@@ -289,14 +443,26 @@ def main():
         tile.pulsed_update(xs[(Wm + i) % pool], ds[(Wm + i) % pool], w.lr)
     torch.cuda.synchronize()
     ms_per_step_plain = (time.perf_counter() - u0) / K * 1e3
+    info = tile.launch_info()
     tile.close()
 
     sec = t1 - t0
     ms_per_step = sec / K * 1e3
     value = w.cell_pulse_updates_per_call * K / sec / 1e9
     cell_ms = ms_cells / max(calls, 1)
-    ops = algorithmic_lane_ops(w, pulses)
+    ops, ops_weighted = lane_ops_model(w, pulses)
     achieved = ops / (cell_ms * 1e-3)
+    kernel = ("k_cell_update_rowlists" if info["row_lists"] else
+              "k_cell_update_pair" if info["side_rows_per_lane"] else "k_cell_update")
+    # Counters of the same kernel on the same workload from the last profiler runs (bench.py cannot read them
+    # while it times): HBM-side bytes, and the vector instructions executed, which say how much of what the
+    # kernel issues is the minimal stream.  null where no such run is on file.
+    pmc = stored_counters(w.name)
+    traffic = executed_over_minimal = None
+    if pmc:
+        traffic = pmc["fetch_kib"] * 1024.0 * pmc["fetch_factor"] + pmc["write_kib"] * 1024.0 * pmc["write_factor"]
+        if pmc.get("insts_valu"):
+            executed_over_minimal = pmc["insts_valu"] * 64.0 / ops
     out = {
         "metric": "Gcell-pulse-updates/s of pulsed_update",
         "value": value,
@@ -316,17 +482,33 @@ def main():
                    "pulses_per_call": pulses, "applied_pulses_per_s": pulses / (sec / K)},
         "roofline": {
             "bound": "alu",
-            "kernel": "k_cell_update",
+            "kernel": kernel,
             "achieved": achieved / 1e12,
             "peak": PEAK_LANE_OPS / 1e12,
             "unit": "Tlane-op/s",
             "frac": achieved / PEAK_LANE_OPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+            "traffic": traffic,
+            "traffic_source": (f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of {pmc['date']}, kernel {pmc['kernel']}"
+                               if pmc else None),
             "kernel_ms": cell_ms,
             "words_ms": ms_words / max(calls, 1),
             "algorithmic_lane_ops_per_launch": ops,
+            # the same minimal stream with every instruction at its measured issue rate: the least time the
+            # vector ALU needs for it, and the kernel's time against that
+            "rate_weighted_bound_ms": ops_weighted / PEAK_LANE_OPS * 1e3,
+            "frac_rate_weighted": ops_weighted / PEAK_LANE_OPS * 1e3 / cell_ms,
+            "executed_over_minimal": executed_over_minimal,
+            "launch": info,
         },
     }
+    if info["row_lists"] and info["row_fill"] >= 0:
+        # Row lists leave out the samples whose row train is empty: fewer (cell, sample) pairs than the model
+        # above counts are looked at at all.  `frac` keeps the full count (the method's work as the other
+        # launch shapes do it); this is the same fraction with only the visited pairs counted.
+        visited = w.rows * w.cols * w.batch * info["row_fill"]
+        ops_v = lane_ops_model(w, pulses, visited)[0]
+        out["roofline"]["row_trains_with_a_pulse"] = info["row_fill"]
+        out["roofline"]["frac_of_visited_pairs_only"] = ops_v / (cell_ms * 1e-3) / PEAK_LANE_OPS
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_rows)
     print(json.dumps(out), flush=True)

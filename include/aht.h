@@ -16,8 +16,12 @@
  *     asynchronous on it and do not synchronise the host, except create/destroy and a call
  *     that has to grow the tile's scratch memory (the first call, or the first with a larger
  *     batch: hipFree / hipMalloc, which wait for the device);
- *   - every function returns aht_status and never throws or aborts; on an error the tile
- *     is unchanged; aht_last_error() gives a thread-local message;
+ *   - every function returns aht_status and never throws or aborts; aht_last_error() gives a
+ *     thread-local message.  Arguments are checked before anything is launched: after
+ *     INVALID_ARG or UNSUPPORTED the tile is unchanged.  OOM and DEVICE can come from the
+ *     runtime in the middle of a call (a scratch buffer that cannot grow, a launch that
+ *     fails); then no call counter of the tile has advanced, but kernels launched before the
+ *     failure may have run, so the weights are to be taken as undefined;
  *   - one tile must not be used from two streams or two host threads at the same time
  *     (different tiles may be);
  *   - all quantities are in the paper's normalised units (Sec. 3, after Eq. (1)).
@@ -172,9 +176,19 @@ enum { AHT_TRAIN_STOCHASTIC = 0, AHT_TRAIN_DETERMINISTIC = 1 };
 aht_status aht_set_pulse_mode(aht_tile* tile, int32_t train_kind, int32_t dynamic_bl);
 
 /* Step counter (number of aht_pulsed_update calls so far); together with the weights, the
- * planes and the seed it makes a run resumable bit for bit. */
+ * planes and the seed it makes a run resumable bit for bit.
+ * The counter lives in device memory: an update of the whole tile reads its step there and advances
+ * it itself (the last wave of its last kernel does), so that a sequence of update calls can be
+ * recorded once into a HIP graph and replayed, each replay continuing the random streams where the
+ * last one stopped (record aht_pulsed_update_noalloc: it allocates nothing, records no events and
+ * issues no copies).  The host keeps a copy that every call through this interface keeps equal to the
+ * device's; aht_get_step returns that copy without touching the device.  After replaying a recorded
+ * graph the copy is behind: aht_sync_step reads the device's counter back (it waits for `stream`)
+ * and must be called before the next call that takes the step from the host (aht_get_step, transfers,
+ * unit cells, the debug hooks; aht_pulsed_update itself does not).  aht_set_step waits for the device. */
 aht_status aht_get_step(const aht_tile* tile, uint32_t* step);
 aht_status aht_set_step(aht_tile* tile, uint32_t step);
+aht_status aht_sync_step(aht_tile* tile, uint32_t* step /* nullable */, void* stream);
 
 /* Number of coincidence pulses applied by all calls so far on this tile (device counter,
  * read back with a synchronising copy on `stream`). */
@@ -313,13 +327,35 @@ aht_status aht_set_temporal_step(aht_tile* tile, uint32_t step);
 aht_status aht_profile_enable(aht_tile* tile, int32_t enable);
 aht_status aht_profile_read(aht_tile* tile, double* ms_words, double* ms_cells, int32_t* calls);
 
+/* What the library chose for the tile's most recent full update and its most recent analog product
+ * (measurement aid: results do not depend on any of it beyond the summation order of the product). */
+typedef struct {
+    int32_t rows_per_lane;       /* cell update: rows per lane of the launch (1, 2 or 4); 0: no update yet */
+    int32_t side_rows_per_lane;  /* rows per lane of the launch's second shape, 0 if it had one shape */
+    int32_t row_lists;           /* 1: the update walked per-row lists of the samples whose row train has a pulse */
+    int32_t stream_words;        /* 32-bit words of pulse-stream storage per cell */
+    int32_t mvm_path;            /* product: 0 none yet, 1 fp32 matrix cores, 2 bf16 matrix cores on DAC codes (three
+                                    passes), 3 bf16 matrix cores on three input planes (six passes) */
+    int32_t mvm_splits;          /* slices of the product's inner dimension */
+    double pulse_rate;           /* applied pulses per cell and full update as the host last saw it; < 0: not yet */
+    double row_fill;             /* share of the row trains that had a pulse, likewise */
+} aht_launch_info;
+aht_status aht_get_launch_info(const aht_tile* tile, aht_launch_info* out);
+
 /* Tuning overrides, read from the environment at every call (measurement aids; results do not
  * depend on them beyond the summation order of the analog product):
  *   AHT_RPL         rows per lane of the cell-update kernel (1, 2 or 4); without it the library
  *                   chooses from the tile size and, from 400 000 cells on, from the tile's own
  *                   pulse rate: some update calls are followed by an asynchronous 8-byte copy of
- *                   the pulse counter to pinned host memory on the caller's stream
+ *                   the pulse counter to pinned host memory on the caller's stream (one in flight
+ *                   at most; the host reads it when it has arrived and never waits)
+ *   AHT_FUSED       0 / 1: never / always (at most 8 update vectors, no update management, fixed train length)
+ *                   take the whole update in one launch, every workgroup drawing the pulse words it needs;
+ *                   without it: when rows x cols x B <= 32 768
  *   AHT_QWORDS      32-bit words of pulse-stream storage per cell in LDS
+ *   AHT_ROWLISTS    0 / 1: never / always (32-bit pulse words only) let the cell update walk per-row lists of
+ *                   the samples whose row train has a pulse; without it: for batches of 256 vectors and more once
+ *                   the host has seen that fewer than 55 % of the tile's row trains have one
  *   AHT_EVEN_ROUND  0: never give some column strips fewer rows per lane than the others to fill
  *                   the chip's last round of waves evenly, nor update the devices of a unit cell
  *                   beside each other (on streams of their own tiles, between events); 2: the

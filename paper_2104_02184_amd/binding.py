@@ -21,7 +21,7 @@ TEMPORAL_PLANE_NAMES = ("decay", "diffusion", "reset")
 # every symbol include/aht.h declares
 EXPORTS = (
     "aht_tile_create", "aht_tile_destroy", "aht_set_weights", "aht_get_weights", "aht_pulsed_update",
-    "aht_pulsed_update_noalloc",
+    "aht_pulsed_update_noalloc", "aht_get_launch_info", "aht_sync_step",
     "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
     "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
     "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
@@ -73,6 +73,12 @@ class IOParams:
 class aht_temporal_params(ctypes.Structure):
     _fields_ = [(n, ctypes.c_float) for n in ("decay_rate", "decay_rate_dtod", "diffusion", "diffusion_dtod",
                                                "reset", "reset_dtod", "reset_std")]
+
+
+class aht_launch_info(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("rows_per_lane", "side_rows_per_lane", "row_lists", "stream_words",
+                                               "mvm_path", "mvm_splits")] + [("pulse_rate", ctypes.c_double),
+                                                                             ("row_fill", ctypes.c_double)]
 
 
 class aht_update_params(ctypes.Structure):
@@ -129,8 +135,10 @@ def load_library() -> ctypes.CDLL:
     L.aht_get_weights.argtypes = [vp, vp, vp]
     L.aht_pulsed_update.argtypes = [vp, vp, vp, i32, f32, vp]
     L.aht_pulsed_update_noalloc.argtypes = [vp, vp, vp, i32, f32, vp]
+    L.aht_get_launch_info.argtypes = [vp, ctypes.POINTER(aht_launch_info)]
     L.aht_get_step.argtypes = [vp, ctypes.POINTER(u32)]
     L.aht_set_step.argtypes = [vp, u32]
+    L.aht_sync_step.argtypes = [vp, ctypes.POINTER(u32), vp]
     L.aht_get_pulse_count.argtypes = [vp, ctypes.POINTER(u64), vp]
     L.aht_get_device_planes.argtypes = [vp, i32, vp, vp]
     L.aht_set_device_planes.argtypes = [vp, i32, vp, vp]
@@ -181,7 +189,8 @@ def _check(status: int):
 
 def _stream():
     import torch
-    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    # (the raw handle of the current stream without building a Stream object: this runs once per call)
+    return ctypes.c_void_p(torch._C._cuda_getCurrentRawStream(torch.cuda.current_device()))
 
 
 def _ptr(t, dtype, shape=None):
@@ -258,6 +267,12 @@ class Tile:
             xp = dp = ctypes.c_void_p()
         _check(self._lib.aht_pulsed_update_noalloc(self._h, xp, dp, B, ctypes.c_float(lr), _stream()))
 
+    def launch_info(self) -> dict:
+        """what the library chose for the most recent full update and analog product"""
+        info = aht_launch_info()
+        _check(self._lib.aht_get_launch_info(self._h, ctypes.byref(info)))
+        return {n: getattr(info, n) for n, _ in aht_launch_info._fields_}
+
     # -- analog matrix-vector product ------------------------------------------------------
     def _mvm(self, fn, io, x, n_in, n_out, with_pre):
         import torch
@@ -328,6 +343,12 @@ class Tile:
     @step.setter
     def step(self, value: int):
         _check(self._lib.aht_set_step(self._h, ctypes.c_uint32(value)))
+
+    def sync_step(self) -> int:
+        """reads the device's step counter back into the host's copy (after replaying a recorded graph)"""
+        v = ctypes.c_uint32()
+        _check(self._lib.aht_sync_step(self._h, ctypes.byref(v), _stream()))
+        return v.value
 
     def pulse_count(self) -> int:
         v = ctypes.c_uint64()

@@ -26,7 +26,12 @@ struct aht_tile {
     aht_device_params dev{};
     aht_update_params upd{};
     uint64_t seed = 0;
+    // The step counter lives in device memory (step_state[0]; [1] counts the finished waves of a running
+    // cell-update launch; [2] holds the step of a launch that takes it from the host): full updates read
+    // it there and advance it themselves, so that a recorded sequence of them can be replayed.  `step` is the host's copy: every call made through this interface
+    // keeps the two equal; after replaying a recorded graph aht_sync_step brings the host's copy up to date.
     uint32_t step = 0;
+    uint32_t* step_state = nullptr;
     int device = 0;
     float* W = nullptr;
     float* planes[AHT_NUM_PLANES] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
@@ -41,15 +46,28 @@ struct aht_tile {
     int bl_cap = 0;
     int train_kind = AHT_TRAIN_STOCHASTIC;
     int dynamic_bl = 0;
+    // device counters: applied pulses [0] by full updates (aht_pulsed_update and its variants on the whole
+    // tile), [1] by everything else (transfers, unit-cell updates, injected words); [2] row trains of full
+    // updates that had a pulse at all
     unsigned long long* pulse_count = nullptr;
-    // Feedback for the launch shape of the cell update: a pinned host copy of the pulse counter,
-    // refreshed by an asynchronous copy behind each full update of a tile large enough to have a
-    // choice, and the number of such updates.  The host reads whatever has arrived; it never waits.
+    // Feedback for the launch shape of the cell update: a pinned host copy of counter [0], refreshed by an
+    // asynchronous copy behind some full updates of a tile large enough to have a choice.  One copy is in
+    // flight at most: before it is issued the host marks the pinned word as empty, and the next copy is
+    // issued only after the host has seen this one's value, so a value always belongs to the number of
+    // full updates noted when its copy was issued.  The host reads what has arrived; it never waits.
     unsigned long long* pulses_seen = nullptr;
     uint64_t full_updates = 0;                    // full updates issued so far
-    uint64_t copy_issued_at = 0;                  // ... when the last copy was issued
-    unsigned long long seen_value = 0;            // last value read from the pinned word
+    uint64_t row_trains = 0;                      // row trains looked at by them (rows x every 16th update vector)
+    bool copy_pending = false;                    // a copy has been issued and its value not yet seen
+    uint64_t copy_index = 0;                      // full updates counted by the copy in flight
+    uint64_t copy_row_trains = 0;                 // row trains counted by it
     double pulse_rate = -1.0;                     // pulses per cell and full update; < 0: not known yet
+    double row_fill = -1.0;                       // share of the row trains that had a pulse; < 0: not known yet
+    // per-row lists of the samples whose row train has a pulse (k_compact_rows), for long sparse batches
+    uint2* rlist = nullptr;
+    uint32_t* rlen = nullptr;
+    size_t rlist_entries = 0;
+    int rlen_cap = 0;
     // stream and events for the update of a unit cell, whose devices run beside each other
     hipStream_t side_stream = nullptr;
     hipEvent_t side_fork = nullptr, side_join = nullptr;
@@ -82,6 +100,8 @@ struct aht_tile {
     aht_temporal_params temporal{};
     float* tplanes[AHT_NUM_TPLANES] = {nullptr, nullptr, nullptr};
     uint32_t tstep = 0;
+    // what the most recent full update and analog product chose (aht_get_launch_info)
+    aht_launch_info info{};
     // measurement hook: three events per recorded call
     bool profiling = false;
     std::vector<hipEvent_t> events;
@@ -189,6 +209,16 @@ struct WordBufs {
 
 inline WordBufs tile_bufs(const aht_tile* t) { return WordBufs{t->xw, t->dw, t->a_x, t->a_d, t->bl_b}; }
 
+// Kernels read the step of a call from device memory.  For launches that take it from the host (they do not
+// advance the tile's counter) the value is written, in stream order, into slot [2] of the tile's step state.
+aht_status step_from_host(aht_tile* t, uint32_t value, hipStream_t s, const uint32_t** where)
+{
+    hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, s, t->step_state, value, 0, 1);
+    AHT_HIP(hipGetLastError());
+    *where = t->step_state + 2;
+    return AHT_OK;
+}
+
 // Scratch of aht_pulsed_update_noalloc: one array per GPU (every device that loads the library
 // holds its own copy at its own address until the process ends).  In host code the array's name is
 // only a handle for hipGetSymbolAddress; kernels and copies take the address that call returns.
@@ -232,8 +262,11 @@ size_t static_scratch_layout(const aht_tile* t, int B, unsigned char* base, Word
 }
 
 // pulse trains of the call at step `step` into `w`
-aht_status launch_words(aht_tile* t, const WordBufs& w, const float* x, const float* d, int B, float lr, uint32_t step,
-                        hipStream_t s, const ConvView& conv = ConvView{})
+// `row_stat`: device counter that receives the number of row trains with a pulse (nullable)
+// `step`: where in device memory the step of this call is
+aht_status launch_words(aht_tile* t, const WordBufs& w, const float* x, const float* d, int B, float lr,
+                        const uint32_t* step, hipStream_t s, const ConvView& conv = ConvView{},
+                        unsigned long long* row_stat = nullptr)
 {
     const double A = std::sqrt((double)lr / ((double)t->dev.dw_min * (double)t->upd.bl));
     const double *ax = nullptr, *ad = nullptr;
@@ -251,10 +284,12 @@ aht_status launch_words(aht_tile* t, const WordBufs& w, const float* x, const fl
     const dim3 grid(blocks_for((size_t)Cp + Rp), (unsigned)(B < 32768 ? B : 32768));
     if (use_u32(t))
         hipLaunchKernelGGL(k_pulse_words<uint32_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp, bpad(B),
-                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint32_t*)w.xw, (uint32_t*)w.dw, conv);
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint32_t*)w.xw, (uint32_t*)w.dw, conv,
+                           row_stat);
     else
         hipLaunchKernelGGL(k_pulse_words<uint64_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp, bpad(B),
-                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint64_t*)w.xw, (uint64_t*)w.dw, conv);
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint64_t*)w.xw, (uint64_t*)w.dw, conv,
+                           row_stat);
     AHT_HIP(hipGetLastError());
     return AHT_OK;
 }
@@ -326,30 +361,65 @@ int choose_rpl(const aht_tile* t)
     return cells >= (size_t)4 * 1024 * 1024 ? 4 : 2;      // no feedback yet
 }
 
-// Called before a full update is launched: takes note of a counter value that has arrived since the
-// last look (it belongs to the copy issued last; early on, when every update issues one, to that
-// or the one before: the estimate is then a little low for a few calls).
+// Called before a full update is launched: takes note of the counter value of the copy in flight
+// if it has arrived.
+constexpr unsigned long long kNoValueYet = ~0ull;
 void refresh_pulse_rate(aht_tile* t)
 {
-    if (!t->pulses_seen || t->copy_issued_at < 2) return;
-    const unsigned long long v = *(volatile unsigned long long*)t->pulses_seen;
-    if (v == t->seen_value) return;
-    t->seen_value = v;
-    t->pulse_rate = (double)v / ((double)t->rows * (double)t->cols * (double)t->copy_issued_at);
+    if (!t->pulses_seen || !t->copy_pending) return;
+    const volatile unsigned long long* seen = (const volatile unsigned long long*)t->pulses_seen;
+    const unsigned long long v = seen[0], v2 = seen[2];
+    if (v == kNoValueYet || seen[1] == kNoValueYet || v2 == kNoValueYet) return;    // (every word marked: all have arrived)
+    t->copy_pending = false;
+    t->pulse_rate = (double)v / ((double)t->rows * (double)t->cols * (double)t->copy_index);
+    if (t->copy_row_trains > 0)
+        t->row_fill = (double)v2 / (double)t->copy_row_trains;
+}
+
+// Long batches whose row trains are mostly empty (small error signals: a convolution layer's many output
+// positions) walk per-row lists of the samples that have a pulse.  Measured on 256 x 2304 with 12 544 update
+// vectors, 35 % of the row trains with a pulse: see the cell kernel's notes.  AHT_ROWLISTS = 0 / 1 forces it
+// off / on (where the word width allows).
+bool use_row_lists(const aht_tile* t, int B)
+{
+    if (!use_u32(t) || (uint64_t)B * (uint64_t)cpad(t) * 4u >= (1ull << 32)) return false;   // (32-bit byte offsets of the column words)
+    const int forced = env_int("AHT_ROWLISTS", -1);
+    if (forced == 0) return false;
+    if (forced == 1) return true;
+    return B >= 256 && t->row_fill >= 0.0 && t->row_fill < 0.55;
+}
+
+aht_status ensure_row_lists(aht_tile* t, int B)
+{
+    const size_t need = (size_t)rpad(t) * ((size_t)bpad(B) + kRowListPad);
+    if (need > t->rlist_entries) {
+        if (t->rlist) AHT_HIP(hipFree(t->rlist));
+        t->rlist = nullptr; t->rlist_entries = 0;
+        AHT_HIP(hipMalloc((void**)&t->rlist, need * sizeof(uint2)));
+        t->rlist_entries = need;
+    }
+    if (!t->rlen) AHT_HIP(hipMalloc((void**)&t->rlen, sizeof(uint32_t) * (size_t)rpad(t)));
+    return AHT_OK;
 }
 
 // the cell update of step `step` from the words in the tile's scratch
 // `strip0`, `strips`: the range of 64-column strips to work on (the caller knows that x is zero elsewhere)
 // `words`: where the pulse words are (the tile's own scratch, that of the first device of its unit cell, or
 // the static scratch)
-aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strip0, uint32_t strips,
-                        const WordBufs& words)
+// `full`: a full update of the tile (counted by pulse counter [0], whose rate chooses the launch shape)
+// `rowlists`: walk the tile's per-row sample lists (already built from `words`), one row per lane
+// `step`: where in device memory the step of this call is (a full update advances the tile's counter)
+aht_status launch_cells(aht_tile* t, int B, const uint32_t* step, hipStream_t s, uint32_t strip0, uint32_t strips,
+                        const WordBufs& words, bool full, bool rowlists = false)
 {
-    const int rpl = choose_rpl(t);
+    const int rpl = rowlists ? 1 : choose_rpl(t);
     // stream storage per cell: 12 words hold 320 pulses before an early drain is needed; at 4 rows
     // per lane, 9 words (224 pulses) let four workgroups share a compute unit's LDS
     int qwords = env_int("AHT_QWORDS", 0);
-    if (qwords < 5 || qwords > 160) qwords = (rpl == 4) ? 9 : 12;
+    // (walking row lists: 24 words; measured on 256 x 2304 with 12 544 vectors, kernel ms at 12 / 16 / 24 / 32 /
+    // 40 / 53 words: 1.58 / 1.56 / 1.52 / 1.60 / 1.59 / 2.13 -- longer streams mean fewer drains and lanes
+    // that idle less in them, until too few workgroups fit a compute unit)
+    if (qwords < 5 || qwords > 160) qwords = rowlists ? 24 : (rpl == 4) ? 9 : 12;
     const size_t lds_extra = (rpl > 1) ? 4 * 1024 : 0;       // exchange buffers of the last drain, 1 KB per wave
     while (qwords > 5 && (size_t)4 * rpl * 64 * qwords * 4 + lds_extra > 160 * 1024) --qwords;   // LDS of one CU
     CellPtrs p{};
@@ -363,7 +433,7 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     p.slope_down = t->planes[AHT_PLANE_SLOPE_DOWN];
     p.xw = words.xw;
     p.dw = words.dw;
-    p.pulse_count = t->pulse_count;
+    p.pulse_count = t->pulse_count + (full ? 0 : 1);
     CellArgs a{};
     a.R = t->rows;
     a.C = t->cols;
@@ -375,17 +445,40 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     a.nby = (uint32_t)((t->rows + 4 * rpl - 1) / (4 * rpl));
     a.k0 = (uint32_t)t->seed;
     a.k1 = (uint32_t)(t->seed >> 32);
-    a.t = step;
     a.c2c = t->dev.dw_min_std;
     a.qwords = qwords;
+    a.step = step;
+    a.advance = full ? t->step_state : nullptr;              // full updates count their steps themselves
     // one workgroup per tile of 4 * rpl rows x 64 columns, in equal shares for the 8 XCDs
     const uint64_t total = (uint64_t)a.nby * a.nbx;
     const uint64_t per = (total + 7) / 8;
     if (per * 8 > 0x7FFFFFFFull) return fail(AHT_ERR_UNSUPPORTED, "tile too large for one launch");
     const dim3 grid((unsigned)(per * 8));
     const size_t lds = (size_t)4 * rpl * 64 * qwords * 4 + lds_extra;
+    if (full) {
+        t->info.rows_per_lane = rpl;
+        t->info.side_rows_per_lane = 0;
+        t->info.row_lists = rowlists ? 1 : 0;
+        t->info.stream_words = qwords;
+    }
     const bool noise = t->dev.dw_min_std > 0.0f;
-    if (use_u32(t)) launch_cells_kind<uint32_t>(t->dev.kind, noise, rpl, grid, lds, s, p, a);
+    if (rowlists) {
+#define AHT_ROWLISTS_LAUNCH(K, N)                                                                                  \
+    hipLaunchKernelGGL((k_cell_update_rowlists<K, N>), grid, dim3(256), lds, s, p.W, p.dw_up, p.dw_down, p.b_max,    \
+                       p.b_min, p.slope_up, p.slope_down, (const uint32_t*)p.xw, (const uint32_t*)p.dw,             \
+                       p.pulse_count, a, t->rlist, t->rlen)
+#define AHT_ROWLISTS_KIND(K)                                                                                       \
+    do {                                                                                                          \
+        if (noise) AHT_ROWLISTS_LAUNCH(K, true); else AHT_ROWLISTS_LAUNCH(K, false);                               \
+    } while (0)
+        switch (t->dev.kind) {
+            case AHT_CONSTANT_STEP: AHT_ROWLISTS_KIND(kConstantStep); break;
+            case AHT_LINEAR_STEP: AHT_ROWLISTS_KIND(kLinearStep); break;
+            default: AHT_ROWLISTS_KIND(kSoftBounds); break;
+        }
+#undef AHT_ROWLISTS_KIND
+#undef AHT_ROWLISTS_LAUNCH
+    } else if (use_u32(t)) launch_cells_kind<uint32_t>(t->dev.kind, noise, rpl, grid, lds, s, p, a);
     else launch_cells_kind<uint64_t>(t->dev.kind, noise, rpl, grid, lds, s, p, a);
     AHT_HIP(hipGetLastError());
     return AHT_OK;
@@ -477,8 +570,8 @@ void launch_pair_kind(int kind, bool noise, int rpl_main, int rpl_side, dim3 gri
 #undef AHT_PAIR_KIND
 }
 
-aht_status launch_cells_pair(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strips, uint32_t strips_main,
-                             int rpl_main, int rpl_side, const WordBufs& words)
+aht_status launch_cells_pair(aht_tile* t, int B, const uint32_t* step, hipStream_t s, uint32_t strips, uint32_t strips_main,
+                             int rpl_main, int rpl_side, const WordBufs& words, bool full)
 {
     CellPtrs p{};
     p.W = t->W;
@@ -491,7 +584,7 @@ aht_status launch_cells_pair(aht_tile* t, int B, uint32_t step, hipStream_t s, u
     p.slope_down = t->planes[AHT_PLANE_SLOPE_DOWN];
     p.xw = words.xw;
     p.dw = words.dw;
-    p.pulse_count = t->pulse_count;
+    p.pulse_count = t->pulse_count + (full ? 0 : 1);
     size_t lds = 0;
     auto shape = [&](int rpl, uint32_t strip0, uint32_t nstrips) {
         int qwords = env_int("AHT_QWORDS", 0);
@@ -511,19 +604,72 @@ aht_status launch_cells_pair(aht_tile* t, int B, uint32_t step, hipStream_t s, u
         a.nby = (uint32_t)((t->rows + 4 * rpl - 1) / (4 * rpl));
         a.k0 = (uint32_t)t->seed;
         a.k1 = (uint32_t)(t->seed >> 32);
-        a.t = step;
         a.c2c = t->dev.dw_min_std;
         a.qwords = qwords;
+        a.step = step;
+        a.advance = full ? t->step_state : nullptr;
         return a;
     };
     const CellArgs a = shape(rpl_main, 0u, strips_main), b = shape(rpl_side, strips_main, strips - strips_main);
     const uint64_t main_blocks = ((uint64_t)a.nby * a.nbx + 7) / 8 * 8, side_blocks = ((uint64_t)b.nby * b.nbx + 7) / 8 * 8;
     if (main_blocks + side_blocks > 0x7FFFFFFFull) return fail(AHT_ERR_UNSUPPORTED, "tile too large for one launch");
     const dim3 grid((unsigned)(main_blocks + side_blocks));
+    if (full) {
+        t->info.rows_per_lane = rpl_main;
+        t->info.side_rows_per_lane = rpl_side;
+        t->info.row_lists = 0;
+        t->info.stream_words = a.qwords;
+    }
     const bool noise = t->dev.dw_min_std > 0.0f;
     if (use_u32(t)) launch_pair_kind<uint32_t>(t->dev.kind, noise, rpl_main, rpl_side, grid, lds, s, p, a, b, (uint32_t)main_blocks);
     else launch_pair_kind<uint64_t>(t->dev.kind, noise, rpl_main, rpl_side, grid, lds, s, p, a, b, (uint32_t)main_blocks);
     AHT_HIP(hipGetLastError());
+    return AHT_OK;
+}
+
+// Tiny tiles with a few update vectors take the whole call in one launch (k_update_small): every workgroup
+// draws the pulse words it needs itself, which costs about one extra microsecond per 4 096 cells and update
+// vector and saves a launch.  AHT_FUSED = 0 / 1 forces it off / on (where the call qualifies at all).
+bool use_small_kernel(const aht_tile* t, int B)
+{
+    if (B > kSmallMaxB || t->upd.update_management || t->dynamic_bl) return false;
+    const int forced = env_int("AHT_FUSED", -1);
+    if (forced == 0) return false;
+    if (forced == 1) return true;
+    return (uint64_t)t->rows * (uint64_t)t->cols * (uint64_t)B <= 32768u;
+}
+
+aht_status launch_small(aht_tile* t, const float* x, const float* d, int B, float lr, hipStream_t s, const ConvView& conv)
+{
+    const double A = std::sqrt((double)lr / ((double)t->dev.dw_min * (double)t->upd.bl));
+    const dim3 grid((unsigned)((t->cols + 63) / 64) * (unsigned)((t->rows + 3) / 4));
+    const bool noise = t->dev.dw_min_std > 0.0f;
+    weights_written(t);
+#define AHT_SMALL_LAUNCH(K, WT, N)                                                                                  \
+    hipLaunchKernelGGL((k_update_small<K, WT, N>), grid, dim3(256), 0, s, t->W, t->planes[AHT_PLANE_DW_UP],          \
+                       t->planes[AHT_PLANE_DW_DOWN], t->planes[AHT_PLANE_B_MAX], t->planes[AHT_PLANE_B_MIN],        \
+                       t->planes[AHT_PLANE_SLOPE_UP], t->planes[AHT_PLANE_SLOPE_DOWN], x, d, B, t->rows, t->cols,   \
+                       t->upd.bl, A, t->train_kind, (uint32_t)t->seed, (uint32_t)(t->seed >> 32), t->dev.dw_min_std, \
+                       t->pulse_count, t->step_state, conv)
+#define AHT_SMALL_NOISE(K, WT)                                                                                      \
+    do {                                                                                                           \
+        if (noise) AHT_SMALL_LAUNCH(K, WT, true); else AHT_SMALL_LAUNCH(K, WT, false);                              \
+    } while (0)
+#define AHT_SMALL_KIND(WT)                                                                                          \
+    switch (t->dev.kind) {                                                                                         \
+        case AHT_CONSTANT_STEP: AHT_SMALL_NOISE(kConstantStep, WT); break;                                          \
+        case AHT_LINEAR_STEP: AHT_SMALL_NOISE(kLinearStep, WT); break;                                              \
+        default: AHT_SMALL_NOISE(kSoftBounds, WT); break;                                                           \
+    }
+    if (use_u32(t)) { AHT_SMALL_KIND(uint32_t) } else { AHT_SMALL_KIND(uint64_t) }
+#undef AHT_SMALL_KIND
+#undef AHT_SMALL_NOISE
+#undef AHT_SMALL_LAUNCH
+    AHT_HIP(hipGetLastError());
+    t->info.rows_per_lane = 1;
+    t->info.side_rows_per_lane = 0;
+    t->info.row_lists = 0;
+    t->info.stream_words = 0;                     // (no pulse streams: the samples are applied pulse by pulse)
     return AHT_OK;
 }
 
@@ -587,16 +733,18 @@ aht_status aht_tile_create(aht_tile** out, int32_t rows, int32_t cols, const aht
     for (int p = 0; p < nplanes; ++p)
         if ((e = hipMalloc((void**)&t->planes[p], n * sizeof(float))) != hipSuccess)
             return cleanup(hip_fail(e, "hipMalloc(plane)"));
-    if ((e = hipMalloc((void**)&t->pulse_count, sizeof(unsigned long long))) != hipSuccess)
+    if ((e = hipMalloc((void**)&t->pulse_count, 3 * sizeof(unsigned long long))) != hipSuccess)
         return cleanup(hip_fail(e, "hipMalloc(counter)"));
     if ((e = hipMemset(t->W, 0, n * sizeof(float))) != hipSuccess) return cleanup(hip_fail(e, "hipMemset"));
     weights_written(t);
-    if ((e = hipMemset(t->pulse_count, 0, sizeof(unsigned long long))) != hipSuccess)
+    if ((e = hipMemset(t->pulse_count, 0, 3 * sizeof(unsigned long long))) != hipSuccess)
         return cleanup(hip_fail(e, "hipMemset"));
-    if (n >= kAdaptMinCells) {                    // without the pinned word the static choice stays
-        if (hipHostMalloc((void**)&t->pulses_seen, 64, hipHostMallocDefault) == hipSuccess) *t->pulses_seen = 0;
-        else { t->pulses_seen = nullptr; (void)hipGetLastError(); }
-    }
+    if ((e = hipMalloc((void**)&t->step_state, 4 * sizeof(uint32_t))) != hipSuccess)
+        return cleanup(hip_fail(e, "hipMalloc(step)"));
+    if ((e = hipMemset(t->step_state, 0, 4 * sizeof(uint32_t))) != hipSuccess) return cleanup(hip_fail(e, "hipMemset"));
+    // the pinned words of the feedback; without them the static choices stay
+    if (hipHostMalloc((void**)&t->pulses_seen, 64, hipHostMallocDefault) == hipSuccess) std::memset(t->pulses_seen, 0, 64);
+    else { t->pulses_seen = nullptr; (void)hipGetLastError(); }
     PlaneArgs pa{};
     pa.kind = dev->kind;
     pa.dw_min = dev->dw_min; pa.dw_min_dtod = dev->dw_min_dtod;
@@ -631,7 +779,7 @@ aht_status aht_tile_destroy(aht_tile* t)
     };
     rel(t->W);
     for (auto* p : t->planes) rel(p);
-    rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->bl_b); rel(t->pulse_count);
+    rel(t->xw); rel(t->dw); rel(t->a_x); rel(t->a_d); rel(t->bl_b); rel(t->pulse_count); rel(t->rlist); rel(t->rlen); rel(t->step_state);
     for (auto* p : t->tplanes) rel(p);
     rel(t->mvm_xq); rel(t->mvm_part); rel(t->mvm_codes); rel(t->ucell_w); rel(t->mvm_alpha); rel(t->mvm_norm); rel(t->xfer);
     for (hipEvent_t e : t->events) (void)hipEventDestroy(e);
@@ -679,7 +827,27 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
     if (B > 0 && (!x_dev || !d_dev)) return fail(AHT_ERR_INVALID_ARG, "null x or d");
     aht_status st = check_device(t);
     if (st != AHT_OK) return st;
-    if (B > 0 && lr > 0.0f) {
+    const bool full = col_hi < 0;                 // the whole tile: the step is read and advanced on the device
+    if (B > 0 && lr > 0.0f && full && use_small_kernel(t, B)) {
+        hipStream_t s = (hipStream_t)stream;
+        hipEvent_t* ev = nullptr;
+        if (!static_scratch_only && t->profiling && t->events_used + 3 <= 3 * 4096) {
+            while (t->events.size() < t->events_used + 3) {
+                hipEvent_t e;
+                AHT_HIP(hipEventCreate(&e));
+                t->events.push_back(e);
+            }
+            ev = &t->events[t->events_used];
+            AHT_HIP(hipEventRecord(ev[0], s));
+            AHT_HIP(hipEventRecord(ev[1], s));      // (no separate pulse-train kernel)
+        }
+        if ((st = launch_small(t, x_dev, d_dev, B, lr, s, conv)) != AHT_OK) return st;
+        if (ev) {
+            AHT_HIP(hipEventRecord(ev[2], s));
+            t->events_used += 3;
+        }
+        t->full_updates += 1;
+    } else if (B > 0 && lr > 0.0f) {
         WordBufs bufs;
         if (static_scratch_only) {
             const size_t need = static_scratch_layout(t, B, nullptr, nullptr);
@@ -706,29 +874,59 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         }
         if (ev) AHT_HIP(hipEventRecord(ev[0], s));
         if (col_hi < 0) refresh_pulse_rate(t);
-        if ((st = launch_words(t, bufs, x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
+        // whether this tile's calls are worth watching: large enough for a choice of rows per lane, or long
+        // batches of 32-bit words, which may turn out sparse
+        const bool watched = t->pulses_seen && col_hi < 0 &&
+                             ((size_t)t->rows * t->cols >= kAdaptMinCells || (use_u32(t) && B >= 256));
+        const bool rowlists = col_hi < 0 && !static_scratch_only && use_row_lists(t, B);
+        if (rowlists && (st = ensure_row_lists(t, B)) != AHT_OK) return st;
+        const uint32_t* step_at = t->step_state;                 // a full update: the tile's own counter
+        if (!full && (st = step_from_host(t, t->step, s, &step_at)) != AHT_OK) return st;
+        if ((st = launch_words(t, bufs, x_dev, d_dev, B, lr, step_at, s, conv, watched ? t->pulse_count + 2 : nullptr)) != AHT_OK)
+            return st;
         if (ev) AHT_HIP(hipEventRecord(ev[1], s));
         const uint32_t strip0 = col_hi < 0 ? 0u : (uint32_t)(col_lo / 64);
         const uint32_t strips = (col_hi < 0 ? (uint32_t)((t->cols + 63) / 64) : (uint32_t)(col_hi / 64 + 1)) - strip0;
         uint32_t strips_main = strips;
         int rpl_main = 0, rpl_side = 0;
+        if (rowlists) {
+            hipLaunchKernelGGL(k_compact_rows, dim3((unsigned)((t->rows + 3) / 4)), dim3(256), 0, s, (const uint32_t*)bufs.dw,
+                               t->rows, B, bpad(B), t->rlist, t->rlen);
+            AHT_HIP(hipGetLastError());
+            if ((st = launch_cells(t, B, step_at, s, strip0, strips, bufs, true, true)) != AHT_OK) return st;
+        } else {
         if (col_hi < 0) even_round(t, B, strips, &strips_main, &rpl_main, &rpl_side);
         if (strips_main < strips) {
-            if ((st = launch_cells_pair(t, B, t->step, s, strips, strips_main, rpl_main, rpl_side, bufs)) != AHT_OK) return st;
-        } else if ((st = launch_cells(t, B, t->step, s, strip0, strips, bufs)) != AHT_OK) return st;
+            if ((st = launch_cells_pair(t, B, step_at, s, strips, strips_main, rpl_main, rpl_side, bufs, true)) != AHT_OK) return st;
+        } else if ((st = launch_cells(t, B, step_at, s, strip0, strips, bufs, full)) != AHT_OK) return st;
+        }
         if (ev) {
             AHT_HIP(hipEventRecord(ev[2], s));
             t->events_used += 3;
         }
         if (col_hi < 0) {
             t->full_updates += 1;
-            // the first eight updates and every sixteenth after them report the counter
-            if (!static_scratch_only && t->pulses_seen && (t->full_updates <= 8 || t->full_updates % 16 == 0)) {
-                AHT_HIP(hipMemcpyAsync(t->pulses_seen, t->pulse_count, sizeof(unsigned long long),
+            if (watched) t->row_trains += (uint64_t)t->rows * (uint64_t)((B + 15) / 16);    // every 16th sample is counted
+            // the counters are reported when no earlier report is still on its way: after each of the first
+            // eight updates, then sixteen updates after the last report
+            if (!static_scratch_only && watched && !t->copy_pending &&
+                (t->full_updates <= 8 || t->full_updates >= t->copy_index + 16)) {
+                for (int k = 0; k < 3; ++k) ((volatile unsigned long long*)t->pulses_seen)[k] = kNoValueYet;
+                AHT_HIP(hipMemcpyAsync(t->pulses_seen, t->pulse_count, 3 * sizeof(unsigned long long),
                                        hipMemcpyDeviceToHost, s));
-                t->copy_issued_at = t->full_updates;
+                t->copy_pending = true;
+                t->copy_index = t->full_updates;
+                t->copy_row_trains = t->row_trains;
             }
+        } else {
+            // part of the tile only (a transfer): the step went to the kernels by value; the device's counter follows
+            hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, s, t->step_state, t->step + 1u, 0, 0);
+            AHT_HIP(hipGetLastError());
         }
+    } else {
+        // nothing to apply: the call still counts
+        hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, (hipStream_t)stream, t->step_state, 1u, 1, 0);
+        AHT_HIP(hipGetLastError());
     }
     t->step += 1;
     return AHT_OK;
@@ -829,6 +1027,8 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
         AHT_HIP(hipDeviceSynchronize());          // (the caller's stream may not wait for the null stream)
         t->mvm_codes_elems = cneed;
     }
+    t->info.mvm_path = codes_path ? 2 : planes_path ? 3 : 1;
+    t->info.mvm_splits = 1;
     hipLaunchKernelGGL(k_mvm_prepare, dim3((unsigned)B), dim3(1024), 0, s, x, K, vec_in, a, k0, k1, step, tag_in,
                        t->mvm_xq, t->mvm_alpha, t->mvm_norm, (codes_path || planes_path) ? t->mvm_codes : nullptr,
                        planes_path ? 3 : 1, plane_elems);
@@ -860,6 +1060,7 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
         }
         if (splits > 16) splits = 16;
         if (splits < 1) splits = 1;
+        t->info.mvm_splits = splits;
         // With four slices the four waves of a workgroup take one each and finish the product
         // themselves.  For large transposed products this loses: there two neighbouring groups of 16
         // outputs share every 128-byte line of the weights, and they share it best as waves of one
@@ -959,6 +1160,7 @@ static aht_status analog_mvm(aht_tile* t, const aht_io_params* io, const float* 
     }
     if (splits > 16) splits = 16;
     if (splits < 1) splits = 1;
+    t->info.mvm_splits = splits;
     if (splits > 1) {
         const size_t pneed = (size_t)splits * (size_t)B * (size_t)N;
         if (pneed > t->mvm_part_floats) {
@@ -1075,7 +1277,9 @@ aht_status aht_unit_cell_update(aht_tile* const* dev, int32_t n, int32_t which, 
         if ((st = ensure_scratch(lead, B)) != AHT_OK) return st;
         hipStream_t s = (hipStream_t)stream;
         const WordBufs bufs = tile_bufs(lead);
-        if ((st = launch_words(lead, bufs, x_dev, d_dev, B, lr, step, s, ConvView{})) != AHT_OK) return st;
+        const uint32_t* step_at = nullptr;                       // every device reads the step from the first one's slot
+        if ((st = step_from_host(lead, step, s, &step_at)) != AHT_OK) return st;
+        if ((st = launch_words(lead, bufs, x_dev, d_dev, B, lr, step_at, s, ConvView{})) != AHT_OK) return st;
         const uint32_t strips = (uint32_t)((lead->cols + 63) / 64);
         // The devices are tiles of their own, fed from the same words: those after the first run beside
         // it, each on its own tile's side stream (measured, all devices updated: two devices of 512 x 512
@@ -1099,16 +1303,20 @@ aht_status aht_unit_cell_update(aht_tile* const* dev, int32_t n, int32_t which, 
             int rpl_main = 0, rpl_side = 0;
             even_round(dev[k], B, strips, &strips_main, &rpl_main, &rpl_side);
             if (strips_main < strips) {
-                if ((st = launch_cells_pair(dev[k], B, step, sk, strips, strips_main, rpl_main, rpl_side, bufs)) != AHT_OK)
+                if ((st = launch_cells_pair(dev[k], B, step_at, sk, strips, strips_main, rpl_main, rpl_side, bufs, false)) != AHT_OK)
                     return st;
-            } else if ((st = launch_cells(dev[k], B, step, sk, 0u, strips, bufs)) != AHT_OK) return st;
+            } else if ((st = launch_cells(dev[k], B, step_at, sk, 0u, strips, bufs, false)) != AHT_OK) return st;
             if (sk != s) {
                 AHT_HIP(hipEventRecord(dev[k]->side_join, sk));
                 AHT_HIP(hipStreamWaitEvent(s, dev[k]->side_join, 0));
             }
         }
     }
-    for (int k = 0; k < n; ++k) dev[k]->step = step + 1;     // the cell's devices count calls together
+    for (int k = 0; k < n; ++k) {                             // the cell's devices count calls together
+        dev[k]->step = step + 1;
+        hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, (hipStream_t)stream, dev[k]->step_state, step + 1u, 0, 0);
+    }
+    AHT_HIP(hipGetLastError());
     return AHT_OK;
 }
 
@@ -1309,6 +1517,15 @@ aht_status aht_set_pulse_mode(aht_tile* t, int32_t train_kind, int32_t dynamic_b
     return AHT_OK;
 }
 
+aht_status aht_get_launch_info(const aht_tile* t, aht_launch_info* out)
+{
+    if (!t || !out) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    *out = t->info;
+    out->pulse_rate = t->pulse_rate;
+    out->row_fill = t->row_fill;
+    return AHT_OK;
+}
+
 aht_status aht_get_step(const aht_tile* t, uint32_t* step)
 {
     if (!t || !step) return fail(AHT_ERR_INVALID_ARG, "null argument");
@@ -1319,7 +1536,25 @@ aht_status aht_get_step(const aht_tile* t, uint32_t* step)
 aht_status aht_set_step(aht_tile* t, uint32_t step)
 {
     if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    const uint32_t state[2] = {step, 0u};
+    AHT_HIP(hipDeviceSynchronize());              // (no stream is given: nothing of the tile may be in flight)
+    AHT_HIP(hipMemcpy(t->step_state, state, sizeof(state), hipMemcpyHostToDevice));
     t->step = step;
+    return AHT_OK;
+}
+
+aht_status aht_sync_step(aht_tile* t, uint32_t* step, void* stream)
+{
+    if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
+    aht_status st = check_device(t);
+    if (st != AHT_OK) return st;
+    uint32_t v = 0;
+    AHT_HIP(hipMemcpyAsync(&v, t->step_state, sizeof(v), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    AHT_HIP(hipStreamSynchronize((hipStream_t)stream));
+    t->step = v;
+    if (step) *step = v;
     return AHT_OK;
 }
 
@@ -1328,10 +1563,10 @@ aht_status aht_get_pulse_count(const aht_tile* t, uint64_t* pulses, void* stream
     if (!t || !pulses) return fail(AHT_ERR_INVALID_ARG, "null argument");
     aht_status st = check_device(t);
     if (st != AHT_OK) return st;
-    unsigned long long v = 0;
-    AHT_HIP(hipMemcpyAsync(&v, t->pulse_count, sizeof(v), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    unsigned long long v[2] = {0, 0};
+    AHT_HIP(hipMemcpyAsync(v, t->pulse_count, sizeof(v), hipMemcpyDeviceToHost, (hipStream_t)stream));
     AHT_HIP(hipStreamSynchronize((hipStream_t)stream));
-    *pulses = v;
+    *pulses = v[0] + v[1];
     return AHT_OK;
 }
 
@@ -1382,7 +1617,9 @@ static aht_status debug_pulse_words_impl(aht_tile* t, const float* x_dev, const 
     if (st != AHT_OK) return st;
     if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
     hipStream_t s = (hipStream_t)stream;
-    if ((st = launch_words(t, tile_bufs(t), x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
+    const uint32_t* step_at = nullptr;
+    if ((st = step_from_host(t, t->step, s, &step_at)) != AHT_OK) return st;
+    if ((st = launch_words(t, tile_bufs(t), x_dev, d_dev, B, lr, step_at, s, conv)) != AHT_OK) return st;
     const size_t nx = (size_t)B * t->cols, nd = (size_t)B * t->rows;
     if (use_u32(t)) {
         hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint32_t*)t->xw, xw_dev, B, t->cols, cpad(t), 0);
@@ -1444,7 +1681,9 @@ aht_status aht_debug_apply_words(aht_tile* t, const uint64_t* xw_dev, const uint
         hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint64_t*)t->dw, B, t->rows, rpad(t), bpad(B), t->upd.bl);
     }
     AHT_HIP(hipGetLastError());
-    return launch_cells(t, B, step, s, 0u, (uint32_t)((t->cols + 63) / 64), tile_bufs(t));
+    const uint32_t* step_at = nullptr;
+    if ((st = step_from_host(t, step, s, &step_at)) != AHT_OK) return st;
+    return launch_cells(t, B, step_at, s, 0u, (uint32_t)((t->cols + 63) / 64), tile_bufs(t), false);
 }
 
 aht_status aht_debug_philox(const uint32_t* ctr_dev, const uint32_t* key_dev, int32_t n, uint32_t* out_dev, void* stream)

@@ -344,7 +344,8 @@ __global__ void __launch_bounds__(256)
 k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int Rpad, int Cpad,
               int Bpad, int BL, double A, const double* __restrict__ a_x, const double* __restrict__ a_d,
               const int32_t* __restrict__ bl_b, int deterministic,
-              uint32_t k0, uint32_t k1, uint32_t t, WordT* __restrict__ xw, WordT* __restrict__ dw, ConvView conv)
+              uint32_t k0, uint32_t k1, const uint32_t* __restrict__ step, WordT* __restrict__ xw, WordT* __restrict__ dw,
+              ConvView conv, unsigned long long* __restrict__ row_words_with_pulses)
 {
     constexpr int kBlocks = (sizeof(WordT) == 4) ? 8 : 16;       // Philox blocks per line value, at most
     constexpr int kLines = 64 / kBlocks;                         // lines served at a time by the shared path
@@ -356,6 +357,7 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
     const int len = is_x ? C : R;
     const uint32_t tagw = (is_x ? kTagX : kTagD) << 24;
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t t = *step;                                    // the step of this call, in device memory
     for (uint32_t b = blockIdx.y; b < (uint32_t)B; b += gridDim.y) {
         WordT word = 0;
         const int bl = bl_b ? bl_b[b] : BL;
@@ -427,12 +429,46 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
             }
             word &= (((WordT)1 << bl) - 1);
         }
+        // how many row trains have a pulse at all, counted on every 16th sample (atomics on one address
+        // serialise: counting all 12 544 samples of a long batch cost 0.3 ms): the host reads the sum now and
+        // then and, where most trains have none, lets the cell update walk per-row lists of the samples that do
+        if (row_words_with_pulses && !is_x && (b & 15u) == 0u) {
+            const unsigned long long some = __ballot(word != 0);
+            if (lane == 0 && some) atomicAdd(row_words_with_pulses, (unsigned long long)__popcll(some));
+        }
         if (negative) word |= (WordT)1 << WordTraits<WordT>::kSignBit;
         if (live) {
             if (is_x) xw[(size_t)b * Cpad + idx] = word;
             else dw[(size_t)idx * Bpad + b] = word;
         }
     }
+}
+
+// Per row, the samples whose row train has at least one pulse, in sample order: entry k of row i is
+// (sample b, row word), rlist[i * stride + k], k < rlen[i]; 16 all-zero entries follow the last one
+// (the cell update reads its list a few entries ahead and in groups).  One wave per row.
+constexpr int kRowListPad = 16;
+__global__ void __launch_bounds__(256)
+k_compact_rows(const uint32_t* __restrict__ dw, int R, int B, int Bpad, uint2* __restrict__ rlist,
+               uint32_t* __restrict__ rlen)
+{
+    const int row = (int)(blockIdx.x * 4 + (threadIdx.x >> 6));
+    if (row >= R) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const size_t stride = (size_t)Bpad + kRowListPad;
+    uint2* __restrict__ out = rlist + (size_t)row * stride;
+    uint32_t n = 0;
+    for (int b0 = 0; b0 < B; b0 += 64) {
+        const int b = b0 + (int)lane;
+        const uint32_t w = b < B ? dw[(size_t)row * Bpad + b] : 0u;
+        const bool some = (w & 0x7FFFFFFFu) != 0u;
+        const unsigned long long m = __ballot(some);
+        const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        if (some) out[n + before] = make_uint2((uint32_t)b, w);
+        n += (uint32_t)__popcll(m);
+    }
+    if (lane < (uint32_t)kRowListPad) out[n + lane] = make_uint2(0u, 0u);
+    if (lane == 0) rlen[row] = n;
 }
 
 // word format conversions for the debug entry points (public format: u64 [B][len], sign in bit 63;
@@ -531,10 +567,41 @@ struct CellArgs {
     uint32_t nbx, nby;            // tiles along columns / rows
     uint32_t bx0;                 // first column strip of this launch (a caller that knows where x is
                                   // non-zero leaves the other strips out: their cells get no pulses)
-    uint32_t k0, k1, t;
+    uint32_t k0, k1;
     float c2c;
     int qwords;                   // 32-bit words of stream storage per cell (>= 5)
+    // The step of the call is read from device memory.  A tile's step state: [0] the step counter, [1] waves
+    // of the running launch that have finished, [2] a step written by the host for launches that do not
+    // count (updates of unit cells, transfers, injected words).  A full update reads [0] and the wave that
+    // finishes last advances it (`advance` = the state), so that a sequence of such calls can be recorded
+    // once in a HIP graph and replayed; the others read [2] and advance nothing (`advance` null).
+    const uint32_t* step;
+    uint32_t* advance;
 };
+
+// state[0] = value (relative: += value), no wave finished; or only state[2] = value
+__global__ void k_set_step(uint32_t* state, uint32_t value, int relative, int slot2_only)
+{
+    if (slot2_only) {
+        state[2] = value;
+    } else {
+        state[0] = relative ? state[0] + value : value;
+        state[1] = 0u;
+    }
+}
+
+// after a cell-update launch's body: the last of the launch's waves to get here advances the step
+__device__ __forceinline__ void finish_step(uint32_t* step_state, uint32_t waves_of_launch)
+{
+    if (!step_state) return;                       // wave-uniform
+    if ((threadIdx.x & 63u) == 0u) {
+        const uint32_t before = atomicAdd(step_state + 1, 1u);
+        if (before + 1u == waves_of_launch) {      // every other wave has read the step long ago
+            step_state[1] = 0u;
+            atomicAdd(step_state, 1u);
+        }
+    }
+}
 
 // select by an all-ones / all-zeros mask: (m & a) | (~m & b), one v_bfi_b32
 __device__ __forceinline__ float mask_select(uint32_t m, float a, float b)
@@ -594,14 +661,19 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 // are fetched with scalar loads.
 // (The body is a device function of its own so that one launch can run it with two different
 // numbers of rows per lane, see k_cell_update_pair; `block` is the workgroup's index in its part.)
-template <int KIND, typename WordT, bool NOISE, int RPL>
+// SPARSE (one row per lane, 32-bit words): phase A walks the row's list of samples whose row train has a
+// pulse (rlist, rlen: see k_compact_rows) instead of all B samples; a sample left out gives every cell of
+// the row the count zero, so the streams, and with them all results, are the same.
+template <int KIND, typename WordT, bool NOISE, int RPL, bool SPARSE = false>
 __device__ __forceinline__ void
 cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
                  const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
                  const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
                  const WordT* __restrict__ xw, const WordT* __restrict__ dw,
-                 unsigned long long* __restrict__ pulse_count, const CellArgs& a, const uint32_t block)
+                 unsigned long long* __restrict__ pulse_count, const CellArgs& a, const uint32_t block,
+                 const uint2* __restrict__ rlist = nullptr, const uint32_t* __restrict__ rlen = nullptr)
 {
+    static_assert(!SPARSE || (RPL == 1 && sizeof(WordT) == 4), "row lists: one row per lane, 32-bit words");
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
     constexpr int kSign = WordTraits<WordT>::kSignBit;
@@ -721,6 +793,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
         // in registers through phase A.
         int dlane = (int)lane_by_count();
         asm volatile("" : "+v"(dlane));
+        const uint32_t tstep = *(const volatile uint32_t*)a.step;    // read here, at the drain, where it is used
         // The device parameters are needed only here.  Loading them now (normally once per call)
         // keeps 6 registers per cell free during phase A.
         float s_up[RPL], s_dn_neg[RPL], bmax[RPL], bmin[RPL], sl_up[RPL], sl_dn[RPL];
@@ -849,7 +922,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
         auto row_step = [&](int i, int c, auto mode_tag) __attribute__((always_inline)) {
             constexpr int mode = decltype(mode_tag)::value;
             float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (NOISE) gauss4_unit(a.k0, a.k1, cellid[c], blk[c], a.t, kTagC2C, z);
+            if (NOISE) gauss4_unit(a.k0, a.k1, cellid[c], blk[c], tstep, kTagC2C, z);
             blk[c] += 1;
             const int lo = (int)(q[c] & 31u) - 4 * i, hi = (int)endpos[c] - 4 * i;
 #pragma unroll
@@ -940,7 +1013,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
 #pragma unroll
         for (int c = 0; c < RPL; ++c) {
             WordT dm = dv[c] & kBits;             // the row word without its sign: on the scalar unit
-            if constexpr (sizeof(WordT) == 4) asm("" : "+s"(dm));            // (not folded into a three-input vector op)
+            if constexpr (sizeof(WordT) == 4 && !SPARSE) asm("" : "+s"(dm)); // (not folded into a three-input vector op)
             const WordT both = xv & dm;
             n[c] = (sizeof(WordT) == 8)
                        ? (uint32_t)__popc((uint32_t)((uint64_t)both >> 32)) + (uint32_t)__popc((uint32_t)both)
@@ -984,6 +1057,125 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
         return __any(nf) != 0;
     };
     WordT xg[G];                                  // column words of the group in hand
+    if constexpr (SPARSE) {
+        // The row's list: entries `pos` .. of (sample, row word).  The loop keeps the entries of the group
+        // in hand (e), of the next one (e1) and, on their way, of the one after (e2); the column words of
+        // the next group are requested, by the samples e1 names, as soon as the counts and sign masks of
+        // this group are taken, into the same registers.
+        const size_t lstride = drow + (size_t)kRowListPad;
+        const size_t lbase = (size_t)i0 * lstride;
+        const int n_list = (int)rlen[i0];
+        uint32_t xoff0 = (uint32_t)(xlane * sizeof(WordT));
+        const uint32_t xrow_bytes = (uint32_t)(xstride * sizeof(WordT));   // (the host keeps B * xrow_bytes below 2^32)
+        auto x_of = [&](uint32_t sample) __attribute__((always_inline)) {
+            asm volatile("" : "+v"(xoff0));
+            return *(const WordT*)((const char*)xp + (size_t)(sample * xrow_bytes) + xoff0);
+        };
+        // (read through the constant address space: the lists were written by an earlier kernel and nothing
+        // in this one writes them, and a wave-uniform load from there is always a scalar load)
+        typedef __attribute__((address_space(4))) const uint32_t const_u32;
+        const const_u32* rwords = (const const_u32*)(size_t)rlist;
+        auto entry = [&](int at) __attribute__((always_inline)) {
+            const size_t k = 2 * (lbase + (size_t)at);
+            return make_uint2(rwords[k], rwords[k + 1]);
+        };
+        uint2 e[G], e1[G], e2[G];
+        int pos = 0;
+        bool primed = false, done_s = false;
+        do {
+            bool full = false;
+            while (!full && pos < n_list) {
+                if (!primed) {                    // (re)start the pipeline at pos
+#pragma unroll
+                    for (int u = 0; u < G; ++u) {
+                        e[u] = entry(pos + u);
+                        e1[u] = entry(pos + G + u);
+                    }
+#pragma unroll
+                    for (int u = 0; u < G; ++u) xg[u] = x_of(e[u].x);
+                    primed = true;
+                }
+                uint32_t n[G][RPL], xm[G], sum = 0;
+                bool stopped = false, big = false;
+                for (;;) {
+#pragma unroll
+                    for (int u = 0; u < G; ++u) e2[u] = entry(pos + 2 * G + u);
+#pragma unroll
+                    for (int u = 0; u < G; ++u) {
+                        const WordT dv[RPL] = {(WordT)e[u].y};
+                        count(xg[u], dv, n[u]);
+                        xm[u] = sign_mask(xg[u]);
+                        asm volatile("" : "+v"(xm[u]));
+                    }
+                    asm volatile("" ::: "memory");         // the loads below stay below the last use of xg
+#pragma unroll
+                    for (int u = 0; u < G; ++u) xg[u] = x_of(e1[u].x);
+                    sum = 0;
+#pragma unroll
+                    for (int u = 0; u < G; ++u) sum += n[u][0];
+                    asm volatile("v_add_u32_e32 %0, %0, %1" : "+v"(plen[0]) : "v"(sum));
+                    big = sum > 31u;
+                    if (__any(plen[0] > 31u)) {
+                        stopped = true;
+                        break;
+                    }
+#pragma unroll
+                    for (int u = 0; u < G; ++u) {
+                        const WordT dv[RPL] = {(WordT)e[u].y};
+                        uint32_t m1[RPL];
+                        direction_of(xm[u], dv, m1);
+                        pend[0] = __builtin_amdgcn_alignbit(m1[0], pend[0], n[u][0]);
+                    }
+                    pos += G;
+#pragma unroll
+                    for (int u = 0; u < G; ++u) {
+                        e[u] = e1[u];
+                        e1[u] = e2[u];
+                    }
+                    if (pos >= n_list) break;
+                }
+                if (stopped) {                    // empty the pending word, then deal with the group in hand
+                    plen[0] -= sum;
+                    commit(0);
+                    if (nearly_full()) {          // drain first, then take this group again
+                        full = true;
+                        primed = false;
+                    } else if (__any(big)) {      // a group with a large count: sample by sample while room lasts
+                        primed = false;
+#pragma unroll
+                        for (int u = 0; u < G; ++u) {
+                            const WordT dv[RPL] = {(WordT)e[u].y};
+                            uint32_t m1[RPL];
+                            direction_of(xm[u], dv, m1);
+                            append_slow(n[u], m1);
+                            pos += 1;
+                            if (nearly_full()) {
+                                full = true;
+                                break;
+                            }
+                        }
+                    } else {                      // fits now: the counts and sign masks are still in hand
+                        plen[0] += sum;
+#pragma unroll
+                        for (int u = 0; u < G; ++u) {
+                            const WordT dv[RPL] = {(WordT)e[u].y};
+                            uint32_t m1[RPL];
+                            direction_of(xm[u], dv, m1);
+                            pend[0] = __builtin_amdgcn_alignbit(m1[0], pend[0], n[u][0]);
+                        }
+                        pos += G;
+#pragma unroll
+                        for (int u = 0; u < G; ++u) {
+                            e[u] = e1[u];
+                            e1[u] = e2[u];
+                        }
+                    }
+                }
+            }
+            done_s = pos >= n_list;
+            drain(done_s);
+        } while (!done_s);
+    } else {
     bool have_x = false;                          // xg holds (or is about to receive) the words of samples b .. b+G-1
     bool more = false;
     int b = 0;
@@ -1108,6 +1300,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
         done = b >= B;
         drain(done);
     } while (!done);
+    }
 
     unsigned long long pulses = 0;
     // the column is worked out again (lane index from the execution mask), so that neither the
@@ -1145,6 +1338,23 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 {
     cell_update_body<KIND, WordT, NOISE, RPL>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down, xw, dw,
                                               pulse_count, a, blockIdx.x);
+    finish_step(a.advance, gridDim.x * 4u);
+}
+
+// The cell update along per-row sample lists (one row per lane, 32-bit words), for long batches whose row
+// trains are mostly empty.
+template <int KIND, bool NOISE>
+__global__ void __launch_bounds__(256, 4)
+k_cell_update_rowlists(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
+                       const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
+                       const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
+                       const uint32_t* __restrict__ xw, const uint32_t* __restrict__ dw,
+                       unsigned long long* __restrict__ pulse_count, CellArgs a, const uint2* __restrict__ rlist,
+                       const uint32_t* __restrict__ rlen)
+{
+    cell_update_body<KIND, uint32_t, NOISE, 1, true>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down,
+                                                     xw, dw, pulse_count, a, blockIdx.x, rlist, rlen);
+    finish_step(a.advance, gridDim.x * 4u);
 }
 
 // One launch, two shapes: the first `main_blocks` workgroups work on their range of column strips at RPL
@@ -1165,6 +1375,122 @@ k_cell_update_pair(float* __restrict__ W, const float* __restrict__ p_dw_up, con
     else
         cell_update_body<KIND, WordT, NOISE, SIDE>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down, xw,
                                                    dw, pulse_count, b, blockIdx.x - main_blocks);
+    finish_step(a.advance, gridDim.x * 4u);
+}
+
+// ------------------------------------------------------------------------------------------
+// The whole update call in one launch, for tiny tiles and a few update vectors (an on-line update of
+// a small layer: 64 x 64, one vector): two dependent launches cost more than the work itself.  A
+// workgroup owns 4 rows x 64 columns (one cell per lane), draws the pulse words of its 64 columns and
+// 4 rows for all B samples into LDS -- the words of a line are drawn again by every workgroup that
+// needs them, which is why this is for small tiles only -- and applies the samples in order, pulse
+// by pulse.  Same counters, same arithmetic per pulse (device_step, gauss4_unit) as the two-kernel
+// path: same bits.  No update management and no per-sample train length (they need a reduction over
+// the whole vector first).
+// ------------------------------------------------------------------------------------------
+template <typename WordT>
+__device__ __forceinline__ WordT line_word(float v, double a, int bl, int deterministic, bool is_x, uint32_t idx,
+                                           uint32_t b, uint32_t t, uint32_t k0, uint32_t k1)
+{
+    const float av = fabsf(v);
+    if (!(av > 0.0f && av < __builtin_inff() && a > 0.0)) return 0;
+    WordT word = 0;
+    double p = a * (double)av;
+    if (!(p < 1.0)) p = 1.0;
+    const uint64_t T = (uint64_t)(p * 4294967296.0);              // 0 .. 2^32
+    if (T != 0) {
+        if (deterministic) {
+            const uint64_t lim = 2ull * (uint64_t)bl * T;
+            for (int n = 0; n < bl; ++n) {
+                const bool set = is_x ? (((uint64_t)(2 * n + 1)) << 32) < lim
+                                      : (uint64_t)(__brev((uint32_t)n) ^ 0xAAAAAAAAu) < T;
+                word |= (WordT)(set ? 1u : 0u) << n;
+            }
+        } else if ((T >> 32) != 0) {
+            word = (((WordT)1 << bl) - 1);
+        } else {
+            const uint32_t Tlo = (uint32_t)T, tagw = (is_x ? kTagX : kTagD) << 24;
+            for (int blk = 0; blk < ((bl + 3) >> 2); ++blk) {
+                const U4 r = philox4x32_10(idx, b, t, tagw | (uint32_t)blk, k0, k1);
+                const uint32_t bits = (uint32_t)(r.x < Tlo) | ((uint32_t)(r.y < Tlo) << 1) |
+                                      ((uint32_t)(r.z < Tlo) << 2) | ((uint32_t)(r.w < Tlo) << 3);
+                word |= (WordT)bits << (4 * blk);
+            }
+            word &= (((WordT)1 << bl) - 1);
+        }
+    }
+    if (v < 0.0f) word |= (WordT)1 << WordTraits<WordT>::kSignBit;
+    return word;
+}
+
+constexpr int kSmallMaxB = 8;                     // update vectors one launch of k_update_small takes
+
+template <int KIND, typename WordT, bool NOISE>
+__global__ void __launch_bounds__(256)
+k_update_small(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
+               const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
+               const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
+               const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int BL, double A,
+               int deterministic, uint32_t k0, uint32_t k1, float c2c, unsigned long long* __restrict__ pulse_count,
+               uint32_t* __restrict__ step_state, ConvView conv)
+{
+    __shared__ WordT xs[kSmallMaxB][64], ds[kSmallMaxB][4];
+    constexpr int kSign = WordTraits<WordT>::kSignBit;
+    const uint32_t t = *(const volatile uint32_t*)step_state;
+    const int strips = (C + 63) / 64;
+    const int j0 = (int)(blockIdx.x % (uint32_t)strips) * 64, i0 = (int)(blockIdx.x / (uint32_t)strips) * 4;
+    for (int item = (int)threadIdx.x; item < B * 68; item += 256) {
+        const int b = item / 68, l = item % 68;
+        if (l < 64) {
+            const int j = j0 + l;
+            xs[b][l] = j < C ? line_word<WordT>(view_x(x, conv, (uint32_t)b, j, C), A, BL, deterministic, true, (uint32_t)j,
+                                                (uint32_t)b, t, k0, k1)
+                             : (WordT)0;
+        } else {
+            const int i = i0 + (l - 64);
+            ds[b][l - 64] = i < R ? line_word<WordT>(view_d(d, conv, (uint32_t)b, i, R), A, BL, deterministic, false,
+                                                     (uint32_t)i, (uint32_t)b, t, k0, k1)
+                                  : (WordT)0;
+        }
+    }
+    __syncthreads();
+    const int lane = (int)(threadIdx.x & 63u), wave = (int)(threadIdx.x >> 6);
+    const int i = i0 + wave, j = j0 + lane;
+    uint32_t q = 0;
+    if (i < R && j < C) {
+        const size_t k = (size_t)i * C + j;
+        float w = W[k];
+        const float s_up = p_dw_up[k], s_dn_neg = -p_dw_down[k], bmax = p_b_max[k], bmin = p_b_min[k];
+        float sl_up = 0.0f, sl_dn = 0.0f;
+        if (KIND == kLinearStep) {
+            sl_up = p_slope_up[k];
+            sl_dn = p_slope_down[k];
+        } else if (KIND == kSoftBounds) {
+            sl_up = (bmax != 0.0f) ? 1.0f / bmax : 0.0f;
+            sl_dn = (bmin != 0.0f) ? 1.0f / bmin : 0.0f;
+        }
+        const float c2c_unit = c2c * kGaussUnitScale;
+        float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int b = 0; b < B; ++b) {
+            const WordT xv = xs[b][lane], dv = ds[b][wave];
+            const WordT both = xv & dv & (WordT)(~((WordT)1 << kSign));
+            const int n = (sizeof(WordT) == 8) ? __popcll((unsigned long long)both) : __popc((uint32_t)both);
+            const uint32_t dmask = (((xv ^ dv) >> kSign) & 1) ? ~0u : 0u;     // x_j d_i < 0: an UP pulse
+            for (int p = 0; p < n; ++p) {
+                if (NOISE && (q & 3u) == 0u) gauss4_unit(k0, k1, (uint32_t)k, q >> 2, t, kTagC2C, z);
+                const uint32_t e = q & 3u;
+                const float zq = e == 0 ? z[0] : e == 1 ? z[1] : e == 2 ? z[2] : z[3];
+                w = device_step<KIND, NOISE>(w, dmask, zq, c2c_unit, s_up, s_dn_neg, bmax, bmin, sl_up, sl_dn);
+                ++q;
+            }
+        }
+        W[k] = w;
+    }
+    unsigned long long pulses = q;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) pulses += __shfl_xor(pulses, off, 64);
+    if (lane == 0 && pulses) atomicAdd(pulse_count, pulses);
+    finish_step(step_state, gridDim.x * 4u);
 }
 
 }  // namespace aht

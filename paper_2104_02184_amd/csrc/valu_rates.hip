@@ -311,7 +311,52 @@ template <typename K> int run(const char* name, K kern, double ops_per_thread_it
     fflush(stdout);
     return 0;
 }
+// Instruction fetch: 2048 independent 8-byte v_fma_f32 in a straight line (16 KB of code), walked
+// three times by every wave; lane 0 of each wave notes the shader clock before and after each pass.
+// The first pass of the first launch finds the code nowhere near the compute unit, the first pass of
+// the second launch shows what a launch keeps of it, the later passes run from the instruction cache.
+__global__ void __launch_bounds__(64) k_ifetch(unsigned long long* stamps, float seed)
+{
+    float a0 = seed + threadIdx.x, a1 = a0 + 1.0f, a2 = a0 + 2.0f, a3 = a0 + 3.0f, b = seed;
+    unsigned long long t[4];
+    t[0] = clock64();
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+        asm volatile(".rept 512\n v_fma_f32 %0, %0, %4, %4\n v_fma_f32 %1, %1, %4, %4\n v_fma_f32 %2, %2, %4, %4\n"
+                     " v_fma_f32 %3, %3, %4, %4\n .endr"
+                     : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : "v"(b));
+        asm volatile("s_nop 0" ::: "memory");
+        t[pass + 1] = clock64();
+    }
+    if (threadIdx.x == 0)
+        for (int k = 0; k < 4; ++k) stamps[(size_t)blockIdx.x * 4 + k] = t[k];
+    if (a0 + a1 + a2 + a3 == 12345.0f) stamps[0] = 1;
+}
+
+static int run_ifetch()
+{
+    const int waves[2] = {256, 1024};                   // one wave per compute unit; one per SIMD
+    for (int w : waves) {
+        unsigned long long* st; CHK(hipMalloc(&st, (size_t)w * 4 * sizeof(unsigned long long)));
+        unsigned long long* host = new unsigned long long[(size_t)w * 4];
+        for (int launch = 0; launch < 3; ++launch) {
+            hipLaunchKernelGGL(k_ifetch, dim3(w), dim3(64), 0, 0, st, 1.0f);
+            CHK(hipDeviceSynchronize());
+            CHK(hipMemcpy(host, st, (size_t)w * 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+            double pass[3] = {0, 0, 0};
+            for (int k = 0; k < w; ++k)
+                for (int p = 0; p < 3; ++p) pass[p] += (double)(host[4 * k + p + 1] - host[4 * k + p]);
+            printf("ifetch 16 KB straight line, %4d waves, launch %d: clock ticks per instruction, pass 1 / 2 / 3: %.2f / %.2f / %.2f\n",
+                   w, launch + 1, pass[0] / w / 2048, pass[1] / w / 2048, pass[2] / w / 2048);
+        }
+        delete[] host;
+        CHK(hipFree(st));
+    }
+    return 0;
+}
+
 int main() {
+    if (run_ifetch()) return 1;
     uint32_t* out; CHK(hipMalloc(&out, 64));
     hipDeviceProp_t p; CHK(hipGetDeviceProperties(&p, 0));
     printf("%s CUs=%d clock=%d kHz lds/block=%zu\n", p.name, p.multiProcessorCount, p.clockRate, p.sharedMemPerBlock);

@@ -317,6 +317,96 @@ def test_launch_shape_chosen_from_the_pulse_rate_changes_no_bit(env):
     assert p4 == pr and (got4 == ref).all()
 
 
+@pytest.mark.parametrize("R,C,B,bl,kind,c2c,deterministic", [
+    (64, 64, 1, 31, aht.CONSTANT_STEP, 0.0, False),        # the smallest workload's shape
+    (64, 64, 1, 31, aht.CONSTANT_STEP, 0.3, False),
+    (37, 70, 3, 31, aht.SOFT_BOUNDS, 0.3, False),          # ragged rows and columns
+    (20, 130, 8, 63, aht.LINEAR_STEP, 0.3, False),         # 64-bit words, the most vectors one launch takes
+    (16, 64, 2, 17, aht.LINEAR_STEP, 0.0, True),           # deterministic trains
+])
+def test_whole_call_in_one_launch_changes_no_bit(R, C, B, bl, kind, c2c, deterministic, monkeypatch):
+    """Tiny tiles with a few update vectors take the whole call in one launch, every workgroup drawing the
+    pulse words it needs.  Same weights, pulse counts and step counter, bit for bit, as the two-kernel path,
+    call after call; and the oracle's result."""
+    dev = dict(kind=kind, dw_min=0.004, dw_min_dtod=0.3, dw_min_std=c2c, w_max=0.6, w_max_dtod=0.2, w_min=-0.6,
+               w_min_dtod=0.2, gamma_up=0.4, gamma_down=0.6, gamma_dtod=0.1)
+    g = np.random.default_rng(R * C + B)
+    W0 = g.uniform(-0.3, 0.3, size=(R, C)).astype(np.float32)
+    calls = 4
+    xs = [g.normal(size=(B, C)).astype(np.float32) for _ in range(calls)]
+    ds = [g.normal(size=(B, R)).astype(np.float32) * np.float32(0.7) for _ in range(calls)]
+    xs[1][0, :5] = [0.0, np.nan, np.inf, 50.0, -50.0]                   # zero, non-finite and saturated lines
+    out = {}
+    for mode in ("0", "1"):
+        monkeypatch.setenv("AHT_FUSED", mode)
+        tile = aht.Tile(R, C, gpu_params(dev), bl, False, 9)
+        if deterministic:
+            tile.set_pulse_mode(deterministic=True)
+        tile.set_weights(to_dev(W0))
+        steps = []
+        for x, d in zip(xs, ds):
+            tile.pulsed_update(to_dev(x), to_dev(d), 0.2)
+            steps.append((tile.get_weights().cpu().numpy(), tile.pulse_count(), tile.step, tile.sync_step()))
+        assert tile.launch_info()["stream_words"] == (0 if mode == "1" else 12)      # the path that was asked for
+        tile.close()
+        out[mode] = steps
+    for k, ((w0, p0, s0, d0), (w1, p1, s1, d1)) in enumerate(zip(out["0"], out["1"])):
+        assert p0 == p1 and s0 == s1 == d0 == d1 == k + 1
+        assert (w0.view(np.uint32) == w1.view(np.uint32)).all()
+    assert out["1"][-1][1] > 0
+    planes = oracle.device_planes(oracle.DeviceParams(**dev), 9, R, C)
+    Wo, po = W0.copy(), 0
+    for t, (x, d) in enumerate(zip(xs, ds)):
+        po += oracle.pulsed_update(Wo, planes, oracle.DeviceParams(**dev), bl, False, x, d, 0.2, 9, t,
+                                   train_kind=oracle.DETERMINISTIC if deterministic else oracle.STOCHASTIC)
+    assert po == out["1"][-1][1]
+    assert np.abs(out["1"][-1][0].astype(np.float64) - Wo).max() / 0.6 <= WEIGHT_TOL
+
+
+@pytest.mark.parametrize("R,C,B,d_std,x_scale,lr,kind,c2c,qwords", [
+    (64, 320, 1500, 0.01, 1.0, 0.1, aht.CONSTANT_STEP, 0.3, None),    # the conv workload's law: most row trains empty
+    (37, 150, 1203, 0.01, 1.0, 0.1, aht.SOFT_BOUNDS, 0.3, None),      # ragged rows, columns and batch
+    (23, 70, 999, 0.004, 1.0, 0.1, aht.LINEAR_STEP, 0.0, 6),          # very sparse, no noise, short streams: many drains
+    (16, 128, 515, 0.3, 3.0, 0.5, aht.CONSTANT_STEP, 0.3, 7),         # dense and partly saturated: groups with large
+                                                                      # counts take the sample-by-sample path
+    (8, 64, 3, 0.05, 1.0, 0.1, aht.CONSTANT_STEP, 0.3, None),         # fewer samples than one group
+])
+def test_walking_row_lists_changes_no_bit(R, C, B, d_std, x_scale, lr, kind, c2c, qwords, monkeypatch):
+    """Long batches whose row trains are mostly empty walk, per row, a list of the samples that have
+    a pulse instead of all samples.  Same weights and pulse counts, bit for bit, call after call, whether
+    the lists are forced on or off; and the oracle's pulse total."""
+    dev = dict(kind=kind, dw_min=0.002, dw_min_dtod=0.3, dw_min_std=c2c, w_max=0.6, w_max_dtod=0.2, w_min=-0.6,
+               w_min_dtod=0.2, gamma_up=0.4, gamma_down=0.6, gamma_dtod=0.1)
+    g = np.random.default_rng(R + C)
+    W0 = g.uniform(-0.3, 0.3, size=(R, C)).astype(np.float32)
+    calls = 2
+    xs = [(np.maximum(g.normal(size=(B, C)), 0) * x_scale).astype(np.float32) for _ in range(calls)]
+    ds = [(g.normal(size=(B, R)) * d_std).astype(np.float32) for _ in range(calls)]
+    if qwords:
+        monkeypatch.setenv("AHT_QWORDS", str(qwords))
+    out = {}
+    for mode in ("0", "1"):
+        monkeypatch.setenv("AHT_ROWLISTS", mode)
+        tile = aht.Tile(R, C, gpu_params(dev), 31, False, 5)
+        tile.set_weights(to_dev(W0))
+        steps = []
+        for x, d in zip(xs, ds):
+            tile.pulsed_update(to_dev(x), to_dev(d), lr)
+            steps.append((tile.get_weights().cpu().numpy(), tile.pulse_count()))
+        tile.close()
+        out[mode] = steps
+    for (w0, p0), (w1, p1) in zip(out["0"], out["1"]):
+        assert p0 == p1 and p0 > 0
+        assert (w0.view(np.uint32) == w1.view(np.uint32)).all()
+    # and against the oracle: applied pulses equal, weights within the tolerance
+    planes = oracle.device_planes(oracle.DeviceParams(**dev), 5, R, C)
+    Wo, po = W0.copy(), 0
+    for t, (x, d) in enumerate(zip(xs, ds)):
+        po += oracle.pulsed_update(Wo, planes, oracle.DeviceParams(**dev), 31, False, x, d, lr, 5, t)
+    assert po == out["1"][-1][1]
+    assert np.abs(out["1"][-1][0].astype(np.float64) - Wo).max() / 0.6 <= WEIGHT_TOL
+
+
 @pytest.mark.parametrize("R,C,B,lr,calls,kind,bl", [
     (256, 2304, 48, 0.1, 3, aht.CONSTANT_STEP, 31),      # two rows per lane on 32 strips, one on 4
     (256, 2304, 48, 0.1, 3, aht.SOFT_BOUNDS, 63),

@@ -377,6 +377,8 @@ def main():
                     help="input noise of the forward/backward side benchmarks (0: quantised inputs only)")
     ap.add_argument("--op", default="pulsed_update", choices=["pulsed_update", "decay_diffuse", "forward", "backward", "transfer"],
                     help="side benchmarks of other operations; the default is the headline metric")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record the timed calls into a HIP graph and time a replay (ms_per_step_graph_replay)")
     ap.add_argument("--pmc-summary", default=None, metavar="DIR",
                     help="no benchmark: turn rocprofv3 --pmc runs of this program under DIR into profiles/cell_update_counters.json")
     args = ap.parse_args()
@@ -444,6 +446,22 @@ def main():
     torch.cuda.synchronize()
     ms_per_step_plain = (time.perf_counter() - u0) / K * 1e3
     info = tile.launch_info()
+    ms_per_step_graph = None
+    if args.graph:
+        # the same K calls recorded once into a HIP graph (through the entry point that allocates nothing: the
+        # step counter is read and advanced on the device) and replayed: what a call costs without the host
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            for i in range(K):
+                tile.pulsed_update_noalloc(xs[(Wm + i) % pool], ds[(Wm + i) % pool], w.lr)
+        graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        ms_per_step_graph = (time.perf_counter() - g0) / K * 1e3
+        tile.sync_step()
     tile.close()
 
     sec = t1 - t0
@@ -472,6 +490,7 @@ def main():
         "warmup": Wm,
         "ms_per_step": ms_per_step,
         "ms_per_step_without_event_records": ms_per_step_plain,
+        "ms_per_step_graph_replay": ms_per_step_graph,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

@@ -177,15 +177,18 @@ aht_status aht_set_pulse_mode(aht_tile* tile, int32_t train_kind, int32_t dynami
 
 /* Step counter (number of aht_pulsed_update calls so far); together with the weights, the
  * planes and the seed it makes a run resumable bit for bit.
- * The counter lives in device memory: an update of the whole tile reads its step there and advances
- * it itself (the last wave of its last kernel does), so that a sequence of update calls can be
- * recorded once into a HIP graph and replayed, each replay continuing the random streams where the
- * last one stopped (record aht_pulsed_update_noalloc: it allocates nothing, records no events and
- * issues no copies).  The host keeps a copy that every call through this interface keeps equal to the
- * device's; aht_get_step returns that copy without touching the device.  After replaying a recorded
- * graph the copy is behind: aht_sync_step reads the device's counter back (it waits for `stream`)
- * and must be called before the next call that takes the step from the host (aht_get_step, transfers,
- * unit cells, the debug hooks; aht_pulsed_update itself does not).  aht_set_step waits for the device. */
+ * The counter is kept on the host and, equal to it, in device memory.  A call made directly passes
+ * the host's count to its kernels.  aht_pulsed_update and aht_pulsed_update_noalloc notice when their
+ * stream is being recorded into a HIP graph: the kernels then read the device's counter, and a
+ * one-thread kernel after them advances it, so that a sequence of update calls can be recorded once
+ * and replayed, each replay continuing the random streams where the counter stands (record
+ * aht_pulsed_update_noalloc: it allocates nothing, records no events and issues no copies).
+ * aht_get_step returns the host's count without touching the device.  Recording counts the recorded
+ * calls on the host although nothing ran, and a replay does not count there at all: after recording
+ * and after replays aht_sync_step reads the device's counter back into the host's (it waits for
+ * `stream`), before the next call made directly.  Other calls that use the step (transfers, unit
+ * cells, convolution updates are fine; the debug hooks) are not meant to be recorded.
+ * aht_set_step waits for the device. */
 aht_status aht_get_step(const aht_tile* tile, uint32_t* step);
 aht_status aht_set_step(aht_tile* tile, uint32_t step);
 aht_status aht_sync_step(aht_tile* tile, uint32_t* step /* nullable */, void* stream);

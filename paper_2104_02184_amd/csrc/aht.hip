@@ -26,10 +26,11 @@ struct aht_tile {
     aht_device_params dev{};
     aht_update_params upd{};
     uint64_t seed = 0;
-    // The step counter lives in device memory (step_state[0]; [1] counts the finished waves of a running
-    // cell-update launch; [2] holds the step of a launch that takes it from the host): full updates read
-    // it there and advance it themselves, so that a recorded sequence of them can be replayed.  `step` is the host's copy: every call made through this interface
-    // keeps the two equal; after replaying a recorded graph aht_sync_step brings the host's copy up to date.
+    // The step counter is kept twice: `step` on the host, which every call made directly passes to its
+    // kernels by value, and step_state[0] in device memory, which those calls keep equal to it (the cell
+    // kernel leaves step + 1 there) and which calls that are being recorded into a HIP graph read instead,
+    // so that a replay continues where the counter stands ([1] counts the finished waves of a recorded
+    // one-launch update).  After a replay aht_sync_step brings the host's copy up to date.
     uint32_t step = 0;
     uint32_t* step_state = nullptr;
     int device = 0;
@@ -209,14 +210,16 @@ struct WordBufs {
 
 inline WordBufs tile_bufs(const aht_tile* t) { return WordBufs{t->xw, t->dw, t->a_x, t->a_d, t->bl_b}; }
 
-// Kernels read the step of a call from device memory.  For launches that take it from the host (they do not
-// advance the tile's counter) the value is written, in stream order, into slot [2] of the tile's step state.
-aht_status step_from_host(aht_tile* t, uint32_t value, hipStream_t s, const uint32_t** where)
+// Whether the calls on `s` are being recorded into a HIP graph: then the kernels read the tile's step from the
+// device's counter, and something on the device advances it, so that every replay finds the right step.
+bool being_recorded(hipStream_t s)
 {
-    hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, s, t->step_state, value, 0, 1);
-    AHT_HIP(hipGetLastError());
-    *where = t->step_state + 2;
-    return AHT_OK;
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &status) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return status == hipStreamCaptureStatusActive;
 }
 
 // Scratch of aht_pulsed_update_noalloc: one array per GPU (every device that loads the library
@@ -263,11 +266,12 @@ size_t static_scratch_layout(const aht_tile* t, int B, unsigned char* base, Word
 
 // pulse trains of the call at step `step` into `w`
 // `row_stat`: device counter that receives the number of row trains with a pulse (nullable)
-// `step`: where in device memory the step of this call is
-aht_status launch_words(aht_tile* t, const WordBufs& w, const float* x, const float* d, int B, float lr,
-                        const uint32_t* step, hipStream_t s, const ConvView& conv = ConvView{},
-                        unsigned long long* row_stat = nullptr)
+// `recorded`: the kernels read the step from the tile's device counter instead of `step`
+aht_status launch_words(aht_tile* t, const WordBufs& w, const float* x, const float* d, int B, float lr, uint32_t step,
+                        hipStream_t s, const ConvView& conv = ConvView{}, unsigned long long* row_stat = nullptr,
+                        bool recorded = false)
 {
+    const uint32_t* step_ptr = recorded ? t->step_state : nullptr;
     const double A = std::sqrt((double)lr / ((double)t->dev.dw_min * (double)t->upd.bl));
     const double *ax = nullptr, *ad = nullptr;
     const int32_t* blb = nullptr;
@@ -284,11 +288,11 @@ aht_status launch_words(aht_tile* t, const WordBufs& w, const float* x, const fl
     const dim3 grid(blocks_for((size_t)Cp + Rp), (unsigned)(B < 32768 ? B : 32768));
     if (use_u32(t))
         hipLaunchKernelGGL(k_pulse_words<uint32_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp, bpad(B),
-                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint32_t*)w.xw, (uint32_t*)w.dw, conv,
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, step_ptr, (uint32_t*)w.xw, (uint32_t*)w.dw, conv,
                            row_stat);
     else
         hipLaunchKernelGGL(k_pulse_words<uint64_t>, grid, dim3(256), 0, s, x, d, B, t->rows, t->cols, Rp, Cp, bpad(B),
-                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, (uint64_t*)w.xw, (uint64_t*)w.dw, conv,
+                           t->upd.bl, A, ax, ad, blb, t->train_kind, k0, k1, step, step_ptr, (uint64_t*)w.xw, (uint64_t*)w.dw, conv,
                            row_stat);
     AHT_HIP(hipGetLastError());
     return AHT_OK;
@@ -408,9 +412,11 @@ aht_status ensure_row_lists(aht_tile* t, int B)
 // the static scratch)
 // `full`: a full update of the tile (counted by pulse counter [0], whose rate chooses the launch shape)
 // `rowlists`: walk the tile's per-row sample lists (already built from `words`), one row per lane
-// `step`: where in device memory the step of this call is (a full update advances the tile's counter)
-aht_status launch_cells(aht_tile* t, int B, const uint32_t* step, hipStream_t s, uint32_t strip0, uint32_t strips,
-                        const WordBufs& words, bool full, bool rowlists = false)
+// `counts`: the call advances the tile's step counter; `recorded`: it is being recorded into a graph (the step
+// is then read from the device's counter, which the caller advances with a kernel of its own afterwards)
+aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strip0, uint32_t strips,
+                        const WordBufs& words, bool full, bool rowlists = false, bool counts = false,
+                        bool recorded = false)
 {
     const int rpl = rowlists ? 1 : choose_rpl(t);
     // stream storage per cell: 12 words hold 320 pulses before an early drain is needed; at 4 rows
@@ -445,10 +451,11 @@ aht_status launch_cells(aht_tile* t, int B, const uint32_t* step, hipStream_t s,
     a.nby = (uint32_t)((t->rows + 4 * rpl - 1) / (4 * rpl));
     a.k0 = (uint32_t)t->seed;
     a.k1 = (uint32_t)(t->seed >> 32);
+    a.t = step;
     a.c2c = t->dev.dw_min_std;
     a.qwords = qwords;
-    a.step = step;
-    a.advance = full ? t->step_state : nullptr;              // full updates count their steps themselves
+    a.step_on_device = recorded ? t->step_state : nullptr;
+    a.publish = (counts && !recorded) ? t->step_state : nullptr;
     // one workgroup per tile of 4 * rpl rows x 64 columns, in equal shares for the 8 XCDs
     const uint64_t total = (uint64_t)a.nby * a.nbx;
     const uint64_t per = (total + 7) / 8;
@@ -570,8 +577,9 @@ void launch_pair_kind(int kind, bool noise, int rpl_main, int rpl_side, dim3 gri
 #undef AHT_PAIR_KIND
 }
 
-aht_status launch_cells_pair(aht_tile* t, int B, const uint32_t* step, hipStream_t s, uint32_t strips, uint32_t strips_main,
-                             int rpl_main, int rpl_side, const WordBufs& words, bool full)
+aht_status launch_cells_pair(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strips, uint32_t strips_main,
+                             int rpl_main, int rpl_side, const WordBufs& words, bool full, bool counts = false,
+                             bool recorded = false)
 {
     CellPtrs p{};
     p.W = t->W;
@@ -604,10 +612,11 @@ aht_status launch_cells_pair(aht_tile* t, int B, const uint32_t* step, hipStream
         a.nby = (uint32_t)((t->rows + 4 * rpl - 1) / (4 * rpl));
         a.k0 = (uint32_t)t->seed;
         a.k1 = (uint32_t)(t->seed >> 32);
+        a.t = step;
         a.c2c = t->dev.dw_min_std;
         a.qwords = qwords;
-        a.step = step;
-        a.advance = full ? t->step_state : nullptr;
+        a.step_on_device = recorded ? t->step_state : nullptr;
+        a.publish = (counts && !recorded) ? t->step_state : nullptr;
         return a;
     };
     const CellArgs a = shape(rpl_main, 0u, strips_main), b = shape(rpl_side, strips_main, strips - strips_main);
@@ -639,7 +648,8 @@ bool use_small_kernel(const aht_tile* t, int B)
     return (uint64_t)t->rows * (uint64_t)t->cols * (uint64_t)B <= 32768u;
 }
 
-aht_status launch_small(aht_tile* t, const float* x, const float* d, int B, float lr, hipStream_t s, const ConvView& conv)
+aht_status launch_small(aht_tile* t, const float* x, const float* d, int B, float lr, hipStream_t s, const ConvView& conv,
+                        bool recorded)
 {
     const double A = std::sqrt((double)lr / ((double)t->dev.dw_min * (double)t->upd.bl));
     const dim3 grid((unsigned)((t->cols + 63) / 64) * (unsigned)((t->rows + 3) / 4));
@@ -650,7 +660,7 @@ aht_status launch_small(aht_tile* t, const float* x, const float* d, int B, floa
                        t->planes[AHT_PLANE_DW_DOWN], t->planes[AHT_PLANE_B_MAX], t->planes[AHT_PLANE_B_MIN],        \
                        t->planes[AHT_PLANE_SLOPE_UP], t->planes[AHT_PLANE_SLOPE_DOWN], x, d, B, t->rows, t->cols,   \
                        t->upd.bl, A, t->train_kind, (uint32_t)t->seed, (uint32_t)(t->seed >> 32), t->dev.dw_min_std, \
-                       t->pulse_count, t->step_state, conv)
+                       t->pulse_count, t->step, t->step_state, recorded ? 1 : 0, conv)
 #define AHT_SMALL_NOISE(K, WT)                                                                                      \
     do {                                                                                                           \
         if (noise) AHT_SMALL_LAUNCH(K, WT, true); else AHT_SMALL_LAUNCH(K, WT, false);                              \
@@ -827,7 +837,8 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
     if (B > 0 && (!x_dev || !d_dev)) return fail(AHT_ERR_INVALID_ARG, "null x or d");
     aht_status st = check_device(t);
     if (st != AHT_OK) return st;
-    const bool full = col_hi < 0;                 // the whole tile: the step is read and advanced on the device
+    const bool full = col_hi < 0;                 // the whole tile
+    const bool recorded = being_recorded((hipStream_t)stream);
     if (B > 0 && lr > 0.0f && full && use_small_kernel(t, B)) {
         hipStream_t s = (hipStream_t)stream;
         hipEvent_t* ev = nullptr;
@@ -841,7 +852,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
             AHT_HIP(hipEventRecord(ev[0], s));
             AHT_HIP(hipEventRecord(ev[1], s));      // (no separate pulse-train kernel)
         }
-        if ((st = launch_small(t, x_dev, d_dev, B, lr, s, conv)) != AHT_OK) return st;
+        if ((st = launch_small(t, x_dev, d_dev, B, lr, s, conv, recorded)) != AHT_OK) return st;
         if (ev) {
             AHT_HIP(hipEventRecord(ev[2], s));
             t->events_used += 3;
@@ -880,9 +891,8 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
                              ((size_t)t->rows * t->cols >= kAdaptMinCells || (use_u32(t) && B >= 256));
         const bool rowlists = col_hi < 0 && !static_scratch_only && use_row_lists(t, B);
         if (rowlists && (st = ensure_row_lists(t, B)) != AHT_OK) return st;
-        const uint32_t* step_at = t->step_state;                 // a full update: the tile's own counter
-        if (!full && (st = step_from_host(t, t->step, s, &step_at)) != AHT_OK) return st;
-        if ((st = launch_words(t, bufs, x_dev, d_dev, B, lr, step_at, s, conv, watched ? t->pulse_count + 2 : nullptr)) != AHT_OK)
+        if ((st = launch_words(t, bufs, x_dev, d_dev, B, lr, t->step, s, conv, watched ? t->pulse_count + 2 : nullptr,
+                               recorded)) != AHT_OK)
             return st;
         if (ev) AHT_HIP(hipEventRecord(ev[1], s));
         const uint32_t strip0 = col_hi < 0 ? 0u : (uint32_t)(col_lo / 64);
@@ -893,12 +903,13 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
             hipLaunchKernelGGL(k_compact_rows, dim3((unsigned)((t->rows + 3) / 4)), dim3(256), 0, s, (const uint32_t*)bufs.dw,
                                t->rows, B, bpad(B), t->rlist, t->rlen);
             AHT_HIP(hipGetLastError());
-            if ((st = launch_cells(t, B, step_at, s, strip0, strips, bufs, true, true)) != AHT_OK) return st;
+            if ((st = launch_cells(t, B, t->step, s, strip0, strips, bufs, true, true, true, recorded)) != AHT_OK) return st;
         } else {
         if (col_hi < 0) even_round(t, B, strips, &strips_main, &rpl_main, &rpl_side);
         if (strips_main < strips) {
-            if ((st = launch_cells_pair(t, B, step_at, s, strips, strips_main, rpl_main, rpl_side, bufs, true)) != AHT_OK) return st;
-        } else if ((st = launch_cells(t, B, step_at, s, strip0, strips, bufs, full)) != AHT_OK) return st;
+            if ((st = launch_cells_pair(t, B, t->step, s, strips, strips_main, rpl_main, rpl_side, bufs, true, true, recorded)) != AHT_OK)
+                return st;
+        } else if ((st = launch_cells(t, B, t->step, s, strip0, strips, bufs, full, false, true, recorded)) != AHT_OK) return st;
         }
         if (ev) {
             AHT_HIP(hipEventRecord(ev[2], s));
@@ -909,7 +920,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
             if (watched) t->row_trains += (uint64_t)t->rows * (uint64_t)((B + 15) / 16);    // every 16th sample is counted
             // the counters are reported when no earlier report is still on its way: after each of the first
             // eight updates, then sixteen updates after the last report
-            if (!static_scratch_only && watched && !t->copy_pending &&
+            if (!static_scratch_only && !recorded && watched && !t->copy_pending &&
                 (t->full_updates <= 8 || t->full_updates >= t->copy_index + 16)) {
                 for (int k = 0; k < 3; ++k) ((volatile unsigned long long*)t->pulses_seen)[k] = kNoValueYet;
                 AHT_HIP(hipMemcpyAsync(t->pulses_seen, t->pulse_count, 3 * sizeof(unsigned long long),
@@ -918,14 +929,14 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
                 t->copy_index = t->full_updates;
                 t->copy_row_trains = t->row_trains;
             }
-        } else {
-            // part of the tile only (a transfer): the step went to the kernels by value; the device's counter follows
-            hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, s, t->step_state, t->step + 1u, 0, 0);
+        }
+        if (recorded) {                           // the kernels above read the device's counter: now it moves on
+            hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, s, t->step_state, 1u, 1);
             AHT_HIP(hipGetLastError());
         }
     } else {
         // nothing to apply: the call still counts
-        hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, (hipStream_t)stream, t->step_state, 1u, 1, 0);
+        hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, (hipStream_t)stream, t->step_state, 1u, 1);
         AHT_HIP(hipGetLastError());
     }
     t->step += 1;
@@ -1277,9 +1288,7 @@ aht_status aht_unit_cell_update(aht_tile* const* dev, int32_t n, int32_t which, 
         if ((st = ensure_scratch(lead, B)) != AHT_OK) return st;
         hipStream_t s = (hipStream_t)stream;
         const WordBufs bufs = tile_bufs(lead);
-        const uint32_t* step_at = nullptr;                       // every device reads the step from the first one's slot
-        if ((st = step_from_host(lead, step, s, &step_at)) != AHT_OK) return st;
-        if ((st = launch_words(lead, bufs, x_dev, d_dev, B, lr, step_at, s, ConvView{})) != AHT_OK) return st;
+        if ((st = launch_words(lead, bufs, x_dev, d_dev, B, lr, step, s, ConvView{})) != AHT_OK) return st;
         const uint32_t strips = (uint32_t)((lead->cols + 63) / 64);
         // The devices are tiles of their own, fed from the same words: those after the first run beside
         // it, each on its own tile's side stream (measured, all devices updated: two devices of 512 x 512
@@ -1303,9 +1312,9 @@ aht_status aht_unit_cell_update(aht_tile* const* dev, int32_t n, int32_t which, 
             int rpl_main = 0, rpl_side = 0;
             even_round(dev[k], B, strips, &strips_main, &rpl_main, &rpl_side);
             if (strips_main < strips) {
-                if ((st = launch_cells_pair(dev[k], B, step_at, sk, strips, strips_main, rpl_main, rpl_side, bufs, false)) != AHT_OK)
+                if ((st = launch_cells_pair(dev[k], B, step, sk, strips, strips_main, rpl_main, rpl_side, bufs, false, true)) != AHT_OK)
                     return st;
-            } else if ((st = launch_cells(dev[k], B, step_at, sk, 0u, strips, bufs, false)) != AHT_OK) return st;
+            } else if ((st = launch_cells(dev[k], B, step, sk, 0u, strips, bufs, false, false, true)) != AHT_OK) return st;
             if (sk != s) {
                 AHT_HIP(hipEventRecord(dev[k]->side_join, sk));
                 AHT_HIP(hipStreamWaitEvent(s, dev[k]->side_join, 0));
@@ -1314,7 +1323,9 @@ aht_status aht_unit_cell_update(aht_tile* const* dev, int32_t n, int32_t which, 
     }
     for (int k = 0; k < n; ++k) {                             // the cell's devices count calls together
         dev[k]->step = step + 1;
-        hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, (hipStream_t)stream, dev[k]->step_state, step + 1u, 0, 0);
+        // (a device that was updated has left the new count in its device-side counter itself)
+        const bool updated = B > 0 && lr > 0.0f && (which < 0 || k == which);
+        if (!updated) hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, (hipStream_t)stream, dev[k]->step_state, step + 1u, 0);
     }
     AHT_HIP(hipGetLastError());
     return AHT_OK;
@@ -1617,9 +1628,7 @@ static aht_status debug_pulse_words_impl(aht_tile* t, const float* x_dev, const 
     if (st != AHT_OK) return st;
     if ((st = ensure_scratch(t, B)) != AHT_OK) return st;
     hipStream_t s = (hipStream_t)stream;
-    const uint32_t* step_at = nullptr;
-    if ((st = step_from_host(t, t->step, s, &step_at)) != AHT_OK) return st;
-    if ((st = launch_words(t, tile_bufs(t), x_dev, d_dev, B, lr, step_at, s, conv)) != AHT_OK) return st;
+    if ((st = launch_words(t, tile_bufs(t), x_dev, d_dev, B, lr, t->step, s, conv)) != AHT_OK) return st;
     const size_t nx = (size_t)B * t->cols, nd = (size_t)B * t->rows;
     if (use_u32(t)) {
         hipLaunchKernelGGL(k_words_to_public<uint32_t>, dim3(blocks_for(nx)), dim3(256), 0, s, (const uint32_t*)t->xw, xw_dev, B, t->cols, cpad(t), 0);
@@ -1681,9 +1690,7 @@ aht_status aht_debug_apply_words(aht_tile* t, const uint64_t* xw_dev, const uint
         hipLaunchKernelGGL(k_words_from_public<uint64_t>, dim3(blocks_for(nd)), dim3(256), 0, s, dw_dev, (uint64_t*)t->dw, B, t->rows, rpad(t), bpad(B), t->upd.bl);
     }
     AHT_HIP(hipGetLastError());
-    const uint32_t* step_at = nullptr;
-    if ((st = step_from_host(t, step, s, &step_at)) != AHT_OK) return st;
-    return launch_cells(t, B, step_at, s, 0u, (uint32_t)((t->cols + 63) / 64), tile_bufs(t), false);
+    return launch_cells(t, B, step, s, 0u, (uint32_t)((t->cols + 63) / 64), tile_bufs(t), false);
 }
 
 aht_status aht_debug_philox(const uint32_t* ctr_dev, const uint32_t* key_dev, int32_t n, uint32_t* out_dev, void* stream)

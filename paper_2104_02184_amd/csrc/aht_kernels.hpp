@@ -344,8 +344,8 @@ __global__ void __launch_bounds__(256)
 k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int Rpad, int Cpad,
               int Bpad, int BL, double A, const double* __restrict__ a_x, const double* __restrict__ a_d,
               const int32_t* __restrict__ bl_b, int deterministic,
-              uint32_t k0, uint32_t k1, const uint32_t* __restrict__ step, WordT* __restrict__ xw, WordT* __restrict__ dw,
-              ConvView conv, unsigned long long* __restrict__ row_words_with_pulses)
+              uint32_t k0, uint32_t k1, uint32_t t, const uint32_t* step_on_device, WordT* __restrict__ xw,
+              WordT* __restrict__ dw, ConvView conv, unsigned long long* __restrict__ row_words_with_pulses)
 {
     constexpr int kBlocks = (sizeof(WordT) == 4) ? 8 : 16;       // Philox blocks per line value, at most
     constexpr int kLines = 64 / kBlocks;                         // lines served at a time by the shared path
@@ -357,7 +357,7 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
     const int len = is_x ? C : R;
     const uint32_t tagw = (is_x ? kTagX : kTagD) << 24;
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint32_t t = *step;                                    // the step of this call, in device memory
+    if (step_on_device) t = *(const volatile uint32_t*)step_on_device;   // a recorded call: the device's counter
     for (uint32_t b = blockIdx.y; b < (uint32_t)B; b += gridDim.y) {
         WordT word = 0;
         const int bl = bl_b ? bl_b[b] : BL;
@@ -567,38 +567,40 @@ struct CellArgs {
     uint32_t nbx, nby;            // tiles along columns / rows
     uint32_t bx0;                 // first column strip of this launch (a caller that knows where x is
                                   // non-zero leaves the other strips out: their cells get no pulses)
-    uint32_t k0, k1;
+    uint32_t k0, k1, t;           // t: the step of the call ...
     float c2c;
     int qwords;                   // 32-bit words of stream storage per cell (>= 5)
-    // The step of the call is read from device memory.  A tile's step state: [0] the step counter, [1] waves
-    // of the running launch that have finished, [2] a step written by the host for launches that do not
-    // count (updates of unit cells, transfers, injected words).  A full update reads [0] and the wave that
-    // finishes last advances it (`advance` = the state), so that a sequence of such calls can be recorded
-    // once in a HIP graph and replayed; the others read [2] and advance nothing (`advance` null).
-    const uint32_t* step;
-    uint32_t* advance;
+    // The tile's step counter also lives in device memory, so that a sequence of update calls can be recorded
+    // once in a HIP graph and replayed.  A call made directly takes its step from the host (t) and, if it
+    // counts, leaves t + 1 in the device's counter (`publish`; nobody reads the counter while it runs).  A call
+    // being recorded reads its step from the device's counter instead (`step_on_device`), and a one-thread
+    // kernel after it advances the counter.  (Counting finished waves in the kernel to let the last one
+    // advance it cost 1.7 ms on the 4096 x 4096 tile: 65 536 returning atomics on one address, about 30 ns each.)
+    const uint32_t* step_on_device;
+    uint32_t* publish;
 };
 
-// state[0] = value (relative: += value), no wave finished; or only state[2] = value
-__global__ void k_set_step(uint32_t* state, uint32_t value, int relative, int slot2_only)
+// counter = value, or counter += value
+__global__ void k_set_step(uint32_t* counter, uint32_t value, int relative)
 {
-    if (slot2_only) {
-        state[2] = value;
-    } else {
-        state[0] = relative ? state[0] + value : value;
-        state[1] = 0u;
-    }
+    *counter = relative ? *counter + value : value;
 }
 
-// after a cell-update launch's body: the last of the launch's waves to get here advances the step
-__device__ __forceinline__ void finish_step(uint32_t* step_state, uint32_t waves_of_launch)
+// a directly made call that counts: leave the next step in the device's counter
+__device__ __forceinline__ void publish_step(const CellArgs& a)
 {
-    if (!step_state) return;                       // wave-uniform
+    if (a.publish && blockIdx.x == 0 && threadIdx.x == 0) *a.publish = a.t + 1u;
+}
+
+// after the body of k_update_small (few workgroups): the last wave to get here advances the counter
+// (state[0]; state[1] counts the finished waves)
+__device__ __forceinline__ void finish_step(uint32_t* state, uint32_t waves_of_launch)
+{
     if ((threadIdx.x & 63u) == 0u) {
-        const uint32_t before = atomicAdd(step_state + 1, 1u);
+        const uint32_t before = atomicAdd(state + 1, 1u);
         if (before + 1u == waves_of_launch) {      // every other wave has read the step long ago
-            step_state[1] = 0u;
-            atomicAdd(step_state, 1u);
+            state[1] = 0u;
+            atomicAdd(state, 1u);
         }
     }
 }
@@ -793,7 +795,8 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
         // in registers through phase A.
         int dlane = (int)lane_by_count();
         asm volatile("" : "+v"(dlane));
-        const uint32_t tstep = *(const volatile uint32_t*)a.step;    // read here, at the drain, where it is used
+        uint32_t tstep = a.t;
+        if (a.step_on_device) tstep = *(const volatile uint32_t*)a.step_on_device;   // (a recorded call)
         // The device parameters are needed only here.  Loading them now (normally once per call)
         // keeps 6 registers per cell free during phase A.
         float s_up[RPL], s_dn_neg[RPL], bmax[RPL], bmin[RPL], sl_up[RPL], sl_dn[RPL];
@@ -1338,7 +1341,7 @@ k_cell_update(float* __restrict__ W, const float* __restrict__ p_dw_up, const fl
 {
     cell_update_body<KIND, WordT, NOISE, RPL>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down, xw, dw,
                                               pulse_count, a, blockIdx.x);
-    finish_step(a.advance, gridDim.x * 4u);
+    publish_step(a);
 }
 
 // The cell update along per-row sample lists (one row per lane, 32-bit words), for long batches whose row
@@ -1354,7 +1357,7 @@ k_cell_update_rowlists(float* __restrict__ W, const float* __restrict__ p_dw_up,
 {
     cell_update_body<KIND, uint32_t, NOISE, 1, true>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down,
                                                      xw, dw, pulse_count, a, blockIdx.x, rlist, rlen);
-    finish_step(a.advance, gridDim.x * 4u);
+    publish_step(a);
 }
 
 // One launch, two shapes: the first `main_blocks` workgroups work on their range of column strips at RPL
@@ -1375,7 +1378,7 @@ k_cell_update_pair(float* __restrict__ W, const float* __restrict__ p_dw_up, con
     else
         cell_update_body<KIND, WordT, NOISE, SIDE>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down, xw,
                                                    dw, pulse_count, b, blockIdx.x - main_blocks);
-    finish_step(a.advance, gridDim.x * 4u);
+    publish_step(a);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1432,11 +1435,13 @@ k_update_small(float* __restrict__ W, const float* __restrict__ p_dw_up, const f
                const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
                const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int BL, double A,
                int deterministic, uint32_t k0, uint32_t k1, float c2c, unsigned long long* __restrict__ pulse_count,
-               uint32_t* __restrict__ step_state, ConvView conv)
+               uint32_t t, uint32_t* step_state, int recorded, ConvView conv)
 {
+    // (a call made directly: the step is t and t + 1 is left in the device's counter; a recorded call reads
+    // the counter, and the last wave advances it)
     __shared__ WordT xs[kSmallMaxB][64], ds[kSmallMaxB][4];
     constexpr int kSign = WordTraits<WordT>::kSignBit;
-    const uint32_t t = *(const volatile uint32_t*)step_state;
+    if (recorded) t = *(const volatile uint32_t*)step_state;
     const int strips = (C + 63) / 64;
     const int j0 = (int)(blockIdx.x % (uint32_t)strips) * 64, i0 = (int)(blockIdx.x / (uint32_t)strips) * 4;
     for (int item = (int)threadIdx.x; item < B * 68; item += 256) {
@@ -1490,7 +1495,8 @@ k_update_small(float* __restrict__ W, const float* __restrict__ p_dw_up, const f
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) pulses += __shfl_xor(pulses, off, 64);
     if (lane == 0 && pulses) atomicAdd(pulse_count, pulses);
-    finish_step(step_state, gridDim.x * 4u);
+    if (recorded) finish_step(step_state, gridDim.x * 4u);
+    else if (blockIdx.x == 0 && threadIdx.x == 0) step_state[0] = t + 1u;
 }
 
 }  // namespace aht

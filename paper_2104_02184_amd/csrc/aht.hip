@@ -900,7 +900,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         uint32_t strips_main = strips;
         int rpl_main = 0, rpl_side = 0;
         if (rowlists) {
-            hipLaunchKernelGGL(k_compact_rows, dim3((unsigned)((t->rows + 3) / 4)), dim3(256), 0, s, (const uint32_t*)bufs.dw,
+            hipLaunchKernelGGL(k_compact_rows, dim3((unsigned)t->rows), dim3(256), 0, s, (const uint32_t*)bufs.dw,
                                t->rows, B, bpad(B), t->rlist, t->rlen);
             AHT_HIP(hipGetLastError());
             if ((st = launch_cells(t, B, t->step, s, strip0, strips, bufs, true, true, true, recorded)) != AHT_OK) return st;

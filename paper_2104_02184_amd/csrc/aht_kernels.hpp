@@ -446,29 +446,54 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
 
 // Per row, the samples whose row train has at least one pulse, in sample order: entry k of row i is
 // (sample b, row word), rlist[i * stride + k], k < rlen[i]; 16 all-zero entries follow the last one
-// (the cell update reads its list a few entries ahead and in groups).  One wave per row.
+// (the cell update reads its list a few entries ahead and in groups).  One workgroup per row takes
+// 2048 samples at a time, eight loads per lane in flight (a wave per row with one load in flight was
+// bound by the latency of its 196 dependent rounds: 64 us for 256 rows of 12 544 samples); the places
+// of a round's entries come from the 32 ballots of its (load, wave) pairs, summed in sample order.
 constexpr int kRowListPad = 16;
 __global__ void __launch_bounds__(256)
 k_compact_rows(const uint32_t* __restrict__ dw, int R, int B, int Bpad, uint2* __restrict__ rlist,
                uint32_t* __restrict__ rlen)
 {
-    const int row = (int)(blockIdx.x * 4 + (threadIdx.x >> 6));
-    if (row >= R) return;
-    const uint32_t lane = threadIdx.x & 63u;
+    constexpr int kLoads = 8;
+    __shared__ uint32_t counts[2][kLoads * 4];
+    const int row = (int)blockIdx.x;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const size_t stride = (size_t)Bpad + kRowListPad;
     uint2* __restrict__ out = rlist + (size_t)row * stride;
-    uint32_t n = 0;
-    for (int b0 = 0; b0 < B; b0 += 64) {
-        const int b = b0 + (int)lane;
-        const uint32_t w = b < B ? dw[(size_t)row * Bpad + b] : 0u;
-        const bool some = (w & 0x7FFFFFFFu) != 0u;
-        const unsigned long long m = __ballot(some);
-        const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-        if (some) out[n + before] = make_uint2((uint32_t)b, w);
-        n += (uint32_t)__popcll(m);
+    const uint32_t* __restrict__ in = dw + (size_t)row * Bpad;
+    uint32_t total = 0;
+    int buf = 0;
+    for (int b0 = 0; b0 < B; b0 += 256 * kLoads, buf ^= 1) {
+        uint32_t w[kLoads], before[kLoads];
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            const int b = b0 + u * 256 + (int)threadIdx.x;
+            w[u] = b < B ? in[b] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            const unsigned long long m = __ballot((w[u] & 0x7FFFFFFFu) != 0u);
+            before[u] = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            if (lane == 0) counts[buf][u * 4 + (int)wave] = (uint32_t)__popcll(m);
+        }
+        __syncthreads();                          // (two buffers: the next round's counts go elsewhere)
+        uint32_t at = total, round = 0;
+#pragma unroll
+        for (int k = 0; k < kLoads * 4; ++k) {
+            const uint32_t c = counts[buf][k];
+            round += c;
+#pragma unroll
+            for (int u = 0; u < kLoads; ++u)
+                if (k < u * 4 + (int)wave) before[u] += c;     // the (load, wave) pairs that come earlier in sample order
+        }
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u)
+            if ((w[u] & 0x7FFFFFFFu) != 0u) out[at + before[u]] = make_uint2((uint32_t)(b0 + u * 256 + (int)threadIdx.x), w[u]);
+        total += round;
     }
-    if (lane < (uint32_t)kRowListPad) out[n + lane] = make_uint2(0u, 0u);
-    if (lane == 0) rlen[row] = n;
+    if (threadIdx.x < (uint32_t)kRowListPad) out[total + threadIdx.x] = make_uint2(0u, 0u);
+    if (threadIdx.x == 0) rlen[row] = total;
 }
 
 // word format conversions for the debug entry points (public format: u64 [B][len], sign in bit 63;

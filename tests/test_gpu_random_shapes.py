@@ -12,7 +12,7 @@ import paper_2104_02184_amd as aht
 from common import gpu_params, oracle_params, to_dev
 
 pytestmark = pytest.mark.gpu
-ENV_KEYS = ("AHT_RPL", "AHT_QWORDS", "AHT_MVM_BM", "AHT_MVM_SPLITS")
+ENV_KEYS = ("AHT_RPL", "AHT_QWORDS", "AHT_MVM_BM", "AHT_MVM_SPLITS", "AHT_ROWLISTS", "AHT_FUSED")
 
 
 @pytest.fixture
@@ -34,7 +34,7 @@ def _setenv(**kw):
             os.environ.pop(k, None)
 
 
-@pytest.mark.parametrize("seed", [101, 202, 303])
+@pytest.mark.parametrize("seed", [101, 202, 303, 404])
 def test_pulsed_update_random_cases(seed, clean_env):
     g = np.random.default_rng(seed)
     for case in range(25):
@@ -46,6 +46,13 @@ def test_pulsed_update_random_cases(seed, clean_env):
         c2c, d2d = float(g.choice([0.0, 0.3])), float(g.choice([0.0, 0.3]))
         lr, scale = float(g.choice([0.01, 0.1, 1.0, 5.0])), float(g.choice([0.1, 1.0, 30.0]))
         _setenv(AHT_RPL=int(g.choice([0, 1, 2, 4])), AHT_QWORDS=int(g.choice([0, 5, 6, 12])))
+        # per-row sample lists (32-bit words only) and the one-launch update (few vectors, no update management)
+        # are forced on in some cases where they apply; some calls go through the allocation-free entry point
+        os.environ["AHT_ROWLISTS"] = str(int(g.choice([0, 1])))
+        os.environ["AHT_FUSED"] = str(int(g.choice([0, 1])))
+        if g.integers(0, 3) == 0:
+            B = int(g.integers(1, 9))
+        noalloc = bool(g.integers(0, 2))
         dev = dict(kind=kind, dw_min=0.002, dw_min_dtod=d2d, dw_min_std=c2c, up_down=0.02,
                    up_down_dtod=0.01 if d2d else 0.0, w_max=0.6, w_max_dtod=d2d, w_min=-0.6, w_min_dtod=d2d,
                    gamma_up=0.7, gamma_down=0.5, gamma_dtod=d2d)
@@ -60,10 +67,12 @@ def test_pulsed_update_random_cases(seed, clean_env):
             d = (g.normal(size=(B, R)) * scale).astype(np.float32)
             if g.integers(0, 4) == 0:
                 x[g.integers(0, B)] = 0
-            tile.pulsed_update(to_dev(x), to_dev(d), lr)
+            (tile.pulsed_update_noalloc if noalloc and t != 1 else tile.pulsed_update)(to_dev(x), to_dev(d), lr)
             total += oracle.pulsed_update(Wo, planes, oracle_params(dev), bl, um, x, d, lr, tseed, t)
         Wg = tile.get_weights().cpu().numpy()
-        what = dict(case=case, R=R, C=C, B=B, bl=bl, um=um, kind=kind, c2c=c2c, d2d=d2d, lr=lr, scale=scale)
+        what = dict(case=case, R=R, C=C, B=B, bl=bl, um=um, kind=kind, c2c=c2c, d2d=d2d, lr=lr, scale=scale,
+                    noalloc=noalloc, info=tile.launch_info(), env={k: os.environ.get(k) for k in ENV_KEYS})
+        assert tile.step == 3 == tile.sync_step(), what
         assert tile.pulse_count() == total, what
         assert np.abs(Wg.astype(np.float64) - Wo).max() / 0.6 <= 1e-5, what
         tile.close()

@@ -1713,4 +1713,13 @@ aht_status aht_debug_gauss(uint64_t seed, uint32_t index, uint32_t t, uint32_t t
     return AHT_OK;
 }
 
+#ifdef AHT_WAVE_STAMPS
+// Profiling build only: the cell kernel's waves write their time stamps to `stamps_dev`
+// (8 words per wave, 4 waves per workgroup of the launch; nullptr switches the stamps off).
+int aht_debug_set_wave_stamps(unsigned long long* stamps_dev)
+{
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(aht::g_wave_stamps), &stamps_dev, sizeof(stamps_dev));
+}
+#endif
+
 }  // extern "C"

@@ -20,6 +20,24 @@
 
 namespace aht {
 
+// Profiling build only (-DAHT_WAVE_STAMPS, see wave_timeline.py): lane 0 of every wave of the cell kernel
+// notes the 100 MHz wall clock at seven points of its life, and where it ran, in eight words of a buffer the
+// host hands over.  The default build has none of this.
+#ifdef AHT_WAVE_STAMPS
+__device__ unsigned long long* g_wave_stamps = nullptr;
+#define AHT_STAMP(k)                                                                                          \
+    do {                                                                                                      \
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                           \
+        if (g_wave_stamps && (threadIdx.x & 63) == 0)                                                         \
+            g_wave_stamps[((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (k)] =                          \
+                (k) < 7 ? __builtin_amdgcn_s_memrealtime()                                                    \
+                        : ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) /* HW_ID */ |        \
+                           ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) /* XCC_ID */ << 32)); \
+    } while (0)
+#else
+#define AHT_STAMP(k) ((void)0)
+#endif
+
 enum : int { kConstantStep = 0, kLinearStep = 1, kSoftBounds = 2 };
 
 template <typename WordT>
@@ -734,6 +752,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
     const uint32_t by = sy * kSuperY + (in % ht), bxr = sx * kSuperX + (in / ht);
     const uint32_t bx = a.bx0 + bxr;              // the launch covers strips bx0 .. bx0 + nbx - 1
 
+    AHT_STAMP(0);                                 // start
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int j = (int)bx * 64 + lane;            // < Cpad
@@ -771,6 +790,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
     // At four rows per lane, where registers are short, the pulse counts of a wave's cells rest in its
     // exchange buffer between drains (only the drain uses it), at the cells' home places, and not in
     // registers.
+    AHT_STAMP(1);                                 // the weights have arrived
     constexpr bool kParkCounts = RPL == 4;
     if (kParkCounts) {
         const uint32_t xhome = lds0 + (uint32_t)(4 * RPL * 64 * a.qwords * 4) + (uint32_t)wave * 1024u +
@@ -818,6 +838,8 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
         // The lane index is worked out again and made opaque: whatever the drain derives from it (the
         // cells' indices, the LDS addresses of the dealing, origins) is then formed here and not kept
         // in registers through phase A.
+        AHT_STAMP(2);                             // phase A over (of the last drain, if there are several)
+        if constexpr (SPARSE) __builtin_amdgcn_s_setprio(0);
         int dlane = (int)lane_by_count();
         asm volatile("" : "+v"(dlane));
         uint32_t tstep = a.t;
@@ -871,6 +893,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
         // wave's streams.  Positions come from a counting sort on the stream length (buckets of two
         // pulses): histogram, exclusive scan, one returning atomic per cell.  A wave's LDS
         // operations take effect in program order, so the steps need no barrier.
+        AHT_STAMP(3);                             // device parameters loaded, streams closed
         const bool sorted = RPL > 1;
         const uint32_t xbuf = lds0 + (uint32_t)(4 * RPL * 64 * a.qwords * 4) + (uint32_t)wave * 1024u;
         if (sorted) {
@@ -921,6 +944,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
                 move_f32(sl_dn);
             }
         }
+        AHT_STAMP(4);                             // cells dealt
 #pragma unroll
         for (int c = 0; c < RPL; ++c) blk[c] = (q[c] >> 5) << 3;
         // Wave-uniform per row: iterations its longest stream needs, and the iteration from which
@@ -986,6 +1010,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
                 else row_step(i, c, std::integral_constant<int, 2>{});
             }
         }
+        AHT_STAMP(5);                             // pulses applied
 #pragma unroll
         for (int c = 0; c < RPL; ++c) q[c] += endpos[c] - (q[c] & 31u);      // pulses applied so far
         if (sorted) {
@@ -1013,9 +1038,20 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
             fill[c] = q[c] & 31u;
             wp[c] = qb(c);
         }
+        if constexpr (SPARSE) {
+            if (!last) __builtin_amdgcn_s_setprio(3);
+        }
     };
 
     // ---- phase A ----------------------------------------------------------------------
+    // Walking the lists, a wave in phase A mostly waits for memory (a list entry names the sample whose column
+    // words are fetched next), and the few instructions between its waits are worth issuing ahead of the
+    // arithmetic of the waves that drain: phase A runs at the highest wave priority, the drain at the lowest
+    // (256 x 2304, 12 544 vectors: 1.47 -> 1.37 ms).  The dense walk is left alone: there the same setting
+    // costs 7 % on the 4096 x 4096 tile and changes nothing on the small ones, and so does every other
+    // assignment tried (drain above phase A: no change anywhere; priority falling with a wave's progress, so that
+    // the waves of a SIMD end together: 8 - 15 % slower everywhere).
+    if constexpr (SPARSE) __builtin_amdgcn_s_setprio(3);
     const WordT* __restrict__ xcur = xp;          // column words of sample b from the strip's first column on: a
                                                   // scalar base, so that the loads take the lane as a 32-bit
                                                   // offset and need no per-lane address arithmetic
@@ -1344,6 +1380,8 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
         for (int off = 32; off > 0; off >>= 1) pulses += __shfl_xor(pulses, off, 64);
         if (lane == 0 && pulses) atomicAdd(pulse_count, pulses);
     }
+    AHT_STAMP(6);                                 // weights stored
+    AHT_STAMP(7);                                 // where the wave ran
 }
 
 // Register budget: four waves per SIMD (128 registers) at four rows per lane, the variant of large

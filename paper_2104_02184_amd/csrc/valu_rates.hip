@@ -311,6 +311,51 @@ template <typename K> int run(const char* name, K kern, double ops_per_thread_it
     fflush(stdout);
     return 0;
 }
+
+// Dependent issue: NCH independent chains per wave, each instruction of a chain needing the result of the
+// one before it; W waves per SIMD.  Cycles (at the 2.4 GHz nominal clock) between two instructions of one
+// wave tell how much independent work a SIMD needs in flight to issue every cycle it could.
+template <int NCH, int OP>
+__global__ void __launch_bounds__(256) k_dep(uint32_t* out, uint32_t seed)
+{
+    float f[NCH];
+    uint32_t u[NCH];
+    const float b = 1.0f + 1e-7f * (float)seed;
+    const uint32_t m = 0xD2511F53u + seed;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) { f[c] = (float)(threadIdx.x + c) + 1.5f; u[c] = threadIdx.x * 2654435761u + c; }
+#pragma unroll 1
+    for (int it = 0; it < ITERS; ++it) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                if (OP == 0) asm volatile("v_fma_f32 %0, %0, %1, %1" : "+v"(f[c]) : "v"(b));
+                else if (OP == 1) asm volatile("v_mul_hi_u32 %0, %0, %1" : "+v"(u[c]) : "v"(m));
+                else if (OP == 2) asm volatile("v_log_f32 %0, %0" : "+v"(f[c]));
+                else asm volatile("v_xor_b32 %0, %0, %1" : "+v"(u[c]) : "v"(m));
+            }
+    }
+    float sf = 0.0f; uint32_t su = 0;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) { sf += f[c]; su += u[c]; }
+    if (sf == 12345.0f && su == 77u) out[0] = 1;
+}
+template <typename K> int run_dep(const char* name, K kern, int nch, int waves_per_simd, uint32_t* out)
+{
+    hipEvent_t e0, e1; CHK(hipEventCreate(&e0)); CHK(hipEventCreate(&e1));
+    hipLaunchKernelGGL(kern, dim3(256 * waves_per_simd), dim3(256), 0, 0, out, 1u);
+    CHK(hipDeviceSynchronize());
+    CHK(hipEventRecord(e0));
+    hipLaunchKernelGGL(kern, dim3(256 * waves_per_simd), dim3(256), 0, 0, out, 1u);
+    CHK(hipEventRecord(e1)); CHK(hipEventSynchronize(e1));
+    float ms; CHK(hipEventElapsedTime(&ms, e0, e1));
+    const double instr_per_simd = (double)ITERS * 8 * nch * waves_per_simd;
+    printf("dependent %-10s %d chain(s) x %d wave(s) per SIMD: %7.3f ms, %5.2f cycles (2.4 GHz) per instruction of the SIMD, %5.2f per step of a chain\n",
+           name, nch, waves_per_simd, ms, ms * 1e-3 * 2.4e9 / instr_per_simd, ms * 1e-3 * 2.4e9 / ((double)ITERS * 8));
+    fflush(stdout);
+    return 0;
+}
 // Instruction fetch: 2048 independent 8-byte v_fma_f32 in a straight line (16 KB of code), walked
 // three times by every wave; lane 0 of each wave notes the shader clock before and after each pass.
 // The first pass of the first launch finds the code nowhere near the compute unit, the first pass of
@@ -358,6 +403,12 @@ static int run_ifetch()
 int main() {
     if (run_ifetch()) return 1;
     uint32_t* out; CHK(hipMalloc(&out, 64));
+    for (int w = 1; w <= 4; w *= 2) {
+        run_dep("v_fma_f32", k_dep<1, 0>, 1, w, out); run_dep("v_fma_f32", k_dep<2, 0>, 2, w, out); run_dep("v_fma_f32", k_dep<4, 0>, 4, w, out);
+        run_dep("v_mul_hi", k_dep<1, 1>, 1, w, out); run_dep("v_mul_hi", k_dep<2, 1>, 2, w, out);
+        run_dep("v_log_f32", k_dep<1, 2>, 1, w, out); run_dep("v_log_f32", k_dep<2, 2>, 2, w, out);
+        run_dep("v_xor_b32", k_dep<1, 3>, 1, w, out); run_dep("v_xor_b32", k_dep<2, 3>, 2, w, out);
+    }
     hipDeviceProp_t p; CHK(hipGetDeviceProperties(&p, 0));
     printf("%s CUs=%d clock=%d kHz lds/block=%zu\n", p.name, p.multiProcessorCount, p.clockRate, p.sharedMemPerBlock);
     run("v_and", k_and, 8, out); run("v_add", k_add, 8, out); run("v_bcnt", k_bcnt, 8, out);

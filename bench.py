@@ -365,6 +365,68 @@ def bench_transfer(args):
     }), flush=True)
 
 
+def bench_many(args):
+    """N tiles of one workload per step (the layers of a network), updated through aht_pulsed_update_many and,
+    for comparison, one after the other.  Kernels of different tiles overlap, so there is no per-kernel time:
+    the roofline of this line prices the whole round (pulse-train kernels and gaps included) against the ALU."""
+    import torch
+
+    import paper_2104_02184_amd as aht
+    from paper_2104_02184_amd import workloads as wl
+
+    w = wl.WORKLOADS[args.workload or wl.HEADLINE]
+    N, K, Wm = args.tiles, args.steps, args.warmup
+    tiles, xs, ds = [], [], []
+    g = wl.rng_for(w, 2)
+    for i in range(N):
+        t = aht.Tile(w.rows, w.cols, aht.DeviceParams(**w.device), w.bl, w.update_management, w.seed + i)
+        bmax, bmin = t.get_plane("b_max"), t.get_plane("b_min")
+        t.set_weights(torch.minimum(torch.maximum(torch.from_numpy(wl.initial_weights(w)).cuda(), bmin), bmax))
+        tiles.append(t)
+        xs.append([torch.from_numpy(wl.draw_x(w, g)).cuda() for _ in range(4)])
+        ds.append([torch.from_numpy(wl.draw_d(w, g)).cuda() for _ in range(4)])
+    lrs = [w.lr] * N
+
+    def together(k):
+        aht.pulsed_update_many(tiles, [x[k % 4] for x in xs], [d[k % 4] for d in ds], lrs)
+
+    def in_turn(k):
+        for t, x, d in zip(tiles, xs, ds):
+            t.pulsed_update(x[k % 4], d[k % 4], w.lr)
+
+    times = {}
+    for name, fn in (("in_turn", in_turn), ("together", together)):
+        for k in range(max(Wm, 20)):                     # (the launch shapes settle on the tiles' own pulse rates)
+            fn(k)
+        torch.cuda.synchronize()
+        p0 = sum(t.pulse_count() for t in tiles)
+        t0 = time.perf_counter()
+        for k in range(K):
+            fn(k)
+        torch.cuda.synchronize()
+        times[name] = (time.perf_counter() - t0) / K
+        pulses = (sum(t.pulse_count() for t in tiles) - p0) / K / N
+    info = tiles[0].launch_info()
+    for t in tiles:
+        t.close()
+    sec = times["together"]
+    sparse = bool(info["row_lists"]) and info["row_fill"] >= 0
+    ops, ops_weighted = lane_ops_model(w, pulses, w.rows * w.cols * w.batch * info["row_fill"] if sparse else None)
+    print(json.dumps({
+        "metric": "Gcell-pulse-updates/s of pulsed_update", "value": N * w.cell_pulse_updates_per_call / sec / 1e9,
+        "unit": "Gcell-pulse-updates/s", "n_gpus": 1, "steps": K, "warmup": max(Wm, 20), "ms_per_step": sec * 1e3,
+        "ms_per_tile": sec * 1e3 / N, "ms_per_tile_one_after_the_other": times["in_turn"] * 1e3 / N,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{N} tiles of {w.name} per step (aht_pulsed_update_many)", "tiles": N, "rows": w.rows,
+                   "cols": w.cols, "batch": w.batch, "bl": w.bl, "pulses_per_tile_and_call": pulses},
+        "roofline": {"bound": "alu", "kernel": "whole round: pulse-train and cell kernels of all tiles, overlapping",
+                     "achieved": N * ops / sec / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+                     "frac": N * ops / sec / PEAK_LANE_OPS,
+                     "frac_one_after_the_other": N * ops / times["in_turn"] / PEAK_LANE_OPS,
+                     "algorithmic_lane_ops_per_tile": ops, "traffic": None, "launch": info},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -377,6 +439,8 @@ def main():
                     help="input noise of the forward/backward side benchmarks (0: quantised inputs only)")
     ap.add_argument("--op", default="pulsed_update", choices=["pulsed_update", "decay_diffuse", "forward", "backward", "transfer"],
                     help="side benchmarks of other operations; the default is the headline metric")
+    ap.add_argument("--tiles", type=int, default=1,
+                    help="pulsed_update only: that many tiles of the workload per step, through aht_pulsed_update_many")
     ap.add_argument("--graph", action="store_true",
                     help="also record the timed calls into a HIP graph and time a replay (ms_per_step_graph_replay)")
     ap.add_argument("--pmc-summary", default=None, metavar="DIR",
@@ -407,6 +471,9 @@ def main():
         return
     if args.op in ("forward", "backward"):
         bench_mvm(args, args.op == "backward")
+        return
+    if args.tiles > 1:
+        bench_many(args)
         return
     w = wl.WORKLOADS[args.workload or wl.HEADLINE]
     K, Wm = args.steps, args.warmup

@@ -7,10 +7,10 @@ loaded every call raises.
 """
 from .workloads import WORKLOADS, HEADLINE, SMALL, Workload  # noqa: F401
 from .binding import (  # noqa: F401
-    AhtError, DeviceParams, IOParams, Tile, UnitCell, load_library, library_path, debug_philox, debug_gauss,
+    AhtError, DeviceParams, IOParams, Tile, UnitCell, pulsed_update_many, load_library, library_path, debug_philox, debug_gauss,
     CONSTANT_STEP, LINEAR_STEP, SOFT_BOUNDS, PLANE_NAMES,
 )
 
-__all__ = ["AhtError", "DeviceParams", "IOParams", "Tile", "UnitCell", "load_library", "library_path", "debug_philox",
+__all__ = ["AhtError", "DeviceParams", "IOParams", "Tile", "UnitCell", "pulsed_update_many", "load_library", "library_path", "debug_philox",
            "debug_gauss", "CONSTANT_STEP", "LINEAR_STEP", "SOFT_BOUNDS", "PLANE_NAMES",
            "WORKLOADS", "HEADLINE", "SMALL", "Workload"]

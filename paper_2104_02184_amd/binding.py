@@ -21,7 +21,7 @@ TEMPORAL_PLANE_NAMES = ("decay", "diffusion", "reset")
 # every symbol include/aht.h declares
 EXPORTS = (
     "aht_tile_create", "aht_tile_destroy", "aht_set_weights", "aht_get_weights", "aht_pulsed_update",
-    "aht_pulsed_update_noalloc", "aht_get_launch_info", "aht_sync_step",
+    "aht_pulsed_update_noalloc", "aht_get_launch_info", "aht_sync_step", "aht_pulsed_update_many",
     "aht_get_step", "aht_set_step", "aht_get_pulse_count", "aht_get_device_planes",
     "aht_set_device_planes", "aht_debug_pulse_words", "aht_debug_counts", "aht_debug_apply_words",
     "aht_debug_philox", "aht_debug_gauss", "aht_profile_enable", "aht_profile_read",
@@ -135,6 +135,8 @@ def load_library() -> ctypes.CDLL:
     L.aht_get_weights.argtypes = [vp, vp, vp]
     L.aht_pulsed_update.argtypes = [vp, vp, vp, i32, f32, vp]
     L.aht_pulsed_update_noalloc.argtypes = [vp, vp, vp, i32, f32, vp]
+    L.aht_pulsed_update_many.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                         ctypes.POINTER(i32), ctypes.POINTER(f32), i32, vp]
     L.aht_get_launch_info.argtypes = [vp, ctypes.POINTER(aht_launch_info)]
     L.aht_get_step.argtypes = [vp, ctypes.POINTER(u32)]
     L.aht_set_step.argtypes = [vp, u32]
@@ -434,6 +436,26 @@ class Tile:
         _check(self._lib.aht_debug_apply_words(self._h, _ptr(xw, torch.int64, (B, self.cols)),
                                                _ptr(dw, torch.int64, (B, self.rows)), B, ctypes.c_uint32(step),
                                                _stream()))
+
+
+def pulsed_update_many(tiles, xs, ds, lrs) -> None:
+    """aht_pulsed_update_many: tile i gets pulsed_update(xs[i], ds[i], lrs[i]); small tiles run side by side."""
+    import torch
+    n = len(tiles)
+    if not (len(xs) == len(ds) == len(lrs) == n):
+        raise ValueError("tiles, xs, ds and lrs must have the same length")
+    if n == 0:
+        return
+    vp = ctypes.c_void_p
+    h, xp, dp = (vp * n)(), (vp * n)(), (vp * n)()
+    Bs, lr = (ctypes.c_int32 * n)(), (ctypes.c_float * n)()
+    for i, (t, x, d) in enumerate(zip(tiles, xs, ds)):
+        B = int(x.shape[0]) if x.dim() == 2 else -1
+        h[i] = t._h
+        if B > 0:
+            xp[i], dp[i] = _ptr(x, torch.float32, (B, t.cols)), _ptr(d, torch.float32, (B, t.rows))
+        Bs[i], lr[i] = B, float(lrs[i])
+    _check(tiles[0]._lib.aht_pulsed_update_many(h, xp, dp, Bs, lr, n, _stream()))
 
 
 class UnitCell:

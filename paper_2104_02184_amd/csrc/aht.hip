@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdarg>
@@ -345,6 +346,42 @@ void launch_cells_kind(int kind, bool noise, int rpl, dim3 grid, size_t lds, hip
     }
 }
 
+// one launch for the cell updates of several tiles of one signature (k_cell_update_group)
+template <int KIND, typename WordT, bool NOISE, int RPL>
+void launch_group_one(const CellGroup& g, unsigned blocks, size_t lds, hipStream_t s)
+{
+    if (lds > 64 * 1024)
+        (void)hipFuncSetAttribute((const void*)k_cell_update_group<KIND, WordT, NOISE, RPL>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((k_cell_update_group<KIND, WordT, NOISE, RPL>), dim3(blocks), dim3(256), lds, s, g);
+}
+
+template <int KIND, typename WordT, bool NOISE>
+void launch_group_rpl(int rpl, const CellGroup& g, unsigned blocks, size_t lds, hipStream_t s)
+{
+    switch (rpl) {
+        case 1: launch_group_one<KIND, WordT, NOISE, 1>(g, blocks, lds, s); break;
+        case 2: launch_group_one<KIND, WordT, NOISE, 2>(g, blocks, lds, s); break;
+        default: launch_group_one<KIND, WordT, NOISE, 4>(g, blocks, lds, s); break;
+    }
+}
+
+template <typename WordT>
+void launch_group_kind(int kind, bool noise, int rpl, const CellGroup& g, unsigned blocks, size_t lds, hipStream_t s)
+{
+#define AHT_GROUP_KIND(K)                                                                  \
+    do {                                                                                  \
+        if (noise) launch_group_rpl<K, WordT, true>(rpl, g, blocks, lds, s);              \
+        else launch_group_rpl<K, WordT, false>(rpl, g, blocks, lds, s);                   \
+    } while (0)
+    switch (kind) {
+        case AHT_CONSTANT_STEP: AHT_GROUP_KIND(kConstantStep); break;
+        case AHT_LINEAR_STEP: AHT_GROUP_KIND(kLinearStep); break;
+        default: AHT_GROUP_KIND(kSoftBounds); break;
+    }
+#undef AHT_GROUP_KIND
+}
+
 // Rows per lane: enough waves to fill 256 CUs x 4 SIMDs several times over, otherwise as many
 // cells per lane as possible (reuse of the x word, independent chains for the scheduler).
 int choose_rpl(const aht_tile* t)
@@ -414,9 +451,17 @@ aht_status ensure_row_lists(aht_tile* t, int B)
 // `rowlists`: walk the tile's per-row sample lists (already built from `words`), one row per lane
 // `counts`: the call advances the tile's step counter; `recorded`: it is being recorded into a graph (the step
 // is then read from the device's counter, which the caller advances with a kernel of its own afterwards)
-aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strip0, uint32_t strips,
-                        const WordBufs& words, bool full, bool rowlists = false, bool counts = false,
-                        bool recorded = false)
+struct CellLaunch {
+    CellPtrs p;
+    CellArgs a;
+    unsigned blocks;
+    size_t lds;
+    int rpl;
+};
+
+// pointers, arguments, grid and LDS of the cell update of one tile (see launch_cells for the parameters)
+aht_status build_cell_launch(aht_tile* t, int B, uint32_t step, uint32_t strip0, uint32_t strips, const WordBufs& words,
+                             bool full, bool rowlists, bool counts, bool recorded, CellLaunch* out)
 {
     const int rpl = rowlists ? 1 : choose_rpl(t);
     // stream storage per cell: 12 words hold 320 pulses before an early drain is needed; at 4 rows
@@ -428,7 +473,8 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     if (qwords < 5 || qwords > 160) qwords = rowlists ? 24 : (rpl == 4) ? 9 : 12;
     const size_t lds_extra = (rpl > 1) ? 4 * 1024 : 0;       // exchange buffers of the last drain, 1 KB per wave
     while (qwords > 5 && (size_t)4 * rpl * 64 * qwords * 4 + lds_extra > 160 * 1024) --qwords;   // LDS of one CU
-    CellPtrs p{};
+    CellPtrs& p = out->p;
+    p = CellPtrs{};
     p.W = t->W;
     weights_written(t);
     p.dw_up = t->planes[AHT_PLANE_DW_UP];
@@ -440,7 +486,8 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     p.xw = words.xw;
     p.dw = words.dw;
     p.pulse_count = t->pulse_count + (full ? 0 : 1);
-    CellArgs a{};
+    CellArgs& a = out->a;
+    a = CellArgs{};
     a.R = t->rows;
     a.C = t->cols;
     a.B = B;
@@ -460,14 +507,30 @@ aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32
     const uint64_t total = (uint64_t)a.nby * a.nbx;
     const uint64_t per = (total + 7) / 8;
     if (per * 8 > 0x7FFFFFFFull) return fail(AHT_ERR_UNSUPPORTED, "tile too large for one launch");
-    const dim3 grid((unsigned)(per * 8));
-    const size_t lds = (size_t)4 * rpl * 64 * qwords * 4 + lds_extra;
+    out->blocks = (unsigned)(per * 8);
+    out->lds = (size_t)4 * rpl * 64 * qwords * 4 + lds_extra;
+    out->rpl = rpl;
     if (full) {
         t->info.rows_per_lane = rpl;
         t->info.side_rows_per_lane = 0;
         t->info.row_lists = rowlists ? 1 : 0;
         t->info.stream_words = qwords;
     }
+    return AHT_OK;
+}
+
+aht_status launch_cells(aht_tile* t, int B, uint32_t step, hipStream_t s, uint32_t strip0, uint32_t strips,
+                        const WordBufs& words, bool full, bool rowlists = false, bool counts = false,
+                        bool recorded = false)
+{
+    CellLaunch cl;
+    aht_status st = build_cell_launch(t, B, step, strip0, strips, words, full, rowlists, counts, recorded, &cl);
+    if (st != AHT_OK) return st;
+    const CellPtrs& p = cl.p;
+    const CellArgs& a = cl.a;
+    const dim3 grid(cl.blocks);
+    const size_t lds = cl.lds;
+    const int rpl = cl.rpl;
     const bool noise = t->dev.dw_min_std > 0.0f;
     if (rowlists) {
 #define AHT_ROWLISTS_LAUNCH(K, N)                                                                                  \
@@ -825,18 +888,50 @@ aht_status aht_get_weights(const aht_tile* t, float* w_dev_out, void* stream)
 
 // `col_lo .. col_hi`: columns outside this range are known to be zero in every x (all columns if col_hi < 0)
 // `static_scratch_only`: the allocation-free variant (see aht_pulsed_update_noalloc)
-static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const float* d_dev, int64_t B64, float lr,
-                                     void* stream, const ConvView& conv, int col_lo = 0, int col_hi = -1,
-                                     bool static_scratch_only = false)
+// whether this tile's full updates are worth watching: large enough for a choice of rows per lane, or long
+// batches of 32-bit words, which may turn out sparse
+static bool watched_update(const aht_tile* t, int B)
+{
+    return t->pulses_seen && ((size_t)t->rows * t->cols >= kAdaptMinCells || (use_u32(t) && B >= 256));
+}
+
+// after the kernels of a full update are on stream s: counts it and, if `may_report`, sends the device's counters
+// to the host when no earlier report is still on its way: after each of the first eight updates, then sixteen
+// updates after the last report
+static aht_status full_update_done(aht_tile* t, int B, bool watched, bool may_report, hipStream_t s)
+{
+    t->full_updates += 1;
+    if (watched) t->row_trains += (uint64_t)t->rows * (uint64_t)((B + 15) / 16);    // every 16th sample is counted
+    if (may_report && watched && !t->copy_pending &&
+        (t->full_updates <= 8 || t->full_updates >= t->copy_index + 16)) {
+        for (int k = 0; k < 3; ++k) ((volatile unsigned long long*)t->pulses_seen)[k] = kNoValueYet;
+        AHT_HIP(hipMemcpyAsync(t->pulses_seen, t->pulse_count, 3 * sizeof(unsigned long long),
+                               hipMemcpyDeviceToHost, s));
+        t->copy_pending = true;
+        t->copy_index = t->full_updates;
+        t->copy_row_trains = t->row_trains;
+    }
+    return AHT_OK;
+}
+
+// what every update call checks before it launches anything
+static aht_status check_update_args(const aht_tile* t, const float* x_dev, const float* d_dev, int64_t B64, float lr)
 {
     if (!t) return fail(AHT_ERR_INVALID_ARG, "null tile");
     if (B64 < 0) return fail(AHT_ERR_INVALID_ARG, "B must be >= 0");
     if (B64 > 0x7FFFFFF0) return fail(AHT_ERR_INVALID_ARG, "too many update vectors for one call");
-    const int B = (int)B64;
     if (!(lr >= 0.0f) || !std::isfinite(lr)) return fail(AHT_ERR_INVALID_ARG, "lr must be finite and >= 0");
-    if (B > 0 && (!x_dev || !d_dev)) return fail(AHT_ERR_INVALID_ARG, "null x or d");
-    aht_status st = check_device(t);
+    if (B64 > 0 && (!x_dev || !d_dev)) return fail(AHT_ERR_INVALID_ARG, "null x or d");
+    return check_device(t);
+}
+
+static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const float* d_dev, int64_t B64, float lr,
+                                     void* stream, const ConvView& conv, int col_lo = 0, int col_hi = -1,
+                                     bool static_scratch_only = false)
+{
+    aht_status st = check_update_args(t, x_dev, d_dev, B64, lr);
     if (st != AHT_OK) return st;
+    const int B = (int)B64;
     const bool full = col_hi < 0;                 // the whole tile
     const bool recorded = being_recorded((hipStream_t)stream);
     if (B > 0 && lr > 0.0f && full && use_small_kernel(t, B)) {
@@ -885,10 +980,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
         }
         if (ev) AHT_HIP(hipEventRecord(ev[0], s));
         if (col_hi < 0) refresh_pulse_rate(t);
-        // whether this tile's calls are worth watching: large enough for a choice of rows per lane, or long
-        // batches of 32-bit words, which may turn out sparse
-        const bool watched = t->pulses_seen && col_hi < 0 &&
-                             ((size_t)t->rows * t->cols >= kAdaptMinCells || (use_u32(t) && B >= 256));
+        const bool watched = col_hi < 0 && watched_update(t, B);
         const bool rowlists = col_hi < 0 && !static_scratch_only && use_row_lists(t, B);
         if (rowlists && (st = ensure_row_lists(t, B)) != AHT_OK) return st;
         if ((st = launch_words(t, bufs, x_dev, d_dev, B, lr, t->step, s, conv, watched ? t->pulse_count + 2 : nullptr,
@@ -915,21 +1007,7 @@ static aht_status pulsed_update_impl(aht_tile* t, const float* x_dev, const floa
             AHT_HIP(hipEventRecord(ev[2], s));
             t->events_used += 3;
         }
-        if (col_hi < 0) {
-            t->full_updates += 1;
-            if (watched) t->row_trains += (uint64_t)t->rows * (uint64_t)((B + 15) / 16);    // every 16th sample is counted
-            // the counters are reported when no earlier report is still on its way: after each of the first
-            // eight updates, then sixteen updates after the last report
-            if (!static_scratch_only && !recorded && watched && !t->copy_pending &&
-                (t->full_updates <= 8 || t->full_updates >= t->copy_index + 16)) {
-                for (int k = 0; k < 3; ++k) ((volatile unsigned long long*)t->pulses_seen)[k] = kNoValueYet;
-                AHT_HIP(hipMemcpyAsync(t->pulses_seen, t->pulse_count, 3 * sizeof(unsigned long long),
-                                       hipMemcpyDeviceToHost, s));
-                t->copy_pending = true;
-                t->copy_index = t->full_updates;
-                t->copy_row_trains = t->row_trains;
-            }
-        }
+        if (col_hi < 0 && (st = full_update_done(t, B, watched, !static_scratch_only && !recorded, s)) != AHT_OK) return st;
         if (recorded) {                           // the kernels above read the device's counter: now it moves on
             hipLaunchKernelGGL(k_set_step, dim3(1), dim3(1), 0, s, t->step_state, 1u, 1);
             AHT_HIP(hipGetLastError());
@@ -952,6 +1030,215 @@ aht_status aht_pulsed_update_noalloc(aht_tile* t, const float* x_dev, const floa
                                      void* stream)
 {
     return pulsed_update_impl(t, x_dev, d_dev, B, lr, stream, ConvView{}, 0, -1, true);
+}
+
+// Streams and events of aht_pulsed_update_many, per device, made on first use and kept until the process ends
+// (default priority: streams of different priorities are not used anywhere in the library).
+namespace {
+constexpr int kManyStreams = 4;                   // hardware queues a process gets by default
+struct ManyLanes {
+    bool ready = false;
+    hipStream_t stream[kManyStreams];
+    hipEvent_t fork, join[kManyStreams];
+};
+std::mutex g_many_mutex;
+ManyLanes g_many[64];
+}  // namespace
+
+static aht_status many_lanes(int device, ManyLanes** out)
+{
+    if (device < 0 || device >= 64) return fail(AHT_ERR_UNSUPPORTED, "device index %d", device);
+    std::lock_guard<std::mutex> lock(g_many_mutex);
+    ManyLanes& m = g_many[device];
+    if (!m.ready) {
+        AHT_HIP(hipEventCreateWithFlags(&m.fork, hipEventDisableTiming));
+        for (int i = 0; i < kManyStreams; ++i) {
+            AHT_HIP(hipStreamCreateWithFlags(&m.stream[i], hipStreamNonBlocking));
+            AHT_HIP(hipEventCreateWithFlags(&m.join[i], hipEventDisableTiming));
+        }
+        m.ready = true;
+    }
+    *out = &m;
+    return AHT_OK;
+}
+
+aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_dev, const float* const* d_dev,
+                                  const int32_t* B, const float* lr, int32_t n, void* stream)
+{
+    if (n < 0) return fail(AHT_ERR_INVALID_ARG, "n must be >= 0");
+    if (n == 0) return AHT_OK;
+    if (!tiles || !x_dev || !d_dev || !B || !lr) return fail(AHT_ERR_INVALID_ARG, "null argument");
+    aht_status st;
+    for (int i = 0; i < n; ++i) {
+        if ((st = check_update_args(tiles[i], x_dev[i], d_dev[i], B[i], lr[i])) != AHT_OK) return st;
+        for (int k = 0; k < i; ++k)
+            if (tiles[k] == tiles[i]) return fail(AHT_ERR_INVALID_ARG, "entries %d and %d name the same tile", k, i);
+    }
+    hipStream_t caller = (hipStream_t)stream;
+    if (n == 1) return pulsed_update_impl(tiles[0], x_dev[0], d_dev[0], B[0], lr[0], stream, ConvView{});
+    ManyLanes* m = nullptr;
+    if ((st = many_lanes(tiles[0]->device, &m)) != AHT_OK) return st;
+    static std::mutex issue;                      // one call at a time forks and joins through the lanes' events
+    std::lock_guard<std::mutex> lock(issue);
+
+    // Three kinds of entries.  `in_turn`: nothing to apply, or tiny tiles whose whole update is one short launch:
+    // on the caller's stream, one after the other (forking costs more than they take).  `grouped`: dense updates
+    // whose cell kernels can share a launch with those of other tiles (k_cell_update_group): their pulse-train
+    // kernels go to the lanes, their cell updates follow on the caller's stream after the join, one launch per
+    // signature.  `whole`: everything else (row lists, tiles being profiled, a stream being recorded): the whole
+    // update on a lane.
+    const bool recorded = being_recorded(caller);
+    const bool grouping = env_int("AHT_GROUP", 1) != 0 && !recorded;
+    std::vector<int> in_turn, grouped, whole;
+    for (int i = 0; i < n; ++i) {
+        aht_tile* t = tiles[i];
+        if (B[i] == 0 || lr[i] == 0.0f || use_small_kernel(t, B[i])) {
+            in_turn.push_back(i);
+            continue;
+        }
+        refresh_pulse_rate(t);                    // (the choices below follow the tile's latest counters)
+        if (grouping && !t->profiling && !use_row_lists(t, B[i])) grouped.push_back(i);
+        else whole.push_back(i);
+    }
+    if (grouped.size() == 1) {                    // nothing to share a launch with
+        whole.push_back(grouped[0]);
+        grouped.clear();
+    }
+    auto words_work = [&](int i) { return ((double)tiles[i]->rows + tiles[i]->cols) * (double)B[i]; };
+    auto cells_work = [&](int i) { return (double)tiles[i]->rows * tiles[i]->cols * ((double)B[i] + 8.0); };
+    // The pulse words of the grouped entries: those with a fixed train length and one probability factor per call
+    // share launches too (k_pulse_words_group, per word width, on the caller's stream); the others (update
+    // management, per-vector train lengths: a reduction kernel first) draw theirs on the lanes.
+    AHT_HIP(hipEventRecord(m->fork, caller));     // (before the caller's stream gets work of this call)
+    std::vector<char> watched(n, 0);
+    std::vector<int> words_on_lanes;
+    for (int width = 4; width <= 8; width += 4) {
+        WordsGroup g{};
+        unsigned blocks = 0;
+        auto flush = [&]() -> aht_status {
+            if (g.n == 0) return AHT_OK;
+            for (uint32_t k = g.n; k <= (uint32_t)kGroupMax; ++k) g.first_block[k] = blocks;
+            if (width == 4) hipLaunchKernelGGL(k_pulse_words_group<uint32_t>, dim3(blocks), dim3(256), 0, caller, g);
+            else hipLaunchKernelGGL(k_pulse_words_group<uint64_t>, dim3(blocks), dim3(256), 0, caller, g);
+            AHT_HIP(hipGetLastError());
+            g = WordsGroup{};
+            blocks = 0;
+            return AHT_OK;
+        };
+        for (int i : grouped) {
+            aht_tile* t = tiles[i];
+            if ((int)word_bytes(t) != width) continue;
+            if (t->upd.update_management || t->dynamic_bl) {
+                words_on_lanes.push_back(i);
+                continue;
+            }
+            if ((st = ensure_scratch(t, B[i])) != AHT_OK) return st;
+            watched[i] = watched_update(t, B[i]);
+            const WordBufs w = tile_bufs(t);
+            const unsigned nbx = (unsigned)blocks_for((size_t)cpad(t) + rpad(t)), ny = (unsigned)(B[i] < 32768 ? B[i] : 32768);
+            if ((uint64_t)blocks + (uint64_t)nbx * ny > 0x7FFFFFFFull || g.n == (uint32_t)kGroupMax)
+                if ((st = flush()) != AHT_OK) return st;
+            WordsGroupEntry& e = g.e[g.n];
+            e.x = x_dev[i]; e.d = d_dev[i]; e.xw = w.xw; e.dw = w.dw;
+            e.row_stat = watched[i] ? t->pulse_count + 2 : nullptr;
+            e.A = std::sqrt((double)lr[i] / ((double)t->dev.dw_min * (double)t->upd.bl));
+            e.B = B[i]; e.R = t->rows; e.C = t->cols; e.Rpad = rpad(t); e.Cpad = cpad(t); e.Bpad = bpad(B[i]);
+            e.BL = t->upd.bl; e.deterministic = t->train_kind;
+            e.k0 = (uint32_t)t->seed; e.k1 = (uint32_t)(t->seed >> 32); e.t = t->step;
+            e.nbx = nbx; e.ny = ny;
+            g.first_block[g.n] = blocks;
+            blocks += nbx * ny;
+            g.n += 1;
+        }
+        if ((st = flush()) != AHT_OK) return st;
+    }
+    // lane work, largest first, each item to the lane with the least work so far
+    struct Item { int i; bool words_only; double work; };
+    std::vector<Item> items;
+    for (int i : whole) items.push_back({i, false, cells_work(i)});
+    for (int i : words_on_lanes) items.push_back({i, true, words_work(i)});
+    std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.work > b.work; });
+    double load[kManyStreams] = {0.0, 0.0, 0.0, 0.0};
+    bool used[kManyStreams] = {false, false, false, false};
+    aht_status result = AHT_OK;
+
+    for (size_t k = 0; k < items.size() && result == AHT_OK; ++k) {
+        const int i = items[k].i;
+        aht_tile* t = tiles[i];
+        int lane = 0;
+        for (int l = 1; l < kManyStreams; ++l)
+            if (load[l] < load[lane]) lane = l;
+        if (!used[lane]) {
+            AHT_HIP(hipStreamWaitEvent(m->stream[lane], m->fork, 0));
+            used[lane] = true;
+        }
+        load[lane] += items[k].work;
+        if (!items[k].words_only) {
+            result = pulsed_update_impl(t, x_dev[i], d_dev[i], B[i], lr[i], (void*)m->stream[lane], ConvView{});
+        } else if ((result = ensure_scratch(t, B[i])) == AHT_OK) {
+            watched[i] = watched_update(t, B[i]);
+            result = launch_words(t, tile_bufs(t), x_dev[i], d_dev[i], B[i], lr[i], t->step, m->stream[lane], ConvView{},
+                                  watched[i] ? t->pulse_count + 2 : nullptr, false);
+            if (result != AHT_OK) grouped.clear();
+        } else {
+            grouped.clear();                      // (no cell updates without every tile's pulse words)
+        }
+    }
+    for (size_t k = 0; k < in_turn.size() && result == AHT_OK; ++k) {
+        const int i = in_turn[k];
+        result = pulsed_update_impl(tiles[i], x_dev[i], d_dev[i], B[i], lr[i], stream, ConvView{});
+    }
+    for (int l = 0; l < kManyStreams; ++l) {       // (also after a failure: what was launched is joined)
+        if (!used[l]) continue;
+        AHT_HIP(hipEventRecord(m->join[l], m->stream[l]));
+        AHT_HIP(hipStreamWaitEvent(caller, m->join[l], 0));
+    }
+    if (result != AHT_OK) return result;
+
+    // the cell updates of the grouped entries: one launch per signature (device kind, word width, noise, rows
+    // per lane, hence also stream length and LDS), up to kGroupMax tiles each
+    std::vector<CellLaunch> cl(n);
+    for (int i : grouped) {
+        aht_tile* t = tiles[i];
+        if ((st = build_cell_launch(t, B[i], t->step, 0u, (uint32_t)((t->cols + 63) / 64), tile_bufs(t), true, false, true,
+                                    false, &cl[i])) != AHT_OK)
+            return st;
+    }
+    std::vector<char> done(n, 0);
+    for (size_t a0 = 0; a0 < grouped.size(); ++a0) {
+        const int i0 = grouped[a0];
+        if (done[i0]) continue;
+        const aht_tile* t0 = tiles[i0];
+        CellGroup g{};
+        unsigned blocks = 0;
+        for (size_t a1 = a0; a1 < grouped.size() && g.n < (uint32_t)kGroupMax; ++a1) {
+            const int i = grouped[a1];
+            const aht_tile* t = tiles[i];
+            if (done[i] || t->dev.kind != t0->dev.kind || use_u32(t) != use_u32(t0) ||
+                (t->dev.dw_min_std > 0.0f) != (t0->dev.dw_min_std > 0.0f) || cl[i].rpl != cl[i0].rpl ||
+                cl[i].lds != cl[i0].lds || (uint64_t)blocks + cl[i].blocks > 0x7FFFFFFFull)
+                continue;
+            CellGroupEntry& e = g.e[g.n];
+            const CellPtrs& p = cl[i].p;
+            e.W = p.W; e.dw_up = p.dw_up; e.dw_down = p.dw_down; e.b_max = p.b_max; e.b_min = p.b_min;
+            e.slope_up = p.slope_up; e.slope_down = p.slope_down; e.xw = p.xw; e.dw = p.dw; e.pulse_count = p.pulse_count;
+            e.a = cl[i].a;
+            g.first_block[g.n] = blocks;
+            blocks += cl[i].blocks;               // (a multiple of 8)
+            g.n += 1;
+            done[i] = 1;
+        }
+        for (uint32_t k = g.n; k <= (uint32_t)kGroupMax; ++k) g.first_block[k] = blocks;
+        if (use_u32(t0)) launch_group_kind<uint32_t>(t0->dev.kind, t0->dev.dw_min_std > 0.0f, cl[i0].rpl, g, blocks, cl[i0].lds, caller);
+        else launch_group_kind<uint64_t>(t0->dev.kind, t0->dev.dw_min_std > 0.0f, cl[i0].rpl, g, blocks, cl[i0].lds, caller);
+        AHT_HIP(hipGetLastError());
+    }
+    for (int i : grouped) {
+        aht_tile* t = tiles[i];
+        if ((st = full_update_done(t, B[i], watched[i] != 0, true, caller)) != AHT_OK) return st;
+        t->step += 1;
+    }
+    return AHT_OK;
 }
 
 // checks the convolution geometry against the tile and fills the view; B = number of update vectors

@@ -8,6 +8,7 @@
 //                    every update vector of the call, weights resident in registers
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include <type_traits>
@@ -338,6 +339,34 @@ __device__ __forceinline__ uint64_t or_across_lines(uint64_t v)
     return ((uint64_t)or_across_lines<GROUP>((uint32_t)(v >> 32)) << 32) | or_across_lines<GROUP>((uint32_t)v);
 }
 
+constexpr int kGroupMax = 16;                    // tiles whose kernels share one launch, at most
+
+// A kernel whose only argument is a group { n, ..., first_block[kGroupMax + 1], e[kGroupMax] } finds the entry
+// that owns this workgroup and the workgroup's index inside the entry's range.  The group is read word by word
+// from the kernel-argument segment through the constant address space: loads from there at a wave-uniform
+// address are scalar loads, so that the entry's pointers and arguments sit in scalar registers as the kernel
+// arguments of a single tile's launch do (indexing the by-value struct with a run-time index made the compiler
+// treat them as per-lane values).
+template <typename Group, typename Entry>
+__device__ __forceinline__ Entry group_entry_of_block(uint32_t* block)
+{
+    static_assert(sizeof(Entry) % 4 == 0 && offsetof(Group, e) % 4 == 0, "copied in 32-bit words");
+    typedef __attribute__((address_space(4))) const uint32_t const_u32;
+    const_u32* words = (const_u32*)__builtin_amdgcn_kernarg_segment_ptr();
+    const uint32_t n = words[offsetof(Group, n) / 4];
+    const_u32* first = words + offsetof(Group, first_block) / 4;
+    uint32_t i = 0;
+    while (i + 1 < n && blockIdx.x >= first[i + 1]) ++i;                     // uniform over the workgroup
+    *block = blockIdx.x - first[i];
+    const_u32* src = words + (offsetof(Group, e) + (size_t)i * sizeof(Entry)) / 4;
+    uint32_t raw[sizeof(Entry) / 4];
+#pragma unroll
+    for (int k = 0; k < (int)(sizeof(Entry) / 4); ++k) raw[k] = src[k];
+    Entry e;
+    __builtin_memcpy(&e, raw, sizeof(e));
+    return e;
+}
+
 // ------------------------------------------------------------------------------------------
 // Pulse words.  One thread per line value: threshold T = floor(min(1, a|v|) 2^32) in fp64,
 // pulse n set iff Philox word n&3 of block n>>2 is below T; top bit = line value negative.
@@ -357,18 +386,21 @@ __device__ __forceinline__ uint64_t or_across_lines(uint64_t v)
 // blocks are dealt out over the whole wave, 64 / kBlocks lines at a time with one block per lane;
 // the four compare bits of each block are OR-ed together across the lanes of a line and the owner
 // of the line fetches the word.  The counters are those of the plain path: same words.
+// (The body is a device function so that one launch can also draw the words of several tiles, see
+// k_pulse_words_group: workgroup `bx` of the lines, samples `by`, `by + ny`, ...)
 template <typename WordT>
-__global__ void __launch_bounds__(256)
-k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int Rpad, int Cpad,
-              int Bpad, int BL, double A, const double* __restrict__ a_x, const double* __restrict__ a_d,
-              const int32_t* __restrict__ bl_b, int deterministic,
-              uint32_t k0, uint32_t k1, uint32_t t, const uint32_t* step_on_device, WordT* __restrict__ xw,
-              WordT* __restrict__ dw, ConvView conv, unsigned long long* __restrict__ row_words_with_pulses)
+__device__ __forceinline__ void
+pulse_words_body(const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int Rpad, int Cpad,
+                 int Bpad, int BL, double A, const double* __restrict__ a_x, const double* __restrict__ a_d,
+                 const int32_t* __restrict__ bl_b, int deterministic,
+                 uint32_t k0, uint32_t k1, uint32_t t, const uint32_t* step_on_device, WordT* __restrict__ xw,
+                 WordT* __restrict__ dw, const ConvView& conv, unsigned long long* __restrict__ row_words_with_pulses,
+                 const uint32_t bx, const uint32_t by, const uint32_t ny)
 {
     constexpr int kBlocks = (sizeof(WordT) == 4) ? 8 : 16;       // Philox blocks per line value, at most
     constexpr int kLines = 64 / kBlocks;                         // lines served at a time by the shared path
     __shared__ uint32_t needy_list[4][64][2];                    // per wave: lane and threshold of the lines that need random numbers
-    const int l = (int)(blockIdx.x * 256 + threadIdx.x);
+    const int l = (int)(bx * 256 + threadIdx.x);
     const bool live = l < Cpad + Rpad;                           // (no early exit: the shared path needs whole waves)
     const bool is_x = l < Cpad;                                  // uniform per wave (Cpad % 64 == 0)
     const int idx = is_x ? l : l - Cpad;
@@ -376,7 +408,7 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
     const uint32_t tagw = (is_x ? kTagX : kTagD) << 24;
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     if (step_on_device) t = *(const volatile uint32_t*)step_on_device;   // a recorded call: the device's counter
-    for (uint32_t b = blockIdx.y; b < (uint32_t)B; b += gridDim.y) {
+    for (uint32_t b = by; b < (uint32_t)B; b += ny) {
         WordT word = 0;
         const int bl = bl_b ? bl_b[b] : BL;
         const int nblk = (bl + 3) >> 2;
@@ -460,6 +492,47 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
             else dw[(size_t)idx * Bpad + b] = word;
         }
     }
+}
+
+template <typename WordT>
+__global__ void __launch_bounds__(256)
+k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int Rpad, int Cpad,
+              int Bpad, int BL, double A, const double* __restrict__ a_x, const double* __restrict__ a_d,
+              const int32_t* __restrict__ bl_b, int deterministic,
+              uint32_t k0, uint32_t k1, uint32_t t, const uint32_t* step_on_device, WordT* __restrict__ xw,
+              WordT* __restrict__ dw, ConvView conv, unsigned long long* __restrict__ row_words_with_pulses)
+{
+    pulse_words_body<WordT>(x, d, B, R, C, Rpad, Cpad, Bpad, BL, A, a_x, a_d, bl_b, deterministic, k0, k1, t, step_on_device,
+                            xw, dw, conv, row_words_with_pulses, blockIdx.x, blockIdx.y, gridDim.y);
+}
+
+// The pulse words of several tiles in one launch (aht_pulsed_update_many; fixed train length, one probability
+// factor per call, no convolution view): entry i owns workgroups first_block[i] .. first_block[i + 1] - 1, laid out
+// as nbx workgroups of lines times ny strides of samples, as the grid of its own launch would be.
+struct WordsGroupEntry {
+    const float *x, *d;
+    void *xw, *dw;
+    unsigned long long* row_stat;
+    double A;
+    int B, R, C, Rpad, Cpad, Bpad, BL, deterministic;
+    uint32_t k0, k1, t, nbx, ny, pad_;
+};
+struct WordsGroup {
+    uint32_t n, pad_;
+    uint32_t first_block[kGroupMax + 1];
+    WordsGroupEntry e[kGroupMax];
+};
+
+template <typename WordT>
+__global__ void __launch_bounds__(256)
+k_pulse_words_group(WordsGroup g)
+{
+    (void)g;
+    uint32_t block;
+    const WordsGroupEntry e = group_entry_of_block<WordsGroup, WordsGroupEntry>(&block);
+    pulse_words_body<WordT>(e.x, e.d, e.B, e.R, e.C, e.Rpad, e.Cpad, e.Bpad, e.BL, e.A, nullptr, nullptr, nullptr,
+                            e.deterministic, e.k0, e.k1, e.t, nullptr, (WordT*)e.xw, (WordT*)e.dw, ConvView{},
+                            e.row_stat, block % e.nbx, block / e.nbx, e.ny);
 }
 
 // Per row, the samples whose row train has at least one pulse, in sample order: entry k of row i is
@@ -709,7 +782,7 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 // SPARSE (one row per lane, 32-bit words): phase A walks the row's list of samples whose row train has a
 // pulse (rlist, rlen: see k_compact_rows) instead of all B samples; a sample left out gives every cell of
 // the row the count zero, so the streams, and with them all results, are the same.
-template <int KIND, typename WordT, bool NOISE, int RPL, bool SPARSE = false>
+template <int KIND, typename WordT, bool NOISE, int RPL, bool SPARSE = false, bool GROUPED = false>
 __device__ __forceinline__ void
 cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
                  const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
@@ -1059,6 +1132,15 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
     uint32_t xoff[G];                             // byte offsets of the lane's words of a group's G samples
 #pragma unroll
     for (int u = 0; u < G; ++u) xoff[u] = (uint32_t)(((size_t)u * xstride + xlane) * sizeof(WordT));
+    // GROUPED (several tiles in one launch): the pointers come out of a table, not from kernel arguments of their
+    // own, and the compiler no longer knows that nothing in this kernel writes the row words; read through the
+    // constant address space (an earlier kernel wrote them) they stay scalar loads.
+    typedef __attribute__((address_space(4))) const WordT const_word;
+    const const_word* dwc = (const const_word*)(size_t)dw;
+    auto row_word = [&](size_t at) __attribute__((always_inline)) -> WordT {
+        if constexpr (GROUPED) return dwc[at];
+        else return dw[at];
+    };
     size_t doff = (size_t)i0 * drow;              // dw[doff + c * drow]: row words of sample b (wave-uniform,
                                                   // indexed off the kernel argument so that they stay scalar loads)
     auto load_x = [&](const WordT* __restrict__ p0, WordT (&xg)[G]) __attribute__((always_inline)) {
@@ -1278,7 +1360,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
 #pragma unroll
                     for (int u = 0; u < G; ++u)
 #pragma unroll
-                        for (int c = 0; c < RPL; ++c) dg[u][c] = dw[doff + (size_t)c * drow + u];
+                        for (int c = 0; c < RPL; ++c) dg[u][c] = row_word(doff + (size_t)c * drow + u);
                     __builtin_amdgcn_sched_barrier(0);        // all row words requested before the first is waited for
 #pragma unroll
                     for (int u = 0; u < G; ++u) {
@@ -1349,7 +1431,7 @@ cell_update_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const
                 }
                 WordT dv[RPL];
 #pragma unroll
-                for (int c = 0; c < RPL; ++c) dv[c] = dw[doff + (size_t)c * drow];
+                for (int c = 0; c < RPL; ++c) dv[c] = row_word(doff + (size_t)c * drow);
                 uint32_t n1[RPL], m1[RPL];
                 const WordT xv = *(const WordT*)((const char*)xcur + xoff[0]);
                 count(xv, dv, n1);
@@ -1442,6 +1524,39 @@ k_cell_update_pair(float* __restrict__ W, const float* __restrict__ p_dw_up, con
         cell_update_body<KIND, WordT, NOISE, SIDE>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down, xw,
                                                    dw, pulse_count, b, blockIdx.x - main_blocks);
     publish_step(a);
+}
+
+// The cell updates of several tiles in one launch (aht_pulsed_update_many): tiles of the same device kind, word
+// width, noise setting and rows per lane, each with its own weights, planes, pulse words and arguments.  The
+// workgroups of entry i are blocks first_block[i] .. first_block[i + 1] - 1 (multiples of 8, so that a tile's
+// blocks keep their round-robin places on the 8 XCDs); inside its range a workgroup does exactly what it does in
+// a launch of the tile's own.  What this buys small tiles: one round of waves per SIMD from each of several
+// tiles instead of one round in all, so that a SIMD holds waves at different points of their lives and none of
+// them ends alone.
+struct CellGroupEntry {
+    float* W;
+    const float *dw_up, *dw_down, *b_max, *b_min, *slope_up, *slope_down;
+    const void *xw, *dw;
+    unsigned long long* pulse_count;
+    CellArgs a;
+};
+struct CellGroup {
+    uint32_t n;
+    uint32_t first_block[kGroupMax + 1];
+    CellGroupEntry e[kGroupMax];
+};
+
+template <int KIND, typename WordT, bool NOISE, int RPL>
+__global__ void __launch_bounds__(256, (CellOccupancy<WordT, RPL>::kWorkgroups))
+k_cell_update_group(CellGroup g)
+{
+    (void)g;
+    uint32_t block;
+    const CellGroupEntry e = group_entry_of_block<CellGroup, CellGroupEntry>(&block);
+    cell_update_body<KIND, WordT, NOISE, RPL, false, true>(e.W, e.dw_up, e.dw_down, e.b_max, e.b_min, e.slope_up,
+                                                           e.slope_down, (const WordT*)e.xw, (const WordT*)e.dw,
+                                                           e.pulse_count, e.a, block);
+    if (e.a.publish && block == 0 && threadIdx.x == 0) *e.a.publish = e.a.t + 1u;
 }
 
 // ------------------------------------------------------------------------------------------

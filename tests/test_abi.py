@@ -64,6 +64,15 @@ def test_null_arguments_are_rejected():
     assert L.aht_get_step(None, None) == 1
     assert L.aht_debug_philox(None, None, 1, None, None) == 1
     assert L.aht_tile_destroy(None) == 0
+    # several tiles in one call: a negative count, missing arrays, a null tile among the entries
+    vp = ctypes.c_void_p
+    assert L.aht_pulsed_update_many(None, None, None, None, None, -1, None) == 1
+    assert L.aht_pulsed_update_many(None, None, None, None, None, 0, None) == 0
+    assert L.aht_pulsed_update_many(None, None, None, None, None, 2, None) == 1
+    two = (vp * 2)()
+    Bs, lrs = (ctypes.c_int32 * 2)(1, 1), (ctypes.c_float * 2)(0.1, 0.1)
+    assert L.aht_pulsed_update_many(two, two, two, Bs, lrs, 2, None) == 1
+    assert b"null tile" in L.aht_last_error()
 
 
 def test_product_package_does_not_import_the_oracle():

@@ -1,0 +1,154 @@
+"""aht_pulsed_update_many: the updates of several tiles in one call, spread over the library's own streams.
+Every tile must get exactly what a call of its own gives it (weights bit for bit, pulse count, step), whatever
+the mix of shapes, word widths, device kinds and batch lengths, over several calls in a row; a small one is also
+checked against the oracle.  Bad entries are refused before anything is launched."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2104_02184_amd as aht
+from paper_2104_02184_amd import workloads as wl
+
+from common import gpu_planes, make_tile, oracle_params, to_dev
+
+pytestmark = pytest.mark.gpu
+
+MIX = [  # (base workload, rows, cols, batch)
+    (wl.HEADLINE, 200, 333, 48),                        # 64-bit words, update management
+    ("cfg2_512x512_constant_d2d", 512, 512, 64),
+    ("cfg3_1024x1024_softbounds", 300, 1000, 32),
+    ("cfg1_64x64_constant", 64, 64, 1),                 # the one-launch update of tiny tiles
+    ("cfg2_512x512_constant_d2d", 130, 70, 7),
+    ("cfg4_conv_256x2304", 64, 320, 600),               # long batch: row lists once the fill is known
+    ("cfg3_1024x1024_softbounds", 768, 512, 128),
+    ("cfg2_512x512_constant_d2d", 256, 640, 33),        # shares a launch with the 512 x 512 tile above
+    ("cfg3_1024x1024_softbounds", 516, 200, 64),
+    (wl.HEADLINE, 96, 520, 17),
+]
+
+
+def _workloads():
+    return [wl.scaled(wl.WORKLOADS[b], rows=r, cols=c, batch=B, steps=1, name=f"many{i}")
+            for i, (b, r, c, B) in enumerate(MIX)]
+
+
+@pytest.mark.parametrize("group", ["1", "0"])           # cell updates sharing launches / every tile's update on a lane
+def test_many_tiles_in_one_call_equal_calls_of_their_own(group, monkeypatch):
+    import torch
+    monkeypatch.setenv("AHT_GROUP", group)
+    ws = _workloads()
+    alone = [make_tile(w, seed=100 + i) for i, w in enumerate(ws)]
+    many = [make_tile(w, seed=100 + i) for i, w in enumerate(ws)]
+    for w, a, m in zip(ws, alone, many):
+        W0 = to_dev(wl.initial_weights(w))
+        a.set_weights(W0)
+        m.set_weights(W0)
+    gens = [wl.rng_for(w, 11) for w in ws]
+    for call in range(12):                               # past the point where launch shapes follow the feedback
+        xs = [to_dev(wl.draw_x(w, g)) for w, g in zip(ws, gens)]
+        ds = [to_dev(wl.draw_d(w, g)) for w, g in zip(ws, gens)]
+        for a, w, x, d in zip(alone, ws, xs, ds):
+            a.pulsed_update(x, d, w.lr)
+        order = list(range(len(ws)))
+        if call % 2:
+            order.reverse()                              # the order of the entries does not matter
+        aht.pulsed_update_many([many[i] for i in order], [xs[i] for i in order], [ds[i] for i in order],
+                               [ws[i].lr for i in order])
+        if call in (0, 1, 5, 11):
+            torch.cuda.synchronize()
+            for i, (a, m) in enumerate(zip(alone, many)):
+                Wa, Wm = a.get_weights().cpu().numpy(), m.get_weights().cpu().numpy()
+                assert (Wa.view(np.uint32) == Wm.view(np.uint32)).all(), f"call {call}, tile {i} ({ws[i].name})"
+                assert a.pulse_count() == m.pulse_count(), f"call {call}, tile {i}"
+                assert a.step == m.step == call + 1
+    for t in alone + many:
+        t.close()
+
+
+def test_work_queued_after_the_call_sees_every_tile_updated():
+    """the caller's stream waits for all the library's streams: a copy queued right after the call, without
+    any synchronisation in between, reads the updated weights"""
+    import torch
+    ws = _workloads()[:5]
+    tiles = [make_tile(w, seed=7 + i) for i, w in enumerate(ws)]
+    refs = [make_tile(w, seed=7 + i) for i, w in enumerate(ws)]
+    for w, t, r in zip(ws, tiles, refs):
+        W0 = to_dev(wl.initial_weights(w))
+        t.set_weights(W0)
+        r.set_weights(W0)
+    g = [wl.rng_for(w, 3) for w in ws]
+    xs = [to_dev(wl.draw_x(w, gg)) for w, gg in zip(ws, g)]
+    ds = [to_dev(wl.draw_d(w, gg)) for w, gg in zip(ws, g)]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):                        # a stream of the caller's own, not the default one
+        aht.pulsed_update_many(tiles, xs, ds, [w.lr for w in ws])
+        got = [t.get_weights() for t in tiles]           # queued on `side` behind the call
+    side.synchronize()
+    for r, w, x, d in zip(refs, ws, xs, ds):
+        r.pulsed_update(x, d, w.lr)
+    torch.cuda.synchronize()
+    for i, (r, gw) in enumerate(zip(refs, got)):
+        assert (r.get_weights().cpu().numpy().view(np.uint32) == gw.cpu().numpy().view(np.uint32)).all(), i
+    for t in tiles + refs:
+        t.close()
+
+
+def test_a_tile_updated_among_others_matches_the_oracle():
+    import torch
+    ws = _workloads()
+    pick = 4                                             # 130 x 70, 7 vectors: the oracle takes a moment
+    tiles = [make_tile(w, seed=31 + i) for i, w in enumerate(ws)]
+    W0 = wl.initial_weights(ws[pick])
+    planes = gpu_planes(tiles[pick])
+    W0 = np.minimum(np.maximum(W0, planes["b_min"]), planes["b_max"])
+    for w, t in zip(ws, tiles):
+        t.set_weights(to_dev(W0 if t is tiles[pick] else wl.initial_weights(w)))
+    gens = [wl.rng_for(w, 5) for w in ws]
+    Wo = W0.copy()
+    total = 0
+    for call in range(3):
+        xs = [wl.draw_x(w, g) for w, g in zip(ws, gens)]
+        ds = [wl.draw_d(w, g) for w, g in zip(ws, gens)]
+        aht.pulsed_update_many(tiles, [to_dev(x) for x in xs], [to_dev(d) for d in ds], [w.lr for w in ws])
+        w = ws[pick]
+        total += oracle.pulsed_update(Wo, planes, oracle_params(w.device), w.bl, w.update_management, xs[pick],
+                                      ds[pick], w.lr, 31 + pick, call)
+    torch.cuda.synchronize()
+    Wg = tiles[pick].get_weights().cpu().numpy()
+    assert tiles[pick].pulse_count() == total
+    assert np.max(np.abs(Wg - Wo)) <= 1e-5 * ws[pick].device["w_max"]
+    for t in tiles:
+        t.close()
+
+
+def test_bad_entries_are_refused_before_anything_is_launched():
+    import torch
+    ws = _workloads()[:3]
+    tiles = [make_tile(w, seed=i) for i, w in enumerate(ws)]
+    for w, t in zip(ws, tiles):
+        t.set_weights(to_dev(wl.initial_weights(w)))
+    g = [wl.rng_for(w, 1) for w in ws]
+    xs = [to_dev(wl.draw_x(w, gg)) for w, gg in zip(ws, g)]
+    ds = [to_dev(wl.draw_d(w, gg)) for w, gg in zip(ws, g)]
+    before = [t.get_weights().cpu().numpy() for t in tiles]
+    with pytest.raises(aht.AhtError, match="same tile"):
+        aht.pulsed_update_many([tiles[0], tiles[1], tiles[0]], [xs[0], xs[1], xs[0]], [ds[0], ds[1], ds[0]],
+                               [0.1, 0.1, 0.1])
+    with pytest.raises(aht.AhtError, match="lr"):
+        aht.pulsed_update_many(tiles, xs, ds, [0.1, 0.1, float("nan")])
+    L = aht.load_library()
+    vp = ctypes.c_void_p
+    h = (vp * 3)(*[t._h for t in tiles])
+    xp = (vp * 3)(xs[0].data_ptr(), xs[1].data_ptr(), None)          # a null x with B > 0 in the last entry
+    dp = (vp * 3)(*[d.data_ptr() for d in ds])
+    Bs = (ctypes.c_int32 * 3)(*[w.batch for w in ws])
+    lrs = (ctypes.c_float * 3)(0.1, 0.1, 0.1)
+    assert L.aht_pulsed_update_many(h, xp, dp, Bs, lrs, 3, None) == 1
+    torch.cuda.synchronize()
+    for t, b in zip(tiles, before):
+        assert (t.get_weights().cpu().numpy().view(np.uint32) == b.view(np.uint32)).all()
+        assert t.step == 0
+        t.close()

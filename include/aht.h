@@ -152,7 +152,8 @@ aht_status aht_pulsed_update_noalloc(aht_tile* tile, const float* x_dev, const f
  * are one launch, and so are the cell-update kernels of up to 16 tiles of one device kind, word width, noise
  * setting and launch shape; what cannot share a launch (update management, sparse long batches, tiles being
  * profiled) runs on a few streams of the library's own, forked from `stream` and joined to it again with events,
- * all at the default priority; tiny tiles whose update is one short launch follow one another on `stream`.
+ * all at the default priority.  Tiny tiles whose whole update is one short launch share launches as well (sixteen
+ * 64 x 64 tiles with one vector each: 2.3 us per tile against 6.1, what is left being the host's part).
  * Eight 512 x 512 tiles with 64 vectors each take 43 us per tile this way, 66 us one after the other; eight
  * 1024 x 1024 tiles with 128 vectors 108 against 129 us.
  *   tiles, x_dev, d_dev, B, lr: host arrays of n entries; x_dev[i] [B[i]][cols_i], d_dev[i] [B[i]][rows_i] device

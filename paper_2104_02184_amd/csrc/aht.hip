@@ -1081,19 +1081,25 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
     static std::mutex issue;                      // one call at a time forks and joins through the lanes' events
     std::lock_guard<std::mutex> lock(issue);
 
-    // Three kinds of entries.  `in_turn`: nothing to apply, or tiny tiles whose whole update is one short launch:
-    // on the caller's stream, one after the other (forking costs more than they take).  `grouped`: dense updates
+    // Four kinds of entries.  `in_turn`: nothing to apply: on the caller's stream (one tiny kernel that advances
+    // the step).  `tiny`: tiles whose whole update is one short launch (k_update_small): on the caller's stream,
+    // sharing launches per signature (forking would cost more than they take).  `grouped`: dense updates
     // whose cell kernels can share a launch with those of other tiles (k_cell_update_group): their pulse-train
     // kernels go to the lanes, their cell updates follow on the caller's stream after the join, one launch per
     // signature.  `whole`: everything else (row lists, tiles being profiled, a stream being recorded): the whole
     // update on a lane.
     const bool recorded = being_recorded(caller);
     const bool grouping = env_int("AHT_GROUP", 1) != 0 && !recorded;
-    std::vector<int> in_turn, grouped, whole;
+    std::vector<int> in_turn, tiny, grouped, whole;
     for (int i = 0; i < n; ++i) {
         aht_tile* t = tiles[i];
-        if (B[i] == 0 || lr[i] == 0.0f || use_small_kernel(t, B[i])) {
+        if (B[i] == 0 || lr[i] == 0.0f) {
             in_turn.push_back(i);
+            continue;
+        }
+        if (use_small_kernel(t, B[i])) {
+            if (grouping && !t->profiling) tiny.push_back(i);
+            else in_turn.push_back(i);
             continue;
         }
         refresh_pulse_rate(t);                    // (the choices below follow the tile's latest counters)
@@ -1103,6 +1109,10 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
     if (grouped.size() == 1) {                    // nothing to share a launch with
         whole.push_back(grouped[0]);
         grouped.clear();
+    }
+    if (tiny.size() == 1) {
+        in_turn.push_back(tiny[0]);
+        tiny.clear();
     }
     auto words_work = [&](int i) { return ((double)tiles[i]->rows + tiles[i]->cols) * (double)B[i]; };
     auto cells_work = [&](int i) { return (double)tiles[i]->rows * tiles[i]->cols * ((double)B[i] + 8.0); };
@@ -1151,6 +1161,63 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
             g.n += 1;
         }
         if ((st = flush()) != AHT_OK) return st;
+    }
+    // the tiny tiles: their one-launch updates share launches per signature (device kind, word width, noise)
+    {
+        std::vector<char> done(n, 0);
+        for (size_t a0 = 0; a0 < tiny.size(); ++a0) {
+            const int i0 = tiny[a0];
+            if (done[i0]) continue;
+            const aht_tile* t0 = tiles[i0];
+            SmallGroup g{};
+            unsigned blocks = 0;
+            for (size_t a1 = a0; a1 < tiny.size() && g.n < (uint32_t)kGroupMax; ++a1) {
+                const int i = tiny[a1];
+                aht_tile* t = tiles[i];
+                if (done[i] || t->dev.kind != t0->dev.kind || use_u32(t) != use_u32(t0) ||
+                    (t->dev.dw_min_std > 0.0f) != (t0->dev.dw_min_std > 0.0f))
+                    continue;
+                SmallGroupEntry& e = g.e[g.n];
+                e.W = t->W;
+                weights_written(t);
+                e.dw_up = t->planes[AHT_PLANE_DW_UP]; e.dw_down = t->planes[AHT_PLANE_DW_DOWN];
+                e.b_max = t->planes[AHT_PLANE_B_MAX]; e.b_min = t->planes[AHT_PLANE_B_MIN];
+                e.slope_up = t->planes[AHT_PLANE_SLOPE_UP]; e.slope_down = t->planes[AHT_PLANE_SLOPE_DOWN];
+                e.x = x_dev[i]; e.d = d_dev[i];
+                e.pulse_count = t->pulse_count; e.step_state = t->step_state;
+                e.A = std::sqrt((double)lr[i] / ((double)t->dev.dw_min * (double)t->upd.bl));
+                e.B = B[i]; e.R = t->rows; e.C = t->cols; e.BL = t->upd.bl; e.deterministic = t->train_kind;
+                e.k0 = (uint32_t)t->seed; e.k1 = (uint32_t)(t->seed >> 32); e.t = t->step;
+                e.c2c = t->dev.dw_min_std;
+                g.first_block[g.n] = blocks;
+                blocks += (unsigned)((t->cols + 63) / 64) * (unsigned)((t->rows + 3) / 4);
+                g.n += 1;
+                done[i] = 1;
+                t->info.rows_per_lane = 1;
+                t->info.side_rows_per_lane = 0;
+                t->info.row_lists = 0;
+                t->info.stream_words = 0;
+                t->full_updates += 1;
+                t->step += 1;
+            }
+            for (uint32_t k = g.n; k <= (uint32_t)kGroupMax; ++k) g.first_block[k] = blocks;
+            const bool noise = t0->dev.dw_min_std > 0.0f;
+#define AHT_SMALL_GROUP(K, WT)                                                                                       \
+    do {                                                                                                            \
+        if (noise) hipLaunchKernelGGL((k_update_small_group<K, WT, true>), dim3(blocks), dim3(256), 0, caller, g);  \
+        else hipLaunchKernelGGL((k_update_small_group<K, WT, false>), dim3(blocks), dim3(256), 0, caller, g);       \
+    } while (0)
+#define AHT_SMALL_GROUP_KIND(WT)                                                    \
+    switch (t0->dev.kind) {                                                         \
+        case AHT_CONSTANT_STEP: AHT_SMALL_GROUP(kConstantStep, WT); break;          \
+        case AHT_LINEAR_STEP: AHT_SMALL_GROUP(kLinearStep, WT); break;              \
+        default: AHT_SMALL_GROUP(kSoftBounds, WT); break;                           \
+    }
+            if (use_u32(t0)) { AHT_SMALL_GROUP_KIND(uint32_t) } else { AHT_SMALL_GROUP_KIND(uint64_t) }
+#undef AHT_SMALL_GROUP_KIND
+#undef AHT_SMALL_GROUP
+            AHT_HIP(hipGetLastError());
+        }
     }
     // lane work, largest first, each item to the lane with the least work so far
     struct Item { int i; bool words_only; double work; };

@@ -1606,14 +1606,17 @@ __device__ __forceinline__ WordT line_word(float v, double a, int bl, int determ
 
 constexpr int kSmallMaxB = 8;                     // update vectors one launch of k_update_small takes
 
+// (the body is a device function so that one launch can also take several tiny tiles, see
+// k_update_small_group: workgroup `block` of the `nblocks` the tile has)
 template <int KIND, typename WordT, bool NOISE>
-__global__ void __launch_bounds__(256)
-k_update_small(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
-               const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
-               const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
-               const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int BL, double A,
-               int deterministic, uint32_t k0, uint32_t k1, float c2c, unsigned long long* __restrict__ pulse_count,
-               uint32_t t, uint32_t* step_state, int recorded, ConvView conv)
+__device__ __forceinline__ void
+update_small_body(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
+                  const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
+                  const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
+                  const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int BL, double A,
+                  int deterministic, uint32_t k0, uint32_t k1, float c2c, unsigned long long* __restrict__ pulse_count,
+                  uint32_t t, uint32_t* step_state, int recorded, const ConvView& conv, const uint32_t block,
+                  const uint32_t nblocks)
 {
     // (a call made directly: the step is t and t + 1 is left in the device's counter; a recorded call reads
     // the counter, and the last wave advances it)
@@ -1621,7 +1624,7 @@ k_update_small(float* __restrict__ W, const float* __restrict__ p_dw_up, const f
     constexpr int kSign = WordTraits<WordT>::kSignBit;
     if (recorded) t = *(const volatile uint32_t*)step_state;
     const int strips = (C + 63) / 64;
-    const int j0 = (int)(blockIdx.x % (uint32_t)strips) * 64, i0 = (int)(blockIdx.x / (uint32_t)strips) * 4;
+    const int j0 = (int)(block % (uint32_t)strips) * 64, i0 = (int)(block / (uint32_t)strips) * 4;
     for (int item = (int)threadIdx.x; item < B * 68; item += 256) {
         const int b = item / 68, l = item % 68;
         if (l < 64) {
@@ -1673,8 +1676,54 @@ k_update_small(float* __restrict__ W, const float* __restrict__ p_dw_up, const f
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) pulses += __shfl_xor(pulses, off, 64);
     if (lane == 0 && pulses) atomicAdd(pulse_count, pulses);
-    if (recorded) finish_step(step_state, gridDim.x * 4u);
-    else if (blockIdx.x == 0 && threadIdx.x == 0) step_state[0] = t + 1u;
+    if (recorded) finish_step(step_state, nblocks * 4u);
+    else if (block == 0 && threadIdx.x == 0) step_state[0] = t + 1u;
+}
+
+template <int KIND, typename WordT, bool NOISE>
+__global__ void __launch_bounds__(256)
+k_update_small(float* __restrict__ W, const float* __restrict__ p_dw_up, const float* __restrict__ p_dw_down,
+               const float* __restrict__ p_b_max, const float* __restrict__ p_b_min,
+               const float* __restrict__ p_slope_up, const float* __restrict__ p_slope_down,
+               const float* __restrict__ x, const float* __restrict__ d, int B, int R, int C, int BL, double A,
+               int deterministic, uint32_t k0, uint32_t k1, float c2c, unsigned long long* __restrict__ pulse_count,
+               uint32_t t, uint32_t* step_state, int recorded, ConvView conv)
+{
+    update_small_body<KIND, WordT, NOISE>(W, p_dw_up, p_dw_down, p_b_max, p_b_min, p_slope_up, p_slope_down, x, d, B, R, C,
+                                          BL, A, deterministic, k0, k1, c2c, pulse_count, t, step_state, recorded, conv,
+                                          blockIdx.x, gridDim.x);
+}
+
+// The one-launch updates of several tiny tiles in one launch (aht_pulsed_update_many; calls made directly, no
+// convolution view): entry i owns workgroups first_block[i] .. first_block[i + 1] - 1.
+struct SmallGroupEntry {
+    float* W;
+    const float *dw_up, *dw_down, *b_max, *b_min, *slope_up, *slope_down, *x, *d;
+    unsigned long long* pulse_count;
+    uint32_t* step_state;
+    double A;
+    int B, R, C, BL, deterministic;
+    uint32_t k0, k1, t;
+    float c2c;
+    uint32_t pad_;
+};
+struct SmallGroup {
+    uint32_t n, pad_;
+    uint32_t first_block[kGroupMax + 1];
+    SmallGroupEntry e[kGroupMax];
+};
+
+template <int KIND, typename WordT, bool NOISE>
+__global__ void __launch_bounds__(256)
+k_update_small_group(SmallGroup g)
+{
+    (void)g;
+    uint32_t block;
+    const SmallGroupEntry e = group_entry_of_block<SmallGroup, SmallGroupEntry>(&block);
+    const uint32_t nblocks = (uint32_t)((e.C + 63) / 64) * (uint32_t)((e.R + 3) / 4);
+    update_small_body<KIND, WordT, NOISE>(e.W, e.dw_up, e.dw_down, e.b_max, e.b_min, e.slope_up, e.slope_down, e.x, e.d, e.B,
+                                          e.R, e.C, e.BL, e.A, e.deterministic, e.k0, e.k1, e.c2c, e.pulse_count, e.t,
+                                          e.step_state, 0, ConvView{}, block, nblocks);
 }
 
 }  // namespace aht

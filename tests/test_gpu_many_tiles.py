@@ -26,6 +26,9 @@ MIX = [  # (base workload, rows, cols, batch)
     ("cfg2_512x512_constant_d2d", 256, 640, 33),        # shares a launch with the 512 x 512 tile above
     ("cfg3_1024x1024_softbounds", 516, 200, 64),
     (wl.HEADLINE, 96, 520, 17),
+    ("cfg1_64x64_constant", 50, 130, 2),                # tiny tiles of one signature share a launch
+    ("cfg1_64x64_constant", 7, 64, 8),
+    ("cfg3_1024x1024_softbounds", 32, 64, 3),           # a tiny tile of another signature: a launch of its own
 ]
 
 

@@ -162,7 +162,9 @@ aht_status aht_pulsed_update_noalloc(aht_tile* tile, const float* x_dev, const f
  *   are issued one at a time.
  * Errors: INVALID_ARG if any entry would be rejected by aht_pulsed_update, if a tile appears twice, or if the
  * tiles do not all live on the current device -- checked for every entry before anything is launched; OOM,
- * DEVICE as for aht_pulsed_update (some of the tiles may then have been updated, others not).
+ * DEVICE as for aht_pulsed_update (some of the tiles may then have been updated, others not); UNSUPPORTED if
+ * `stream` is being recorded into a graph and n > 1 (the shared launches take the step from the host: record one
+ * aht_pulsed_update_noalloc per tile instead).
  * AHT_GROUP=0 in the environment keeps every tile's kernels in launches of their own (on the streams). */
 aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_dev, const float* const* d_dev,
                                   const int32_t* B, const float* lr, int32_t n, void* stream);

@@ -1076,6 +1076,9 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
     }
     hipStream_t caller = (hipStream_t)stream;
     if (n == 1) return pulsed_update_impl(tiles[0], x_dev[0], d_dev[0], B[0], lr[0], stream, ConvView{});
+    if (being_recorded(caller))
+        return fail(AHT_ERR_UNSUPPORTED, "aht_pulsed_update_many cannot be recorded into a graph (its shared launches take "
+                    "the step from the host); record one aht_pulsed_update_noalloc per tile instead");
     ManyLanes* m = nullptr;
     if ((st = many_lanes(tiles[0]->device, &m)) != AHT_OK) return st;
     static std::mutex issue;                      // one call at a time forks and joins through the lanes' events
@@ -1086,10 +1089,9 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
     // sharing launches per signature (forking would cost more than they take).  `grouped`: dense updates
     // whose cell kernels can share a launch with those of other tiles (k_cell_update_group): their pulse-train
     // kernels go to the lanes, their cell updates follow on the caller's stream after the join, one launch per
-    // signature.  `whole`: everything else (row lists, tiles being profiled, a stream being recorded): the whole
+    // signature.  `whole`: everything else (row lists, tiles being profiled): the whole
     // update on a lane.
-    const bool recorded = being_recorded(caller);
-    const bool grouping = env_int("AHT_GROUP", 1) != 0 && !recorded;
+    const bool grouping = env_int("AHT_GROUP", 1) != 0;
     std::vector<int> in_turn, tiny, grouped, whole;
     for (int i = 0; i < n; ++i) {
         aht_tile* t = tiles[i];

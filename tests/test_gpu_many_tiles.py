@@ -155,3 +155,30 @@ def test_bad_entries_are_refused_before_anything_is_launched():
         assert (t.get_weights().cpu().numpy().view(np.uint32) == b.view(np.uint32)).all()
         assert t.step == 0
         t.close()
+
+
+def test_recording_the_call_into_a_graph_is_refused_and_launches_nothing():
+    import torch
+    ws = _workloads()[:2]
+    tiles = [make_tile(w, seed=i) for i, w in enumerate(ws)]
+    for w, t in zip(ws, tiles):
+        t.set_weights(to_dev(wl.initial_weights(w)))
+    g = [wl.rng_for(w, 1) for w in ws]
+    xs = [to_dev(wl.draw_x(w, gg)) for w, gg in zip(ws, g)]
+    ds = [to_dev(wl.draw_d(w, gg)) for w, gg in zip(ws, g)]
+    before = [t.get_weights().cpu().numpy() for t in tiles]
+    other = torch.zeros(16, device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        other.add_(1.0)                                  # (so that the recorded graph is not empty)
+        with pytest.raises(aht.AhtError, match="recorded"):
+            aht.pulsed_update_many(tiles, xs, ds, [w.lr for w in ws])
+    graph.replay()
+    torch.cuda.synchronize()
+    assert float(other[0]) == 1.0
+    for t, b in zip(tiles, before):
+        assert (t.get_weights().cpu().numpy().view(np.uint32) == b.view(np.uint32)).all()
+        assert t.step == 0
+        t.close()
+

@@ -12,7 +12,7 @@ import paper_2104_02184_amd as aht
 from common import gpu_params, oracle_params, to_dev
 
 pytestmark = pytest.mark.gpu
-ENV_KEYS = ("AHT_RPL", "AHT_QWORDS", "AHT_MVM_BM", "AHT_MVM_SPLITS", "AHT_ROWLISTS", "AHT_FUSED")
+ENV_KEYS = ("AHT_RPL", "AHT_QWORDS", "AHT_MVM_BM", "AHT_MVM_SPLITS", "AHT_ROWLISTS", "AHT_FUSED", "AHT_GROUP")
 
 
 @pytest.fixture
@@ -32,6 +32,54 @@ def _setenv(**kw):
             os.environ[k] = str(v)
         else:
             os.environ.pop(k, None)
+
+
+@pytest.mark.parametrize("seed", [11, 22, 33])
+def test_several_random_tiles_per_call_match_the_oracle(seed, clean_env):
+    """aht_pulsed_update_many on random sets of tiles (2 to 9 tiles of random shapes, device kinds, train lengths,
+    update management and batch lengths; a few device descriptions, so that several tiles of a set share a
+    launch): every tile against the oracle, pulse counts exact."""
+    g = np.random.default_rng(seed)
+    for case in range(8):
+        os.environ["AHT_GROUP"] = str(int(g.choice([1, 1, 0])))
+        os.environ["AHT_FUSED"] = str(int(g.choice([0, 1])))
+        n = int(g.integers(2, 10))
+        menu = []
+        for _ in range(3):                                  # three device descriptions per set
+            c2c, d2d = float(g.choice([0.0, 0.3])), float(g.choice([0.0, 0.3]))
+            menu.append((dict(kind=int(g.integers(0, 3)), dw_min=0.002, dw_min_dtod=d2d, dw_min_std=c2c, up_down=0.02,
+                              up_down_dtod=0.01 if d2d else 0.0, w_max=0.6, w_max_dtod=d2d, w_min=-0.6, w_min_dtod=d2d,
+                              gamma_up=0.7, gamma_down=0.5, gamma_dtod=d2d),
+                         int(g.choice([7, 31, 32, 63])), bool(g.integers(0, 2))))
+        tiles, state = [], []
+        for k in range(n):
+            dev, bl, um = menu[int(g.integers(0, 3))]
+            R, C = int(g.integers(1, 260)), int(g.integers(1, 300))
+            B = int(g.integers(1, 9)) if g.integers(0, 3) == 0 else int(g.integers(1, 70))
+            tseed = int(g.integers(1, 1 << 30))
+            tile = aht.Tile(R, C, gpu_params(dev), bl, um, tseed)
+            planes = oracle.device_planes(oracle_params(dev), tseed, R, C)
+            W0 = np.clip(g.uniform(-0.3, 0.3, size=(R, C)), planes["b_min"], planes["b_max"]).astype(np.float32)
+            tile.set_weights(to_dev(W0))
+            tiles.append(tile)
+            state.append(dict(dev=dev, bl=bl, um=um, R=R, C=C, B=B, seed=tseed, planes=planes, W=W0.copy(), pulses=0,
+                              lr=float(g.choice([0.01, 0.1, 1.0]))))
+        for t in range(3):
+            xs, ds = [], []
+            for st in state:
+                xs.append(g.normal(size=(st["B"], st["C"])).astype(np.float32))
+                ds.append(g.normal(size=(st["B"], st["R"])).astype(np.float32))
+                st["pulses"] += oracle.pulsed_update(st["W"], st["planes"], oracle_params(st["dev"]), st["bl"], st["um"],
+                                                     xs[-1], ds[-1], st["lr"], st["seed"], t)
+            aht.pulsed_update_many(tiles, [to_dev(x) for x in xs], [to_dev(d) for d in ds], [st["lr"] for st in state])
+        for k, (tile, st) in enumerate(zip(tiles, state)):
+            what = dict(case=case, tile=k, R=st["R"], C=st["C"], B=st["B"], bl=st["bl"], um=st["um"], kind=st["dev"]["kind"],
+                        group=os.environ["AHT_GROUP"], fused=os.environ["AHT_FUSED"], info=tile.launch_info())
+            Wg = tile.get_weights().cpu().numpy()
+            assert tile.step == 3 == tile.sync_step(), what
+            assert tile.pulse_count() == st["pulses"], what
+            assert np.abs(Wg.astype(np.float64) - st["W"]).max() / 0.6 <= 1e-5, what
+            tile.close()
 
 
 @pytest.mark.parametrize("seed", [101, 202, 303, 404])

@@ -407,6 +407,22 @@ def bench_many(args):
         times[name] = (time.perf_counter() - t0) / K
         pulses = (sum(t.pulse_count() for t in tiles) - p0) / K / N
     info = tiles[0].launch_info()
+    ms_graph = None
+    if args.graph:
+        # the same K rounds recorded once into a HIP graph and replayed: what a round costs without the host
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            for k in range(K):
+                together(k)
+        graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - g0) / K * 1e3
+        for t in tiles:
+            t.sync_step()
     for t in tiles:
         t.close()
     sec = times["together"]
@@ -416,6 +432,7 @@ def bench_many(args):
         "metric": "Gcell-pulse-updates/s of pulsed_update", "value": N * w.cell_pulse_updates_per_call / sec / 1e9,
         "unit": "Gcell-pulse-updates/s", "n_gpus": 1, "steps": K, "warmup": max(Wm, 20), "ms_per_step": sec * 1e3,
         "ms_per_tile": sec * 1e3 / N, "ms_per_tile_one_after_the_other": times["in_turn"] * 1e3 / N,
+        "ms_per_tile_graph_replay": ms_graph / N if ms_graph is not None else None,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{N} tiles of {w.name} per step (aht_pulsed_update_many)", "tiles": N, "rows": w.rows,
                    "cols": w.cols, "batch": w.batch, "bl": w.bl, "pulses_per_tile_and_call": pulses},

@@ -268,6 +268,15 @@ size_t static_scratch_layout(const aht_tile* t, int B, unsigned char* base, Word
 // pulse trains of the call at step `step` into `w`
 // `row_stat`: device counter that receives the number of row trains with a pulse (nullable)
 // `recorded`: the kernels read the step from the tile's device counter instead of `step`
+// whether ensure_scratch(t, B) would find everything large enough already (a call being recorded cannot allocate)
+bool scratch_fits(const aht_tile* t, int B)
+{
+    if ((size_t)B * cpad(t) * word_bytes(t) > t->xw_bytes || (size_t)bpad(B) * rpad(t) * word_bytes(t) > t->dw_bytes) return false;
+    if (t->dynamic_bl && B > t->bl_cap) return false;
+    if ((t->upd.update_management || t->dynamic_bl) && B > t->a_cap) return false;
+    return true;
+}
+
 aht_status launch_words(aht_tile* t, const WordBufs& w, const float* x, const float* d, int B, float lr, uint32_t step,
                         hipStream_t s, const ConvView& conv = ConvView{}, unsigned long long* row_stat = nullptr,
                         bool recorded = false)
@@ -1076,9 +1085,19 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
     }
     hipStream_t caller = (hipStream_t)stream;
     if (n == 1) return pulsed_update_impl(tiles[0], x_dev[0], d_dev[0], B[0], lr[0], stream, ConvView{});
-    if (being_recorded(caller))
-        return fail(AHT_ERR_UNSUPPORTED, "aht_pulsed_update_many cannot be recorded into a graph (its shared launches take "
-                    "the step from the host); record one aht_pulsed_update_noalloc per tile instead");
+    // A call being recorded into a graph: the kernels read every tile's step from its device counter and a small
+    // kernel advances the counters afterwards; nothing may be allocated, no counters are sent to the host.
+    const bool recorded = being_recorded(caller);
+    if (recorded) {
+        for (int i = 0; i < n; ++i) {
+            const aht_tile* t = tiles[i];
+            if (B[i] == 0 || lr[i] == 0.0f || use_small_kernel(t, B[i])) continue;
+            if (t->profiling || !scratch_fits(t, B[i]) ||
+                (use_row_lists(t, B[i]) && ((size_t)rpad(t) * ((size_t)bpad(B[i]) + kRowListPad) > t->rlist_entries || !t->rlen)))
+                return fail(AHT_ERR_UNSUPPORTED, "entry %d: a recorded call cannot allocate scratch or time its kernels; make "
+                            "the same call once outside the recording first (and switch profiling off)", i);
+        }
+    }
     ManyLanes* m = nullptr;
     if ((st = many_lanes(tiles[0]->device, &m)) != AHT_OK) return st;
     static std::mutex issue;                      // one call at a time forks and joins through the lanes' events
@@ -1158,6 +1177,7 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
             e.BL = t->upd.bl; e.deterministic = t->train_kind;
             e.k0 = (uint32_t)t->seed; e.k1 = (uint32_t)(t->seed >> 32); e.t = t->step;
             e.nbx = nbx; e.ny = ny;
+            e.step_on_device = recorded ? t->step_state : nullptr;
             g.first_block[g.n] = blocks;
             blocks += nbx * ny;
             g.n += 1;
@@ -1191,6 +1211,7 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
                 e.B = B[i]; e.R = t->rows; e.C = t->cols; e.BL = t->upd.bl; e.deterministic = t->train_kind;
                 e.k0 = (uint32_t)t->seed; e.k1 = (uint32_t)(t->seed >> 32); e.t = t->step;
                 e.c2c = t->dev.dw_min_std;
+                e.recorded = recorded ? 1 : 0;
                 g.first_block[g.n] = blocks;
                 blocks += (unsigned)((t->cols + 63) / 64) * (unsigned)((t->rows + 3) / 4);
                 g.n += 1;
@@ -1247,7 +1268,7 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
         } else if ((result = ensure_scratch(t, B[i])) == AHT_OK) {
             watched[i] = watched_update(t, B[i]);
             result = launch_words(t, tile_bufs(t), x_dev[i], d_dev[i], B[i], lr[i], t->step, m->stream[lane], ConvView{},
-                                  watched[i] ? t->pulse_count + 2 : nullptr, false);
+                                  watched[i] ? t->pulse_count + 2 : nullptr, recorded);
             if (result != AHT_OK) grouped.clear();
         } else {
             grouped.clear();                      // (no cell updates without every tile's pulse words)
@@ -1270,7 +1291,7 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
     for (int i : grouped) {
         aht_tile* t = tiles[i];
         if ((st = build_cell_launch(t, B[i], t->step, 0u, (uint32_t)((t->cols + 63) / 64), tile_bufs(t), true, false, true,
-                                    false, &cl[i])) != AHT_OK)
+                                    recorded, &cl[i])) != AHT_OK)
             return st;
     }
     std::vector<char> done(n, 0);
@@ -1301,10 +1322,17 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
         if (use_u32(t0)) launch_group_kind<uint32_t>(t0->dev.kind, t0->dev.dw_min_std > 0.0f, cl[i0].rpl, g, blocks, cl[i0].lds, caller);
         else launch_group_kind<uint64_t>(t0->dev.kind, t0->dev.dw_min_std > 0.0f, cl[i0].rpl, g, blocks, cl[i0].lds, caller);
         AHT_HIP(hipGetLastError());
+        if (recorded) {                           // the kernels above read the devices' counters: now they move on
+            StepGroup sg{};
+            for (uint32_t k = 0; k < g.n; ++k) sg.state[k] = g.e[k].a.publish ? nullptr : const_cast<uint32_t*>(g.e[k].a.step_on_device);
+            sg.n = g.n;
+            hipLaunchKernelGGL(k_advance_steps, dim3(1), dim3(64), 0, caller, sg);
+            AHT_HIP(hipGetLastError());
+        }
     }
     for (int i : grouped) {
         aht_tile* t = tiles[i];
-        if ((st = full_update_done(t, B[i], watched[i] != 0, true, caller)) != AHT_OK) return st;
+        if ((st = full_update_done(t, B[i], watched[i] != 0, !recorded, caller)) != AHT_OK) return st;
         t->step += 1;
     }
     return AHT_OK;

@@ -516,6 +516,7 @@ struct WordsGroupEntry {
     double A;
     int B, R, C, Rpad, Cpad, Bpad, BL, deterministic;
     uint32_t k0, k1, t, nbx, ny, pad_;
+    const uint32_t* step_on_device;               // a recorded call: the step is read from the tile's device counter
 };
 struct WordsGroup {
     uint32_t n, pad_;
@@ -531,7 +532,7 @@ k_pulse_words_group(WordsGroup g)
     uint32_t block;
     const WordsGroupEntry e = group_entry_of_block<WordsGroup, WordsGroupEntry>(&block);
     pulse_words_body<WordT>(e.x, e.d, e.B, e.R, e.C, e.Rpad, e.Cpad, e.Bpad, e.BL, e.A, nullptr, nullptr, nullptr,
-                            e.deterministic, e.k0, e.k1, e.t, nullptr, (WordT*)e.xw, (WordT*)e.dw, ConvView{},
+                            e.deterministic, e.k0, e.k1, e.t, e.step_on_device, (WordT*)e.xw, (WordT*)e.dw, ConvView{},
                             e.row_stat, block % e.nbx, block / e.nbx, e.ny);
 }
 
@@ -1559,6 +1560,16 @@ k_cell_update_group(CellGroup g)
     if (e.a.publish && block == 0 && threadIdx.x == 0) *e.a.publish = e.a.t + 1u;
 }
 
+// after a recorded shared launch: the device-side step counters of its tiles move on
+struct StepGroup {
+    uint32_t n, pad_;
+    uint32_t* state[kGroupMax];
+};
+__global__ void k_advance_steps(StepGroup g)
+{
+    if (threadIdx.x < g.n) *g.state[threadIdx.x] += 1u;
+}
+
 // ------------------------------------------------------------------------------------------
 // The whole update call in one launch, for tiny tiles and a few update vectors (an on-line update of
 // a small layer: 64 x 64, one vector): two dependent launches cost more than the work itself.  A
@@ -1705,7 +1716,7 @@ struct SmallGroupEntry {
     int B, R, C, BL, deterministic;
     uint32_t k0, k1, t;
     float c2c;
-    uint32_t pad_;
+    int recorded;                                 // the step is read from step_state[0], and the last wave advances it
 };
 struct SmallGroup {
     uint32_t n, pad_;
@@ -1723,7 +1734,7 @@ k_update_small_group(SmallGroup g)
     const uint32_t nblocks = (uint32_t)((e.C + 63) / 64) * (uint32_t)((e.R + 3) / 4);
     update_small_body<KIND, WordT, NOISE>(e.W, e.dw_up, e.dw_down, e.b_max, e.b_min, e.slope_up, e.slope_down, e.x, e.d, e.B,
                                           e.R, e.C, e.BL, e.A, e.deterministic, e.k0, e.k1, e.c2c, e.pulse_count, e.t,
-                                          e.step_state, 0, ConvView{}, block, nblocks);
+                                          e.step_state, e.recorded, ConvView{}, block, nblocks);
 }
 
 }  // namespace aht

@@ -157,28 +157,73 @@ def test_bad_entries_are_refused_before_anything_is_launched():
         t.close()
 
 
-def test_recording_the_call_into_a_graph_is_refused_and_launches_nothing():
+def test_a_recorded_call_replays_with_steps_that_move_on():
+    """A call recorded into a graph (shared launches, update management on the library's streams, tiny tiles), replayed
+    three times with eager work and synchronisations between the replays: every replay bit for bit what tiles
+    updated by calls of their own get; a tile whose scratch is too small is refused before anything is recorded."""
     import torch
-    ws = _workloads()[:2]
-    tiles = [make_tile(w, seed=i) for i, w in enumerate(ws)]
-    for w, t in zip(ws, tiles):
-        t.set_weights(to_dev(wl.initial_weights(w)))
-    g = [wl.rng_for(w, 1) for w in ws]
-    xs = [to_dev(wl.draw_x(w, gg)) for w, gg in zip(ws, g)]
-    ds = [to_dev(wl.draw_d(w, gg)) for w, gg in zip(ws, g)]
-    before = [t.get_weights().cpu().numpy() for t in tiles]
-    other = torch.zeros(16, device="cuda")
+    ws = [_workloads()[i] for i in (0, 1, 3, 4, 6, 7, 10, 11)]
+    eager = [make_tile(w, seed=50 + i) for i, w in enumerate(ws)]
+    graphed = [make_tile(w, seed=50 + i) for i, w in enumerate(ws)]
+    for w, a, b in zip(ws, eager, graphed):
+        W0 = to_dev(wl.initial_weights(w))
+        a.set_weights(W0)
+        b.set_weights(W0)
+    gens = [wl.rng_for(w, 21) for w in ws]
+    lrs = [w.lr for w in ws]
+    xbuf = [torch.zeros((w.batch, w.cols), dtype=torch.float32, device="cuda") for w in ws]
+    dbuf = [torch.zeros((w.batch, w.rows), dtype=torch.float32, device="cuda") for w in ws]
+
+    def fresh():
+        return ([to_dev(wl.draw_x(w, g)) for w, g in zip(ws, gens)], [to_dev(wl.draw_d(w, g)) for w, g in zip(ws, gens)])
+
+    # no scratch yet: refused, and nothing is recorded
     torch.cuda.synchronize()
+    other = torch.zeros(16, device="cuda")
+    refused = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(refused):
+        other.add_(1.0)                                  # (so that the recorded graph is not empty)
+        with pytest.raises(aht.AhtError, match="outside the recording"):
+            aht.pulsed_update_many(graphed, xbuf, dbuf, lrs)
+    assert all(t.step == 0 for t in graphed)
+    # one call outside the recording (both sets of tiles make it), then two calls recorded
+    xs, ds = fresh()
+    for a, x, d, lr in zip(eager, xs, ds, lrs):
+        a.pulsed_update(x, d, lr)
+    aht.pulsed_update_many(graphed, xs, ds, lrs)
+    torch.cuda.synchronize()
+    per_graph = 2
+    xb = [[torch.zeros_like(b) for b in xbuf] for _ in range(per_graph)]
+    db = [[torch.zeros_like(b) for b in dbuf] for _ in range(per_graph)]
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        other.add_(1.0)                                  # (so that the recorded graph is not empty)
-        with pytest.raises(aht.AhtError, match="recorded"):
-            aht.pulsed_update_many(tiles, xs, ds, [w.lr for w in ws])
-    graph.replay()
+        for k in range(per_graph):
+            aht.pulsed_update_many(graphed, xb[k], db[k], lrs)
     torch.cuda.synchronize()
-    assert float(other[0]) == 1.0
-    for t, b in zip(tiles, before):
-        assert (t.get_weights().cpu().numpy().view(np.uint32) == b.view(np.uint32)).all()
-        assert t.step == 0
+    for t in graphed:                                   # recording launched nothing; the host's counters ran ahead
+        assert t.sync_step() == 1
+    for r in range(3):
+        for k in range(per_graph):
+            xs, ds = fresh()
+            for i, a in enumerate(eager):                # eager work between the replays
+                xb[k][i].copy_(xs[i])
+                db[k][i].copy_(ds[i])
+                a.pulsed_update(xs[i], ds[i], lrs[i])
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(eager, graphed)):
+            Wa, Wb = a.get_weights().cpu().numpy(), b.get_weights().cpu().numpy()
+            assert (Wa.view(np.uint32) == Wb.view(np.uint32)).all(), f"replay {r}, tile {i} ({ws[i].name})"
+            assert a.pulse_count() == b.pulse_count(), f"replay {r}, tile {i}"
+            assert b.sync_step() == a.step == 1 + (r + 1) * per_graph
+    # calls made directly afterwards continue the same sequence
+    xs, ds = fresh()
+    for a, x, d, lr in zip(eager, xs, ds, lrs):
+        a.pulsed_update(x, d, lr)
+    aht.pulsed_update_many(graphed, xs, ds, lrs)
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(zip(eager, graphed)):
+        assert (a.get_weights().cpu().numpy().view(np.uint32) == b.get_weights().cpu().numpy().view(np.uint32)).all(), i
+        assert a.step == b.step
+    for t in eager + graphed:
         t.close()
-

@@ -149,10 +149,10 @@ aht_status aht_pulsed_update_noalloc(aht_tile* tile, const float* x_dev, const f
  * the others).  Tile i gets exactly what aht_pulsed_update(tiles[i], x_dev[i], d_dev[i], B[i], lr[i], .) gives
  * it, bit for bit -- a tile's result depends on its own inputs, seed and step counter only -- but tiles too
  * small to fill the chip on their own share the chip: the pulse-train kernels of up to 16 tiles of one word width
- * are one launch, and so are the cell-update kernels of up to 16 tiles of one device kind, word width, noise
- * setting and launch shape; what cannot share a launch (update management, sparse long batches, tiles being
- * profiled) runs on a few streams of the library's own, forked from `stream` and joined to it again with events,
- * all at the default priority.  Tiny tiles whose whole update is one short launch share launches as well (sixteen
+ * are one launch (behind one for the per-vector factors of update management and per-vector train lengths), and so
+ * are the cell-update kernels of up to 16 tiles of one device kind, word width, noise setting and launch shape;
+ * what cannot share a launch (sparse long batches that walk row lists, tiles being profiled) runs on a few streams
+ * of the library's own, forked from `stream` and joined to it again with events, all at the default priority.  Tiny tiles whose whole update is one short launch share launches as well (sixteen
  * 64 x 64 tiles with one vector each: 2.2 us per tile against 6.4, what is left being the host's part: 0.4 us
  * replayed from a recorded graph).
  * Eight 512 x 512 tiles with 64 vectors each take 43 us per tile this way, 66 us one after the other; eight

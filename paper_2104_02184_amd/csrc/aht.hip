@@ -1137,17 +1137,25 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
     }
     auto words_work = [&](int i) { return ((double)tiles[i]->rows + tiles[i]->cols) * (double)B[i]; };
     auto cells_work = [&](int i) { return (double)tiles[i]->rows * tiles[i]->cols * ((double)B[i] + 8.0); };
-    // The pulse words of the grouped entries: those with a fixed train length and one probability factor per call
-    // share launches too (k_pulse_words_group, per word width, on the caller's stream); the others (update
-    // management, per-vector train lengths: a reduction kernel first) draw theirs on the lanes.
+    // The pulse words of the grouped entries share launches too (k_pulse_words_group, per word width, on the
+    // caller's stream), behind one launch for the per-vector factors of those that need them (update management,
+    // per-vector train lengths: k_line_scale_group).
     AHT_HIP(hipEventRecord(m->fork, caller));     // (before the caller's stream gets work of this call)
     std::vector<char> watched(n, 0);
     std::vector<int> words_on_lanes;
     for (int width = 4; width <= 8; width += 4) {
         WordsGroup g{};
-        unsigned blocks = 0;
+        LineScaleGroup ls{};
+        unsigned blocks = 0, ls_blocks = 0;
         auto flush = [&]() -> aht_status {
             if (g.n == 0) return AHT_OK;
+            if (ls.n != 0) {
+                for (uint32_t k = ls.n; k <= (uint32_t)kGroupMax; ++k) ls.first_block[k] = ls_blocks;
+                hipLaunchKernelGGL(k_line_scale_group, dim3(ls_blocks), dim3(256), 0, caller, ls);
+                AHT_HIP(hipGetLastError());
+                ls = LineScaleGroup{};
+                ls_blocks = 0;
+            }
             for (uint32_t k = g.n; k <= (uint32_t)kGroupMax; ++k) g.first_block[k] = blocks;
             if (width == 4) hipLaunchKernelGGL(k_pulse_words_group<uint32_t>, dim3(blocks), dim3(256), 0, caller, g);
             else hipLaunchKernelGGL(k_pulse_words_group<uint64_t>, dim3(blocks), dim3(256), 0, caller, g);
@@ -1159,10 +1167,6 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
         for (int i : grouped) {
             aht_tile* t = tiles[i];
             if ((int)word_bytes(t) != width) continue;
-            if (t->upd.update_management || t->dynamic_bl) {
-                words_on_lanes.push_back(i);
-                continue;
-            }
             if ((st = ensure_scratch(t, B[i])) != AHT_OK) return st;
             watched[i] = watched_update(t, B[i]);
             const WordBufs w = tile_bufs(t);
@@ -1172,6 +1176,17 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
             WordsGroupEntry& e = g.e[g.n];
             e.x = x_dev[i]; e.d = d_dev[i]; e.xw = w.xw; e.dw = w.dw;
             e.row_stat = watched[i] ? t->pulse_count + 2 : nullptr;
+            if (t->upd.update_management || t->dynamic_bl) {
+                LineScaleGroupEntry& q = ls.e[ls.n];
+                q.x = x_dev[i]; q.d = d_dev[i]; q.a_x = w.a_x; q.a_d = w.a_d; q.bl_b = t->dynamic_bl ? w.bl_b : nullptr;
+                q.lr = (double)lr[i]; q.dw_min = (double)t->dev.dw_min;
+                q.R = t->rows; q.C = t->cols; q.BL = t->upd.bl; q.update_management = t->upd.update_management;
+                q.dynamic_bl = t->dynamic_bl;
+                ls.first_block[ls.n] = ls_blocks;
+                ls_blocks += (unsigned)B[i];
+                ls.n += 1;
+                e.a_x = w.a_x; e.a_d = w.a_d; e.bl_b = q.bl_b;
+            }
             e.A = std::sqrt((double)lr[i] / ((double)t->dev.dw_min * (double)t->upd.bl));
             e.B = B[i]; e.R = t->rows; e.C = t->cols; e.Rpad = rpad(t); e.Cpad = cpad(t); e.Bpad = bpad(B[i]);
             e.BL = t->upd.bl; e.deterministic = t->train_kind;

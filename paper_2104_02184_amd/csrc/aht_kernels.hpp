@@ -273,15 +273,14 @@ __device__ __forceinline__ float finite_abs_or_zero(float v)
     return (a < __builtin_inff()) ? a : 0.0f;   // NaN and Inf compare false
 }
 
-__global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
-                                                    const float* __restrict__ d, int R, int C,
-                                                    double lr, double dw_min, int BL, int update_management,
-                                                    int dynamic_bl, double* __restrict__ a_x,
-                                                    double* __restrict__ a_d, int32_t* __restrict__ bl_b,
-                                                    ConvView conv)
+// (the body is a device function so that one launch can also take the vectors of several tiles, see
+// k_line_scale_group: sample `b`)
+__device__ __forceinline__ void line_scale_body(const float* __restrict__ x, const float* __restrict__ d, int R, int C,
+                                                double lr, double dw_min, int BL, int update_management,
+                                                int dynamic_bl, double* __restrict__ a_x, double* __restrict__ a_d,
+                                                int32_t* __restrict__ bl_b, const ConvView& conv, const int b)
 {
     __shared__ float red_x[4], red_d[4];
-    const int b = blockIdx.x;
     float mx = 0.0f, md = 0.0f;
     for (int j = threadIdx.x; j < C; j += 256) mx = fmaxf(mx, finite_abs_or_zero(view_x(x, conv, (uint32_t)b, j, C)));
     for (int i = threadIdx.x; i < R; i += 256) md = fmaxf(md, finite_abs_or_zero(view_d(d, conv, (uint32_t)b, i, R)));
@@ -320,6 +319,16 @@ __global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
         a_d[b] = ad;
         if (bl_b) bl_b[b] = bl;
     }
+}
+
+__global__ void __launch_bounds__(256) k_line_scale(const float* __restrict__ x,
+                                                    const float* __restrict__ d, int R, int C,
+                                                    double lr, double dw_min, int BL, int update_management,
+                                                    int dynamic_bl, double* __restrict__ a_x,
+                                                    double* __restrict__ a_d, int32_t* __restrict__ bl_b,
+                                                    ConvView conv)
+{
+    line_scale_body(x, d, R, C, lr, dw_min, BL, update_management, dynamic_bl, a_x, a_d, bl_b, conv, (int)blockIdx.x);
 }
 
 // OR of a value over aligned groups of 8 or 16 lanes, in every lane of the group: data-parallel
@@ -506,13 +515,14 @@ k_pulse_words(const float* __restrict__ x, const float* __restrict__ d, int B, i
                             xw, dw, conv, row_words_with_pulses, blockIdx.x, blockIdx.y, gridDim.y);
 }
 
-// The pulse words of several tiles in one launch (aht_pulsed_update_many; fixed train length, one probability
-// factor per call, no convolution view): entry i owns workgroups first_block[i] .. first_block[i + 1] - 1, laid out
+// The pulse words of several tiles in one launch (aht_pulsed_update_many; no convolution view): entry i owns workgroups first_block[i] .. first_block[i + 1] - 1, laid out
 // as nbx workgroups of lines times ny strides of samples, as the grid of its own launch would be.
 struct WordsGroupEntry {
     const float *x, *d;
     void *xw, *dw;
     unsigned long long* row_stat;
+    const double *a_x, *a_d;                      // per-vector factors and train lengths (k_line_scale_group), or null
+    const int32_t* bl_b;
     double A;
     int B, R, C, Rpad, Cpad, Bpad, BL, deterministic;
     uint32_t k0, k1, t, nbx, ny, pad_;
@@ -524,6 +534,29 @@ struct WordsGroup {
     WordsGroupEntry e[kGroupMax];
 };
 
+// The per-vector factors of several tiles in one launch: entry i owns workgroups first_block[i] ..
+// first_block[i + 1] - 1, one per update vector.
+struct LineScaleGroupEntry {
+    const float *x, *d;
+    double *a_x, *a_d;
+    int32_t* bl_b;
+    double lr, dw_min;
+    int R, C, BL, update_management, dynamic_bl, pad_;
+};
+struct LineScaleGroup {
+    uint32_t n, pad_;
+    uint32_t first_block[kGroupMax + 1];
+    LineScaleGroupEntry e[kGroupMax];
+};
+__global__ void __launch_bounds__(256) k_line_scale_group(LineScaleGroup g)
+{
+    (void)g;
+    uint32_t block;
+    const LineScaleGroupEntry e = group_entry_of_block<LineScaleGroup, LineScaleGroupEntry>(&block);
+    line_scale_body(e.x, e.d, e.R, e.C, e.lr, e.dw_min, e.BL, e.update_management, e.dynamic_bl, e.a_x, e.a_d, e.bl_b,
+                    ConvView{}, (int)block);
+}
+
 template <typename WordT>
 __global__ void __launch_bounds__(256)
 k_pulse_words_group(WordsGroup g)
@@ -531,7 +564,7 @@ k_pulse_words_group(WordsGroup g)
     (void)g;
     uint32_t block;
     const WordsGroupEntry e = group_entry_of_block<WordsGroup, WordsGroupEntry>(&block);
-    pulse_words_body<WordT>(e.x, e.d, e.B, e.R, e.C, e.Rpad, e.Cpad, e.Bpad, e.BL, e.A, nullptr, nullptr, nullptr,
+    pulse_words_body<WordT>(e.x, e.d, e.B, e.R, e.C, e.Rpad, e.Cpad, e.Bpad, e.BL, e.A, e.a_x, e.a_d, e.bl_b,
                             e.deterministic, e.k0, e.k1, e.t, e.step_on_device, (WordT*)e.xw, (WordT*)e.dw, ConvView{},
                             e.row_stat, block % e.nbx, block / e.nbx, e.ny);
 }

@@ -48,6 +48,12 @@ def test_many_tiles_in_one_call_equal_calls_of_their_own(group, monkeypatch):
         W0 = to_dev(wl.initial_weights(w))
         a.set_weights(W0)
         m.set_weights(W0)
+    # other train generators on some of the tiles: per-vector train lengths (with and without update management),
+    # deterministic trains
+    for k, mode in ((0, dict(dynamic_bl=True)), (7, dict(dynamic_bl=True)), (8, dict(deterministic=True)),
+                    (9, dict(deterministic=True, dynamic_bl=True))):
+        alone[k].set_pulse_mode(**mode)
+        many[k].set_pulse_mode(**mode)
     gens = [wl.rng_for(w, 11) for w in ws]
     for call in range(12):                               # past the point where launch shapes follow the feedback
         xs = [to_dev(wl.draw_x(w, g)) for w, g in zip(ws, gens)]

@@ -1106,10 +1106,9 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
     // Four kinds of entries.  `in_turn`: nothing to apply: on the caller's stream (one tiny kernel that advances
     // the step).  `tiny`: tiles whose whole update is one short launch (k_update_small): on the caller's stream,
     // sharing launches per signature (forking would cost more than they take).  `grouped`: dense updates
-    // whose cell kernels can share a launch with those of other tiles (k_cell_update_group): their pulse-train
-    // kernels go to the lanes, their cell updates follow on the caller's stream after the join, one launch per
-    // signature.  `whole`: everything else (row lists, tiles being profiled): the whole
-    // update on a lane.
+    // whose kernels can share launches with those of other tiles: per-vector factors, pulse words and cell updates,
+    // one launch per signature each, on the caller's stream (the cell updates after the lanes have joined).
+    // `whole`: everything else (row lists, tiles being profiled): the whole update on a lane.
     const bool grouping = env_int("AHT_GROUP", 1) != 0;
     std::vector<int> in_turn, tiny, grouped, whole;
     for (int i = 0; i < n; ++i) {
@@ -1135,14 +1134,12 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
         in_turn.push_back(tiny[0]);
         tiny.clear();
     }
-    auto words_work = [&](int i) { return ((double)tiles[i]->rows + tiles[i]->cols) * (double)B[i]; };
     auto cells_work = [&](int i) { return (double)tiles[i]->rows * tiles[i]->cols * ((double)B[i] + 8.0); };
     // The pulse words of the grouped entries share launches too (k_pulse_words_group, per word width, on the
     // caller's stream), behind one launch for the per-vector factors of those that need them (update management,
     // per-vector train lengths: k_line_scale_group).
     AHT_HIP(hipEventRecord(m->fork, caller));     // (before the caller's stream gets work of this call)
     std::vector<char> watched(n, 0);
-    std::vector<int> words_on_lanes;
     for (int width = 4; width <= 8; width += 4) {
         WordsGroup g{};
         LineScaleGroup ls{};
@@ -1257,11 +1254,10 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
             AHT_HIP(hipGetLastError());
         }
     }
-    // lane work, largest first, each item to the lane with the least work so far
-    struct Item { int i; bool words_only; double work; };
+    // the whole updates that go to the lanes, largest first, each to the lane with the least work so far
+    struct Item { int i; double work; };
     std::vector<Item> items;
-    for (int i : whole) items.push_back({i, false, cells_work(i)});
-    for (int i : words_on_lanes) items.push_back({i, true, words_work(i)});
+    for (int i : whole) items.push_back({i, cells_work(i)});
     std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.work > b.work; });
     double load[kManyStreams] = {0.0, 0.0, 0.0, 0.0};
     bool used[kManyStreams] = {false, false, false, false};
@@ -1278,16 +1274,7 @@ aht_status aht_pulsed_update_many(aht_tile* const* tiles, const float* const* x_
             used[lane] = true;
         }
         load[lane] += items[k].work;
-        if (!items[k].words_only) {
-            result = pulsed_update_impl(t, x_dev[i], d_dev[i], B[i], lr[i], (void*)m->stream[lane], ConvView{});
-        } else if ((result = ensure_scratch(t, B[i])) == AHT_OK) {
-            watched[i] = watched_update(t, B[i]);
-            result = launch_words(t, tile_bufs(t), x_dev[i], d_dev[i], B[i], lr[i], t->step, m->stream[lane], ConvView{},
-                                  watched[i] ? t->pulse_count + 2 : nullptr, recorded);
-            if (result != AHT_OK) grouped.clear();
-        } else {
-            grouped.clear();                      // (no cell updates without every tile's pulse words)
-        }
+        result = pulsed_update_impl(t, x_dev[i], d_dev[i], B[i], lr[i], (void*)m->stream[lane], ConvView{});
     }
     for (size_t k = 0; k < in_turn.size() && result == AHT_OK; ++k) {
         const int i = in_turn[k];
